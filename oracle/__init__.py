@@ -1,0 +1,223 @@
+"""CPU oracle for the Blossom attention hot path -- TEST INFRASTRUCTURE.
+
+Thin ctypes marshalling around ``blossom_oracle.c`` (plain C, fp64 attention,
+canonical fp32 block scoring).  Only ``tests/``, ``__graft_entry__.smoke()``
+and the ``cpu_baseline`` leg of ``bench.py`` may import this package; the
+product path never does, and this package never imports the HIP binding.
+
+All arithmetic lives in the C file; this module only converts numpy arrays to
+pointers and allocates outputs.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+import subprocess
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_SRC = os.path.join(_HERE, "blossom_oracle.c")
+_LIB = os.path.join(_HERE, "libblossom_oracle.so")
+
+_c_int = ctypes.c_int
+_c_dbl = ctypes.c_double
+_vp = ctypes.c_void_p
+
+
+def build(force: bool = False) -> str:
+    """Compile the oracle with gcc.  No fast-math, no FMA contraction."""
+    if force or not os.path.exists(_LIB) or os.path.getmtime(_LIB) < os.path.getmtime(_SRC):
+        cmd = ["gcc", "-O2", "-std=c11", "-fopenmp", "-fPIC", "-shared", "-ffp-contract=off",
+               "-fno-fast-math", "-Wall", "-Wextra", "-o", _LIB, _SRC, "-lm"]
+        subprocess.run(cmd, check=True)
+    return _LIB
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    global _lib
+    if _lib is None:
+        build()
+        L = ctypes.CDLL(_LIB)
+        L.oracle_num_threads.restype = _c_int
+        L.oracle_select_blocks.restype = _c_int
+        L.oracle_select_blocks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
+        L.oracle_build_masks.restype = _c_int
+        L.oracle_build_masks.argtypes = [_c_int] * 5 + [_vp, _vp, _vp]
+        L.oracle_masked_attention.restype = _c_int
+        L.oracle_masked_attention.argtypes = [_c_int, _c_int, _vp, _vp, _vp, _vp, _c_dbl, _vp, _vp]
+        L.oracle_attn_fwd.restype = _c_int
+        L.oracle_attn_fwd.argtypes = ([_c_int] * 7 + [_c_dbl, _c_int] + [_vp] * 7 + [_vp, _c_int]
+                                      + [_vp] * 7)
+        L.oracle_attn_bwd.restype = _c_int
+        L.oracle_attn_bwd.argtypes = ([_c_int] * 7 + [_c_dbl, _c_int] + [_vp] * 8 + [_vp, _c_int]
+                                      + [_vp] * 5)
+        L.oracle_dense_causal_fwd.restype = _c_int
+        L.oracle_dense_causal_fwd.argtypes = ([_c_int] * 4 + [_c_dbl, _c_int] + [_vp] * 4
+                                              + [_vp, _c_int, _vp, _vp])
+        _lib = L
+    return _lib
+
+
+def num_threads() -> int:
+    return int(lib().oracle_num_threads())
+
+
+def _p(a):
+    return None if a is None else a.ctypes.data_as(_vp)
+
+
+def _in(a, f64):
+    return np.ascontiguousarray(a, dtype=np.float64 if f64 else np.float32)
+
+
+def _bh(bh_list, B, H):
+    if bh_list is None:
+        return None, B * H
+    a = np.ascontiguousarray(bh_list, dtype=np.int32)
+    assert a.ndim == 1 and a.size > 0 and a.min() >= 0 and a.max() < B * H
+    return a, int(a.size)
+
+
+def _check(rc, what):
+    if rc != 0:
+        raise RuntimeError(f"oracle {what} failed with code {rc}")
+
+
+def select_blocks(Q, K, valid_len, block, topk, bh_list=None, want_scores=False):
+    """Steps 1-3.  Q, K: [B,H,L,d] float32.  Returns sel [B,H,NB,k] int32 (rows of pairs
+    not in bh_list are left at -2) and, if asked, scores [n_bh,NB,NB] float32."""
+    Q = _in(Q, False)
+    K = _in(K, False)
+    B, H, L, d = Q.shape
+    NB = -(-L // block)
+    vl = np.ascontiguousarray(valid_len, dtype=np.int32)
+    assert vl.shape == (B,)
+    bh, n_bh = _bh(bh_list, B, H)
+    sel = np.full((B, H, NB, topk), -2, dtype=np.int32)
+    scores = np.zeros((n_bh, NB, NB), dtype=np.float32) if want_scores else None
+    rc = lib().oracle_select_blocks(B, H, L, d, block, topk, _p(Q), _p(K), _p(vl), _p(bh), n_bh,
+                                    _p(sel), _p(scores))
+    _check(rc, "select_blocks")
+    return (sel, scores) if want_scores else sel
+
+
+def build_masks(L, block, topk, window, n_valid, sel_bh):
+    """The two materialised masks of one (row, head): uint8 [L,L] each."""
+    s = np.ascontiguousarray(sel_bh, dtype=np.int32)
+    NB = -(-L // block)
+    assert s.shape == (NB, topk)
+    M_lt = np.zeros((L, L), dtype=np.uint8)
+    M_st = np.zeros((L, L), dtype=np.uint8)
+    _check(lib().oracle_build_masks(L, block, topk, window, int(n_valid), _p(s), _p(M_lt), _p(M_st)),
+           "build_masks")
+    return M_lt, M_st
+
+
+def masked_attention(q, k, v, M, scale):
+    """Eq. 1 for one head: q,k,v [L,d] float64, M uint8 [L,L].  Returns o [L,d], lse [L]."""
+    q = _in(q, True)
+    k = _in(k, True)
+    v = _in(v, True)
+    M = np.ascontiguousarray(M, dtype=np.uint8)
+    L, d = q.shape
+    o = np.zeros((L, d), dtype=np.float64)
+    lse = np.zeros(L, dtype=np.float64)
+    _check(lib().oracle_masked_attention(L, d, _p(q), _p(k), _p(v), _p(M), float(scale), _p(o), _p(lse)),
+           "masked_attention")
+    return o, lse
+
+
+@dataclass
+class Fwd:
+    O: np.ndarray        # [n_bh,L,d] float64
+    o_lt: np.ndarray
+    o_st: np.ndarray
+    lse_lt: np.ndarray   # [n_bh,L]
+    lse_st: np.ndarray
+    alpha: np.ndarray
+    nnz_lt: int
+    nnz_st: int
+
+
+def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale=None,
+             bh_list=None, f64=False) -> Fwd:
+    Q = _in(Q, f64)
+    K = _in(K, f64)
+    V = _in(V, f64)
+    B, H, L, d = Q.shape
+    if scale is None or scale == 0.0:
+        scale = 1.0 / np.sqrt(d)
+    vl = np.ascontiguousarray(valid_len, dtype=np.int32)
+    sel = np.ascontiguousarray(sel, dtype=np.int32)
+    NB = -(-L // block)
+    assert sel.shape == (B, H, NB, topk)
+    gw = _in(gate_w, f64)
+    assert gw.shape == (H, 2 * d)
+    gb = None if gate_b is None else _in(gate_b, f64)
+    bh, n_bh = _bh(bh_list, B, H)
+    z = lambda *s: np.zeros(s, dtype=np.float64)
+    out = Fwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L), z(n_bh, L), z(n_bh, L), 0, 0)
+    nnz = np.zeros(2, dtype=np.int64)
+    rc = lib().oracle_attn_fwd(B, H, L, d, block, topk, window, float(scale), int(f64),
+                               _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(bh), n_bh,
+                               _p(out.O), _p(out.o_lt), _p(out.o_st), _p(out.lse_lt), _p(out.lse_st),
+                               _p(out.alpha), _p(nnz))
+    _check(rc, "attn_fwd")
+    out.nnz_lt, out.nnz_st = int(nnz[0]), int(nnz[1])
+    return out
+
+
+@dataclass
+class Bwd:
+    dQ: np.ndarray        # [n_bh,L,d] float64
+    dK: np.ndarray
+    dV: np.ndarray
+    d_gate_w: np.ndarray  # [H,2d], summed over the listed pairs
+    d_gate_b: np.ndarray  # [H]
+
+
+def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, scale=None,
+             bh_list=None, f64=False) -> Bwd:
+    Q = _in(Q, f64)
+    K = _in(K, f64)
+    V = _in(V, f64)
+    dO = _in(dO, f64)
+    B, H, L, d = Q.shape
+    assert dO.shape == Q.shape
+    if scale is None or scale == 0.0:
+        scale = 1.0 / np.sqrt(d)
+    vl = np.ascontiguousarray(valid_len, dtype=np.int32)
+    sel = np.ascontiguousarray(sel, dtype=np.int32)
+    gw = _in(gate_w, f64)
+    gb = None if gate_b is None else _in(gate_b, f64)
+    bh, n_bh = _bh(bh_list, B, H)
+    z = lambda *s: np.zeros(s, dtype=np.float64)
+    out = Bwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(H, 2 * d), z(H))
+    rc = lib().oracle_attn_bwd(B, H, L, d, block, topk, window, float(scale), int(f64),
+                               _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(dO),
+                               _p(bh), n_bh, _p(out.dQ), _p(out.dK), _p(out.dV),
+                               _p(out.d_gate_w), _p(out.d_gate_b))
+    _check(rc, "attn_bwd")
+    return out
+
+
+def dense_causal_fwd(Q, K, V, valid_len, scale=None, bh_list=None, f64=False):
+    Q = _in(Q, f64)
+    K = _in(K, f64)
+    V = _in(V, f64)
+    B, H, L, d = Q.shape
+    if scale is None or scale == 0.0:
+        scale = 1.0 / np.sqrt(d)
+    vl = np.ascontiguousarray(valid_len, dtype=np.int32)
+    bh, n_bh = _bh(bh_list, B, H)
+    O = np.zeros((n_bh, L, d), dtype=np.float64)
+    lse = np.zeros((n_bh, L), dtype=np.float64)
+    rc = lib().oracle_dense_causal_fwd(B, H, L, d, float(scale), int(f64), _p(Q), _p(K), _p(V),
+                                       _p(vl), _p(bh), n_bh, _p(O), _p(lse))
+    _check(rc, "dense_causal_fwd")
+    return O, lse

@@ -1,0 +1,543 @@
+/*
+ * blossom_oracle.c -- TEST INFRASTRUCTURE, not part of the product path.
+ *
+ * A plain, slow, CPU-only statement of what the Blossom attention hot path
+ * computes (BlossomRec, arXiv 2512.13368, Sec. 3.4-3.6), used only by the test
+ * suite, the smoke check and the CPU-baseline leg of the benchmark.  It shares
+ * no code, header, table or helper with the HIP library and is never called by
+ * it.  Attention arithmetic is fp64; block scoring uses a fixed fp32 recipe so
+ * that the selected block indices are a single well-defined integer answer.
+ *
+ * Geometry (one block size b for query blocks, compression blocks and
+ * selection blocks, i.e. Eq. 8 with l = s = l' = b, for which the score
+ * mapping of Eq. 11 is the identity):
+ *   NB = ceil(L/b) blocks; block I covers positions [I*b, min((I+1)*b, L)).
+ *   Row r of the batch has n valid positions, left padded: p0 = L-n .. L-1.
+ *
+ * Steps, in the paper's order:
+ *   1. Block compression (Eq. 9) with phi = mean over the block's valid keys;
+ *      the query block is pooled the same way (unnormalised sum).
+ *   2. Importance score of key block J for query block I (Eq. 10): the inner
+ *      product of the pooled vectors.  The softmax of Eq. 10 is monotone per
+ *      query block and is dropped: it cannot change a top-k.
+ *   3. Top-k (Eq. 13): the query block's own block is always taken and counts
+ *      toward k; the other k-1 come from strictly earlier blocks that hold at
+ *      least one valid key, ordered by (score descending, index ascending).
+ *   4. Long-term branch: softmax attention (Eq. 1) over the keys of the
+ *      selected blocks (Eq. 14, 16), causal inside the own block.
+ *   5. Short-term branch: softmax attention under the causal half of the
+ *      local-window term of Eq. 15: 0 <= i-j < w (Eq. 17).
+ *   6. Gate (Eq. 18-19): alpha = sigmoid(Wg . [o_lt ; o_st] + bg) per
+ *      (position, head); O = alpha*o_lt + (1-alpha)*o_st.
+ *   7. Backward: the chain rule through steps 4-6 with the selection frozen.
+ *
+ * Both branch masks are materialised as L x L byte matrices and the attention
+ * is the masked softmax of Eq. 1 written out; nothing is blocked, fused or
+ * reordered.
+ *
+ * Canonical fp32 scoring recipe (what makes the indices bit-exact):
+ *   Qsum_I[c]  = sequential fp32 sum, ascending position, from +0.0f, valid only
+ *   Kmean_J[c] = (same kind of sum over K) / (float)count, IEEE division
+ *   s[I][J]    = acc = +0.0f; for c = 0..d-1: acc = fmaf(Qsum_I[c], Kmean_J[c], acc)
+ * Build with -ffp-contract=off and without fast-math.
+ *
+ * Parity status: every function here is pinned by tests/test_oracle_*.py
+ * (dense special case against a library attention routine, forced gates,
+ * brute-force subset enumeration, hand-computed integer fixture, finite
+ * differences, invariances).  Absolute outputs for random inputs have no
+ * printed reference in the paper: beyond those pins they are "parity unpinned".
+ */
+#include <math.h>
+#include <stdint.h>
+#include <stdlib.h>
+#include <string.h>
+#ifdef _OPENMP
+#include <omp.h>
+#endif
+
+static int n_blocks(int L, int b) { return (L + b - 1) / b; }
+static int imin(int a, int b) { return a < b ? a : b; }
+
+int oracle_num_threads(void)
+{
+#ifdef _OPENMP
+    return omp_get_max_threads();
+#else
+    return 1;
+#endif
+}
+
+/* ------------------------------------------------------------------------- */
+/* Steps 1-3: pooling, scoring, top-k (fp32 canonical recipe), one (row, head) */
+/* ------------------------------------------------------------------------- */
+static int select_one(int L, int d, int b, int k, const float *q, const float *key,
+                      int n_valid, int32_t *sel /* [NB*k] */, float *scores /* [NB*NB] or NULL */)
+{
+    const int NB = n_blocks(L, b);
+    const int p0 = L - n_valid;
+    float *qsum = (float *)calloc((size_t)NB * d, sizeof(float));
+    float *kmean = (float *)calloc((size_t)NB * d, sizeof(float));
+    float *sc = (float *)calloc((size_t)NB, sizeof(float));
+    uint8_t *chosen = (uint8_t *)calloc((size_t)NB, 1);
+    if (!qsum || !kmean || !sc || !chosen) {
+        free(qsum); free(kmean); free(sc); free(chosen);
+        return -1;
+    }
+    for (int I = 0; I < NB; ++I) {
+        const int lo = I * b, hi = imin(lo + b, L);
+        for (int c = 0; c < d; ++c) {
+            float aq = 0.0f, ak = 0.0f;
+            int cnt = 0;
+            for (int t = lo; t < hi; ++t) {
+                if (t < p0) continue;
+                aq = aq + q[(size_t)t * d + c];
+                ak = ak + key[(size_t)t * d + c];
+                ++cnt;
+            }
+            qsum[(size_t)I * d + c] = aq;
+            kmean[(size_t)I * d + c] = cnt > 0 ? ak / (float)cnt : 0.0f;
+        }
+    }
+    if (scores)
+        for (size_t i = 0; i < (size_t)NB * NB; ++i) scores[i] = 0.0f;
+
+    const int J_first = p0 / b;
+    for (int I = 0; I < NB; ++I) {
+        int32_t *out = sel + (size_t)I * k;
+        for (int e = 0; e < k; ++e) out[e] = -1;
+        const int hi = imin((I + 1) * b, L);
+        if (hi <= p0) continue; /* no valid query in this block */
+        const int n_cand = I - J_first; /* candidates J_first .. I-1 */
+        const int take = imin(k - 1, n_cand);
+        for (int J = J_first; J < I; ++J) {
+            float acc = 0.0f;
+            for (int c = 0; c < d; ++c)
+                acc = fmaf(qsum[(size_t)I * d + c], kmean[(size_t)J * d + c], acc);
+            sc[J] = acc;
+            chosen[J] = 0;
+            if (scores) scores[(size_t)I * NB + J] = acc;
+        }
+        for (int r = 0; r < take; ++r) {
+            int best = -1;
+            for (int J = J_first; J < I; ++J) {
+                if (chosen[J]) continue;
+                /* strict '>' keeps the lowest index among equal scores */
+                if (best < 0 || sc[J] > sc[best]) best = J;
+            }
+            chosen[best] = 1;
+        }
+        int e = 0;
+        for (int J = J_first; J < I; ++J)
+            if (chosen[J]) out[e++] = J;
+        out[e++] = I;
+    }
+    free(qsum); free(kmean); free(sc); free(chosen);
+    return 0;
+}
+
+/*
+ * Block selection for the (row, head) pairs listed in bh_list (flattened
+ * r*H + h; NULL = all, in order).  sel is the full [B,H,NB,k] array; only the
+ * listed pairs are written.  scores (optional) is [n_bh, NB, NB], entry
+ * [I][J] valid for J_first <= J < I.
+ */
+int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
+                         const float *Q, const float *K, const int32_t *valid_len,
+                         const int32_t *bh_list, int n_bh,
+                         int32_t *sel, float *scores)
+{
+    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || k < 1) return -2;
+    const int NB = n_blocks(L, b);
+    const int total = bh_list ? n_bh : B * H;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int it = 0; it < total; ++it) {
+        const int bh = bh_list ? bh_list[it] : it;
+        const int r = bh / H;
+        int n = valid_len[r];
+        if (n < 0) n = 0;
+        if (n > L) n = L;
+        const size_t off = (size_t)bh * L * d;
+        int rc = select_one(L, d, b, k, Q + off, K + off, n,
+                            sel + (size_t)bh * NB * k,
+                            scores ? scores + (size_t)it * NB * NB : NULL);
+        if (rc) {
+#pragma omp atomic write
+            err = rc;
+        }
+    }
+    return err;
+}
+
+/* ------------------------------------------------------------------------- */
+/* The two masks, materialised (Eq. 14 as a mask; Eq. 15 first case, causal). */
+/* ------------------------------------------------------------------------- */
+static void build_masks_one(int L, int b, int k, int w, int n_valid, const int32_t *sel,
+                            uint8_t *M_lt, uint8_t *M_st)
+{
+    const int p0 = L - n_valid;
+    for (int i = 0; i < L; ++i) {
+        const int32_t *si = sel + (size_t)(i / b) * k;
+        for (int j = 0; j < L; ++j) {
+            uint8_t lt = 0, st = 0;
+            if (i >= p0 && j >= p0) {
+                if (j <= i) {
+                    const int bj = j / b;
+                    for (int e = 0; e < k; ++e)
+                        if (si[e] == bj) lt = 1;
+                }
+                const int dist = i - j;
+                if (dist >= 0 && dist < w) st = 1;
+            }
+            M_lt[(size_t)i * L + j] = lt;
+            M_st[(size_t)i * L + j] = st;
+        }
+    }
+}
+
+int oracle_build_masks(int L, int b, int k, int w, int n_valid, const int32_t *sel_bh,
+                       uint8_t *M_lt, uint8_t *M_st)
+{
+    if (n_valid < 0) n_valid = 0;
+    if (n_valid > L) n_valid = L;
+    build_masks_one(L, b, k, w, n_valid, sel_bh, M_lt, M_st);
+    return 0;
+}
+
+static void dense_causal_mask(int L, int n_valid, uint8_t *M)
+{
+    const int p0 = L - n_valid;
+    for (int i = 0; i < L; ++i)
+        for (int j = 0; j < L; ++j)
+            M[(size_t)i * L + j] = (uint8_t)(i >= p0 && j >= p0 && j <= i);
+}
+
+/* ------------------------------------------------------------------------- */
+/* Eq. 1: softmax(scale*Q K^T + log M) V, one head, fp64.                      */
+/* Rows with an empty mask (pad rows) give o = 0 and lse = 0.                  */
+/* ------------------------------------------------------------------------- */
+static void masked_attention(int L, int d, const double *q, const double *key, const double *v,
+                             const uint8_t *M, double scale, double *o, double *lse,
+                             long long *nnz)
+{
+    double *s = (double *)malloc((size_t)L * sizeof(double));
+    long long cnt = 0;
+    for (int i = 0; i < L; ++i) {
+        const uint8_t *mi = M + (size_t)i * L;
+        double *oi = o + (size_t)i * d;
+        for (int c = 0; c < d; ++c) oi[c] = 0.0;
+        double mx = -INFINITY;
+        int any = 0;
+        for (int j = 0; j < L; ++j) {
+            if (!mi[j]) continue;
+            double acc = 0.0;
+            for (int c = 0; c < d; ++c) acc += q[(size_t)i * d + c] * key[(size_t)j * d + c];
+            s[j] = scale * acc;
+            if (s[j] > mx) mx = s[j];
+            any = 1;
+            ++cnt;
+        }
+        if (!any) {
+            lse[i] = 0.0;
+            continue;
+        }
+        double z = 0.0;
+        for (int j = 0; j < L; ++j)
+            if (mi[j]) z += exp(s[j] - mx);
+        const double l = mx + log(z);
+        lse[i] = l;
+        for (int j = 0; j < L; ++j) {
+            if (!mi[j]) continue;
+            const double p = exp(s[j] - l);
+            for (int c = 0; c < d; ++c) oi[c] += p * v[(size_t)j * d + c];
+        }
+    }
+    if (nnz) *nnz = cnt;
+    free(s);
+}
+
+/* public single-head entry point, used by the tests to pin Eq. 1 itself */
+int oracle_masked_attention(int L, int d, const double *q, const double *key, const double *v,
+                            const uint8_t *M, double scale, double *o, double *lse)
+{
+    masked_attention(L, d, q, key, v, M, scale, o, lse, NULL);
+    return 0;
+}
+
+static void widen(const void *src, int is_f64, size_t off, size_t n, double *dst)
+{
+    if (is_f64) {
+        memcpy(dst, (const double *)src + off, n * sizeof(double));
+    } else {
+        const float *s = (const float *)src + off;
+        for (size_t i = 0; i < n; ++i) dst[i] = (double)s[i];
+    }
+}
+
+static double load1(const void *src, int is_f64, size_t idx)
+{
+    return is_f64 ? ((const double *)src)[idx] : (double)((const float *)src)[idx];
+}
+
+/* ------------------------------------------------------------------------- */
+/* Steps 4-6 for the listed (row, head) pairs.                                 */
+/* Inputs Q,K,V: full [B,H,L,d] (float, or double when in_f64).                */
+/* gate_w [H,2d], gate_b [H] or NULL (same element type as Q).                 */
+/* Outputs are compact, indexed by position in bh_list:                        */
+/*   O, o_lt, o_st [n_bh,L,d]; lse_lt, lse_st, alpha [n_bh,L]; any may be NULL */
+/*   nnz [2]: number of unmasked (i,j) pairs in the two branches, summed.      */
+/* ------------------------------------------------------------------------- */
+int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, double scale,
+                    int in_f64, const void *Q, const void *K, const void *V,
+                    const int32_t *valid_len, const int32_t *sel,
+                    const void *gate_w, const void *gate_b,
+                    const int32_t *bh_list, int n_bh,
+                    double *O, double *o_lt, double *o_st,
+                    double *lse_lt, double *lse_st, double *alpha, long long *nnz)
+{
+    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || k < 1 || w < 1) return -2;
+    const int NB = n_blocks(L, b);
+    const int total = bh_list ? n_bh : B * H;
+    const size_t Ld = (size_t)L * d;
+    long long nnz_lt = 0, nnz_st = 0;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1) reduction(+ : nnz_lt, nnz_st)
+    for (int it = 0; it < total; ++it) {
+        const int bh = bh_list ? bh_list[it] : it;
+        const int r = bh / H, h = bh % H;
+        int n = valid_len[r];
+        if (n < 0) n = 0;
+        if (n > L) n = L;
+        const int p0 = L - n;
+        double *q = (double *)malloc(Ld * sizeof(double));
+        double *key = (double *)malloc(Ld * sizeof(double));
+        double *v = (double *)malloc(Ld * sizeof(double));
+        double *ol = (double *)malloc(Ld * sizeof(double));
+        double *os = (double *)malloc(Ld * sizeof(double));
+        double *ll = (double *)malloc((size_t)L * sizeof(double));
+        double *ls = (double *)malloc((size_t)L * sizeof(double));
+        uint8_t *M_lt = (uint8_t *)malloc((size_t)L * L);
+        uint8_t *M_st = (uint8_t *)malloc((size_t)L * L);
+        if (!q || !key || !v || !ol || !os || !ll || !ls || !M_lt || !M_st) {
+#pragma omp atomic write
+            err = -1;
+        } else {
+            widen(Q, in_f64, (size_t)bh * Ld, Ld, q);
+            widen(K, in_f64, (size_t)bh * Ld, Ld, key);
+            widen(V, in_f64, (size_t)bh * Ld, Ld, v);
+            build_masks_one(L, b, k, w, n, sel + (size_t)bh * NB * k, M_lt, M_st);
+            long long c_lt = 0, c_st = 0;
+            masked_attention(L, d, q, key, v, M_lt, scale, ol, ll, &c_lt);
+            masked_attention(L, d, q, key, v, M_st, scale, os, ls, &c_st);
+            nnz_lt += c_lt;
+            nnz_st += c_st;
+            for (int i = 0; i < L; ++i) {
+                double a = 0.0;
+                if (i >= p0) {
+                    double z = gate_b ? load1(gate_b, in_f64, (size_t)h) : 0.0;
+                    for (int c = 0; c < d; ++c) {
+                        z += load1(gate_w, in_f64, (size_t)h * 2 * d + c) * ol[(size_t)i * d + c];
+                        z += load1(gate_w, in_f64, (size_t)h * 2 * d + d + c) * os[(size_t)i * d + c];
+                    }
+                    a = 1.0 / (1.0 + exp(-z));
+                }
+                if (alpha) alpha[(size_t)it * L + i] = a;
+                if (O)
+                    for (int c = 0; c < d; ++c) {
+                        const size_t x = (size_t)i * d + c;
+                        O[(size_t)it * Ld + x] = (i >= p0) ? a * ol[x] + (1.0 - a) * os[x] : 0.0;
+                    }
+            }
+            if (o_lt) memcpy(o_lt + (size_t)it * Ld, ol, Ld * sizeof(double));
+            if (o_st) memcpy(o_st + (size_t)it * Ld, os, Ld * sizeof(double));
+            if (lse_lt) memcpy(lse_lt + (size_t)it * L, ll, (size_t)L * sizeof(double));
+            if (lse_st) memcpy(lse_st + (size_t)it * L, ls, (size_t)L * sizeof(double));
+        }
+        free(q); free(key); free(v); free(ol); free(os); free(ll); free(ls);
+        free(M_lt); free(M_st);
+    }
+    if (nnz) {
+        nnz[0] = nnz_lt;
+        nnz[1] = nnz_st;
+    }
+    return err;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Backward of one branch through Eq. 1 with mask M, given dO_x and o_x:       */
+/*   D_i = dO_x[i].o_x[i];  P = exp(S - lse);  dP_ij = dO_x[i].v_j;            */
+/*   dS = P (dP - D);  dq_i += scale dS k_j;  dk_j += scale dS q_i;            */
+/*   dv_j += P dO_x[i].            Accumulates into dq, dk, dv.                */
+/* ------------------------------------------------------------------------- */
+static void masked_attention_bwd(int L, int d, const double *q, const double *key, const double *v,
+                                 const uint8_t *M, double scale, const double *o, const double *lse,
+                                 const double *dO, double *dq, double *dk, double *dv)
+{
+    for (int i = 0; i < L; ++i) {
+        const uint8_t *mi = M + (size_t)i * L;
+        const double *doi = dO + (size_t)i * d;
+        double D = 0.0;
+        for (int c = 0; c < d; ++c) D += doi[c] * o[(size_t)i * d + c];
+        for (int j = 0; j < L; ++j) {
+            if (!mi[j]) continue;
+            double sdot = 0.0, dP = 0.0;
+            for (int c = 0; c < d; ++c) {
+                sdot += q[(size_t)i * d + c] * key[(size_t)j * d + c];
+                dP += doi[c] * v[(size_t)j * d + c];
+            }
+            const double p = exp(scale * sdot - lse[i]);
+            const double dS = p * (dP - D);
+            for (int c = 0; c < d; ++c) {
+                dq[(size_t)i * d + c] += scale * dS * key[(size_t)j * d + c];
+                dk[(size_t)j * d + c] += scale * dS * q[(size_t)i * d + c];
+                dv[(size_t)j * d + c] += p * doi[c];
+            }
+        }
+    }
+}
+
+/*
+ * Step 7 for the listed pairs.  dO has the layout and element type of Q.
+ * dQ, dK, dV [n_bh,L,d] compact; d_gate_w [H,2d], d_gate_b [H] are summed over
+ * the listed pairs only, in list order.
+ */
+int oracle_attn_bwd(int B, int H, int L, int d, int b, int k, int w, double scale,
+                    int in_f64, const void *Q, const void *K, const void *V,
+                    const int32_t *valid_len, const int32_t *sel,
+                    const void *gate_w, const void *gate_b, const void *dO,
+                    const int32_t *bh_list, int n_bh,
+                    double *dQ, double *dK, double *dV, double *d_gate_w, double *d_gate_b)
+{
+    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || k < 1 || w < 1) return -2;
+    const int NB = n_blocks(L, b);
+    const int total = bh_list ? n_bh : B * H;
+    const size_t Ld = (size_t)L * d;
+    const int G = 2 * d + 1;
+    double *gpart = (double *)calloc((size_t)total * G, sizeof(double));
+    if (!gpart) return -1;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int it = 0; it < total; ++it) {
+        const int bh = bh_list ? bh_list[it] : it;
+        const int r = bh / H, h = bh % H;
+        int n = valid_len[r];
+        if (n < 0) n = 0;
+        if (n > L) n = L;
+        const int p0 = L - n;
+        double *q = (double *)malloc(Ld * sizeof(double));
+        double *key = (double *)malloc(Ld * sizeof(double));
+        double *v = (double *)malloc(Ld * sizeof(double));
+        double *g = (double *)malloc(Ld * sizeof(double));
+        double *ol = (double *)malloc(Ld * sizeof(double));
+        double *os = (double *)malloc(Ld * sizeof(double));
+        double *gl = (double *)malloc(Ld * sizeof(double));
+        double *gs = (double *)malloc(Ld * sizeof(double));
+        double *ll = (double *)malloc((size_t)L * sizeof(double));
+        double *ls = (double *)malloc((size_t)L * sizeof(double));
+        double *dq = (double *)calloc(Ld, sizeof(double));
+        double *dk = (double *)calloc(Ld, sizeof(double));
+        double *dv = (double *)calloc(Ld, sizeof(double));
+        uint8_t *M_lt = (uint8_t *)malloc((size_t)L * L);
+        uint8_t *M_st = (uint8_t *)malloc((size_t)L * L);
+        if (!q || !key || !v || !g || !ol || !os || !gl || !gs || !ll || !ls || !dq || !dk || !dv ||
+            !M_lt || !M_st) {
+#pragma omp atomic write
+            err = -1;
+        } else {
+            widen(Q, in_f64, (size_t)bh * Ld, Ld, q);
+            widen(K, in_f64, (size_t)bh * Ld, Ld, key);
+            widen(V, in_f64, (size_t)bh * Ld, Ld, v);
+            widen(dO, in_f64, (size_t)bh * Ld, Ld, g);
+            build_masks_one(L, b, k, w, n, sel + (size_t)bh * NB * k, M_lt, M_st);
+            masked_attention(L, d, q, key, v, M_lt, scale, ol, ll, NULL);
+            masked_attention(L, d, q, key, v, M_st, scale, os, ls, NULL);
+            double *gp = gpart + (size_t)it * G;
+            for (int i = 0; i < L; ++i) {
+                double *gli = gl + (size_t)i * d, *gsi = gs + (size_t)i * d;
+                if (i < p0) {
+                    for (int c = 0; c < d; ++c) gli[c] = gsi[c] = 0.0;
+                    continue;
+                }
+                double z = gate_b ? load1(gate_b, in_f64, (size_t)h) : 0.0;
+                for (int c = 0; c < d; ++c) {
+                    z += load1(gate_w, in_f64, (size_t)h * 2 * d + c) * ol[(size_t)i * d + c];
+                    z += load1(gate_w, in_f64, (size_t)h * 2 * d + d + c) * os[(size_t)i * d + c];
+                }
+                const double a = 1.0 / (1.0 + exp(-z));
+                double gdot = 0.0;
+                for (int c = 0; c < d; ++c)
+                    gdot += g[(size_t)i * d + c] * (ol[(size_t)i * d + c] - os[(size_t)i * d + c]);
+                const double dz = gdot * a * (1.0 - a);
+                for (int c = 0; c < d; ++c) {
+                    gp[c] += dz * ol[(size_t)i * d + c];
+                    gp[d + c] += dz * os[(size_t)i * d + c];
+                    gli[c] = a * g[(size_t)i * d + c] +
+                             dz * load1(gate_w, in_f64, (size_t)h * 2 * d + c);
+                    gsi[c] = (1.0 - a) * g[(size_t)i * d + c] +
+                             dz * load1(gate_w, in_f64, (size_t)h * 2 * d + d + c);
+                }
+                gp[2 * d] += dz;
+            }
+            masked_attention_bwd(L, d, q, key, v, M_lt, scale, ol, ll, gl, dq, dk, dv);
+            masked_attention_bwd(L, d, q, key, v, M_st, scale, os, ls, gs, dq, dk, dv);
+            if (dQ) memcpy(dQ + (size_t)it * Ld, dq, Ld * sizeof(double));
+            if (dK) memcpy(dK + (size_t)it * Ld, dk, Ld * sizeof(double));
+            if (dV) memcpy(dV + (size_t)it * Ld, dv, Ld * sizeof(double));
+        }
+        free(q); free(key); free(v); free(g); free(ol); free(os); free(gl); free(gs);
+        free(ll); free(ls); free(dq); free(dk); free(dv); free(M_lt); free(M_st);
+    }
+    if (d_gate_w) memset(d_gate_w, 0, (size_t)H * 2 * d * sizeof(double));
+    if (d_gate_b) memset(d_gate_b, 0, (size_t)H * sizeof(double));
+    for (int it = 0; it < total; ++it) {
+        const int bh = bh_list ? bh_list[it] : it;
+        const int h = bh % H;
+        const double *gp = gpart + (size_t)it * G;
+        if (d_gate_w)
+            for (int c = 0; c < 2 * d; ++c) d_gate_w[(size_t)h * 2 * d + c] += gp[c];
+        if (d_gate_b) d_gate_b[h] += gp[2 * d];
+    }
+    free(gpart);
+    return err;
+}
+
+/* ------------------------------------------------------------------------- */
+/* Dense causal attention over the valid suffix (Eq. 1 with the causal mask):  */
+/* what the comparison kernel computes.  O [n_bh,L,d], lse [n_bh,L].           */
+/* ------------------------------------------------------------------------- */
+int oracle_dense_causal_fwd(int B, int H, int L, int d, double scale,
+                            int in_f64, const void *Q, const void *K, const void *V,
+                            const int32_t *valid_len, const int32_t *bh_list, int n_bh,
+                            double *O, double *lse)
+{
+    if (B < 1 || H < 1 || L < 1 || d < 1) return -2;
+    const int total = bh_list ? n_bh : B * H;
+    const size_t Ld = (size_t)L * d;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int it = 0; it < total; ++it) {
+        const int bh = bh_list ? bh_list[it] : it;
+        const int r = bh / H;
+        int n = valid_len[r];
+        if (n < 0) n = 0;
+        if (n > L) n = L;
+        double *q = (double *)malloc(Ld * sizeof(double));
+        double *key = (double *)malloc(Ld * sizeof(double));
+        double *v = (double *)malloc(Ld * sizeof(double));
+        double *l = (double *)malloc((size_t)L * sizeof(double));
+        uint8_t *M = (uint8_t *)malloc((size_t)L * L);
+        if (!q || !key || !v || !l || !M) {
+#pragma omp atomic write
+            err = -1;
+        } else {
+            widen(Q, in_f64, (size_t)bh * Ld, Ld, q);
+            widen(K, in_f64, (size_t)bh * Ld, Ld, key);
+            widen(V, in_f64, (size_t)bh * Ld, Ld, v);
+            dense_causal_mask(L, n, M);
+            masked_attention(L, d, q, key, v, M, scale, O + (size_t)it * Ld, l, NULL);
+            if (lse) memcpy(lse + (size_t)it * L, l, (size_t)L * sizeof(double));
+        }
+        free(q); free(key); free(v); free(l); free(M);
+    }
+    return err;
+}
