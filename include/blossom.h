@@ -1,0 +1,153 @@
+/*
+ * blossom.h -- C ABI of libblossom.so: Blossom attention for MI355X (gfx950).
+ *
+ * Blossom attention (BlossomRec, arXiv 2512.13368, Sec. 3.3-3.6) replaces dense
+ * causal self-attention in a Transformer sequential recommender by two sparse
+ * branches and a gate:
+ *   - long-term branch (LTIS, Sec. 3.4): key blocks are compressed (Eq. 9),
+ *     scored against the query (Eq. 10), the top-k blocks are kept (Eq. 13) and
+ *     attention runs over the keys of the kept blocks only (Eq. 14, 16);
+ *   - short-term branch (STIS, Sec. 3.5): attention under a local mask
+ *     (Eq. 15, 17); this library implements the causal local-window term;
+ *   - learnable gate (Sec. 3.6, Eq. 18-19): a sigmoid of a linear map of both
+ *     branch outputs blends them.
+ *
+ * Conventions shared by every entry point
+ *   - All tensor pointers are DEVICE pointers on the current HIP device unless a
+ *     comment says "host".  `blossom_params` itself is read on the host.
+ *   - Q, K, V, O, dO, dQ, dK, dV, o_lt, o_st: [B,H,L,d], contiguous, d fastest,
+ *     element type given by `dtype`, base address 16-byte aligned.
+ *   - One block size `block` (b) serves as query-block, compression-block and
+ *     selection-block size (Eq. 8 with l = s = l' = b, for which the score
+ *     mapping of Eq. 11 is the identity).  NB = ceil(L/b); block I covers
+ *     positions [I*b, min((I+1)*b, L)).
+ *   - Row r of the batch has valid_len[r] valid positions, LEFT padded: valid
+ *     positions are L-valid_len[r] .. L-1.  Values outside [0,L] are clamped.
+ *     Pad queries give O = o_lt = o_st = 0 and lse = 0; pad keys are never read
+ *     into a softmax or a pooled block; gradients of pad positions are 0.
+ *   - Ownership: the caller owns every buffer, including the workspace.  The
+ *     library allocates nothing, frees nothing and never synchronises; all work
+ *     is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
+ *     default stream).  Outputs are overwritten, never accumulated into.
+ *   - Errors: 0 on success, a negative BLOSSOM_ERR_* otherwise.  All argument
+ *     checks run before the first HIP call, so they work on a host with no GPU.
+ *     No global state; thread-safe.  Inputs are assumed finite.
+ */
+#ifndef BLOSSOM_H_
+#define BLOSSOM_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+enum {
+  BLOSSOM_OK = 0,
+  BLOSSOM_ERR_NULL = -1,        /* a required pointer is NULL                                  */
+  BLOSSOM_ERR_SHAPE = -2,       /* B, H or L < 1, or L/b too large (NB > 4096)                 */
+  BLOSSOM_ERR_UNSUPPORTED = -3, /* d not in {32,64}, b not in {8,16,32,64}, dtype, stis_mode   */
+  BLOSSOM_ERR_PARAM = -4,       /* topk < 1, window < 1, softmax_scale < 0 or not finite       */
+  BLOSSOM_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned                     */
+  BLOSSOM_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than blossom_workspace_bytes()    */
+  BLOSSOM_ERR_LAUNCH = -7       /* a kernel launch failed (hipGetLastError)                    */
+};
+
+enum { BLOSSOM_F32 = 0, BLOSSOM_BF16 = 1 };
+enum { BLOSSOM_WS_SELECT = 0, BLOSSOM_WS_FWD = 1, BLOSSOM_WS_BWD = 2, BLOSSOM_WS_DENSE = 3 };
+
+typedef struct {
+  int32_t B, H, L, d;     /* batch rows, heads, sequence length, head dimension                */
+  int32_t block;          /* b                                                                  */
+  int32_t topk;           /* k: blocks per query block INCLUDING its own (diagonal) block       */
+  int32_t window;         /* w: query i sees keys j with 0 <= i-j < w in the short-term branch  */
+  int32_t dtype;          /* BLOSSOM_F32 or BLOSSOM_BF16 (fp32 accumulation either way)         */
+  float softmax_scale;    /* logits are softmax_scale * q.k ; 0.0f means 1/sqrt(d) (Eq. 1)      */
+  int32_t stis_mode;      /* 0 = causal local window.  Other values: BLOSSOM_ERR_UNSUPPORTED    */
+  int32_t save_for_bwd;   /* fwd only: 1 = also write o_lt, o_st, lse_lt, lse_st                */
+} blossom_params;
+
+/* Bytes of device workspace an entry point needs (host call, no HIP).  `which` is a
+ * BLOSSOM_WS_* value.  Returns 0 for invalid params or when no workspace is needed. */
+size_t blossom_workspace_bytes(const blossom_params *p, int which);
+
+/*
+ * Long-term block selection (Sec. 3.4: Eq. 9 with phi = mean pooling, Eq. 10, Eq. 13).
+ * For each (row, head, query block I) holding a valid query, writes the ascending list of
+ * selected key blocks: block I itself plus the best min(k-1, I-J_first) earlier blocks
+ * J_first <= J < I (J_first = first block holding a valid key), ordered by (score
+ * descending, block index ascending); unused slots and blocks without a valid query hold -1.
+ * The score of J for I is sum_c Qsum_I[c]*Kmean_J[c], evaluated in fp32 exactly as:
+ * Qsum/Ksum = sequential sums over the block's valid positions in ascending order from
+ * +0.0f; Kmean = Ksum/(float)count (IEEE division); score = fused multiply-add chain over
+ * c = 0..d-1 from +0.0f.  +0.0 and -0.0 compare equal.
+ *   Q, K        in   [B,H,L,d]
+ *   valid_len   in   int32 [B]
+ *   sel         out  int32 [B,H,NB,topk]
+ *   ws          scratch, >= blossom_workspace_bytes(p, BLOSSOM_WS_SELECT), 16-byte aligned
+ */
+int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
+                          const int32_t *valid_len, int32_t *sel,
+                          void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Fused forward (Eq. 1 under the two masks, Eq. 16-19).  For every valid query i of block I:
+ *   o_lt[i] = softmax over { j : block(j) in sel[I], j <= i, j valid } of scale*q_i.k_j, times V
+ *   o_st[i] = softmax over { j : 0 <= i-j < window, j valid } of the same logits, times V
+ *   alpha   = sigmoid( gate_w[h,0:d].o_lt[i] + gate_w[h,d:2d].o_st[i] + gate_b[h] )
+ *   O[i]    = alpha*o_lt[i] + (1-alpha)*o_st[i]
+ *   lse_x[i] = log sum exp of the branch's logits (natural log).
+ *   sel        in   int32 [B,H,NB,topk] as written by blossom_select_blocks (entries must be
+ *                   -1 or in [0,NB); each query block with a valid query must list itself)
+ *   gate_w     in   fp32 [H,2d];  gate_b in fp32 [H] or NULL (= 0)
+ *   O          out  [B,H,L,d]
+ *   o_lt,o_st  out  [B,H,L,d], lse_lt,lse_st out fp32 [B,H,L]; required iff save_for_bwd
+ *   ws         scratch for BLOSSOM_WS_FWD (may be NULL when that size is 0)
+ */
+int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                     const int32_t *valid_len, const int32_t *sel,
+                     const float *gate_w, const float *gate_b,
+                     void *O, void *o_lt, void *o_st, float *lse_lt, float *lse_st,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Backward of blossom_attn_fwd with the block selection held fixed (the top-k of Eq. 13 is
+ * not differentiable).  Chain rule through Eq. 19, 18, 16/17 and Eq. 1:
+ *   g = dO.(o_lt-o_st); dz = g*alpha*(1-alpha); d_gate_w[h] += dz*[o_lt;o_st]; d_gate_b[h] += dz
+ *   dO_lt = alpha*dO + dz*gate_w[h,0:d];  dO_st = (1-alpha)*dO + dz*gate_w[h,d:2d]
+ *   per branch x: D = dO_x.o_x; P = exp(S-lse_x); dV += P^T dO_x; dS = P*(dO_x V^T - D);
+ *                 dQ += scale*dS K; dK += scale*dS^T Q
+ *   o_lt,o_st,lse_lt,lse_st  in   as saved by the forward
+ *   dO                       in   [B,H,L,d]
+ *   dQ,dK,dV                 out  [B,H,L,d] (input dtype)
+ *   d_gate_w                 out  fp32 [H,2d];  d_gate_b out fp32 [H] (may be NULL)
+ * Results are deterministic: no floating-point atomics are used.
+ */
+int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                     const int32_t *valid_len, const int32_t *sel,
+                     const float *gate_w, const float *gate_b,
+                     const void *o_lt, const void *o_st, const float *lse_lt, const float *lse_st,
+                     const void *dO,
+                     void *dQ, void *dK, void *dV, float *d_gate_w, float *d_gate_b,
+                     void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Comparison kernel: dense causal attention over the valid suffix (Eq. 1 with the causal
+ * mask), built in the same tile style.  topk, window, stis_mode and save_for_bwd are ignored.
+ *   O out [B,H,L,d];  lse out fp32 [B,H,L] or NULL
+ */
+int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                             const int32_t *valid_len, void *O, float *lse,
+                             void *ws, size_t ws_bytes, void *hip_stream);
+
+/* Static, human-readable text for an error code (host). */
+const char *blossom_strerror(int code);
+
+/* Library version string, e.g. "blossom-gfx950 0.1" (host). */
+const char *blossom_version(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BLOSSOM_H_ */

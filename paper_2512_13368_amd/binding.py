@@ -1,0 +1,264 @@
+"""Python binding of libblossom.so: argument marshalling only.
+
+Every step of the path runs in the HIP kernels behind the C ABI of
+``include/blossom.h``; this module turns torch device tensors into pointers,
+allocates outputs and workspaces with torch, and raises on error codes.  There
+is no CPU fallback: a missing library is an ImportError-like failure.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libblossom.so")
+
+F32, BF16 = 0, 1
+WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
+
+EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_attn_fwd", "blossom_attn_bwd",
+           "blossom_dense_causal_fwd", "blossom_strerror", "blossom_version")
+
+
+class BlossomParams(ctypes.Structure):
+    _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
+                ("block", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
+                ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
+                ("stis_mode", ctypes.c_int32), ("save_for_bwd", ctypes.c_int32)]
+
+
+class BlossomError(RuntimeError):
+    def __init__(self, code: int, where: str):
+        self.code = code
+        super().__init__(f"{where}: {strerror(code)} (code {code})")
+
+
+_lib = None
+
+
+def lib() -> ctypes.CDLL:
+    """Open libblossom.so (after torch, so that both use one HIP runtime instance)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError(
+                f"{LIB_PATH} is missing: build it with `python -c 'import __graft_entry__ as g; g.build()'`"
+                " (there is no fallback path)")
+        import torch  # noqa: F401  (loads torch's HIP runtime first)
+        L = ctypes.CDLL(LIB_PATH)
+        vp, i32p, fp = ctypes.c_void_p, ctypes.c_void_p, ctypes.c_void_p
+        pp = ctypes.POINTER(BlossomParams)
+        L.blossom_workspace_bytes.restype = ctypes.c_size_t
+        L.blossom_workspace_bytes.argtypes = [pp, ctypes.c_int]
+        L.blossom_select_blocks.restype = ctypes.c_int
+        L.blossom_select_blocks.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
+        L.blossom_attn_fwd.restype = ctypes.c_int
+        L.blossom_attn_fwd.argtypes = [pp, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, vp, fp, fp, vp,
+                                       ctypes.c_size_t, vp]
+        L.blossom_attn_bwd.restype = ctypes.c_int
+        L.blossom_attn_bwd.argtypes = [pp, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, fp, fp, vp, vp, vp, vp,
+                                       fp, fp, vp, ctypes.c_size_t, vp]
+        L.blossom_dense_causal_fwd.restype = ctypes.c_int
+        L.blossom_dense_causal_fwd.argtypes = [pp, vp, vp, vp, i32p, vp, fp, vp, ctypes.c_size_t, vp]
+        L.blossom_strerror.restype = ctypes.c_char_p
+        L.blossom_strerror.argtypes = [ctypes.c_int]
+        L.blossom_version.restype = ctypes.c_char_p
+        L.blossom_version.argtypes = []
+        _lib = L
+    return _lib
+
+
+def strerror(code: int) -> str:
+    return lib().blossom_strerror(int(code)).decode()
+
+
+def version() -> str:
+    return lib().blossom_version().decode()
+
+
+@dataclass
+class Params:
+    B: int
+    H: int
+    L: int
+    d: int
+    block: int
+    topk: int
+    window: int
+    dtype: int = F32
+    softmax_scale: float = 0.0
+    stis_mode: int = 0
+    save_for_bwd: int = 0
+
+    @property
+    def NB(self) -> int:
+        return -(-self.L // self.block)
+
+    def c(self) -> BlossomParams:
+        return BlossomParams(self.B, self.H, self.L, self.d, self.block, self.topk, self.window,
+                             self.dtype, self.softmax_scale, self.stis_mode, self.save_for_bwd)
+
+
+def workspace_bytes(p: Params, which: int) -> int:
+    cp = p.c()
+    return int(lib().blossom_workspace_bytes(ctypes.byref(cp), which))
+
+
+def _ptr(t):
+    return None if t is None else ctypes.c_void_p(t.data_ptr())
+
+
+def _stream(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def _torch_dtype(p: Params):
+    import torch
+    return torch.float32 if p.dtype == F32 else torch.bfloat16
+
+
+def _check_tensor(t, shape, dtype, name):
+    if t is None:
+        return
+    if tuple(t.shape) != tuple(shape) or t.dtype != dtype or not t.is_contiguous() or not t.is_cuda:
+        raise ValueError(f"{name}: expected contiguous cuda tensor {tuple(shape)} {dtype}, got "
+                         f"{tuple(t.shape)} {t.dtype} contiguous={t.is_contiguous()} cuda={t.is_cuda}")
+
+
+def _workspace(p: Params, which: int, ws, device):
+    import torch
+    need = workspace_bytes(p, which)
+    if ws is None and need > 0:
+        ws = torch.empty(need, dtype=torch.uint8, device=device)
+    nbytes = 0 if ws is None else ws.numel() * ws.element_size()
+    return ws, nbytes
+
+
+def select_blocks(p: Params, Q, K, valid_len, sel=None, ws=None, stream=None):
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    _check_tensor(Q, shp, _torch_dtype(p), "Q")
+    _check_tensor(K, shp, _torch_dtype(p), "K")
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    if sel is None:
+        sel = torch.empty((p.B, p.H, p.NB, p.topk), dtype=torch.int32, device=Q.device)
+    _check_tensor(sel, (p.B, p.H, p.NB, p.topk), torch.int32, "sel")
+    ws, nbytes = _workspace(p, WS_SELECT, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_select_blocks(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(valid_len), _ptr(sel),
+                                     _ptr(ws), nbytes, _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_select_blocks")
+    return sel
+
+
+@dataclass
+class FwdOut:
+    O: object
+    o_lt: object = None
+    o_st: object = None
+    lse_lt: object = None
+    lse_st: object = None
+
+
+def attn_fwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b=None, out: FwdOut | None = None,
+             ws=None, stream=None) -> FwdOut:
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    dt = _torch_dtype(p)
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _check_tensor(t, shp, dt, nm)
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    _check_tensor(sel, (p.B, p.H, p.NB, p.topk), torch.int32, "sel")
+    _check_tensor(gate_w, (p.H, 2 * p.d), torch.float32, "gate_w")
+    _check_tensor(gate_b, (p.H,), torch.float32, "gate_b")
+    if out is None:
+        out = FwdOut(torch.empty(shp, dtype=dt, device=Q.device))
+        if p.save_for_bwd:
+            out.o_lt = torch.empty(shp, dtype=dt, device=Q.device)
+            out.o_st = torch.empty(shp, dtype=dt, device=Q.device)
+            out.lse_lt = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
+            out.lse_st = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
+    _check_tensor(out.O, shp, dt, "O")
+    _check_tensor(out.o_lt, shp, dt, "o_lt")
+    _check_tensor(out.o_st, shp, dt, "o_st")
+    _check_tensor(out.lse_lt, shp[:3], torch.float32, "lse_lt")
+    _check_tensor(out.lse_st, shp[:3], torch.float32, "lse_st")
+    ws, nbytes = _workspace(p, WS_FWD, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_attn_fwd(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len), _ptr(sel),
+                                _ptr(gate_w), _ptr(gate_b), _ptr(out.O), _ptr(out.o_lt), _ptr(out.o_st),
+                                _ptr(out.lse_lt), _ptr(out.lse_st), _ptr(ws), nbytes, _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_attn_fwd")
+    return out
+
+
+@dataclass
+class BwdOut:
+    dQ: object
+    dK: object
+    dV: object
+    d_gate_w: object
+    d_gate_b: object
+
+
+def attn_bwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b, fwd: FwdOut, dO,
+             out: BwdOut | None = None, ws=None, stream=None) -> BwdOut:
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    dt = _torch_dtype(p)
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO"), (fwd.o_lt, "o_lt"), (fwd.o_st, "o_st")):
+        if t is None:
+            raise ValueError(f"{nm} is required")
+        _check_tensor(t, shp, dt, nm)
+    for t, nm in ((fwd.lse_lt, "lse_lt"), (fwd.lse_st, "lse_st")):
+        if t is None:
+            raise ValueError(f"{nm} is required")
+        _check_tensor(t, shp[:3], torch.float32, nm)
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    _check_tensor(sel, (p.B, p.H, p.NB, p.topk), torch.int32, "sel")
+    _check_tensor(gate_w, (p.H, 2 * p.d), torch.float32, "gate_w")
+    _check_tensor(gate_b, (p.H,), torch.float32, "gate_b")
+    if out is None:
+        out = BwdOut(torch.empty(shp, dtype=dt, device=Q.device), torch.empty(shp, dtype=dt, device=Q.device),
+                     torch.empty(shp, dtype=dt, device=Q.device),
+                     torch.empty((p.H, 2 * p.d), dtype=torch.float32, device=Q.device),
+                     torch.empty((p.H,), dtype=torch.float32, device=Q.device))
+    for t, nm in ((out.dQ, "dQ"), (out.dK, "dK"), (out.dV, "dV")):
+        _check_tensor(t, shp, dt, nm)
+    _check_tensor(out.d_gate_w, (p.H, 2 * p.d), torch.float32, "d_gate_w")
+    _check_tensor(out.d_gate_b, (p.H,), torch.float32, "d_gate_b")
+    ws, nbytes = _workspace(p, WS_BWD, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_attn_bwd(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len), _ptr(sel),
+                                _ptr(gate_w), _ptr(gate_b), _ptr(fwd.o_lt), _ptr(fwd.o_st),
+                                _ptr(fwd.lse_lt), _ptr(fwd.lse_st), _ptr(dO), _ptr(out.dQ), _ptr(out.dK),
+                                _ptr(out.dV), _ptr(out.d_gate_w), _ptr(out.d_gate_b), _ptr(ws), nbytes,
+                                _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_attn_bwd")
+    return out
+
+
+def dense_causal_fwd(p: Params, Q, K, V, valid_len, O=None, lse=None, ws=None, stream=None):
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    dt = _torch_dtype(p)
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V")):
+        _check_tensor(t, shp, dt, nm)
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    if O is None:
+        O = torch.empty(shp, dtype=dt, device=Q.device)
+    _check_tensor(O, shp, dt, "O")
+    _check_tensor(lse, shp[:3], torch.float32, "lse")
+    ws, nbytes = _workspace(p, WS_DENSE, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_dense_causal_fwd(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len),
+                                        _ptr(O), _ptr(lse), _ptr(ws), nbytes, _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_dense_causal_fwd")
+    return O, lse

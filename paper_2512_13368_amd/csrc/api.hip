@@ -1,0 +1,177 @@
+// C ABI of libblossom.so: argument validation (before any HIP call), workspace sizing and
+// dispatch to the kernel launchers.  See include/blossom.h for the contract.
+#include "../../include/blossom.h"
+
+#include <cmath>
+
+#include "launch.h"
+
+using namespace blossom;
+
+namespace {
+
+bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
+
+// Validates the parameter block and fills the kernel-side description.
+int check_params(const blossom_params *p, KParams *kp)
+{
+  if (!p) return BLOSSOM_ERR_NULL;
+  if (p->B < 1 || p->H < 1 || p->L < 1) return BLOSSOM_ERR_SHAPE;
+  if (p->d != 32 && p->d != 64) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->block != 8 && p->block != 16 && p->block != 32 && p->block != 64) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->dtype != BLOSSOM_F32 && p->dtype != BLOSSOM_BF16) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->stis_mode != 0) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->topk < 1 || p->window < 1) return BLOSSOM_ERR_PARAM;
+  if (!std::isfinite(p->softmax_scale) || p->softmax_scale < 0.0f) return BLOSSOM_ERR_PARAM;
+  const long NB = ((long)p->L + p->block - 1) / p->block;
+  if (NB > 4096) return BLOSSOM_ERR_SHAPE;
+  if ((long)p->B * p->H * NB > 0x7FFFFFFFL) return BLOSSOM_ERR_SHAPE;
+  if ((double)p->B * p->H * p->L * p->d > 9.0e18) return BLOSSOM_ERR_SHAPE;
+  kp->B = p->B; kp->H = p->H; kp->L = p->L; kp->d = p->d;
+  kp->b = p->block; kp->k = p->topk; kp->w = p->window; kp->NB = (int)NB;
+  kp->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->d);
+  return BLOSSOM_OK;
+}
+
+size_t ws_bytes_for(const KParams &kp, int which)
+{
+  switch (which) {
+    case BLOSSOM_WS_SELECT: return select_workspace_bytes(kp);
+    case BLOSSOM_WS_FWD: return 0;
+    case BLOSSOM_WS_BWD: return bwd_workspace_bytes(kp);
+    case BLOSSOM_WS_DENSE: return 0;
+    default: return 0;
+  }
+}
+
+int check_ws(const KParams &kp, int which, const void *ws, size_t ws_bytes)
+{
+  const size_t need = ws_bytes_for(kp, which);
+  if (need == 0) return BLOSSOM_OK;
+  if (!ws || ws_bytes < need) return BLOSSOM_ERR_WORKSPACE;
+  if (!aligned16(ws)) return BLOSSOM_ERR_ALIGN;
+  return BLOSSOM_OK;
+}
+
+int launch_status()
+{
+  return hipGetLastError() == hipSuccess ? BLOSSOM_OK : BLOSSOM_ERR_LAUNCH;
+}
+
+}  // namespace
+
+extern "C" {
+
+size_t blossom_workspace_bytes(const blossom_params *p, int which)
+{
+  KParams kp;
+  if (check_params(p, &kp) != BLOSSOM_OK) return 0;
+  return ws_bytes_for(kp, which);
+}
+
+int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
+                          const int32_t *valid_len, int32_t *sel, void *ws, size_t ws_bytes,
+                          void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (!Q || !K || !valid_len || !sel) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K)) return BLOSSOM_ERR_ALIGN;
+  rc = check_ws(kp, BLOSSOM_WS_SELECT, ws, ws_bytes);
+  if (rc) return rc;
+  launch_select(kp, p->dtype, Q, K, valid_len, sel, ws, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                     const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                     const float *gate_b, void *O, void *o_lt, void *o_st, float *lse_lt,
+                     float *lse_st, void *ws, size_t ws_bytes, void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (!Q || !K || !V || !valid_len || !sel || !gate_w || !O) return BLOSSOM_ERR_NULL;
+  if (p->save_for_bwd && (!o_lt || !o_st || !lse_lt || !lse_st)) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return BLOSSOM_ERR_ALIGN;
+  if (p->save_for_bwd && (!aligned16(o_lt) || !aligned16(o_st))) return BLOSSOM_ERR_ALIGN;
+  rc = check_ws(kp, BLOSSOM_WS_FWD, ws, ws_bytes);
+  if (rc) return rc;
+  FwdArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.sel = sel;
+  a.gate_w = gate_w; a.gate_b = gate_b; a.O = O;
+  if (p->save_for_bwd) {
+    a.o_lt = o_lt; a.o_st = o_st; a.lse_lt = lse_lt; a.lse_st = lse_st;
+  }
+  a.dense = 0;
+  launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                     const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                     const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                     const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
+                     float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (!Q || !K || !V || !valid_len || !sel || !gate_w || !o_lt || !o_st || !lse_lt || !lse_st ||
+      !dO || !dQ || !dK || !dV || !d_gate_w)
+    return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(o_lt) || !aligned16(o_st) ||
+      !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
+    return BLOSSOM_ERR_ALIGN;
+  rc = check_ws(kp, BLOSSOM_WS_BWD, ws, ws_bytes);
+  if (rc) return rc;
+  BwdArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.sel = sel;
+  a.gate_w = gate_w; a.gate_b = gate_b; a.o_lt = o_lt; a.o_st = o_st;
+  a.lse_lt = lse_lt; a.lse_st = lse_st; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV;
+  a.d_gate_w = d_gate_w; a.d_gate_b = d_gate_b; a.ws = ws;
+  launch_bwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                             const int32_t *valid_len, void *O, float *lse, void *ws,
+                             size_t ws_bytes, void *hip_stream)
+{
+  blossom_params q;
+  if (!p) return BLOSSOM_ERR_NULL;
+  q = *p;
+  q.topk = 1; q.window = 1; q.stis_mode = 0; q.save_for_bwd = 0;  // ignored fields
+  KParams kp;
+  int rc = check_params(&q, &kp);
+  if (rc) return rc;
+  if (!Q || !K || !V || !valid_len || !O) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return BLOSSOM_ERR_ALIGN;
+  rc = check_ws(kp, BLOSSOM_WS_DENSE, ws, ws_bytes);
+  if (rc) return rc;
+  FwdArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.O = O; a.lse_lt = lse;
+  a.dense = 1;
+  launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+const char *blossom_strerror(int code)
+{
+  switch (code) {
+    case BLOSSOM_OK: return "ok";
+    case BLOSSOM_ERR_NULL: return "a required pointer is NULL";
+    case BLOSSOM_ERR_SHAPE: return "bad shape: B, H, L must be >= 1 and ceil(L/block) <= 4096";
+    case BLOSSOM_ERR_UNSUPPORTED: return "unsupported d, block, dtype or stis_mode";
+    case BLOSSOM_ERR_PARAM: return "bad parameter: topk >= 1, window >= 1, finite softmax_scale >= 0";
+    case BLOSSOM_ERR_ALIGN: return "tensor or workspace pointer not 16-byte aligned";
+    case BLOSSOM_ERR_WORKSPACE: return "workspace missing or too small";
+    case BLOSSOM_ERR_LAUNCH: return "kernel launch failed";
+    default: return "unknown error code";
+  }
+}
+
+const char *blossom_version(void) { return "blossom-gfx950 0.1"; }
+
+}  // extern "C"

@@ -1,0 +1,71 @@
+// Shared device-side helpers of the Blossom attention kernels (gfx950 only).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+namespace blossom {
+
+// Kernel-side problem description (passed by value).
+struct KParams {
+  int B, H, L, d;
+  int b;        // block size
+  int k;        // top-k (own block included)
+  int w;        // short-term window
+  int NB;       // ceil(L / b)
+  float scale;  // softmax scale (already resolved, > 0)
+};
+
+struct bf16_t {
+  uint16_t bits;
+};
+
+__device__ __forceinline__ float bf16_to_f32(uint16_t h) { return __uint_as_float(((uint32_t)h) << 16); }
+
+// Round to nearest even; inputs are finite.
+__device__ __forceinline__ uint16_t f32_to_bf16(float x)
+{
+  uint32_t u = __float_as_uint(x);
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+__device__ __forceinline__ float to_f32(float x) { return x; }
+__device__ __forceinline__ float to_f32(bf16_t x) { return bf16_to_f32(x.bits); }
+
+template <typename T>
+__device__ __forceinline__ T from_f32(float x);
+template <>
+__device__ __forceinline__ float from_f32<float>(float x) { return x; }
+template <>
+__device__ __forceinline__ bf16_t from_f32<bf16_t>(float x) { return bf16_t{f32_to_bf16(x)}; }
+
+// Load 4 consecutive elements (16-byte aligned for fp32, 8-byte for bf16) as floats.
+__device__ __forceinline__ void load4(const float *p, float (&o)[4])
+{
+  const float4 v = *reinterpret_cast<const float4 *>(p);
+  o[0] = v.x; o[1] = v.y; o[2] = v.z; o[3] = v.w;
+}
+__device__ __forceinline__ void load4(const bf16_t *p, float (&o)[4])
+{
+  const uint2 v = *reinterpret_cast<const uint2 *>(p);
+  o[0] = __uint_as_float(v.x << 16);
+  o[1] = __uint_as_float(v.x & 0xFFFF0000u);
+  o[2] = __uint_as_float(v.y << 16);
+  o[3] = __uint_as_float(v.y & 0xFFFF0000u);
+}
+__device__ __forceinline__ void store4(float *p, const float (&o)[4])
+{
+  *reinterpret_cast<float4 *>(p) = make_float4(o[0], o[1], o[2], o[3]);
+}
+__device__ __forceinline__ void store4(bf16_t *p, const float (&o)[4])
+{
+  uint2 v;
+  v.x = (uint32_t)f32_to_bf16(o[0]) | ((uint32_t)f32_to_bf16(o[1]) << 16);
+  v.y = (uint32_t)f32_to_bf16(o[2]) | ((uint32_t)f32_to_bf16(o[3]) << 16);
+  *reinterpret_cast<uint2 *>(p) = v;
+}
+
+__device__ __forceinline__ int clamp_len(int n, int L) { return n < 0 ? 0 : (n > L ? L : n); }
+
+}  // namespace blossom

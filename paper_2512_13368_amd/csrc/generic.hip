@@ -1,0 +1,707 @@
+// Scalar-ALU kernels of the fused attention path for every supported (dtype, d, b):
+// forward (both branches + gate, Eq. 1, 16-19), dense causal comparison, and the backward
+// pass (gate backward, dQ, inverse selection list, dK/dV, gate-gradient reduction).
+//
+// Lane mapping: one wavefront per (row, head, block).  A lane owns one row of the block and
+// one "phase" of the key (or query) tile: with block size b there are 64/b phases, each
+// walking every (64/b)-th row of a tile staged in LDS with its own online-softmax state;
+// the phases are merged with wavefront shuffles at the end.  All accumulation is fp32.
+#include "common.h"
+#include "launch.h"
+
+namespace blossom {
+
+namespace {
+
+constexpr float kNegInf = -__builtin_huge_valf();
+
+template <typename T, int D>
+__device__ __forceinline__ void load_row(const T *src, float (&r)[D])
+{
+#pragma unroll
+  for (int c = 0; c < D; c += 4) {
+    float x[4];
+    load4(src + c, x);
+    r[c] = x[0]; r[c + 1] = x[1]; r[c + 2] = x[2]; r[c + 3] = x[3];
+  }
+}
+
+template <typename T, int D>
+__device__ __forceinline__ void store_row(T *dst, const float (&r)[D])
+{
+#pragma unroll
+  for (int c = 0; c < D; c += 4) {
+    const float x[4] = {r[c], r[c + 1], r[c + 2], r[c + 3]};
+    store4(dst + c, x);
+  }
+}
+
+// Stage rows [J*b, J*b+b) of one head's [L,D] tensor into LDS as fp32; rows >= L become 0.
+template <typename T, int D>
+__device__ __forceinline__ void stage_tile(const T *head, int J, int b, int L, float (*dst)[D + 1], int lane)
+{
+  const int groups = b * (D / 4);
+  for (int idx = lane; idx < groups; idx += 64) {
+    const int rr = idx / (D / 4);
+    const int c4 = (idx % (D / 4)) * 4;
+    const int pos = J * b + rr;
+    float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    if (pos < L) load4(head + (size_t)pos * D + c4, x);
+    dst[rr][c4] = x[0]; dst[rr][c4 + 1] = x[1]; dst[rr][c4 + 2] = x[2]; dst[rr][c4 + 3] = x[3];
+  }
+}
+
+__device__ __forceinline__ int first_window_block(int I, int b, int w, int J_first)
+{
+  const int lowpos = I * b - (w - 1);
+  const int J = lowpos <= 0 ? 0 : lowpos / b;
+  return J > J_first ? J : J_first;
+}
+
+}  // namespace
+
+// =============================================================================================
+// Forward
+// =============================================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                         const T *__restrict__ V,
+                                                         const int *__restrict__ valid_len,
+                                                         const int *__restrict__ sel,
+                                                         const float *__restrict__ gate_w,
+                                                         const float *__restrict__ gate_b,
+                                                         T *__restrict__ O, T *__restrict__ o_lt_out,
+                                                         T *__restrict__ o_st_out,
+                                                         float *__restrict__ lse_lt_out,
+                                                         float *__restrict__ lse_st_out, int dense,
+                                                         KParams p)
+{
+  __shared__ float Ks[64][D + 1];
+  __shared__ float Vs[64][D + 1];
+  __shared__ float Os[64][D + 1];  // short-term output of each row, parked during the long-term pass
+
+  const int lane = threadIdx.x;
+  const int b = p.b;
+  const int nph = 64 / b;
+  const int row = lane % b;
+  const int phase = lane / b;
+  const int bh = blockIdx.x / p.NB;
+  const int I = p.NB - 1 - (int)(blockIdx.x % p.NB);  // late (long) blocks first
+  const int h = bh % p.H;
+  const int n = clamp_len(valid_len[bh / p.H], p.L);
+  const int p0 = p.L - n;
+  const int i = I * b + row;
+  const bool in_range = i < p.L;
+  const bool active = in_range && i >= p0;
+  const size_t head = (size_t)bh * p.L * D;
+  const size_t rowoff = head + (size_t)i * D;
+  const size_t lrow = (size_t)bh * p.L + i;
+
+  float acc[D];
+  if (min((I + 1) * b, p.L) <= p0) {  // no valid query in the block: outputs are zero
+    if (phase == 0 && in_range) {
+#pragma unroll
+      for (int c = 0; c < D; ++c) acc[c] = 0.0f;
+      store_row<T, D>(O + rowoff, acc);
+      if (o_lt_out) store_row<T, D>(o_lt_out + rowoff, acc);
+      if (o_st_out) store_row<T, D>(o_st_out + rowoff, acc);
+      if (lse_lt_out) lse_lt_out[lrow] = 0.0f;
+      if (lse_st_out) lse_st_out[lrow] = 0.0f;
+    }
+    return;
+  }
+
+  float q[D];
+  if (active) {
+    load_row<T, D>(Q + rowoff, q);
+  } else {
+#pragma unroll
+    for (int c = 0; c < D; ++c) q[c] = 0.0f;
+  }
+  const int J_first = p0 / b;
+  const T *Kh = K + head;
+  const T *Vh = V + head;
+  float m, l;
+
+  auto tile = [&](int J, bool windowed) {
+    __syncthreads();
+    stage_tile<T, D>(Kh, J, b, p.L, Ks, lane);
+    stage_tile<T, D>(Vh, J, b, p.L, Vs, lane);
+    __syncthreads();
+    for (int jj = phase; jj < b; jj += nph) {
+      const int j = J * b + jj;
+      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || i - j < p.w);
+      if (vis) {
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < D; ++c) s = fmaf(q[c], Ks[jj][c], s);
+        s *= p.scale;
+        if (s > m) {
+          const float corr = __expf(m - s);
+          l *= corr;
+#pragma unroll
+          for (int c = 0; c < D; ++c) acc[c] *= corr;
+          m = s;
+        }
+        const float pj = __expf(s - m);
+        l += pj;
+#pragma unroll
+        for (int c = 0; c < D; ++c) acc[c] = fmaf(pj, Vs[jj][c], acc[c]);
+      }
+    }
+  };
+
+  auto finish = [&]() -> float {  // merge the phases, normalise; returns lse
+    for (int off = b; off < 64; off <<= 1) {
+      const float m2 = __shfl_xor(m, off);
+      const float l2 = __shfl_xor(l, off);
+      const float mn = fmaxf(m, m2);
+      const float c1 = (m == kNegInf) ? 0.0f : __expf(m - mn);
+      const float c2 = (m2 == kNegInf) ? 0.0f : __expf(m2 - mn);
+      l = l * c1 + l2 * c2;
+#pragma unroll
+      for (int c = 0; c < D; ++c) {
+        const float a2 = __shfl_xor(acc[c], off);
+        acc[c] = acc[c] * c1 + a2 * c2;
+      }
+      m = mn;
+    }
+    float lse = 0.0f;
+    if (active) {  // the query itself is always visible, so l > 0
+      const float inv = 1.0f / l;
+#pragma unroll
+      for (int c = 0; c < D; ++c) acc[c] *= inv;
+      lse = m + logf(l);
+    } else {
+#pragma unroll
+      for (int c = 0; c < D; ++c) acc[c] = 0.0f;
+    }
+    return lse;
+  };
+
+  auto reset = [&]() {
+    m = kNegInf;
+    l = 0.0f;
+#pragma unroll
+    for (int c = 0; c < D; ++c) acc[c] = 0.0f;
+  };
+
+  if (dense) {
+    reset();
+    for (int J = J_first; J <= I; ++J) tile(J, false);
+    const float lse = finish();
+    if (phase == 0 && in_range) {
+      store_row<T, D>(O + rowoff, acc);
+      if (lse_lt_out) lse_lt_out[lrow] = lse;
+    }
+    return;
+  }
+
+  // ---- short-term branch: causal window ----
+  reset();
+  for (int J = first_window_block(I, b, p.w, J_first); J <= I; ++J) tile(J, true);
+  const float lse_st = finish();
+  float z = gate_b ? gate_b[h] : 0.0f;
+  if (phase == 0) {
+    const float *ws = gate_w + (size_t)h * 2 * D + D;
+#pragma unroll
+    for (int c = 0; c < D; ++c) {
+      Os[row][c] = acc[c];
+      z = fmaf(ws[c], acc[c], z);
+    }
+    if (in_range) {
+      if (o_st_out) store_row<T, D>(o_st_out + rowoff, acc);
+      if (lse_st_out) lse_st_out[lrow] = lse_st;
+    }
+  }
+
+  // ---- long-term branch: selected blocks ----
+  reset();
+  const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
+  for (int e = 0; e < p.k; ++e) {
+    const int J = my_sel[e];
+    if (J < 0 || J >= p.NB) continue;
+    tile(J, false);
+  }
+  const float lse_lt = finish();
+
+  // ---- gate and blend (Eq. 18-19) ----
+  if (phase == 0 && in_range) {
+    if (o_lt_out) store_row<T, D>(o_lt_out + rowoff, acc);
+    if (lse_lt_out) lse_lt_out[lrow] = lse_lt;
+    const float *wl = gate_w + (size_t)h * 2 * D;
+#pragma unroll
+    for (int c = 0; c < D; ++c) z = fmaf(wl[c], acc[c], z);
+    const float alpha = active ? 1.0f / (1.0f + __expf(-z)) : 0.0f;
+#pragma unroll
+    for (int c = 0; c < D; ++c) acc[c] = alpha * acc[c] + (1.0f - alpha) * Os[row][c];
+    store_row<T, D>(O + rowoff, acc);
+  }
+}
+
+// =============================================================================================
+// Backward, step 1: gate backward per row + per-chunk partial gate-weight gradients.
+//   rowstat[row] = (alpha, dz, D_lt, D_st);  partial[(bh*nchunk+chunk)][0..2D] (2D = bias)
+// =============================================================================================
+constexpr int kPrepRows = 128;
+
+template <typename T, int D>
+__global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const T *__restrict__ o_lt,
+                                                             const T *__restrict__ o_st,
+                                                             const T *__restrict__ dO,
+                                                             const int *__restrict__ valid_len,
+                                                             const float *__restrict__ gate_w,
+                                                             const float *__restrict__ gate_b,
+                                                             float4 *__restrict__ rowstat,
+                                                             float *__restrict__ partial, KParams p)
+{
+  __shared__ float dz_s[kPrepRows];
+  const int t = threadIdx.x;
+  const int nchunk = (p.L + kPrepRows - 1) / kPrepRows;
+  const int bh = blockIdx.x / nchunk;
+  const int chunk = blockIdx.x % nchunk;
+  const int h = bh % p.H;
+  const int n = clamp_len(valid_len[bh / p.H], p.L);
+  const int p0 = p.L - n;
+  const int i = chunk * kPrepRows + t;
+  const size_t head = (size_t)bh * p.L * D;
+  const float *wl = gate_w + (size_t)h * 2 * D;
+  const float *ws = wl + D;
+  float dz = 0.0f;
+  if (i < p.L) {
+    float4 st = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    if (i >= p0) {
+      float a_ll = 0.0f, a_ss = 0.0f, w_l = 0.0f, w_s = 0.0f;
+      for (int c = 0; c < D; c += 4) {
+        float g[4], ol[4], os[4];
+        load4(dO + head + (size_t)i * D + c, g);
+        load4(o_lt + head + (size_t)i * D + c, ol);
+        load4(o_st + head + (size_t)i * D + c, os);
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          a_ll = fmaf(g[e], ol[e], a_ll);
+          a_ss = fmaf(g[e], os[e], a_ss);
+          w_l = fmaf(wl[c + e], ol[e], w_l);
+          w_s = fmaf(ws[c + e], os[e], w_s);
+        }
+      }
+      const float z = (gate_b ? gate_b[h] : 0.0f) + w_l + w_s;
+      const float alpha = 1.0f / (1.0f + __expf(-z));
+      dz = (a_ll - a_ss) * alpha * (1.0f - alpha);
+      st.x = alpha;
+      st.y = dz;
+      st.z = alpha * a_ll + dz * w_l;           // D_lt = dO_lt . o_lt
+      st.w = (1.0f - alpha) * a_ss + dz * w_s;  // D_st = dO_st . o_st
+    }
+    rowstat[(size_t)bh * p.L + i] = st;
+  }
+  dz_s[t] = dz;
+  __syncthreads();
+  const int r_lo = max(chunk * kPrepRows, p0);
+  const int r_hi = min((chunk + 1) * kPrepRows, p.L);
+  float *out = partial + (size_t)blockIdx.x * (2 * D + 1);
+  for (int c = t; c < 2 * D; c += kPrepRows) {
+    const T *src = (c < D ? o_lt : o_st) + head + (c < D ? c : c - D);
+    float acc = 0.0f;
+    for (int r = r_lo; r < r_hi; ++r)
+      acc = fmaf(dz_s[r - chunk * kPrepRows], to_f32(src[(size_t)r * D]), acc);
+    out[c] = acc;
+  }
+  if (t == 0) {
+    float acc = 0.0f;
+    for (int r = r_lo; r < r_hi; ++r) acc += dz_s[r - chunk * kPrepRows];
+    out[2 * D] = acc;
+  }
+}
+
+// Fixed-order reduction of the partial gate gradients over rows of the batch and chunks.
+__global__ __launch_bounds__(256) void bwd_gate_reduce_kernel(const float *__restrict__ partial,
+                                                              float *__restrict__ d_gate_w,
+                                                              float *__restrict__ d_gate_b, int nchunk,
+                                                              KParams p)
+{
+  const int h = blockIdx.x;
+  const int G = 2 * p.d + 1;
+  for (int c = threadIdx.x; c < G; c += blockDim.x) {
+    float acc = 0.0f;
+    for (int r = 0; r < p.B; ++r)
+      for (int ch = 0; ch < nchunk; ++ch)
+        acc += partial[(((size_t)r * p.H + h) * nchunk + ch) * G + c];
+    if (c < 2 * p.d) d_gate_w[(size_t)h * 2 * p.d + c] = acc;
+    else if (d_gate_b) d_gate_b[h] = acc;
+  }
+}
+
+// =============================================================================================
+// Backward, step 2: dQ (query-block stationary, same tile walk as the forward).
+//   dP_ij = dO_x[i].v_j = a_x[i]*(dO[i].v_j) + dz[i]*(gate_w_x.v_j)
+// =============================================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                            const T *__restrict__ V,
+                                                            const int *__restrict__ valid_len,
+                                                            const int *__restrict__ sel,
+                                                            const float *__restrict__ gate_w,
+                                                            const float *__restrict__ lse_lt,
+                                                            const float *__restrict__ lse_st,
+                                                            const T *__restrict__ dO,
+                                                            const float4 *__restrict__ rowstat,
+                                                            T *__restrict__ dQ, KParams p)
+{
+  __shared__ float Ks[64][D + 1];
+  __shared__ float Vs[64][D + 1];
+  __shared__ float wv[64];  // gate_w_x . v_j of the staged tile
+
+  const int lane = threadIdx.x;
+  const int b = p.b;
+  const int nph = 64 / b;
+  const int row = lane % b;
+  const int phase = lane / b;
+  const int bh = blockIdx.x / p.NB;
+  const int I = p.NB - 1 - (int)(blockIdx.x % p.NB);
+  const int h = bh % p.H;
+  const int n = clamp_len(valid_len[bh / p.H], p.L);
+  const int p0 = p.L - n;
+  const int i = I * b + row;
+  const bool in_range = i < p.L;
+  const bool active = in_range && i >= p0;
+  const size_t head = (size_t)bh * p.L * D;
+  const size_t rowoff = head + (size_t)i * D;
+
+  float dq[D];
+#pragma unroll
+  for (int c = 0; c < D; ++c) dq[c] = 0.0f;
+  if (min((I + 1) * b, p.L) <= p0) {
+    if (phase == 0 && in_range) store_row<T, D>(dQ + rowoff, dq);
+    return;
+  }
+  float q[D], g[D];
+  float4 st = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+  float l_lt = 0.0f, l_st = 0.0f;
+  if (active) {
+    load_row<T, D>(Q + rowoff, q);
+    load_row<T, D>(dO + rowoff, g);
+    st = rowstat[(size_t)bh * p.L + i];
+    l_lt = lse_lt[(size_t)bh * p.L + i];
+    l_st = lse_st[(size_t)bh * p.L + i];
+  } else {
+#pragma unroll
+    for (int c = 0; c < D; ++c) { q[c] = 0.0f; g[c] = 0.0f; }
+  }
+  const int J_first = p0 / b;
+  const T *Kh = K + head;
+  const T *Vh = V + head;
+
+  auto tile = [&](int J, bool windowed) {
+    const float *wx = gate_w + (size_t)h * 2 * D + (windowed ? D : 0);
+    const float a_x = windowed ? 1.0f - st.x : st.x;
+    const float D_x = windowed ? st.w : st.z;
+    const float lse = windowed ? l_st : l_lt;
+    __syncthreads();
+    stage_tile<T, D>(Kh, J, b, p.L, Ks, lane);
+    stage_tile<T, D>(Vh, J, b, p.L, Vs, lane);
+    __syncthreads();
+    if (lane < b) {
+      float a = 0.0f;
+      for (int c = 0; c < D; ++c) a = fmaf(wx[c], Vs[lane][c], a);
+      wv[lane] = a;
+    }
+    __syncthreads();
+    for (int jj = phase; jj < b; jj += nph) {
+      const int j = J * b + jj;
+      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || i - j < p.w);
+      if (vis) {
+        float s = 0.0f, gv = 0.0f;
+#pragma unroll
+        for (int c = 0; c < D; ++c) {
+          s = fmaf(q[c], Ks[jj][c], s);
+          gv = fmaf(g[c], Vs[jj][c], gv);
+        }
+        const float pj = __expf(s * p.scale - lse);
+        const float dS = pj * (a_x * gv + st.y * wv[jj] - D_x);
+#pragma unroll
+        for (int c = 0; c < D; ++c) dq[c] = fmaf(dS, Ks[jj][c], dq[c]);
+      }
+    }
+  };
+
+  for (int J = first_window_block(I, b, p.w, J_first); J <= I; ++J) tile(J, true);
+  const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
+  for (int e = 0; e < p.k; ++e) {
+    const int J = my_sel[e];
+    if (J < 0 || J >= p.NB) continue;
+    tile(J, false);
+  }
+  for (int off = b; off < 64; off <<= 1) {
+#pragma unroll
+    for (int c = 0; c < D; ++c) dq[c] += __shfl_xor(dq[c], off);
+  }
+  if (phase == 0 && in_range) {
+#pragma unroll
+    for (int c = 0; c < D; ++c) dq[c] *= p.scale;
+    store_row<T, D>(dQ + rowoff, dq);
+  }
+}
+
+// =============================================================================================
+// Backward, step 3: inverse selection list.  For each key block J of a (row, head): the
+// ascending list of query blocks I whose selection holds J.  offs [B*H,(NB+1)], items [B*H,NB*k].
+// =============================================================================================
+constexpr int kMaxNBInv = 4096;
+
+__global__ __launch_bounds__(256) void inverse_list_kernel(const int *__restrict__ sel, int *__restrict__ offs,
+                                                           int *__restrict__ items, KParams p)
+{
+  __shared__ int cnt[kMaxNBInv + 1];
+  const int bh = blockIdx.x;
+  const int *s = sel + (size_t)bh * p.NB * p.k;
+  for (int J = threadIdx.x; J < p.NB; J += blockDim.x) {
+    int c = 0;
+    for (int I = J; I < p.NB; ++I)
+      for (int e = 0; e < p.k; ++e) c += (s[(size_t)I * p.k + e] == J) ? 1 : 0;
+    cnt[J] = c;
+  }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    int run = 0;
+    for (int J = 0; J < p.NB; ++J) {
+      const int c = cnt[J];
+      cnt[J] = run;
+      run += c;
+    }
+    cnt[p.NB] = run;
+  }
+  __syncthreads();
+  int *o = offs + (size_t)bh * (p.NB + 1);
+  int *it = items + (size_t)bh * p.NB * p.k;
+  for (int J = threadIdx.x; J <= p.NB; J += blockDim.x) o[J] = cnt[J];
+  for (int J = threadIdx.x; J < p.NB; J += blockDim.x) {
+    int pos = cnt[J];
+    for (int I = J; I < p.NB; ++I)
+      for (int e = 0; e < p.k; ++e)
+        if (s[(size_t)I * p.k + e] == J) it[pos++] = I;
+  }
+}
+
+// =============================================================================================
+// Backward, step 4: dK / dV (key-block stationary).  blockIdx.y = 0 computes dV, 1 computes dK.
+// A lane owns one key row and one phase of the query tile.
+// =============================================================================================
+template <typename T, int D>
+__global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                             const T *__restrict__ V,
+                                                             const int *__restrict__ valid_len,
+                                                             const float *__restrict__ gate_w,
+                                                             const float *__restrict__ lse_lt,
+                                                             const float *__restrict__ lse_st,
+                                                             const T *__restrict__ dO,
+                                                             const float4 *__restrict__ rowstat,
+                                                             const int *__restrict__ offs,
+                                                             const int *__restrict__ items,
+                                                             T *__restrict__ dK, T *__restrict__ dV,
+                                                             KParams p)
+{
+  __shared__ float Qs[64][D + 1];
+  __shared__ float Gs[64][D + 1];  // dO_x rows of the staged query tile
+  __shared__ float lse_s[64];
+  __shared__ float Dx_s[64];
+
+  const int lane = threadIdx.x;
+  const int b = p.b;
+  const int nph = 64 / b;
+  const int jj = lane % b;
+  const int phase = lane / b;
+  const int bh = blockIdx.x / p.NB;
+  const int J = (int)(blockIdx.x % p.NB);
+  const bool want_dk = blockIdx.y == 1;
+  const int h = bh % p.H;
+  const int n = clamp_len(valid_len[bh / p.H], p.L);
+  const int p0 = p.L - n;
+  const int j = J * b + jj;
+  const bool in_range = j < p.L;
+  const bool key_ok = in_range && j >= p0;
+  const size_t head = (size_t)bh * p.L * D;
+  T *out = (want_dk ? dK : dV) + head + (size_t)j * D;
+
+  float acc[D];
+#pragma unroll
+  for (int c = 0; c < D; ++c) acc[c] = 0.0f;
+  if (min((J + 1) * b, p.L) <= p0) {  // no valid key in the block
+    if (phase == 0 && in_range) store_row<T, D>(out, acc);
+    return;
+  }
+  float kr[D], vr[D];
+  if (key_ok) {
+    load_row<T, D>(K + head + (size_t)j * D, kr);
+    if (want_dk) load_row<T, D>(V + head + (size_t)j * D, vr);
+  } else {
+#pragma unroll
+    for (int c = 0; c < D; ++c) { kr[c] = 0.0f; vr[c] = 0.0f; }
+  }
+  const T *Qh = Q + head;
+  const T *Gh = dO + head;
+
+  auto tile = [&](int I, bool windowed) {
+    const float *wx = gate_w + (size_t)h * 2 * D + (windowed ? D : 0);
+    __syncthreads();
+    stage_tile<T, D>(Qh, I, b, p.L, Qs, lane);
+    // dO_x = a_x*dO + dz*gate_w_x, formed while staging
+    const int groups = b * (D / 4);
+    for (int idx = lane; idx < groups; idx += 64) {
+      const int rr = idx / (D / 4);
+      const int c4 = (idx % (D / 4)) * 4;
+      const int pos = I * b + rr;
+      float x[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+      if (pos < p.L && pos >= p0) {
+        load4(Gh + (size_t)pos * D + c4, x);
+        const float4 st = rowstat[(size_t)bh * p.L + pos];
+        const float a_x = windowed ? 1.0f - st.x : st.x;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) x[e] = a_x * x[e] + st.y * wx[c4 + e];
+      }
+      Gs[rr][c4] = x[0]; Gs[rr][c4 + 1] = x[1]; Gs[rr][c4 + 2] = x[2]; Gs[rr][c4 + 3] = x[3];
+    }
+    if (lane < b) {
+      const int pos = I * b + lane;
+      float l = 0.0f, dx = 0.0f;
+      if (pos < p.L && pos >= p0) {
+        const float4 st = rowstat[(size_t)bh * p.L + pos];
+        l = windowed ? lse_st[(size_t)bh * p.L + pos] : lse_lt[(size_t)bh * p.L + pos];
+        dx = windowed ? st.w : st.z;
+      }
+      lse_s[lane] = l;
+      Dx_s[lane] = dx;
+    }
+    __syncthreads();
+    for (int ii = phase; ii < b; ii += nph) {
+      const int i = I * b + ii;
+      const bool vis = key_ok && i < p.L && i >= p0 && j <= i && (!windowed || i - j < p.w);
+      if (vis) {
+        float s = 0.0f;
+#pragma unroll
+        for (int c = 0; c < D; ++c) s = fmaf(Qs[ii][c], kr[c], s);
+        const float pj = __expf(s * p.scale - lse_s[ii]);
+        if (want_dk) {
+          float dP = 0.0f;
+#pragma unroll
+          for (int c = 0; c < D; ++c) dP = fmaf(Gs[ii][c], vr[c], dP);
+          const float dS = pj * (dP - Dx_s[ii]);
+#pragma unroll
+          for (int c = 0; c < D; ++c) acc[c] = fmaf(dS, Qs[ii][c], acc[c]);
+        } else {
+#pragma unroll
+          for (int c = 0; c < D; ++c) acc[c] = fmaf(pj, Gs[ii][c], acc[c]);
+        }
+      }
+    }
+  };
+
+  // short-term branch: query blocks whose window reaches this key block
+  {
+    const long last_q = (long)J * b + (b - 1) + (p.w - 1);
+    const int I_hi = (int)min((long)(p.NB - 1), last_q / b);
+    for (int I = J; I <= I_hi; ++I) tile(I, true);
+  }
+  // long-term branch: query blocks that selected this key block
+  {
+    const int *o = offs + (size_t)bh * (p.NB + 1);
+    const int *it = items + (size_t)bh * p.NB * p.k;
+    const int e_lo = o[J], e_hi = o[J + 1];
+    for (int e = e_lo; e < e_hi; ++e) tile(it[e], false);
+  }
+  for (int off = b; off < 64; off <<= 1) {
+#pragma unroll
+    for (int c = 0; c < D; ++c) acc[c] += __shfl_xor(acc[c], off);
+  }
+  if (phase == 0 && in_range) {
+    if (want_dk) {
+#pragma unroll
+      for (int c = 0; c < D; ++c) acc[c] *= p.scale;
+    }
+    store_row<T, D>(out, acc);
+  }
+}
+
+// =============================================================================================
+// Launchers
+// =============================================================================================
+template <typename T, int D>
+static void launch_fwd_t(const KParams &p, const FwdArgs &a, hipStream_t st)
+{
+  hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64), 0, st,
+                     (const T *)a.Q, (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w,
+                     a.gate_b, (T *)a.O, (T *)a.o_lt, (T *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
+}
+
+void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st)
+{
+  if (dtype == 0) {
+    if (p.d == 32) launch_fwd_t<float, 32>(p, a, st);
+    else launch_fwd_t<float, 64>(p, a, st);
+  } else {
+    if (p.d == 32) launch_fwd_t<bf16_t, 32>(p, a, st);
+    else launch_fwd_t<bf16_t, 64>(p, a, st);
+  }
+}
+
+namespace {
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+
+struct BwdWs {
+  size_t rowstat, offs, items, partial, total;
+  int nchunk;
+};
+
+BwdWs bwd_layout(const KParams &p)
+{
+  BwdWs w;
+  const size_t BH = (size_t)p.B * p.H;
+  w.nchunk = (p.L + kPrepRows - 1) / kPrepRows;
+  w.rowstat = 0;
+  w.offs = align256(w.rowstat + BH * p.L * sizeof(float4));
+  w.items = align256(w.offs + BH * (p.NB + 1) * sizeof(int));
+  w.partial = align256(w.items + BH * p.NB * p.k * sizeof(int));
+  w.total = align256(w.partial + BH * w.nchunk * (2 * p.d + 1) * sizeof(float));
+  return w;
+}
+}  // namespace
+
+size_t bwd_workspace_bytes(const KParams &p) { return bwd_layout(p).total; }
+
+template <typename T, int D>
+static void launch_bwd_t(const KParams &p, const BwdArgs &a, hipStream_t st)
+{
+  const BwdWs w = bwd_layout(p);
+  char *ws = reinterpret_cast<char *>(a.ws);
+  float4 *rowstat = reinterpret_cast<float4 *>(ws + w.rowstat);
+  int *offs = reinterpret_cast<int *>(ws + w.offs);
+  int *items = reinterpret_cast<int *>(ws + w.items);
+  float *partial = reinterpret_cast<float *>(ws + w.partial);
+  const unsigned BH = (unsigned)(p.B * p.H);
+
+  hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(kPrepRows), 0, st,
+                     (const T *)a.o_lt, (const T *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
+                     a.gate_b, rowstat, partial, p);
+  hipLaunchKernelGGL(bwd_gate_reduce_kernel, dim3((unsigned)p.H), dim3(256), 0, st, partial, a.d_gate_w,
+                     a.d_gate_b, w.nchunk, p);
+  hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(256), 0, st, a.sel, offs, items, p);
+  hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64), 0, st, (const T *)a.Q,
+                     (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st,
+                     (const T *)a.dO, rowstat, (T *)a.dQ, p);
+  hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D>), dim3(BH * p.NB, 2), dim3(64), 0, st, (const T *)a.Q,
+                     (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
+                     (const T *)a.dO, rowstat, offs, items, (T *)a.dK, (T *)a.dV, p);
+}
+
+void launch_bwd_generic(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st)
+{
+  if (dtype == 0) {
+    if (p.d == 32) launch_bwd_t<float, 32>(p, a, st);
+    else launch_bwd_t<float, 64>(p, a, st);
+  } else {
+    if (p.d == 32) launch_bwd_t<bf16_t, 32>(p, a, st);
+    else launch_bwd_t<bf16_t, 64>(p, a, st);
+  }
+}
+
+}  // namespace blossom

@@ -1,0 +1,47 @@
+// Host-side launch entry points of the kernel translation units (internal to the library).
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+
+#include "common.h"
+
+namespace blossom {
+
+// Pointers of one forward call (device memory; element type per `dtype`).
+struct FwdArgs {
+  const void *Q, *K, *V;
+  const int *valid_len;
+  const int *sel;          // nullptr in dense mode
+  const float *gate_w;     // [H,2d]
+  const float *gate_b;     // [H] or nullptr
+  void *O;
+  void *o_lt, *o_st;       // or nullptr
+  float *lse_lt, *lse_st;  // or nullptr (dense mode: lse_lt = lse)
+  int dense;               // 1: dense causal attention, single branch, no gate
+};
+
+struct BwdArgs {
+  const void *Q, *K, *V;
+  const int *valid_len;
+  const int *sel;
+  const float *gate_w, *gate_b;
+  const void *o_lt, *o_st;
+  const float *lse_lt, *lse_st;
+  const void *dO;
+  void *dQ, *dK, *dV;
+  float *d_gate_w, *d_gate_b;
+  void *ws;
+};
+
+// select.hip
+size_t select_workspace_bytes(const KParams &p);
+void launch_select(const KParams &p, int dtype, const void *Q, const void *K, const int *valid_len,
+                   int *sel, void *ws, hipStream_t st);
+
+// generic.hip: scalar-ALU kernels for every supported (dtype, d, b)
+void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
+size_t bwd_workspace_bytes(const KParams &p);
+void launch_bwd_generic(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st);
+
+}  // namespace blossom

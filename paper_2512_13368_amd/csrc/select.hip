@@ -1,0 +1,156 @@
+// Long-term block selection (Sec. 3.4): block compression (Eq. 9, phi = mean over the
+// block's valid keys), importance scores (Eq. 10) and top-k (Eq. 13).
+//
+// The scores decide integers, so their arithmetic is fixed exactly: sequential fp32 sums in
+// ascending position, one IEEE division, one fused-multiply-add chain over the channels.
+// This file is compiled with -ffp-contract=off; the only fused operations are the explicit
+// __fmaf_rn calls.  Plain ALUs only: the work is O(NB^2 d) per head and HBM-bound on the
+// pooling pass.
+#include "common.h"
+#include "launch.h"
+
+namespace blossom {
+
+// ---- pooling ------------------------------------------------------------------------------
+// One lane owns 4 channels of one block of one tensor and walks the block's valid positions
+// in ascending order.  qsum  [B,H,NB,d]   (unnormalised sums of Q)
+//                     kmeanT[B,H,d,NB]   (means of K, transposed so that the scoring pass
+//                                         reads consecutive blocks with consecutive lanes)
+template <typename T, int D>
+__global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                   const int *__restrict__ valid_len,
+                                                   float *__restrict__ qsum, float *__restrict__ kmeanT,
+                                                   KParams p)
+{
+  constexpr int LPT = D / 4;  // lanes per (tensor, row-head, block) task
+  const long n_bhj = (long)p.B * p.H * p.NB;
+  const long task = (long)blockIdx.x * (256 / LPT) + threadIdx.x / LPT;
+  if (task >= 2 * n_bhj) return;
+  const int c4 = (threadIdx.x % LPT) * 4;
+  const int which = task >= n_bhj;
+  const long rem = which ? task - n_bhj : task;
+  const int bh = (int)(rem / p.NB);
+  const int J = (int)(rem % p.NB);
+  const int n = clamp_len(valid_len[bh / p.H], p.L);
+  const int p0 = p.L - n;
+  const int lo = max(J * p.b, p0);
+  const int hi = min((J + 1) * p.b, p.L);
+  const T *src = (which ? K : Q) + (size_t)bh * p.L * D + c4;
+  float a[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll 8
+  for (int t = lo; t < hi; ++t) {
+    float x[4];
+    load4(src + (size_t)t * D, x);
+    a[0] = a[0] + x[0];
+    a[1] = a[1] + x[1];
+    a[2] = a[2] + x[2];
+    a[3] = a[3] + x[3];
+  }
+  if (!which) {
+    store4(qsum + ((size_t)bh * p.NB + J) * D + c4, a);
+  } else {
+    const int cnt = hi - lo;
+    const float fc = (float)cnt;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float m = cnt > 0 ? __fdiv_rn(a[e], fc) : 0.0f;
+      kmeanT[((size_t)bh * D + c4 + e) * p.NB + J] = m;
+    }
+  }
+}
+
+// ---- scoring + top-k ----------------------------------------------------------------------
+// One wavefront per (row, head, query block I).  Lane-strided candidates J_first <= J < I;
+// scores are parked in LDS; a candidate is selected iff fewer than `take` candidates beat it
+// under (score descending, index ascending); ballots and prefix popcounts emit the list in
+// ascending order.
+constexpr int kMaxNB = 4096;
+
+template <int D>
+__global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict__ qsum,
+                                                        const float *__restrict__ kmeanT,
+                                                        const int *__restrict__ valid_len,
+                                                        int *__restrict__ sel, KParams p)
+{
+  __shared__ float qs[D];
+  __shared__ float sc[kMaxNB];
+  const int lane = threadIdx.x;
+  const int I = blockIdx.x % p.NB;
+  const int bh = blockIdx.x / p.NB;
+  const int n = clamp_len(valid_len[bh / p.H], p.L);
+  const int p0 = p.L - n;
+  int *out = sel + ((size_t)bh * p.NB + I) * p.k;
+  const int hi = min((I + 1) * p.b, p.L);
+  if (hi <= p0) {  // no valid query in this block
+    for (int e = lane; e < p.k; e += 64) out[e] = -1;
+    return;
+  }
+  const int J_first = p0 / p.b;
+  const int n_cand = I - J_first;
+  const int take = min(p.k - 1, n_cand);
+  for (int c = lane; c < D; c += 64) qs[c] = qsum[((size_t)bh * p.NB + I) * D + c];
+  __syncthreads();
+  const float *km = kmeanT + (size_t)bh * D * p.NB;
+  for (int J = J_first + lane; J < I; J += 64) {
+    float acc = 0.0f;
+#pragma unroll 8
+    for (int c = 0; c < D; ++c) acc = __fmaf_rn(qs[c], km[(size_t)c * p.NB + J], acc);
+    sc[J] = acc;
+  }
+  __syncthreads();
+  int base = 0;
+  for (int J0 = J_first; J0 < I; J0 += 64) {
+    const int J = J0 + lane;
+    bool chosen = false;
+    if (J < I) {
+      const float s = sc[J];
+      int rank = 0;
+      for (int Jo = J_first; Jo < I; ++Jo) {
+        const float so = sc[Jo];
+        rank += (so > s || (so == s && Jo < J)) ? 1 : 0;
+      }
+      chosen = rank < take;
+    }
+    const unsigned long long mask = __ballot(chosen);
+    if (chosen) {
+      const unsigned long long below = mask & ((1ull << lane) - 1ull);
+      out[base + __popcll(below)] = J;
+    }
+    base += __popcll(mask);
+  }
+  // base == take here; the own block closes the list, the rest is padding
+  if (lane == 0) out[base] = I;
+  for (int e = base + 1 + lane; e < p.k; e += 64) out[e] = -1;
+}
+
+// ---- launchers ----------------------------------------------------------------------------
+template <typename T, int D>
+static void launch_select_t(const KParams &p, const void *Q, const void *K, const int *valid_len,
+                            int *sel, void *ws, hipStream_t st)
+{
+  float *qsum = reinterpret_cast<float *>(ws);
+  float *kmeanT = qsum + (size_t)p.B * p.H * p.NB * D;
+  const long tasks = 2L * p.B * p.H * p.NB;
+  const int per_wg = 256 / (D / 4);
+  const unsigned grid = (unsigned)((tasks + per_wg - 1) / per_wg);
+  hipLaunchKernelGGL((pool_kernel<T, D>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
+                     valid_len, qsum, kmeanT, p);
+  hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64), 0, st,
+                     qsum, kmeanT, valid_len, sel, p);
+}
+
+size_t select_workspace_bytes(const KParams &p) { return 2 * (size_t)p.B * p.H * p.NB * p.d * sizeof(float); }
+
+void launch_select(const KParams &p, int dtype, const void *Q, const void *K, const int *valid_len,
+                   int *sel, void *ws, hipStream_t st)
+{
+  if (dtype == 0) {
+    if (p.d == 32) launch_select_t<float, 32>(p, Q, K, valid_len, sel, ws, st);
+    else launch_select_t<float, 64>(p, Q, K, valid_len, sel, ws, st);
+  } else {
+    if (p.d == 32) launch_select_t<bf16_t, 32>(p, Q, K, valid_len, sel, ws, st);
+    else launch_select_t<bf16_t, 64>(p, Q, K, valid_len, sel, ws, st);
+  }
+}
+
+}  // namespace blossom

@@ -1,0 +1,110 @@
+"""Host-only checks of the C ABI: the library loads, exports what include/blossom.h declares,
+and rejects bad arguments before touching the GPU (no kernel is launched here)."""
+import ctypes
+import os
+import re
+
+import pytest
+
+from paper_2512_13368_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def lib():
+    if not os.path.exists(B.LIB_PATH):
+        import __graft_entry__ as g
+        g.build()
+    return B.lib()
+
+
+def test_exports_match_header(lib):
+    hdr = open(os.path.join(ROOT, "include", "blossom.h")).read()
+    declared = set(re.findall(r"\b(blossom_[a-z_]+)\s*\(", hdr))
+    assert declared == set(B.EXPORTS)
+    for name in declared:
+        assert hasattr(lib, name), name
+    assert B.version().startswith("blossom-gfx950")
+
+
+def _p(**kw):
+    base = dict(B=2, H=2, L=50, d=32, block=8, topk=2, window=8, dtype=B.F32)
+    base.update(kw)
+    return B.Params(**base)
+
+
+def test_workspace_sizes(lib):
+    p = _p()
+    NB = 7
+    assert B.workspace_bytes(p, B.WS_SELECT) == 2 * 2 * 2 * NB * 32 * 4
+    assert B.workspace_bytes(p, B.WS_FWD) == 0
+    assert B.workspace_bytes(p, B.WS_BWD) >= 2 * 2 * 50 * 16
+    assert B.workspace_bytes(_p(d=48), B.WS_SELECT) == 0          # invalid params -> 0
+    assert B.workspace_bytes(p, 99) == 0
+
+
+def _select(lib, p, Q=16, K=16, vl=16, sel=16, ws=16, ws_bytes=1 << 30):
+    cp = p.c()
+    vp = ctypes.c_void_p
+    return lib.blossom_select_blocks(ctypes.byref(cp), vp(Q), vp(K), vp(vl), vp(sel), vp(ws), ws_bytes, None)
+
+
+def test_validation_codes_select(lib):
+    # Pointers below are fake non-NULL addresses: every call must fail before they are used.
+    assert _select(lib, _p(d=48)) == -3
+    assert _select(lib, _p(block=12)) == -3
+    assert _select(lib, _p(dtype=7)) == -3
+    assert _select(lib, _p(stis_mode=1)) == -3
+    assert _select(lib, _p(B=0)) == -2
+    assert _select(lib, _p(L=0)) == -2
+    assert _select(lib, _p(L=8 * 4097)) == -2                       # more than 4096 blocks
+    assert _select(lib, _p(topk=0)) == -4
+    assert _select(lib, _p(window=0)) == -4
+    assert _select(lib, _p(softmax_scale=-1.0)) == -4
+    assert _select(lib, _p(softmax_scale=float("nan"))) == -4
+    assert _select(lib, _p(), Q=0) == -1
+    assert _select(lib, _p(), sel=0) == -1
+    assert _select(lib, _p(), Q=24) == -5                           # misaligned
+    assert _select(lib, _p(), ws=0) == -6
+    assert _select(lib, _p(), ws_bytes=16) == -6
+    assert _select(lib, _p(), ws=24) == -5
+    assert lib.blossom_select_blocks(None, None, None, None, None, None, 0, None) == -1
+
+
+def test_validation_codes_fwd_bwd_dense(lib):
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    cp = _p().c()
+    fwd = lambda **k: lib.blossom_attn_fwd(ctypes.byref(k.get("p", cp)), k.get("Q", a), a, a, a, a,
+                                           k.get("gw", a), None, k.get("O", a), k.get("o_lt", None), None,
+                                           None, None, None, 0, None)
+    assert fwd(Q=None) == -1
+    assert fwd(gw=None) == -1
+    assert fwd(O=vp(4100)) == -5
+    assert fwd(p=_p(save_for_bwd=1).c()) == -1                      # saved outputs required
+    assert fwd(p=_p(d=16).c()) == -3
+    bwd = lambda **k: lib.blossom_attn_bwd(ctypes.byref(k.get("p", cp)), a, a, a, a, a, a, None, a, a, a, a,
+                                           k.get("dO", a), a, a, a, k.get("dgw", a), None,
+                                           k.get("ws", a), k.get("n", 1 << 30), None)
+    assert bwd(dO=None) == -1
+    assert bwd(dgw=None) == -1
+    assert bwd(ws=None) == -6
+    assert bwd(n=8) == -6
+    assert bwd(p=_p(topk=0).c()) == -4
+    dense = lambda **k: lib.blossom_dense_causal_fwd(ctypes.byref(k.get("p", cp)), k.get("Q", a), a, a, a,
+                                                     k.get("O", a), None, None, 0, None)
+    assert dense(Q=None) == -1
+    assert dense(O=vp(4104)) == -5
+    assert dense(p=_p(block=5).c()) == -3
+    assert dense(p=_p(topk=0, window=0).c(), Q=None) == -1          # ignored fields never reject
+
+
+def test_strerror(lib):
+    seen = set()
+    for code in range(0, -8, -1):
+        s = B.strerror(code)
+        assert s and s != "unknown error code"
+        seen.add(s)
+    assert len(seen) == 8
+    assert B.strerror(-99) == "unknown error code"

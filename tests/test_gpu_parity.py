@@ -1,0 +1,193 @@
+"""GPU parity: the HIP path behind the C ABI against the CPU oracle on the same seeded inputs.
+
+Block selection must match bit-exactly; outputs and gradients within
+|x-ref| <= tol*(|ref| + rms(ref)), tol = 1e-4 (fp32) or 2e-2 (bf16 storage, fp32 accumulate).
+Small cases compare every element; the full-size workloads compare all selections and the
+outputs of sampled (row, head) pairs the oracle can afford.
+"""
+import numpy as np
+import pytest
+import torch
+
+import oracle
+from gpu_util import TOL, Dev, assert_close, host, params, pick_pairs
+from paper_2512_13368_amd import binding as B
+from paper_2512_13368_amd.inputs import WORKLOADS, make_inputs, with_shape
+
+pytestmark = pytest.mark.gpu
+
+
+def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale=None):
+    if x is None:
+        x = make_inputs(w, want_dO=True)
+    if gate_scale is not None:  # stronger gate weights exercise the gate path beyond alpha ~ 0.5
+        rng = np.random.default_rng(w.seed + 7)
+        x.gate_w = (rng.standard_normal(x.gate_w.shape) * gate_scale).astype(np.float32)
+        x.gate_b = (rng.standard_normal(x.gate_b.shape) * 0.5).astype(np.float32)
+    backward = w.backward if backward is None else backward
+    tol = TOL[w.dtype]
+    print(f"case {w.name} B{w.B} H{w.H} L{w.L} d{w.d} b{w.block} k{w.topk} w{w.window} {w.dtype} "
+          f"bwd={backward}", flush=True)
+    dv = Dev(x)
+    p = params(w, save_for_bwd=1)
+    sel = B.select_blocks(p, dv.Q, dv.K, dv.vl)
+    f = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
+    g = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO) if backward else None
+    torch.cuda.synchronize()
+
+    # --- selection: every (row, head), bit-exact ---
+    sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk)
+    np.testing.assert_array_equal(sel.cpu().numpy(), sel_ref)
+
+    # --- outputs: listed pairs ---
+    bh = None if pairs is None else np.asarray(pairs, np.int32)
+    take = (lambda t: host(t).reshape(w.B * w.H, *t.shape[2:])[bh if bh is not None else slice(None)])
+    fr = oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk,
+                         w.window, bh_list=bh)
+    assert_close(take(f.o_lt), fr.o_lt, tol, "o_lt")
+    assert_close(take(f.o_st), fr.o_st, tol, "o_st")
+    assert_close(take(f.O), fr.O, tol, "O")
+    assert_close(take(f.lse_lt), fr.lse_lt, tol, "lse_lt")
+    assert_close(take(f.lse_st), fr.lse_st, tol, "lse_st")
+    # pad rows are exactly zero
+    for r in range(w.B):
+        p0 = w.L - int(x.valid_len[r])
+        if p0 > 0:
+            assert float(f.O[r, :, :p0].abs().max()) == 0.0
+            assert float(f.o_lt[r, :, :p0].abs().max()) == 0.0 and float(f.o_st[r, :, :p0].abs().max()) == 0.0
+
+    # forward without the saved tensors gives the same O
+    p0_ = params(w, save_for_bwd=0)
+    f2 = B.attn_fwd(p0_, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
+    assert torch.equal(f2.O, f.O)
+
+    if backward:
+        gr = oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block,
+                             w.topk, w.window, bh_list=bh)
+        assert_close(take(g.dQ), gr.dQ, tol, "dQ")
+        assert_close(take(g.dK), gr.dK, tol, "dK")
+        assert_close(take(g.dV), gr.dV, tol, "dV")
+        if bh is None:  # gate gradients sum over every pair
+            assert_close(host(g.d_gate_w), gr.d_gate_w, tol, "d_gate_w")
+            assert_close(host(g.d_gate_b), gr.d_gate_b, tol, "d_gate_b")
+        for r in range(w.B):
+            p0 = w.L - int(x.valid_len[r])
+            if p0 > 0:
+                for t in (g.dQ, g.dK, g.dV):
+                    assert float(t[r, :, :p0].abs().max()) == 0.0
+        # determinism: a second run is bitwise identical
+        g2 = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO)
+        for a, b_ in ((g.dQ, g2.dQ), (g.dK, g2.dK), (g.dV, g2.dV), (g.d_gate_w, g2.d_gate_w),
+                      (g.d_gate_b, g2.d_gate_b)):
+            assert torch.equal(a, b_)
+
+    if check_dense:
+        lse = torch.empty((w.B, w.H, w.L), dtype=torch.float32, device="cuda")
+        Od, _ = B.dense_causal_fwd(p, dv.Q, dv.K, dv.V, dv.vl, lse=lse)
+        torch.cuda.synchronize()
+        Or, lr = oracle.dense_causal_fwd(x.Q, x.K, x.V, x.valid_len, bh_list=bh)
+        assert_close(take(Od), Or, tol, "dense O")
+        assert_close(take(lse), lr, tol, "dense lse")
+    return x, sel, f, g
+
+
+def test_cfg1_all_elements():
+    run_case(WORKLOADS["cfg1"], backward=True, check_dense=True)
+    run_case(WORKLOADS["cfg1"], backward=True, gate_scale=0.5)
+
+
+def test_cfg2_all_elements():
+    run_case(WORKLOADS["cfg2"], backward=True, check_dense=True)
+
+
+def test_cfg3_reduced_all_elements():
+    run_case(with_shape(WORKLOADS["cfg3"], B=6), backward=True, check_dense=True, gate_scale=0.3)
+
+
+def test_cfg3_full_size_sampled():
+    w = WORKLOADS["cfg3"]
+    run_case(w, pairs=pick_pairs(w, 12), backward=False)
+
+
+def test_cfg4_reduced_all_elements():
+    # several query blocks per head with the real block/top-k/window, small enough for every element
+    run_case(with_shape(WORKLOADS["cfg4"], B=2, H=2, L=1536, len_lo=700, len_hi=1536), backward=True,
+             check_dense=True)
+
+
+def test_cfg4_full_size_sampled():
+    w = WORKLOADS["cfg4"]
+    run_case(w, pairs=pick_pairs(w, 3), backward=False)
+
+
+def test_cfg5_full_size_sampled():
+    w = WORKLOADS["cfg5"]
+    run_case(w, pairs=pick_pairs(w, 8), backward=True)
+
+
+@pytest.mark.parametrize("dtype,d,b", [("fp32", 32, 8), ("fp32", 64, 16), ("bf16", 32, 32), ("bf16", 64, 8),
+                                       ("fp32", 64, 64), ("bf16", 32, 64), ("fp32", 32, 32), ("bf16", 64, 16)])
+def test_shape_matrix(dtype, d, b):
+    # ragged tail (L not a multiple of b), mixed lengths, every supported (dtype, d, b)
+    L = 3 * b + b // 2 + 1
+    w = with_shape(WORKLOADS["cfg1"], name=f"m-{dtype}-{d}-{b}", B=3, H=2, L=L, d=d, block=b, topk=3,
+                   window=b + 3, dtype=dtype, len_lo=1, len_hi=L, qkv_scaled=(dtype == "bf16"), seed=200 + d + b)
+    run_case(w, backward=True, check_dense=True, gate_scale=0.4)
+
+
+def test_edge_cases():
+    base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
+    x = make_inputs(base, want_dO=True)
+    x.valid_len[:] = [0, 1, 50, 8, 9]          # empty row, single item, full row, one block, block + 1
+    run_case(base, x=x, backward=True, check_dense=True)
+    # top-k covering all blocks and window >= L: both branches are dense causal attention
+    w = with_shape(base, name="dense-limit", topk=base.NB, window=base.L)
+    x2, sel, f, _ = run_case(w, x=make_inputs(w, want_dO=True), backward=True, check_dense=True)
+    dv = Dev(x2)
+    Od, _ = B.dense_causal_fwd(params(w), dv.Q, dv.K, dv.V, dv.vl)
+    torch.cuda.synchronize()
+    assert_close(host(f.o_lt), host(Od), 1e-5, "o_lt vs dense kernel")
+    assert_close(host(f.o_st), host(Od), 1e-5, "o_st vs dense kernel")
+    # k = 1 (own block only), w = 1 (self only), k larger than the number of blocks
+    run_case(with_shape(base, name="k1w1", topk=1, window=1), backward=True)
+    run_case(with_shape(base, name="kbig", topk=12, window=200), backward=True)
+
+
+def test_forced_gate():
+    w = WORKLOADS["cfg1"]
+    x = make_inputs(w, want_dO=True)
+    dv = Dev(x)
+    p = params(w, save_for_bwd=1)
+    sel = B.select_blocks(p, dv.Q, dv.K, dv.vl)
+    zero = torch.zeros_like(dv.gw)
+    big = torch.full_like(dv.gb, 1e4)
+    f1 = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, zero, big)
+    f0 = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, zero, -big)
+    fn = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, zero, None)
+    torch.cuda.synchronize()
+    assert torch.equal(f1.O, f1.o_lt) and torch.equal(f0.O, f0.o_st)
+    assert_close(host(fn.O), 0.5 * (host(fn.o_lt) + host(fn.o_st)), 1e-6, "gate_b = NULL")
+
+
+def test_selection_only_large_and_invariances():
+    # selection at every full size is cheap for the oracle: compare all of it
+    for name in ("cfg3", "cfg4"):
+        w = WORKLOADS[name]
+        x = make_inputs(w, want_dO=False)
+        dv = Dev(x)
+        sel = B.select_blocks(params(w), dv.Q, dv.K, dv.vl)
+        torch.cuda.synchronize()
+        np.testing.assert_array_equal(sel.cpu().numpy(),
+                                      oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk))
+        del dv
+        torch.cuda.empty_cache()
+    # planted ties: identical key blocks must resolve to the lowest index
+    w = with_shape(WORKLOADS["cfg1"], name="ties", B=2, H=2, L=64, d=32, block=8, topk=3, len_lo=64, len_hi=64,
+                   seed=401)
+    x = make_inputs(w)
+    x.K[:, :, 16:24] = x.K[:, :, 0:8]
+    x.K[:, :, 40:48] = x.K[:, :, 0:8]
+    dv = Dev(x)
+    sel = B.select_blocks(params(w), dv.Q, dv.K, dv.vl)
+    torch.cuda.synchronize()
+    np.testing.assert_array_equal(sel.cpu().numpy(), oracle.select_blocks(x.Q, x.K, x.valid_len, 8, 3))
