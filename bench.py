@@ -100,7 +100,8 @@ def main():
     shp = (w.B, w.H, w.L, w.d)
     sel = torch.empty((w.B, w.H, w.NB, w.topk), dtype=torch.int32, device=dev)
     mk = lambda: torch.empty(shp, dtype=tdt, device=dev)
-    fo = B.FwdOut(mk(), mk(), mk(), torch.empty(shp[:3], dtype=torch.float32, device=dev),
+    mk32 = lambda: torch.empty(shp, dtype=torch.float32, device=dev)
+    fo = B.FwdOut(mk(), mk32(), mk32(), torch.empty(shp[:3], dtype=torch.float32, device=dev),
                   torch.empty(shp[:3], dtype=torch.float32, device=dev))
     fo_nosave = B.FwdOut(fo.O)
     bo = B.BwdOut(mk(), mk(), mk(), torch.empty((w.H, 2 * w.d), dtype=torch.float32, device=dev),

@@ -15,8 +15,12 @@
  * Conventions shared by every entry point
  *   - All tensor pointers are DEVICE pointers on the current HIP device unless a
  *     comment says "host".  `blossom_params` itself is read on the host.
- *   - Q, K, V, O, dO, dQ, dK, dV, o_lt, o_st: [B,H,L,d], contiguous, d fastest,
- *     element type given by `dtype`, base address 16-byte aligned.
+ *   - Q, K, V, O, dO, dQ, dK, dV: [B,H,L,d], contiguous, d fastest, element type
+ *     given by `dtype`, base address 16-byte aligned.  The saved branch outputs
+ *     o_lt, o_st have the same shape but are ALWAYS fp32: backward forms
+ *     D = dO_x.o_x from them, and rounding o_x to bf16 would leave an error of
+ *     relative size 2^-9 |o_x| in every dS of the row, which dominates the
+ *     gradient of rows that see only a few keys.
  *   - One block size `block` (b) serves as query-block, compression-block and
  *     selection-block size (Eq. 8 with l = s = l' = b, for which the score
  *     mapping of Eq. 11 is the identity).  NB = ceil(L/b); block I covers
@@ -102,7 +106,7 @@ int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
  *                   -1 or in [0,NB); each query block with a valid query must list itself)
  *   gate_w     in   fp32 [H,2d];  gate_b in fp32 [H] or NULL (= 0)
  *   O          out  [B,H,L,d]
- *   o_lt,o_st  out  [B,H,L,d], lse_lt,lse_st out fp32 [B,H,L]; required iff save_for_bwd
+ *   o_lt,o_st  out  fp32 [B,H,L,d], lse_lt,lse_st out fp32 [B,H,L]; required iff save_for_bwd
  *   ws         scratch for BLOSSOM_WS_FWD (may be NULL when that size is 0)
  */
 int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,

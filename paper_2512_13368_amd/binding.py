@@ -178,13 +178,13 @@ def attn_fwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b=None, out: FwdOu
     if out is None:
         out = FwdOut(torch.empty(shp, dtype=dt, device=Q.device))
         if p.save_for_bwd:
-            out.o_lt = torch.empty(shp, dtype=dt, device=Q.device)
-            out.o_st = torch.empty(shp, dtype=dt, device=Q.device)
+            out.o_lt = torch.empty(shp, dtype=torch.float32, device=Q.device)
+            out.o_st = torch.empty(shp, dtype=torch.float32, device=Q.device)
             out.lse_lt = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
             out.lse_st = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
     _check_tensor(out.O, shp, dt, "O")
-    _check_tensor(out.o_lt, shp, dt, "o_lt")
-    _check_tensor(out.o_st, shp, dt, "o_st")
+    _check_tensor(out.o_lt, shp, torch.float32, "o_lt")
+    _check_tensor(out.o_st, shp, torch.float32, "o_st")
     _check_tensor(out.lse_lt, shp[:3], torch.float32, "lse_lt")
     _check_tensor(out.lse_st, shp[:3], torch.float32, "lse_st")
     ws, nbytes = _workspace(p, WS_FWD, ws, Q.device)
@@ -211,10 +211,14 @@ def attn_bwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b, fwd: FwdOut, dO
     import torch
     shp = (p.B, p.H, p.L, p.d)
     dt = _torch_dtype(p)
-    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO"), (fwd.o_lt, "o_lt"), (fwd.o_st, "o_st")):
+    for t, nm in ((Q, "Q"), (K, "K"), (V, "V"), (dO, "dO")):
         if t is None:
             raise ValueError(f"{nm} is required")
         _check_tensor(t, shp, dt, nm)
+    for t, nm in ((fwd.o_lt, "o_lt"), (fwd.o_st, "o_st")):
+        if t is None:
+            raise ValueError(f"{nm} is required")
+        _check_tensor(t, shp, torch.float32, nm)
     for t, nm in ((fwd.lse_lt, "lse_lt"), (fwd.lse_st, "lse_st")):
         if t is None:
             raise ValueError(f"{nm} is required")

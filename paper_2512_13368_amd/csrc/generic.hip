@@ -70,8 +70,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
                                                          const int *__restrict__ sel,
                                                          const float *__restrict__ gate_w,
                                                          const float *__restrict__ gate_b,
-                                                         T *__restrict__ O, T *__restrict__ o_lt_out,
-                                                         T *__restrict__ o_st_out,
+                                                         T *__restrict__ O, float *__restrict__ o_lt_out,
+                                                         float *__restrict__ o_st_out,
                                                          float *__restrict__ lse_lt_out,
                                                          float *__restrict__ lse_st_out, int dense,
                                                          KParams p)
@@ -103,8 +103,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
 #pragma unroll
       for (int c = 0; c < D; ++c) acc[c] = 0.0f;
       store_row<T, D>(O + rowoff, acc);
-      if (o_lt_out) store_row<T, D>(o_lt_out + rowoff, acc);
-      if (o_st_out) store_row<T, D>(o_st_out + rowoff, acc);
+      if (o_lt_out) store_row<float, D>(o_lt_out + rowoff, acc);
+      if (o_st_out) store_row<float, D>(o_st_out + rowoff, acc);
       if (lse_lt_out) lse_lt_out[lrow] = 0.0f;
       if (lse_st_out) lse_st_out[lrow] = 0.0f;
     }
@@ -210,7 +210,7 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
       z = fmaf(ws[c], acc[c], z);
     }
     if (in_range) {
-      if (o_st_out) store_row<T, D>(o_st_out + rowoff, acc);
+      if (o_st_out) store_row<float, D>(o_st_out + rowoff, acc);
       if (lse_st_out) lse_st_out[lrow] = lse_st;
     }
   }
@@ -227,7 +227,7 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
 
   // ---- gate and blend (Eq. 18-19) ----
   if (phase == 0 && in_range) {
-    if (o_lt_out) store_row<T, D>(o_lt_out + rowoff, acc);
+    if (o_lt_out) store_row<float, D>(o_lt_out + rowoff, acc);
     if (lse_lt_out) lse_lt_out[lrow] = lse_lt;
     const float *wl = gate_w + (size_t)h * 2 * D;
 #pragma unroll
@@ -246,8 +246,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
 constexpr int kPrepRows = 128;
 
 template <typename T, int D>
-__global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const T *__restrict__ o_lt,
-                                                             const T *__restrict__ o_st,
+__global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const float *__restrict__ o_lt,
+                                                             const float *__restrict__ o_st,
                                                              const T *__restrict__ dO,
                                                              const int *__restrict__ valid_len,
                                                              const float *__restrict__ gate_w,
@@ -301,10 +301,10 @@ __global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const T *__restrict
   const int r_hi = min((chunk + 1) * kPrepRows, p.L);
   float *out = partial + (size_t)blockIdx.x * (2 * D + 1);
   for (int c = t; c < 2 * D; c += kPrepRows) {
-    const T *src = (c < D ? o_lt : o_st) + head + (c < D ? c : c - D);
+    const float *src = (c < D ? o_lt : o_st) + head + (c < D ? c : c - D);
     float acc = 0.0f;
     for (int r = r_lo; r < r_hi; ++r)
-      acc = fmaf(dz_s[r - chunk * kPrepRows], to_f32(src[(size_t)r * D]), acc);
+      acc = fmaf(dz_s[r - chunk * kPrepRows], src[(size_t)r * D], acc);
     out[c] = acc;
   }
   if (t == 0) {
@@ -630,7 +630,7 @@ static void launch_fwd_t(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
   hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64), 0, st,
                      (const T *)a.Q, (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w,
-                     a.gate_b, (T *)a.O, (T *)a.o_lt, (T *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
+                     a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
 }
 
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st)
@@ -680,7 +680,7 @@ static void launch_bwd_t(const KParams &p, const BwdArgs &a, hipStream_t st)
   const unsigned BH = (unsigned)(p.B * p.H);
 
   hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(kPrepRows), 0, st,
-                     (const T *)a.o_lt, (const T *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
+                     (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
                      a.gate_b, rowstat, partial, p);
   hipLaunchKernelGGL(bwd_gate_reduce_kernel, dim3((unsigned)p.H), dim3(256), 0, st, partial, a.d_gate_w,
                      a.d_gate_b, w.nchunk, p);
