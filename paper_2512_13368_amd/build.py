@@ -16,6 +16,7 @@ SOURCES = {
     "api.hip": [],
     "select.hip": ["-ffp-contract=off"],
     "generic.hip": [],
+    "mfma_fwd.hip": [],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

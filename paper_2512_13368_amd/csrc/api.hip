@@ -105,7 +105,8 @@ int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, cons
     a.o_lt = o_lt; a.o_st = o_st; a.lse_lt = lse_lt; a.lse_st = lse_st;
   }
   a.dense = 0;
-  launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
+  if (fwd_mfma_supported(kp, p->dtype)) launch_fwd_mfma(kp, a, (hipStream_t)hip_stream);
+  else launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();
 }
 
@@ -153,7 +154,8 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
   FwdArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.O = O; a.lse_lt = lse;
   a.dense = 1;
-  launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
+  if (fwd_mfma_supported(kp, p->dtype)) launch_fwd_mfma(kp, a, (hipStream_t)hip_stream);
+  else launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();
 }
 

@@ -44,4 +44,8 @@ void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream
 size_t bwd_workspace_bytes(const KParams &p);
 void launch_bwd_generic(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st);
 
+// mfma_fwd.hip: matrix-core forward for bf16, d = 64, b in {32, 64}
+bool fwd_mfma_supported(const KParams &p, int dtype);
+void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st);
+
 }  // namespace blossom

@@ -126,13 +126,17 @@ def test_cfg5_full_size_sampled():
 
 
 @pytest.mark.parametrize("dtype,d,b", [("fp32", 32, 8), ("fp32", 64, 16), ("bf16", 32, 32), ("bf16", 64, 8),
-                                       ("fp32", 64, 64), ("bf16", 32, 64), ("fp32", 32, 32), ("bf16", 64, 16)])
+                                       ("fp32", 64, 64), ("bf16", 32, 64), ("fp32", 32, 32), ("bf16", 64, 16),
+                                       ("bf16", 64, 32), ("bf16", 64, 64)])
 def test_shape_matrix(dtype, d, b):
     # ragged tail (L not a multiple of b), mixed lengths, every supported (dtype, d, b)
     L = 3 * b + b // 2 + 1
     w = with_shape(WORKLOADS["cfg1"], name=f"m-{dtype}-{d}-{b}", B=3, H=2, L=L, d=d, block=b, topk=3,
                    window=b + 3, dtype=dtype, len_lo=1, len_hi=L, qkv_scaled=(dtype == "bf16"), seed=200 + d + b)
-    run_case(w, backward=True, check_dense=True, gate_scale=0.4)
+    x = make_inputs(w, want_dO=True)
+    # a full row (the two branches differ), a row starting inside a block, a row shorter than a block
+    x.valid_len[:] = [L, L - b - 3, b // 2 + 1]
+    run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
 
 
 def test_edge_cases():
