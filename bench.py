@@ -66,6 +66,9 @@ def main():
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "dense"], default=None,
+                    help="profiling aid: run only this stage --steps times (after the others ran once) "
+                         "and print its average time; the headline line is not produced")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
@@ -114,6 +117,26 @@ def main():
         B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel)
         B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo)
         B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd)
+
+    if args.stage:
+        step()  # every buffer a later stage reads is filled once
+        fn = {"select": lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel),
+              "fwd": lambda: B.attn_fwd(p_nosave, Q, K, V, vl, sel, gw, gb, out=fo_nosave),
+              "fwd_save": lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo),
+              "bwd": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd),
+              "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense)}[args.stage]
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        print(json.dumps({"stage": args.stage, "workload": w.name, "steps": args.steps,
+                          "avg_ms": round(e0.elapsed_time(e1) / args.steps, 4)}))
+        return
 
     for _ in range(args.warmup):
         step()

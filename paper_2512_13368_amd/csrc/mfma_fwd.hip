@@ -3,16 +3,23 @@
 //
 // Work split: one workgroup per (row, head, query block); one wavefront per 32 query rows.
 // K/V tiles of the short-term window and of the selected blocks are gathered by the selection
-// list from HBM/L2 with coalesced 16-byte loads, staged in LDS (double buffered) and shared by
-// the workgroup's wavefronts.
+// list with direct global->LDS loads (16 bytes per lane, whole 128-byte rows per 8 lanes),
+// double buffered, XOR-swizzled so that the operand reads below are bank-conflict free, and
+// shared by the workgroup's wavefronts.
 //
-// Per 32-key sub-tile a wavefront computes S^T = K Q^T with four v_mfma_f32_32x32x16_bf16
-// (keys are the M dimension, so every lane owns ONE query column and 16 of its logits: the
-// row maximum and row sum are in-lane reductions plus one exchange with lane^32), applies the
-// online softmax in fp32, and feeds P^T straight from the accumulator registers (converted to
-// bf16) as the B operand of O^T += V^T P^T (four more MFMAs).  The key order inside a
-// contraction slab is whatever the accumulator layout dictates; V^T is read from LDS with the
-// transposing ds_read_b64_tr_b16 in exactly that order, so P never moves between lanes.
+// Per 32-key unit a wavefront computes S^T = K Q^T with four v_mfma_f32_32x32x16_bf16 (keys
+// are the M dimension, so every lane owns ONE query column and 16 of its logits: row maximum
+// and row sum are in-lane reductions plus one exchange with lane^32), applies the online
+// softmax in fp32, and feeds P^T straight from the accumulator registers (converted to bf16)
+// as the B operand of O^T += V^T P^T (four more MFMAs).  The key order inside a contraction
+// slab is whatever the accumulator layout dictates; V^T is read from LDS with the transposing
+// ds_read_b64_tr_b16 in exactly that order, so P never moves between lanes.
+//
+// Pipeline: the logits of tile t+1 are issued to the matrix cores in the same straight-line
+// region as the exponentials of tile t and its P V products, so MFMA and VALU work of one
+// wavefront can overlap; K therefore runs one tile ahead of V in LDS.  The running maximum is
+// only raised when it grows by more than 2^8 (probabilities stay below 2^8, far inside bf16
+// range), which removes nearly all accumulator rescaling.
 #include "common.h"
 #include "launch.h"
 
@@ -21,58 +28,31 @@ namespace blossom {
 namespace {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
 
 constexpr int D = 64;
-constexpr int KSTR = 72;  // bf16 elements per K row in LDS: 144 B, conflict-free 16-byte row reads
-constexpr int VSTR = 80;  // 160 B rows for the 4-row x 32-byte patches of the transposing read
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegInf = -__builtin_huge_valf();
+constexpr float kRaise = 8.0f;  // log2 units by which the maximum must grow before it is raised
+constexpr int kMaxTiles = 96;   // window blocks + selected blocks one query block may walk (host-checked)
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
 
 // Maps the hardware workgroup id (dealt round-robin over the 8 XCDs) to a virtual id such that
 // each XCD works through a contiguous range: all query blocks of a head then share one L2.
 __device__ __forceinline__ unsigned xcd_remap(unsigned pid, unsigned total)
 {
   constexpr unsigned X = 8;
-  const unsigned per = (total + X - 1) / X;      // ids of a "tall" XCD
+  const unsigned per = (total + X - 1) / X;  // ids of a "tall" XCD
   const unsigned tall = total % X ? total % X : X;
   const unsigned xcd = pid % X, local = pid / X;
   return xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-}
-
-struct Tile16 {  // one thread's share of a staged K or V tile: 4 x 16 bytes
-  uint4 r[4];
-};
-
-template <int BLK>
-__device__ __forceinline__ void tile_load(const uint16_t *head, int J, int L, int tid, Tile16 &t)
-{
-  constexpr int NT = BLK * 2;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int c = tid + NT * u;
-    const int row = c >> 3, col = c & 7;
-    const int pos = J * BLK + row;
-    t.r[u] = pos < L ? *reinterpret_cast<const uint4 *>(head + (size_t)pos * D + col * 8)
-                     : make_uint4(0u, 0u, 0u, 0u);
-  }
-}
-
-template <int BLK, int STR>
-__device__ __forceinline__ void tile_store(uint16_t *lds, int tid, const Tile16 &t)
-{
-  constexpr int NT = BLK * 2;
-#pragma unroll
-  for (int u = 0; u < 4; ++u) {
-    const int c = tid + NT * u;
-    const int row = c >> 3, col = c & 7;
-    *reinterpret_cast<uint4 *>(lds + row * STR + col * 8) = t.r[u];
-  }
 }
 
 }  // namespace
@@ -92,8 +72,16 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
                                                            float *__restrict__ lse_st_out, int dense,
                                                            KParams p)
 {
-  __shared__ __attribute__((aligned(16))) uint16_t Ks[2][BLK * KSTR];
-  __shared__ __attribute__((aligned(16))) uint16_t Vs[2][BLK * VSTR];
+  constexpr int UNITS = BLK / 32;  // 32-key units per tile
+  constexpr int TILE = BLK * D;    // bf16 elements of one staged tile (rows of 128 bytes, swizzled)
+  // Four separate arrays (not one indexed by parity): the compiler can then prove that a
+  // prefetch in flight into one buffer does not alias the operand reads of another, and does
+  // not wait for the prefetch before those reads.
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks0[TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
+  __shared__ int tiles[kMaxTiles];  // key blocks in processing order: window blocks, then selected blocks
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -136,18 +124,14 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   // Q^T operand: lane (query lq, half lh) holds Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk.
   bf16x8 qf[4];
   {
-    const uint16_t *qrow = Q + head + (size_t)(iq < p.L ? iq : 0) * D;
+    const uint16_t *qrow = Q + head + (size_t)min(iq, p.L - 1) * D;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      uint4 v = *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh);
-      if (iq >= p.L) v = make_uint4(0u, 0u, 0u, 0u);
-      qf[kk] = __builtin_bit_cast(bf16x8, v);
-    }
+    for (int kk = 0; kk < 4; ++kk)
+      qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh));
   }
 
+  // ---- tile list: window blocks J_lo..I, then the selection list up to its first -1 ----
   const int J_first = p0 / BLK;
-  const uint16_t *Kh = K + head;
-  const uint16_t *Vh = V + head;
   const int *my_sel = dense ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
   int J_lo, n_st, n_all;
   if (dense) {
@@ -159,17 +143,65 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
     J_lo = max(J_lo, J_first);
     n_st = I - J_lo + 1;
-    n_all = n_st + p.k;
+    int n_lt = 0;
+    while (n_lt < p.k) {
+      const int J = my_sel[n_lt];
+      if (J < 0 || J >= p.NB) break;
+      ++n_lt;
+    }
+    n_all = n_st + n_lt;
   }
-  auto tile_of = [&](int t) -> int {  // key block of step t, or -1
+  // The list lives in LDS so that walking it never waits on the vector-memory counter, which
+  // also tracks the tile prefetches in flight.
+  if (!dense) {
+    for (int t = tid; t < n_all; t += BLK * 2) tiles[t] = t < n_st ? J_lo + t : my_sel[t - n_st];
+  }
+  __syncthreads();
+  auto tile_of = [&](int t) -> int {
     if (dense) return J_first + t;
-    if (t < n_st) return J_lo + t;
-    const int J = my_sel[t - n_st];
-    return (J >= 0 && J < p.NB) ? J : -1;
+    return __builtin_amdgcn_readfirstlane(tiles[t]);
   };
-  auto next_valid = [&](int t) -> int {
-    while (t < n_all && tile_of(t) < 0) ++t;
-    return t;
+
+  // ---- staging: each wavefront moves 4 x 1 KB of K and of V per tile ----
+  // LDS position of 16-byte chunk c of row r:  r*128 + ((c ^ swz(r)) * 16),
+  //   swzK(r) = r & 7 (8 rows x one chunk column = 8 distinct positions for the row-per-lane reads)
+  //   swzV(r) = 2*(r & 3) (4 rows x two chunk columns = 8 distinct positions for the transposing reads)
+  const uint16_t *Kh = K + head;
+  const uint16_t *Vh = V + head;
+  const int ld_row = 32 * wv + (lane >> 3);  // + 8*u
+  const int ld_ck = ((lane & 7) ^ (lane >> 3)) * 8;
+  const int ld_cv = ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8;
+  auto stage = [&](const uint16_t *src_head, uint16_t *dst_tile, int J, int col) {
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const int row = min(J * BLK + ld_row + 8 * u, p.L - 1);
+      const uint16_t *src = src_head + (unsigned)(row * D + col);
+      __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+    }
+  };
+
+  // ---- per-lane LDS read offsets (elements) ----
+  int koff[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) koff[kk] = lq * D + (((2 * kk + lh) ^ (lq & 7)) * 8);
+  const int r16 = lane & 15;
+  int voff[2];
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+    voff[mb] = (4 * lh + (r16 >> 2)) * D +
+               (((4 * mb + 2 * ((lane >> 4) & 1) + ((r16 & 3) >> 1)) ^ (2 * (r16 >> 2))) * 8) + 4 * (r16 & 1);
+
+  auto qk = [&](const uint16_t *ks, f32x16 (&sacc)[UNITS]) {
+#pragma unroll
+    for (int s = 0; s < UNITS; ++s) {
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[s][i] = 0.0f;
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + 32 * s * D + koff[kk]);
+        sacc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[s], 0, 0, 0);
+      }
+    }
   };
 
   const float c2 = p.scale * kLog2e;
@@ -181,8 +213,7 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
 #pragma unroll
     for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.0f; oacc[1][i] = 0.0f; }
   };
-  // normalise the running state into oacc, return lse (natural log)
-  auto finish = [&]() -> float {
+  auto finish = [&]() -> float {  // normalise the running state into oacc, return lse (natural log)
     const float l_tot = l_run + __shfl_xor(l_run, 32);
     const bool ok = q_ok && l_tot > 0.0f;
     const float inv = ok ? 1.0f / l_tot : 0.0f;
@@ -203,113 +234,121 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   } else {
     hp_st = p.w < kFewKeys || q0 - p0 + 1 < kFewKeys;
     int past = 0;
-    for (int e = 0; e < p.k && past < kFewKeys; ++e) {
+    for (int e = 0; e < n_all - n_st && past < kFewKeys; ++e) {
       const int J = my_sel[e];
-      if (J >= 0 && J < I) past += max(0, min((J + 1) * BLK, p.L) - max(J * BLK, p0));
+      if (J < I) past += max(0, min((J + 1) * BLK, p.L) - max(J * BLK, p0));
     }
     hp_lt = past < kFewKeys;
   }
 
-  auto compute_tile = [&](int buf, int J, bool windowed) {
+  // softmax of tile J (logits in sacc) and O^T += V^T P^T; also issues the logits of the next tile
+  auto tile_body = [&](const uint16_t *vs, const uint16_t *ks_next, int J, bool windowed, f32x16 (&sacc)[UNITS],
+                       f32x16 (&snext)[UNITS]) {
     const bool hp = __builtin_amdgcn_readfirstlane((int)(windowed ? hp_st : hp_lt)) != 0;
-    const uint16_t *ks = Ks[buf];
-    const uint16_t *vs = Vs[buf];
-    const bool tile_masked = windowed || J == I || J * BLK < p0;
+    if (windowed || J == I || J * BLK < p0) {
 #pragma unroll
-    for (int s = 0; s < BLK / 32; ++s) {
-      const int k0 = J * BLK + 32 * s;
-      // wave-uniform skips: all keys after all queries, before the window, or all padding
-      if (k0 > q0 + 31) continue;
-      if (windowed && k0 + 31 < q0 - p.w + 1) continue;
-      if (k0 + 31 < p0) continue;
-      f32x16 sacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[i] = 0.0f;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + (32 * s + lq) * KSTR + 16 * kk + 8 * lh);
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc, 0, 0, 0);
-      }
-      if (tile_masked) {
+      for (int s = 0; s < UNITS; ++s)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int key = k0 + 8 * (i >> 2) + 4 * lh + (i & 3);
-          const bool vis = key <= iq && key >= p0 && (!windowed || iq - key < p.w);
-          sacc[i] = vis ? sacc[i] : kNegInf;
+          const int key = J * BLK + 32 * s + 8 * (i >> 2) + 4 * lh + (i & 3);
+          const bool vis = (key <= iq) & (key >= p0) & ((!windowed) | (iq - key < p.w));
+          sacc[s][i] = vis ? sacc[s][i] : kNegInf;
         }
-      }
-      float mx = sacc[0];
+    }
+    float mx = sacc[0][0];
 #pragma unroll
-      for (int i = 1; i < 16; ++i) mx = fmaxf(mx, sacc[i]);
-      mx = fmaxf(mx, __shfl_xor(mx, 32));
-      const float m_new = fmaxf(m_run, mx * c2);
-      const float m_use = m_new == kNegInf ? 0.0f : m_new;
-      const float alpha = __builtin_amdgcn_exp2f(m_run - m_use);
-      float rs = 0.0f;
-      bf16x8 pf[2], pf_lo[2];
+    for (int s = 0; s < UNITS; ++s)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) {
-        const float pi = __builtin_amdgcn_exp2f(fmaf(sacc[i], c2, -m_use));
-        rs += pi;
-        pf[i >> 3][i & 7] = (__bf16)pi;
-        sacc[i] = pi;
-      }
-      if (hp) {
+      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[s][i]);
+    mx = fmaxf(mx, __shfl_xor(mx, 32));
+    const float m_cand = mx * c2;
+    const bool upd = m_cand > m_run + kRaise;  // also true for the first visible key (m_run = -inf)
+    if (__any(upd)) {
+      const float m_new = upd ? m_cand : m_run;
+      const float alpha = upd ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;
+      l_run *= alpha;
 #pragma unroll
-        for (int i = 0; i < 16; ++i)
-          pf_lo[i >> 3][i & 7] = (__bf16)(sacc[i] - (float)pf[i >> 3][i & 7]);
-      }
-      l_run = l_run * alpha + rs;
+      for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
       m_run = m_new;
-      if (__any(alpha != 1.0f)) {
+    }
+    const float m_use = m_run == kNegInf ? 0.0f : m_run;
+
+    // ---- one straight-line region: exponentials of this tile, logits of the next, P V ----
+    qk(ks_next, snext);
+    bf16x8 pf[UNITS][2];
+    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
 #pragma unroll
-        for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
+    for (int s = 0; s < UNITS; ++s) {
+#pragma unroll
+      for (int i = 0; i < 16; i += 2) {
+        const float pa = __builtin_amdgcn_exp2f(fmaf(sacc[s][i], c2, -m_use));
+        const float pb = __builtin_amdgcn_exp2f(fmaf(sacc[s][i + 1], c2, -m_use));
+        sacc[s][i] = pa;
+        sacc[s][i + 1] = pb;
+        const bf16x2 pk = {(__bf16)pa, (__bf16)pb};
+        pf[s][i >> 3][i & 7] = pk[0];
+        pf[s][i >> 3][(i & 7) + 1] = pk[1];
+        l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);  // sums what the MFMA will see
       }
-      // O^T[d][q] += sum_key V^T[d][key] P^T[key][q]
+    }
 #pragma unroll
-      for (int t = 0; t < 2; ++t) {
+    for (int s = 0; s < UNITS; ++s)
+#pragma unroll
+      for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
-          const int r16 = lane & 15;
-          const int dbase = 32 * mb + 16 * ((lane >> 4) & 1) + 4 * (r16 & 3);
-          const int krow = 32 * s + 16 * t + 4 * lh + (r16 >> 2);
-          const uint16_t *a0 = vs + krow * VSTR + dbase;
+          const uint16_t *a0 = vs + (32 * s + 16 * t) * D + voff[mb];
           const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * VSTR));
+          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * D));
           const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[t],
+          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s][t],
                                                              oacc[mb], 0, 0, 0);
-          if (hp)
-            oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf_lo[t],
-                                                               oacc[mb], 0, 0, 0);
         }
+    if (hp) {  // second bf16 term of P
+#pragma unroll
+      for (int s = 0; s < UNITS; ++s) {
+        bf16x8 pl[2];
+#pragma unroll
+        for (int i = 0; i < 16; i += 2) {
+          const bf16x2 pk = {(__bf16)(sacc[s][i] - (float)pf[s][i >> 3][i & 7]),
+                             (__bf16)(sacc[s][i + 1] - (float)pf[s][i >> 3][(i & 7) + 1])};
+          pl[i >> 3][i & 7] = pk[0];
+          pl[i >> 3][(i & 7) + 1] = pk[1];
+          l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
+        }
+#pragma unroll
+        for (int t = 0; t < 2; ++t)
+#pragma unroll
+          for (int mb = 0; mb < 2; ++mb) {
+            const uint16_t *a0 = vs + (32 * s + 16 * t) * D + voff[mb];
+            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
+            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * D));
+            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
+            oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pl[t],
+                                                               oacc[mb], 0, 0, 0);
+          }
       }
     }
   };
 
-  // ---- software pipeline over the tile list ----
+  // ---- pipeline over the tile list: K runs one tile ahead of V ----
   f32x16 ost[2];  // normalised short-term output, parked while the long-term branch runs
   float lse_st = 0.0f;
   bool st_open = !dense;
   reset();
-  int t = next_valid(0);
-  Tile16 kreg, vreg;
-  if (t < n_all) {
-    const int J = tile_of(t);
-    tile_load<BLK>(Kh, J, p.L, tid, kreg);
-    tile_load<BLK>(Vh, J, p.L, tid, vreg);
-    tile_store<BLK, KSTR>(Ks[0], tid, kreg);
-    tile_store<BLK, VSTR>(Vs[0], tid, vreg);
-  }
+  f32x16 sA[UNITS], sB[UNITS];
+  stage(Kh, Ks0, tile_of(0), ld_ck);
+  stage(Vh, Vs0, tile_of(0), ld_cv);
+  if (n_all > 1) stage(Kh, Ks1, tile_of(1), ld_ck);
   __syncthreads();
-  int cur = 0;
-  while (t < n_all) {
-    const int tn = next_valid(t + 1);
-    if (tn < n_all) {
-      const int Jn = tile_of(tn);
-      tile_load<BLK>(Kh, Jn, p.L, tid, kreg);
-      tile_load<BLK>(Vh, Jn, p.L, tid, vreg);
-    }
+  qk(Ks0, sA);
+  __syncthreads();  // Ks0 may be overwritten from here on
+
+  // step t: prefetch K(t+2) and V(t+1), compute tile t from its logits and V(t), issue logits of t+1
+  auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *v_cur, const uint16_t *k_next,
+                  f32x16 (&scur)[UNITS], f32x16 (&snext)[UNITS]) {
+    if (t + 2 < n_all) stage(Kh, k_fill, tile_of(t + 2), ld_ck);
+    if (t + 1 < n_all) stage(Vh, v_fill, tile_of(t + 1), ld_cv);
     if (st_open && t >= n_st) {  // the window tiles are done: close the short-term branch
       lse_st = finish();
       ost[0] = oacc[0];
@@ -317,16 +356,14 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
       reset();
       st_open = false;
     }
-    compute_tile(cur, tile_of(t), t < n_st);
-    if (tn < n_all) {
-      tile_store<BLK, KSTR>(Ks[cur ^ 1], tid, kreg);
-      tile_store<BLK, VSTR>(Vs[cur ^ 1], tid, vreg);
-    }
+    tile_body(v_cur, k_next, tile_of(t), t < n_st, scur, snext);
     __syncthreads();
-    cur ^= 1;
-    t = tn;
+  };
+  for (int t = 0; t < n_all; t += 2) {
+    step(t, Ks0, Vs1, Vs0, Ks1, sA, sB);
+    if (t + 1 < n_all) step(t + 1, Ks1, Vs0, Vs1, Ks0, sB, sA);
   }
-  if (st_open) {  // a selection list without any usable entry
+  if (st_open) {  // no usable selection entry at all
     lse_st = finish();
     ost[0] = oacc[0];
     ost[1] = oacc[1];
@@ -358,10 +395,18 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int dd = 32 * mb + 8 * (i >> 2) + 4 * lh + (i & 3);
-      z = fmaf(wl[dd], oacc[mb][i], z);
-      z = fmaf(ws[dd], ost[mb][i], z);
+    for (int g = 0; g < 4; ++g) {
+      const int d0 = 32 * mb + 8 * g + 4 * lh;
+      const float4 a = *reinterpret_cast<const float4 *>(wl + d0);
+      const float4 b = *reinterpret_cast<const float4 *>(ws + d0);
+      z = fmaf(a.x, oacc[mb][4 * g], z);
+      z = fmaf(a.y, oacc[mb][4 * g + 1], z);
+      z = fmaf(a.z, oacc[mb][4 * g + 2], z);
+      z = fmaf(a.w, oacc[mb][4 * g + 3], z);
+      z = fmaf(b.x, ost[mb][4 * g], z);
+      z = fmaf(b.y, ost[mb][4 * g + 1], z);
+      z = fmaf(b.z, ost[mb][4 * g + 2], z);
+      z = fmaf(b.w, ost[mb][4 * g + 3], z);
     }
   z += __shfl_xor(z, 32);
   z += gate_b ? gate_b[h] : 0.0f;
@@ -392,7 +437,12 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   }
 }
 
-bool fwd_mfma_supported(const KParams &p, int dtype) { return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64); }
+bool fwd_mfma_supported(const KParams &p, int dtype)
+{
+  if (dtype != 1 || p.d != 64 || (p.b != 32 && p.b != 64)) return false;
+  // window blocks (at most (w-1)/b + 2) plus selected blocks must fit the in-LDS tile list
+  return (long)(p.w - 1) / p.b + 2 + p.k <= kMaxTiles;
+}
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
