@@ -17,9 +17,14 @@
 //
 // Pipeline: the logits of tile t+1 are issued to the matrix cores in the same straight-line
 // region as the exponentials of tile t and its P V products, so MFMA and VALU work of one
-// wavefront can overlap; K therefore runs one tile ahead of V in LDS.  The running maximum is
-// only raised when it grows by more than 2^8 (probabilities stay below 2^8, far inside bf16
-// range), which removes nearly all accumulator rescaling.
+// wavefront can overlap; K therefore runs one tile ahead of V in LDS.
+//
+// Softmax bookkeeping: Q is pre-multiplied by scale*log2(e) (rounded to bf16 once), and the
+// logits accumulator of a tile starts at minus the row's current reference m_ref instead of
+// zero, so the MFMA result is directly the exponent s*c - m_ref and each probability costs one
+// v_exp_f32.  m_ref is only moved when a row's tile maximum exceeds 2^8 above it (then the
+// tile's exponents, the running sum and the output accumulators are shifted), or on the first
+// visible key of a branch; probabilities therefore stay below 2^8, far inside bf16 range.
 #include "common.h"
 #include "launch.h"
 
@@ -32,6 +37,7 @@ typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 typedef short s16x4 __attribute__((ext_vector_type(4)));
 typedef short s16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr int D = 64;
 constexpr float kLog2e = 1.4426950408889634f;
@@ -39,6 +45,7 @@ constexpr float kLn2 = 0.6931471805599453f;
 constexpr float kNegInf = -__builtin_huge_valf();
 constexpr float kRaise = 8.0f;  // log2 units by which the maximum must grow before it is raised
 constexpr int kMaxTiles = 96;   // window blocks + selected blocks one query block may walk (host-checked)
+constexpr int kFewKeys = 32;    // rows seeing fewer keys than this get two-term bf16 probabilities
 
 typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
 typedef __attribute__((address_space(3))) void lds_void;
@@ -82,6 +89,7 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
   __shared__ int tiles[kMaxTiles];  // key blocks in processing order: window blocks, then selected blocks
+  __shared__ float gate_s[2 * D];   // this head's gate weights, fetched at the start, used at the very end
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -121,40 +129,66 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     return;
   }
 
-  // Q^T operand: lane (query lq, half lh) holds Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk.
+  // Q^T operand: lane (query lq, half lh) holds c*Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk,
+  // c = scale*log2(e), rounded to bf16: the matrix cores then produce base-2 exponents directly.
+  const float c2 = p.scale * kLog2e;
   bf16x8 qf[4];
   {
     const uint16_t *qrow = Q + head + (size_t)min(iq, p.L - 1) * D;
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-      qf[kk] = __builtin_bit_cast(bf16x8, *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh));
+    for (int kk = 0; kk < 4; ++kk) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        qf[kk][2 * e] = (__bf16)(__uint_as_float(w[e] << 16) * c2);
+        qf[kk][2 * e + 1] = (__bf16)(__uint_as_float(w[e] & 0xFFFF0000u) * c2);
+      }
+    }
   }
 
+  if (!dense)
+    for (int c = tid; c < 2 * D; c += BLK * 2) gate_s[c] = gate_w[(size_t)h * 2 * D + c];
+
   // ---- tile list: window blocks J_lo..I, then the selection list up to its first -1 ----
+  // Every wavefront reads the whole selection row with one vector load per 64 entries and
+  // derives the counts from ballots (no chain of dependent scalar loads); the list itself is
+  // parked in LDS so that walking it never waits on the vector-memory counter, which also
+  // tracks the tile prefetches in flight.
   const int J_first = p0 / BLK;
-  const int *my_sel = dense ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
   int J_lo, n_st, n_all;
+  bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
   if (dense) {
     J_lo = J_first;
     n_st = 0;
     n_all = I - J_first + 1;
   } else {
+    const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
     const int lowpos = I * BLK - (p.w - 1);
     J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
     J_lo = max(J_lo, J_first);
     n_st = I - J_lo + 1;
+    if (wv == 0)
+      for (int t = lane; t < n_st; t += 64) tiles[t] = J_lo + t;
     int n_lt = 0;
-    while (n_lt < p.k) {
-      const int J = my_sel[n_lt];
-      if (J < 0 || J >= p.NB) break;
-      ++n_lt;
+    bool open = true;
+    for (int e0 = 0; e0 < p.k; e0 += 64) {
+      const int e = e0 + lane;
+      const int J = e < p.k ? my_sel[e] : -1;
+      const bool ok = J >= 0 && J < p.NB;
+      const unsigned long long okm = __ballot(ok);
+      const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);  // entries before the first -1
+      if (open) {
+        const bool mine = lane < lead;
+        if (wv == 0 && mine) tiles[n_st + e] = J;
+        // a full earlier block already brings a whole block of keys; only a partial first block may not
+        const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
+        if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
+        n_lt += lead;
+        open = lead == 64;
+      }
     }
     n_all = n_st + n_lt;
-  }
-  // The list lives in LDS so that walking it never waits on the vector-memory counter, which
-  // also tracks the tile prefetches in flight.
-  if (!dense) {
-    for (int t = tid; t < n_all; t += BLK * 2) tiles[t] = t < n_st ? J_lo + t : my_sel[t - n_st];
   }
   __syncthreads();
   auto tile_of = [&](int t) -> int {
@@ -171,12 +205,23 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   const int ld_row = 32 * wv + (lane >> 3);  // + 8*u
   const int ld_ck = ((lane & 7) ^ (lane >> 3)) * 8;
   const int ld_cv = ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8;
-  auto stage = [&](const uint16_t *src_head, uint16_t *dst_tile, int J, int col) {
+  const uint16_t *k_lane = Kh + ld_row * D + ld_ck;  // this lane's chunk inside block 0
+  const uint16_t *v_lane = Vh + ld_row * D + ld_cv;
+  const bool ragged = p.L % BLK != 0;
+  auto stage = [&](const uint16_t *src_lane, uint16_t *dst_tile, int J) {
+    if (!ragged || J != p.NB - 1) {
+      const uint16_t *src = src_lane + (size_t)J * TILE;  // lane pointer + uniform tile offset
 #pragma unroll
-    for (int u = 0; u < 4; ++u) {
-      const int row = min(J * BLK + ld_row + 8 * u, p.L - 1);
-      const uint16_t *src = src_head + (unsigned)(row * D + col);
-      __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+      for (int u = 0; u < 4; ++u)
+        __builtin_amdgcn_global_load_lds((glb_void *)(src + 8 * u * D),
+                                         (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+    } else {  // last, partial block: rows past the end are clamped (they are causally masked anyway)
+#pragma unroll
+      for (int u = 0; u < 4; ++u) {
+        const int over = max(0, J * BLK + ld_row + 8 * u - (p.L - 1));
+        const uint16_t *src = src_lane + (size_t)J * TILE + (8 * u - over) * D;
+        __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+      }
     }
   };
 
@@ -191,24 +236,13 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     voff[mb] = (4 * lh + (r16 >> 2)) * D +
                (((4 * mb + 2 * ((lane >> 4) & 1) + ((r16 & 3) >> 1)) ^ (2 * (r16 >> 2))) * 8) + 4 * (r16 & 1);
 
-  auto qk = [&](const uint16_t *ks, f32x16 (&sacc)[UNITS]) {
-#pragma unroll
-    for (int s = 0; s < UNITS; ++s) {
-#pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[s][i] = 0.0f;
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + 32 * s * D + koff[kk]);
-        sacc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[s], 0, 0, 0);
-      }
-    }
-  };
-
-  const float c2 = p.scale * kLog2e;
+  // Per-row softmax state.  m_ref: reference exponent (log2 units) the accumulators are relative
+  // to; fresh: nothing accumulated yet in this branch; l_run: this lane's part of the row sum.
   f32x16 oacc[2];
-  float m_run, l_run;
+  float m_ref = 0.0f, l_run;
+  bool fresh;
   auto reset = [&]() {
-    m_run = kNegInf;
+    fresh = true;
     l_run = 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.0f; oacc[1][i] = 0.0f; }
@@ -219,91 +253,149 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     const float inv = ok ? 1.0f / l_tot : 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; ++i) { oacc[0][i] *= inv; oacc[1][i] *= inv; }
-    return ok ? (m_run + __log2f(l_tot)) * kLn2 : 0.0f;
+    return ok ? (m_ref + __log2f(l_tot)) * kLn2 : 0.0f;
+  };
+  // exponents of one tile: sacc = c*K Q^T - m_ref
+  auto qk = [&](const uint16_t *ks, f32x16 (&sacc)[UNITS]) {
+    const float init = -m_ref;
+#pragma unroll
+    for (int s = 0; s < UNITS; ++s)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) sacc[s][i] = init;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int s = 0; s < UNITS; ++s) {
+        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + 32 * s * D + koff[kk]);
+        sacc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[s], 0, 0, 0);
+      }
   };
 
   // Rows that see only a few keys have large probabilities, and rounding those to bf16 would
   // leave a relative error of 2^-9 in the saved branch outputs, which backward amplifies
   // through D = dO_x.o_x.  Wavefronts that may hold such rows (fewer than kFewKeys keys) feed
   // P to the matrix cores as a two-term bf16 sum (hi + lo); everyone else uses one term.
-  constexpr int kFewKeys = 32;
   bool hp_st, hp_lt;
   if (dense) {
     hp_st = false;
     hp_lt = q0 - p0 + 1 < kFewKeys;
   } else {
     hp_st = p.w < kFewKeys || q0 - p0 + 1 < kFewKeys;
-    int past = 0;
-    for (int e = 0; e < n_all - n_st && past < kFewKeys; ++e) {
-      const int J = my_sel[e];
-      if (J < I) past += max(0, min((J + 1) * BLK, p.L) - max(J * BLK, p0));
-    }
-    hp_lt = past < kFewKeys;
+    hp_lt = lt_few;
   }
 
-  // softmax of tile J (logits in sacc) and O^T += V^T P^T; also issues the logits of the next tile
-  auto tile_body = [&](const uint16_t *vs, const uint16_t *ks_next, int J, bool windowed, f32x16 (&sacc)[UNITS],
-                       f32x16 (&snext)[UNITS]) {
-    const bool hp = __builtin_amdgcn_readfirstlane((int)(windowed ? hp_st : hp_lt)) != 0;
+  // ---- per-tile pieces ----
+  // prep: mask the exponents of tile J and move the row reference if needed (see file header).
+  auto prep = [&](int J, bool windowed, f32x16 (&sacc)[UNITS]) {
     if (windowed || J == I || J * BLK < p0) {
+      // visible <=> lo <= key <= iq with lo = max(p0, iq - w + 1); per lane this is one range
+      // test on the element's compile-time key offset
+      const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
+      const int base = J * BLK + 4 * lh;
+      const unsigned span = (unsigned)(iq - lo);  // wraps to huge when iq < lo: handled by q-validity below
+      const bool any = iq >= lo;
 #pragma unroll
       for (int s = 0; s < UNITS; ++s)
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
-          const int key = J * BLK + 32 * s + 8 * (i >> 2) + 4 * lh + (i & 3);
-          const bool vis = (key <= iq) & (key >= p0) & ((!windowed) | (iq - key < p.w));
+          const int key = base + 32 * s + 8 * (i >> 2) + (i & 3);
+          const bool vis = any & ((unsigned)(key - lo) <= span);
           sacc[s][i] = vis ? sacc[s][i] : kNegInf;
         }
     }
-    float mx = sacc[0][0];
+    float m4[4];
+#pragma unroll
+    for (int c = 0; c < 4; ++c) m4[c] = sacc[0][c];
 #pragma unroll
     for (int s = 0; s < UNITS; ++s)
 #pragma unroll
-      for (int i = 0; i < 16; ++i) mx = fmaxf(mx, sacc[s][i]);
-    mx = fmaxf(mx, __shfl_xor(mx, 32));
-    const float m_cand = mx * c2;
-    const bool upd = m_cand > m_run + kRaise;  // also true for the first visible key (m_run = -inf)
+      for (int i = (s == 0 ? 4 : 0); i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], sacc[s][i]);
+    float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
+    {  // other half of the row lives in lane^32
+      const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+    }
+    // move the reference: first visible key of the branch, or the tile maximum ran away upwards
+    const bool upd = fresh ? mx != kNegInf : mx > kRaise;
     if (__any(upd)) {
-      const float m_new = upd ? m_cand : m_run;
-      const float alpha = upd ? __builtin_amdgcn_exp2f(m_run - m_new) : 1.0f;
+      const float dlt = upd ? mx : 0.0f;
+      const float alpha = (upd && !fresh) ? __builtin_amdgcn_exp2f(-dlt) : 1.0f;
       l_run *= alpha;
 #pragma unroll
       for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
-      m_run = m_new;
+#pragma unroll
+      for (int s = 0; s < UNITS; ++s)
+#pragma unroll
+        for (int i = 0; i < 16; ++i) sacc[s][i] -= dlt;
+      m_ref += dlt;
+      fresh = fresh && !upd;
     }
-    const float m_use = m_run == kNegInf ? 0.0f : m_run;
+  };
 
-    // ---- one straight-line region: exponentials of this tile, logits of the next, P V ----
-    qk(ks_next, snext);
-    bf16x8 pf[UNITS][2];
-    const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
+  // exponentials of one 32-key unit: sacc <- p (fp32), pf <- bf16(p), l_run += sum of bf16(p)
+  auto expo = [&](f32x16 &sacc, bf16x8 (&pf)[2]) {
 #pragma unroll
-    for (int s = 0; s < UNITS; ++s) {
-#pragma unroll
-      for (int i = 0; i < 16; i += 2) {
-        const float pa = __builtin_amdgcn_exp2f(fmaf(sacc[s][i], c2, -m_use));
-        const float pb = __builtin_amdgcn_exp2f(fmaf(sacc[s][i + 1], c2, -m_use));
-        sacc[s][i] = pa;
-        sacc[s][i + 1] = pb;
-        const bf16x2 pk = {(__bf16)pa, (__bf16)pb};
-        pf[s][i >> 3][i & 7] = pk[0];
-        pf[s][i >> 3][(i & 7) + 1] = pk[1];
-        l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);  // sums what the MFMA will see
-      }
+    for (int i = 0; i < 16; i += 2) {
+      const float pa = __builtin_amdgcn_exp2f(sacc[i]);
+      const float pb = __builtin_amdgcn_exp2f(sacc[i + 1]);
+      sacc[i] = pa;
+      sacc[i + 1] = pb;
+      const bf16x2 pk = {(__bf16)pa, (__bf16)pb};
+      pf[i >> 3][i & 7] = pk[0];
+      pf[i >> 3][(i & 7) + 1] = pk[1];
+      l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);  // sums what the MFMA will see
     }
+  };
+  // V^T operands of one unit: [t][mb], keys in accumulator order
+  auto load_v = [&](const uint16_t *vs, int s, bf16x8 (&vf)[2][2]) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb) {
+        const uint16_t *a0 = vs + (32 * s + 16 * t) * D + voff[mb];
+        const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
+        const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * D));
+        vf[t][mb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
+      }
+  };
+  auto pv = [&](const bf16x8 (&vf)[2][2], const bf16x8 (&pf)[2]) {
+#pragma unroll
+    for (int t = 0; t < 2; ++t)
+#pragma unroll
+      for (int mb = 0; mb < 2; ++mb)
+        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][mb], pf[t], oacc[mb], 0, 0, 0);
+  };
+
+  // One tile: logits of the next tile (K from ks_next), exponentials of this one and P V.
+  auto tile_body = [&](const uint16_t *vs, const uint16_t *ks_next, bool windowed,
+                       f32x16 (&sacc)[UNITS], f32x16 (&snext)[UNITS]) {
+    const bool hp = __builtin_amdgcn_readfirstlane((int)(windowed ? hp_st : hp_lt)) != 0;
+    bf16x8 kf[UNITS][4];
 #pragma unroll
     for (int s = 0; s < UNITS; ++s)
 #pragma unroll
-      for (int t = 0; t < 2; ++t)
+      for (int kk = 0; kk < 4; ++kk)
+        kf[s][kk] = *reinterpret_cast<const bf16x8 *>(ks_next + 32 * s * D + koff[kk]);
+    bf16x8 vf[2][2];
+    load_v(vs, 0, vf);
+    const float init = -m_ref;
 #pragma unroll
-        for (int mb = 0; mb < 2; ++mb) {
-          const uint16_t *a0 = vs + (32 * s + 16 * t) * D + voff[mb];
-          const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
-          const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * D));
-          const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-          oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pf[s][t],
-                                                             oacc[mb], 0, 0, 0);
-        }
+    for (int s = 0; s < UNITS; ++s)
+#pragma unroll
+      for (int i = 0; i < 16; ++i) snext[s][i] = init;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+      for (int s = 0; s < UNITS; ++s)
+        snext[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s][kk], qf[kk], snext[s], 0, 0, 0);
+    bf16x8 pf[UNITS][2];
+#pragma unroll
+    for (int s = 0; s < UNITS; ++s) {
+      expo(sacc[s], pf[s]);
+      pv(vf, pf[s]);
+      if (s + 1 < UNITS) load_v(vs, s + 1, vf);
+    }
     if (hp) {  // second bf16 term of P
 #pragma unroll
       for (int s = 0; s < UNITS; ++s) {
@@ -316,17 +408,8 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
           pl[i >> 3][(i & 7) + 1] = pk[1];
           l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
         }
-#pragma unroll
-        for (int t = 0; t < 2; ++t)
-#pragma unroll
-          for (int mb = 0; mb < 2; ++mb) {
-            const uint16_t *a0 = vs + (32 * s + 16 * t) * D + voff[mb];
-            const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
-            const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * D));
-            const s16x8 both = __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7);
-            oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, both), pl[t],
-                                                               oacc[mb], 0, 0, 0);
-          }
+        load_v(vs, s, vf);
+        pv(vf, pl);
       }
     }
   };
@@ -337,26 +420,31 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   bool st_open = !dense;
   reset();
   f32x16 sA[UNITS], sB[UNITS];
-  stage(Kh, Ks0, tile_of(0), ld_ck);
-  stage(Vh, Vs0, tile_of(0), ld_cv);
-  if (n_all > 1) stage(Kh, Ks1, tile_of(1), ld_ck);
+  stage(k_lane, Ks0, tile_of(0));
+  stage(v_lane, Vs0, tile_of(0));
+  if (n_all > 1) stage(k_lane, Ks1, tile_of(1));
   __syncthreads();
   qk(Ks0, sA);
   __syncthreads();  // Ks0 may be overwritten from here on
+  auto close_st = [&]() {
+    lse_st = finish();
+    ost[0] = oacc[0];
+    ost[1] = oacc[1];
+    reset();
+    st_open = false;
+  };
+  if (st_open && n_st == 0) close_st();
+  prep(tile_of(0), 0 < n_st, sA);
 
-  // step t: prefetch K(t+2) and V(t+1), compute tile t from its logits and V(t), issue logits of t+1
+  // step t: prefetch K(t+2) and V(t+1); exponentials and P V of tile t; logits, mask and
+  // maximum of tile t+1 (the latter overlap the last P V products)
   auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *v_cur, const uint16_t *k_next,
                   f32x16 (&scur)[UNITS], f32x16 (&snext)[UNITS]) {
-    if (t + 2 < n_all) stage(Kh, k_fill, tile_of(t + 2), ld_ck);
-    if (t + 1 < n_all) stage(Vh, v_fill, tile_of(t + 1), ld_cv);
-    if (st_open && t >= n_st) {  // the window tiles are done: close the short-term branch
-      lse_st = finish();
-      ost[0] = oacc[0];
-      ost[1] = oacc[1];
-      reset();
-      st_open = false;
-    }
-    tile_body(v_cur, k_next, tile_of(t), t < n_st, scur, snext);
+    if (t + 2 < n_all) stage(k_lane, k_fill, tile_of(t + 2));
+    if (t + 1 < n_all) stage(v_lane, v_fill, tile_of(t + 1));
+    tile_body(v_cur, k_next, t < n_st, scur, snext);
+    if (st_open && t + 1 >= n_st) close_st();  // the window tiles are done: close the short-term branch
+    if (t + 1 < n_all) prep(tile_of(t + 1), t + 1 < n_st, snext);
     __syncthreads();
   };
   for (int t = 0; t < n_all; t += 2) {
@@ -389,8 +477,8 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     if (lh == 0 && lse_lt_out) lse_lt_out[lrow] = lse_lt;
     return;
   }
-  const float *wl = gate_w + (size_t)h * 2 * D;
-  const float *ws = wl + D;
+  const float *wl = gate_s;
+  const float *ws = gate_s + D;
   float z = 0.0f;
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
