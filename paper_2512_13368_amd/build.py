@@ -19,6 +19,7 @@ SOURCES = {
     # accumulators of the matrix instructions stay in VGPRs: the online softmax rescales them
     # with VALU instructions, and AGPR placement costs a register copy per element per tile
     "mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

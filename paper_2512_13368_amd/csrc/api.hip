@@ -33,20 +33,20 @@ int check_params(const blossom_params *p, KParams *kp)
   return BLOSSOM_OK;
 }
 
-size_t ws_bytes_for(const KParams &kp, int which)
+size_t ws_bytes_for(const KParams &kp, int dtype, int which)
 {
   switch (which) {
     case BLOSSOM_WS_SELECT: return select_workspace_bytes(kp);
     case BLOSSOM_WS_FWD: return 0;
-    case BLOSSOM_WS_BWD: return bwd_workspace_bytes(kp);
+    case BLOSSOM_WS_BWD: return bwd_workspace_bytes(kp, dtype);
     case BLOSSOM_WS_DENSE: return 0;
     default: return 0;
   }
 }
 
-int check_ws(const KParams &kp, int which, const void *ws, size_t ws_bytes)
+int check_ws(const KParams &kp, int dtype, int which, const void *ws, size_t ws_bytes)
 {
-  const size_t need = ws_bytes_for(kp, which);
+  const size_t need = ws_bytes_for(kp, dtype, which);
   if (need == 0) return BLOSSOM_OK;
   if (!ws || ws_bytes < need) return BLOSSOM_ERR_WORKSPACE;
   if (!aligned16(ws)) return BLOSSOM_ERR_ALIGN;
@@ -66,7 +66,7 @@ size_t blossom_workspace_bytes(const blossom_params *p, int which)
 {
   KParams kp;
   if (check_params(p, &kp) != BLOSSOM_OK) return 0;
-  return ws_bytes_for(kp, which);
+  return ws_bytes_for(kp, p->dtype, which);
 }
 
 int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
@@ -78,7 +78,7 @@ int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
   if (rc) return rc;
   if (!Q || !K || !valid_len || !sel) return BLOSSOM_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K)) return BLOSSOM_ERR_ALIGN;
-  rc = check_ws(kp, BLOSSOM_WS_SELECT, ws, ws_bytes);
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
   if (rc) return rc;
   launch_select(kp, p->dtype, Q, K, valid_len, sel, ws, (hipStream_t)hip_stream);
   return launch_status();
@@ -96,7 +96,7 @@ int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, cons
   if (p->save_for_bwd && (!o_lt || !o_st || !lse_lt || !lse_st)) return BLOSSOM_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return BLOSSOM_ERR_ALIGN;
   if (p->save_for_bwd && (!aligned16(o_lt) || !aligned16(o_st))) return BLOSSOM_ERR_ALIGN;
-  rc = check_ws(kp, BLOSSOM_WS_FWD, ws, ws_bytes);
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_FWD, ws, ws_bytes);
   if (rc) return rc;
   FwdArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.sel = sel;
@@ -125,14 +125,14 @@ int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, cons
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(o_lt) || !aligned16(o_st) ||
       !aligned16(dO) || !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
     return BLOSSOM_ERR_ALIGN;
-  rc = check_ws(kp, BLOSSOM_WS_BWD, ws, ws_bytes);
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_BWD, ws, ws_bytes);
   if (rc) return rc;
   BwdArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.sel = sel;
   a.gate_w = gate_w; a.gate_b = gate_b; a.o_lt = o_lt; a.o_st = o_st;
   a.lse_lt = lse_lt; a.lse_st = lse_st; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV;
   a.d_gate_w = d_gate_w; a.d_gate_b = d_gate_b; a.ws = ws;
-  launch_bwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
+  launch_bwd(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();
 }
 
@@ -149,7 +149,7 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
   if (rc) return rc;
   if (!Q || !K || !V || !valid_len || !O) return BLOSSOM_ERR_NULL;
   if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return BLOSSOM_ERR_ALIGN;
-  rc = check_ws(kp, BLOSSOM_WS_DENSE, ws, ws_bytes);
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_DENSE, ws, ws_bytes);
   if (rc) return rc;
   FwdArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.O = O; a.lse_lt = lse;

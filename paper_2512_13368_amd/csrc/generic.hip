@@ -253,7 +253,10 @@ __global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const float *__rest
                                                              const float *__restrict__ gate_w,
                                                              const float *__restrict__ gate_b,
                                                              float4 *__restrict__ rowstat,
-                                                             float *__restrict__ partial, KParams p)
+                                                             float *__restrict__ partial,
+                                                             const T *__restrict__ V,
+                                                             float4 *__restrict__ rowB,
+                                                             float2 *__restrict__ rowC, KParams p)
 {
   __shared__ float dz_s[kPrepRows];
   const int t = threadIdx.x;
@@ -270,6 +273,8 @@ __global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const float *__rest
   float dz = 0.0f;
   if (i < p.L) {
     float4 st = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    float4 rb = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
+    float2 rc = make_float2(0.0f, 0.0f);
     if (i >= p0) {
       float a_ll = 0.0f, a_ss = 0.0f, w_l = 0.0f, w_s = 0.0f;
       for (int c = 0; c < D; c += 4) {
@@ -292,8 +297,26 @@ __global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const float *__rest
       st.y = dz;
       st.z = alpha * a_ll + dz * w_l;           // D_lt = dO_lt . o_lt
       st.w = (1.0f - alpha) * a_ss + dz * w_s;  // D_st = dO_st . o_st
+      rb = make_float4(a_ll, a_ss, w_l, w_s);   // dO.o_lt, dO.o_st, Wg_lt.o_lt, Wg_st.o_st
+      if (rowC) {                               // Wg_lt.v_i, Wg_st.v_i
+        float v_l = 0.0f, v_s = 0.0f;
+        for (int c = 0; c < D; c += 4) {
+          float v[4];
+          load4(V + head + (size_t)i * D + c, v);
+#pragma unroll
+          for (int e = 0; e < 4; ++e) {
+            v_l = fmaf(wl[c + e], v[e], v_l);
+            v_s = fmaf(ws[c + e], v[e], v_s);
+          }
+        }
+        rc = make_float2(v_l, v_s);
+      }
     }
     rowstat[(size_t)bh * p.L + i] = st;
+    if (rowB) {
+      rowB[(size_t)bh * p.L + i] = rb;
+      rowC[(size_t)bh * p.L + i] = rc;
+    }
   }
   dz_s[t] = dz;
   __syncthreads();
@@ -646,61 +669,68 @@ void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream
 
 namespace {
 inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
-
-struct BwdWs {
-  size_t rowstat, offs, items, partial, total;
-  int nchunk;
-};
-
-BwdWs bwd_layout(const KParams &p)
-{
-  BwdWs w;
-  const size_t BH = (size_t)p.B * p.H;
-  w.nchunk = (p.L + kPrepRows - 1) / kPrepRows;
-  w.rowstat = 0;
-  w.offs = align256(w.rowstat + BH * p.L * sizeof(float4));
-  w.items = align256(w.offs + BH * (p.NB + 1) * sizeof(int));
-  w.partial = align256(w.items + BH * p.NB * p.k * sizeof(int));
-  w.total = align256(w.partial + BH * w.nchunk * (2 * p.d + 1) * sizeof(float));
-  return w;
-}
 }  // namespace
 
-size_t bwd_workspace_bytes(const KParams &p) { return bwd_layout(p).total; }
+BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws)
+{
+  BwdWorkspace w{};
+  char *base = reinterpret_cast<char *>(ws);
+  const size_t BH = (size_t)p.B * p.H;
+  w.nchunk = (p.L + kPrepRows - 1) / kPrepRows;
+  size_t off = 0;
+  w.rowstat = reinterpret_cast<float4 *>(base + off);
+  off = align256(off + BH * p.L * sizeof(float4));
+  w.offs = reinterpret_cast<int *>(base + off);
+  off = align256(off + BH * (p.NB + 1) * sizeof(int));
+  w.items = reinterpret_cast<int *>(base + off);
+  off = align256(off + BH * p.NB * p.k * sizeof(int));
+  w.partial = reinterpret_cast<float *>(base + off);
+  off = align256(off + BH * w.nchunk * (2 * p.d + 1) * sizeof(float));
+  if (bwd_mfma_supported(p, dtype)) {
+    w.rowB = reinterpret_cast<float4 *>(base + off);
+    off = align256(off + BH * p.L * sizeof(float4));
+    w.rowC = reinterpret_cast<float2 *>(base + off);
+    off = align256(off + BH * p.L * sizeof(float2));
+  }
+  w.total = off;
+  return w;
+}
+
+size_t bwd_workspace_bytes(const KParams &p, int dtype) { return bwd_carve(p, dtype, nullptr).total; }
 
 template <typename T, int D>
-static void launch_bwd_t(const KParams &p, const BwdArgs &a, hipStream_t st)
+static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st)
 {
-  const BwdWs w = bwd_layout(p);
-  char *ws = reinterpret_cast<char *>(a.ws);
-  float4 *rowstat = reinterpret_cast<float4 *>(ws + w.rowstat);
-  int *offs = reinterpret_cast<int *>(ws + w.offs);
-  int *items = reinterpret_cast<int *>(ws + w.items);
-  float *partial = reinterpret_cast<float *>(ws + w.partial);
+  const BwdWorkspace w = bwd_carve(p, dtype, a.ws);
   const unsigned BH = (unsigned)(p.B * p.H);
+  const bool mfma = bwd_mfma_supported(p, dtype);
 
   hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(kPrepRows), 0, st,
                      (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
-                     a.gate_b, rowstat, partial, p);
-  hipLaunchKernelGGL(bwd_gate_reduce_kernel, dim3((unsigned)p.H), dim3(256), 0, st, partial, a.d_gate_w,
+                     a.gate_b, w.rowstat, w.partial, (const T *)a.V, w.rowB, w.rowC, p);
+  hipLaunchKernelGGL(bwd_gate_reduce_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.partial, a.d_gate_w,
                      a.d_gate_b, w.nchunk, p);
-  hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(256), 0, st, a.sel, offs, items, p);
+  hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(256), 0, st, a.sel, w.offs, w.items, p);
+  if (mfma) {
+    launch_bwd_mfma(p, a, w, st);
+    return;
+  }
   hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64), 0, st, (const T *)a.Q,
                      (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st,
-                     (const T *)a.dO, rowstat, (T *)a.dQ, p);
+                     (const T *)a.dO, w.rowstat, (T *)a.dQ, p);
   hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D>), dim3(BH * p.NB, 2), dim3(64), 0, st, (const T *)a.Q,
                      (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
-                     (const T *)a.dO, rowstat, offs, items, (T *)a.dK, (T *)a.dV, p);
+                     (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
 }
 
-void launch_bwd_generic(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st)
+void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st)
 {
   if (dtype == 0) {
-    if (p.d == 32) launch_bwd_t<float, 32>(p, a, st);
-    else launch_bwd_t<float, 64>(p, a, st);
+    if (p.d == 32) launch_bwd_t<float, 32>(p, dtype, a, st);
+    else launch_bwd_t<float, 64>(p, dtype, a, st);
   } else {
-    if (p.d == 32) launch_bwd_t<bf16_t, 32>(p, a, st);
-    else launch_bwd_t<bf16_t, 64>(p, a, st);
+    if (p.d == 32) launch_bwd_t<bf16_t, 32>(p, dtype, a, st);
+    else launch_bwd_t<bf16_t, 64>(p, dtype, a, st);
   }
 }
 

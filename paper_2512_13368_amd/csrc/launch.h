@@ -39,13 +39,30 @@ size_t select_workspace_bytes(const KParams &p);
 void launch_select(const KParams &p, int dtype, const void *Q, const void *K, const int *valid_len,
                    int *sel, void *ws, hipStream_t st);
 
+// Backward workspace, carved from the caller's buffer.
+struct BwdWorkspace {
+  float4 *rowstat;   // [B*H*L] (alpha, dz, D_lt, D_st)
+  int *offs;         // [B*H,(NB+1)] inverse selection list: offsets
+  int *items;        // [B*H,NB*k]   inverse selection list: query blocks, ascending per key block
+  float *partial;    // [B*H*nchunk,(2d+1)] partial gate-weight gradients
+  float4 *rowB;      // [B*H*L] (dO.o_lt, dO.o_st, Wg_lt.o_lt, Wg_st.o_st), matrix-core path only
+  float2 *rowC;      // [B*H*L] (Wg_lt.v, Wg_st.v), matrix-core path only
+  int nchunk;
+  size_t total;
+};
+
 // generic.hip: scalar-ALU kernels for every supported (dtype, d, b)
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
-size_t bwd_workspace_bytes(const KParams &p);
-void launch_bwd_generic(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st);
+BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws);
+size_t bwd_workspace_bytes(const KParams &p, int dtype);
+void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st);
 
 // mfma_fwd.hip: matrix-core forward for bf16, d = 64, b in {32, 64}
 bool fwd_mfma_supported(const KParams &p, int dtype);
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st);
+
+// mfma_bwd.hip: matrix-core dQ and dK/dV for bf16, d = 64, b in {32, 64}
+bool bwd_mfma_supported(const KParams &p, int dtype);
+void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, hipStream_t st);
 
 }  // namespace blossom

@@ -1,0 +1,50 @@
+// Types and small helpers shared by the matrix-core kernels (bf16, d = 64, gfx950).
+#pragma once
+
+#include "common.h"
+
+namespace blossom {
+namespace mfma {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+typedef short s16x4 __attribute__((ext_vector_type(4)));
+typedef short s16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x16 __attribute__((ext_vector_type(16)));
+typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+
+typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
+typedef __attribute__((address_space(3))) void lds_void;
+typedef const __attribute__((address_space(1))) void glb_void;
+
+constexpr int D = 64;
+constexpr float kLog2e = 1.4426950408889634f;
+constexpr float kLn2 = 0.6931471805599453f;
+constexpr float kNegInf = -__builtin_huge_valf();
+
+// Maps the hardware workgroup id (dealt round-robin over the 8 XCDs) to a virtual id such that
+// each XCD works through a contiguous range: all blocks of a head then share one L2.
+__device__ __forceinline__ unsigned xcd_remap(unsigned pid, unsigned total)
+{
+  constexpr unsigned X = 8;
+  const unsigned per = (total + X - 1) / X;  // ids of a "tall" XCD
+  const unsigned tall = total % X ? total % X : X;
+  const unsigned xcd = pid % X, local = pid / X;
+  return xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
+}
+
+// A staged tile is BLK rows of 128 bytes; 16-byte chunk c of row r sits at chunk position
+// c ^ swz(r).  This swizzle serves both operand read patterns without bank conflicts:
+//  - row-per-lane 16-byte reads (8 consecutive rows, one chunk column): swz is a bijection of
+//    r mod 8, so the 8 lanes of a 128-byte LDS cycle hit 8 distinct positions;
+//  - transposing 8-byte reads (4 consecutive rows r0..r0+3, r0 % 4 == 0, two adjacent chunk
+//    columns c0, c0+1 with c0 even): positions (c0 ^ swz) and (c0 ^ swz ^ 1) over the four rows
+//    are 8 distinct values because swz(r) = 2*(r%4) + (r/4)%2 differs in bits 1-2 between rows.
+__device__ __forceinline__ int swz(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+
+// bf16 pair -> two floats and back (round to nearest even through the hardware conversion)
+__device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
+__device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
+
+}  // namespace mfma
+}  // namespace blossom
