@@ -241,115 +241,158 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
 
 // =============================================================================================
 // Backward, step 1: gate backward per row + per-chunk partial gate-weight gradients.
-//   rowstat[row] = (alpha, dz, D_lt, D_st);  partial[(bh*nchunk+chunk)][0..2D] (2D = bias)
+//   rowstat[row] = (alpha, dz, D_lt, D_st)
+//   rowB[row]    = (dO.o_lt, dO.o_st, Wg_lt.o_lt, Wg_st.o_st)      (matrix-core path)
+//   rowC[row]    = (Wg_lt.v, Wg_st.v)                               (matrix-core path)
+//   partial[(bh*nchunk+chunk)][0..2D] (2D = bias)
+// D/4 lanes share a row (16-byte loads, whole rows coalesced), several rows per wavefront step;
+// every tensor is read exactly once; the row sums are xor-shuffle reductions over the lanes of
+// a row, the gate-weight partials accumulate in registers and meet in LDS in a fixed order.
 // =============================================================================================
 constexpr int kPrepRows = 128;
 
 template <typename T, int D>
-__global__ __launch_bounds__(kPrepRows) void bwd_prep_kernel(const float *__restrict__ o_lt,
-                                                             const float *__restrict__ o_st,
-                                                             const T *__restrict__ dO,
-                                                             const int *__restrict__ valid_len,
-                                                             const float *__restrict__ gate_w,
-                                                             const float *__restrict__ gate_b,
-                                                             float4 *__restrict__ rowstat,
-                                                             float *__restrict__ partial,
-                                                             const T *__restrict__ V,
-                                                             float4 *__restrict__ rowB,
-                                                             float2 *__restrict__ rowC, KParams p)
+__global__ __launch_bounds__(256) void bwd_prep_kernel(const float *__restrict__ o_lt,
+                                                       const float *__restrict__ o_st,
+                                                       const T *__restrict__ dO,
+                                                       const int *__restrict__ valid_len,
+                                                       const float *__restrict__ gate_w,
+                                                       const float *__restrict__ gate_b,
+                                                       float4 *__restrict__ rowstat,
+                                                       float *__restrict__ partial,
+                                                       const T *__restrict__ V,
+                                                       float4 *__restrict__ rowB,
+                                                       float2 *__restrict__ rowC, KParams p)
 {
-  __shared__ float dz_s[kPrepRows];
+  constexpr int LPR = D / 4;        // lanes per row
+  constexpr int RPW = 64 / LPR;     // rows per wavefront step
+  constexpr int RPS = 4 * RPW;      // rows per workgroup step
+  constexpr int G = 2 * D + 1;
+  __shared__ float red[4 * RPW][G];
   const int t = threadIdx.x;
+  const int wave = t >> 6, lane = t & 63;
+  const int sub = lane % LPR, rg = lane / LPR;
+  const int c4 = sub * 4;
   const int nchunk = (p.L + kPrepRows - 1) / kPrepRows;
   const int bh = blockIdx.x / nchunk;
   const int chunk = blockIdx.x % nchunk;
   const int h = bh % p.H;
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
-  const int i = chunk * kPrepRows + t;
   const size_t head = (size_t)bh * p.L * D;
-  const float *wl = gate_w + (size_t)h * 2 * D;
-  const float *ws = wl + D;
-  float dz = 0.0f;
-  if (i < p.L) {
-    float4 st = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    float4 rb = make_float4(0.0f, 0.0f, 0.0f, 0.0f);
-    float2 rc = make_float2(0.0f, 0.0f);
-    if (i >= p0) {
-      float a_ll = 0.0f, a_ss = 0.0f, w_l = 0.0f, w_s = 0.0f;
-      for (int c = 0; c < D; c += 4) {
-        float g[4], ol[4], os[4];
-        load4(dO + head + (size_t)i * D + c, g);
-        load4(o_lt + head + (size_t)i * D + c, ol);
-        load4(o_st + head + (size_t)i * D + c, os);
+  float wl[4], ws[4];
+  load4(gate_w + (size_t)h * 2 * D + c4, wl);
+  load4(gate_w + (size_t)h * 2 * D + D + c4, ws);
+  const float bias = gate_b ? gate_b[h] : 0.0f;
+  float acc_l[4] = {0.0f, 0.0f, 0.0f, 0.0f}, acc_s[4] = {0.0f, 0.0f, 0.0f, 0.0f}, acc_b = 0.0f;
+
+  for (int base = 0; base < kPrepRows; base += RPS) {
+    const int i = chunk * kPrepRows + base + wave * RPW + rg;
+    const bool inb = i < p.L;
+    const bool valid = inb && i >= p0;
+    float g[4] = {0.f, 0.f, 0.f, 0.f}, ol[4] = {0.f, 0.f, 0.f, 0.f}, os[4] = {0.f, 0.f, 0.f, 0.f};
+    float v[4] = {0.f, 0.f, 0.f, 0.f};
+    if (valid) {
+      const size_t ro = head + (size_t)i * D + c4;
+      load4(dO + ro, g);
+      load4(o_lt + ro, ol);
+      load4(o_st + ro, os);
+      if (rowC) load4(V + ro, v);
+    }
+    float a_ll = 0.f, a_ss = 0.f, w_l = 0.f, w_s = 0.f, v_l = 0.f, v_s = 0.f;
 #pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          a_ll = fmaf(g[e], ol[e], a_ll);
-          a_ss = fmaf(g[e], os[e], a_ss);
-          w_l = fmaf(wl[c + e], ol[e], w_l);
-          w_s = fmaf(ws[c + e], os[e], w_s);
-        }
-      }
-      const float z = (gate_b ? gate_b[h] : 0.0f) + w_l + w_s;
+    for (int e = 0; e < 4; ++e) {
+      a_ll = fmaf(g[e], ol[e], a_ll);
+      a_ss = fmaf(g[e], os[e], a_ss);
+      w_l = fmaf(wl[e], ol[e], w_l);
+      w_s = fmaf(ws[e], os[e], w_s);
+      v_l = fmaf(wl[e], v[e], v_l);
+      v_s = fmaf(ws[e], v[e], v_s);
+    }
+#pragma unroll
+    for (int off = 1; off < LPR; off <<= 1) {
+      a_ll += __shfl_xor(a_ll, off);
+      a_ss += __shfl_xor(a_ss, off);
+      w_l += __shfl_xor(w_l, off);
+      w_s += __shfl_xor(w_s, off);
+      v_l += __shfl_xor(v_l, off);
+      v_s += __shfl_xor(v_s, off);
+    }
+    float4 st = make_float4(0.f, 0.f, 0.f, 0.f);
+    float4 rb = make_float4(0.f, 0.f, 0.f, 0.f);
+    float2 rc = make_float2(0.f, 0.f);
+    float dz = 0.0f;
+    if (valid) {
+      const float z = bias + w_l + w_s;
       const float alpha = 1.0f / (1.0f + __expf(-z));
       dz = (a_ll - a_ss) * alpha * (1.0f - alpha);
-      st.x = alpha;
-      st.y = dz;
-      st.z = alpha * a_ll + dz * w_l;           // D_lt = dO_lt . o_lt
-      st.w = (1.0f - alpha) * a_ss + dz * w_s;  // D_st = dO_st . o_st
-      rb = make_float4(a_ll, a_ss, w_l, w_s);   // dO.o_lt, dO.o_st, Wg_lt.o_lt, Wg_st.o_st
-      if (rowC) {                               // Wg_lt.v_i, Wg_st.v_i
-        float v_l = 0.0f, v_s = 0.0f;
-        for (int c = 0; c < D; c += 4) {
-          float v[4];
-          load4(V + head + (size_t)i * D + c, v);
-#pragma unroll
-          for (int e = 0; e < 4; ++e) {
-            v_l = fmaf(wl[c + e], v[e], v_l);
-            v_s = fmaf(ws[c + e], v[e], v_s);
-          }
-        }
-        rc = make_float2(v_l, v_s);
+      st = make_float4(alpha, dz, alpha * a_ll + dz * w_l, (1.0f - alpha) * a_ss + dz * w_s);
+      rb = make_float4(a_ll, a_ss, w_l, w_s);
+      rc = make_float2(v_l, v_s);
+    }
+    if (inb && sub == 0) {
+      rowstat[(size_t)bh * p.L + i] = st;
+      if (rowB) {
+        rowB[(size_t)bh * p.L + i] = rb;
+        rowC[(size_t)bh * p.L + i] = rc;
       }
     }
-    rowstat[(size_t)bh * p.L + i] = st;
-    if (rowB) {
-      rowB[(size_t)bh * p.L + i] = rb;
-      rowC[(size_t)bh * p.L + i] = rc;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      acc_l[e] = fmaf(dz, ol[e], acc_l[e]);
+      acc_s[e] = fmaf(dz, os[e], acc_s[e]);
     }
+    acc_b += dz;
   }
-  dz_s[t] = dz;
+  const int slot = wave * RPW + rg;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    red[slot][c4 + e] = acc_l[e];
+    red[slot][D + c4 + e] = acc_s[e];
+  }
+  if (sub == 0) red[slot][2 * D] = acc_b;
   __syncthreads();
-  const int r_lo = max(chunk * kPrepRows, p0);
-  const int r_hi = min((chunk + 1) * kPrepRows, p.L);
-  float *out = partial + (size_t)blockIdx.x * (2 * D + 1);
-  for (int c = t; c < 2 * D; c += kPrepRows) {
-    const float *src = (c < D ? o_lt : o_st) + head + (c < D ? c : c - D);
+  float *out = partial + (size_t)blockIdx.x * G;
+  for (int c = t; c < G; c += 256) {
     float acc = 0.0f;
-    for (int r = r_lo; r < r_hi; ++r)
-      acc = fmaf(dz_s[r - chunk * kPrepRows], src[(size_t)r * D], acc);
+#pragma unroll
+    for (int sl = 0; sl < 4 * RPW; ++sl) acc += red[sl][c];
     out[c] = acc;
-  }
-  if (t == 0) {
-    float acc = 0.0f;
-    for (int r = r_lo; r < r_hi; ++r) acc += dz_s[r - chunk * kPrepRows];
-    out[2 * D] = acc;
   }
 }
 
-// Fixed-order reduction of the partial gate gradients over rows of the batch and chunks.
-__global__ __launch_bounds__(256) void bwd_gate_reduce_kernel(const float *__restrict__ partial,
-                                                              float *__restrict__ d_gate_w,
-                                                              float *__restrict__ d_gate_b, int nchunk,
-                                                              KParams p)
+// Fixed-order reduction of the partial gate gradients over batch rows and chunks, two levels:
+// level 1 sums kGateSlices contiguous slices of a head's partials, level 2 sums the slices.
+constexpr int kGateSlices = 32;
+
+__global__ __launch_bounds__(256) void bwd_gate_reduce1_kernel(const float *__restrict__ partial,
+                                                               float *__restrict__ stage2, int nchunk, KParams p)
+{
+  const int h = blockIdx.x;
+  const int sl = blockIdx.y;
+  const int G = 2 * p.d + 1;
+  const int N = p.B * nchunk;  // partial rows of this head, ordered by (batch row, chunk)
+  const int per = (N + kGateSlices - 1) / kGateSlices;
+  const int lo = sl * per, hi = min(N, lo + per);
+  for (int c = threadIdx.x; c < G; c += blockDim.x) {
+    float acc = 0.0f;
+    for (int nn = lo; nn < hi; ++nn) {
+      const int r = nn / nchunk, ch = nn % nchunk;
+      acc += partial[(((size_t)r * p.H + h) * nchunk + ch) * G + c];
+    }
+    stage2[((size_t)h * kGateSlices + sl) * G + c] = acc;
+  }
+}
+
+__global__ __launch_bounds__(256) void bwd_gate_reduce2_kernel(const float *__restrict__ stage2,
+                                                               float *__restrict__ d_gate_w,
+                                                               float *__restrict__ d_gate_b, KParams p)
 {
   const int h = blockIdx.x;
   const int G = 2 * p.d + 1;
   for (int c = threadIdx.x; c < G; c += blockDim.x) {
     float acc = 0.0f;
-    for (int r = 0; r < p.B; ++r)
-      for (int ch = 0; ch < nchunk; ++ch)
-        acc += partial[(((size_t)r * p.H + h) * nchunk + ch) * G + c];
+    for (int sl = 0; sl < kGateSlices; ++sl) acc += stage2[((size_t)h * kGateSlices + sl) * G + c];
     if (c < 2 * p.d) d_gate_w[(size_t)h * 2 * p.d + c] = acc;
     else if (d_gate_b) d_gate_b[h] = acc;
   }
@@ -469,40 +512,58 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
 // =============================================================================================
 // Backward, step 3: inverse selection list.  For each key block J of a (row, head): the
 // ascending list of query blocks I whose selection holds J.  offs [B*H,(NB+1)], items [B*H,NB*k].
+// One wavefront per (row, head).  Counting and filling use LDS integer atomics, one selection
+// row per wavefront instruction: a row lists distinct blocks, and the LDS executes one
+// wavefront's instructions in order, so each list comes out ascending in I and the result is
+// deterministic.
 // =============================================================================================
 constexpr int kMaxNBInv = 4096;
 
-__global__ __launch_bounds__(256) void inverse_list_kernel(const int *__restrict__ sel, int *__restrict__ offs,
-                                                           int *__restrict__ items, KParams p)
+__global__ __launch_bounds__(64) void inverse_list_kernel(const int *__restrict__ sel, int *__restrict__ offs,
+                                                          int *__restrict__ items, KParams p)
 {
-  __shared__ int cnt[kMaxNBInv + 1];
+  __shared__ int cnt[kMaxNBInv + 64];
+  const int lane = threadIdx.x;
   const int bh = blockIdx.x;
   const int *s = sel + (size_t)bh * p.NB * p.k;
-  for (int J = threadIdx.x; J < p.NB; J += blockDim.x) {
-    int c = 0;
-    for (int I = J; I < p.NB; ++I)
-      for (int e = 0; e < p.k; ++e) c += (s[(size_t)I * p.k + e] == J) ? 1 : 0;
-    cnt[J] = c;
-  }
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    int run = 0;
-    for (int J = 0; J < p.NB; ++J) {
-      const int c = cnt[J];
-      cnt[J] = run;
-      run += c;
-    }
-    cnt[p.NB] = run;
-  }
-  __syncthreads();
   int *o = offs + (size_t)bh * (p.NB + 1);
   int *it = items + (size_t)bh * p.NB * p.k;
-  for (int J = threadIdx.x; J <= p.NB; J += blockDim.x) o[J] = cnt[J];
-  for (int J = threadIdx.x; J < p.NB; J += blockDim.x) {
-    int pos = cnt[J];
-    for (int I = J; I < p.NB; ++I)
-      for (int e = 0; e < p.k; ++e)
-        if (s[(size_t)I * p.k + e] == J) it[pos++] = I;
+  for (int J = lane; J <= p.NB; J += 64) cnt[J] = 0;
+  __syncthreads();
+  for (int e0 = 0; e0 < p.k; e0 += 64) {
+    const int e = e0 + lane;
+#pragma unroll 8
+    for (int I = 0; I < p.NB; ++I) {
+      const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
+      if (J >= 0 && J <= I) atomicAdd(&cnt[J], 1);
+    }
+  }
+  __syncthreads();
+  // exclusive scan of cnt[0..NB) in chunks of 64; cnt[NB] receives the total
+  int carry = 0;
+  for (int J0 = 0; J0 <= p.NB; J0 += 64) {
+    const int J = J0 + lane;
+    const int c = J < p.NB ? cnt[J] : 0;
+    int incl = c;
+#pragma unroll
+    for (int off = 1; off < 64; off <<= 1) {
+      const int up = __shfl_up(incl, off);
+      if (lane >= off) incl += up;
+    }
+    if (J <= p.NB) {
+      cnt[J] = carry + incl - c;
+      o[J] = carry + incl - c;
+    }
+    carry += __shfl(incl, 63);
+  }
+  __syncthreads();
+  for (int e0 = 0; e0 < p.k; e0 += 64) {
+    const int e = e0 + lane;
+#pragma unroll 8
+    for (int I = 0; I < p.NB; ++I) {
+      const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
+      if (J >= 0 && J <= I) it[atomicAdd(&cnt[J], 1)] = I;
+    }
   }
 }
 
@@ -686,6 +747,8 @@ BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws)
   off = align256(off + BH * p.NB * p.k * sizeof(int));
   w.partial = reinterpret_cast<float *>(base + off);
   off = align256(off + BH * w.nchunk * (2 * p.d + 1) * sizeof(float));
+  w.stage2 = reinterpret_cast<float *>(base + off);
+  off = align256(off + (size_t)p.H * kGateSlices * (2 * p.d + 1) * sizeof(float));
   if (bwd_mfma_supported(p, dtype)) {
     w.rowB = reinterpret_cast<float4 *>(base + off);
     off = align256(off + BH * p.L * sizeof(float4));
@@ -705,12 +768,14 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, hipStrea
   const unsigned BH = (unsigned)(p.B * p.H);
   const bool mfma = bwd_mfma_supported(p, dtype);
 
-  hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(kPrepRows), 0, st,
+  hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(256), 0, st,
                      (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
                      a.gate_b, w.rowstat, w.partial, (const T *)a.V, w.rowB, w.rowC, p);
-  hipLaunchKernelGGL(bwd_gate_reduce_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.partial, a.d_gate_w,
-                     a.d_gate_b, w.nchunk, p);
-  hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(256), 0, st, a.sel, w.offs, w.items, p);
+  hipLaunchKernelGGL(bwd_gate_reduce1_kernel, dim3((unsigned)p.H, kGateSlices), dim3(256), 0, st, w.partial,
+                     w.stage2, w.nchunk, p);
+  hipLaunchKernelGGL(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
+                     a.d_gate_b, p);
+  hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64), 0, st, a.sel, w.offs, w.items, p);
   if (mfma) {
     launch_bwd_mfma(p, a, w, st);
     return;

@@ -45,6 +45,7 @@ struct BwdWorkspace {
   int *offs;         // [B*H,(NB+1)] inverse selection list: offsets
   int *items;        // [B*H,NB*k]   inverse selection list: query blocks, ascending per key block
   float *partial;    // [B*H*nchunk,(2d+1)] partial gate-weight gradients
+  float *stage2;     // [H,slices,(2d+1)] second reduction level
   float4 *rowB;      // [B*H*L] (dO.o_lt, dO.o_st, Wg_lt.o_lt, Wg_st.o_st), matrix-core path only
   float2 *rowC;      // [B*H*L] (Wg_lt.v, Wg_st.v), matrix-core path only
   int nchunk;

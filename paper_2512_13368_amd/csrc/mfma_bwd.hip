@@ -156,7 +156,7 @@ constexpr float kBigProb = 0.03125f;  // a_x*P above this triggers the two-term 
 //                     dQ^T += K^T dS^T      (K^T through the transposing LDS read)
 // =============================================================================================
 template <int BLK>
-__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2), amdgpu_num_vgpr(256))) void bwd_dq_mfma_kernel(const uint16_t *__restrict__ Q,
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(const uint16_t *__restrict__ Q,
                                                               const uint16_t *__restrict__ K,
                                                               const uint16_t *__restrict__ V,
                                                               const int *__restrict__ valid_len,
@@ -266,7 +266,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2), 
   const uint16_t *v_lane = V + head + sg.ld_row * D + Stager<BLK>::lane_col(lane);
   const ReadOffsets ro = read_offsets(lane);
   // Wg_x.v_j of key tile J for the branch the tile belongs to (0 past the end)
-  auto key_const = [&](int J, bool windowed) -> float {
+  auto key_const = [&](int J, bool windowed) __attribute__((always_inline)) -> float {
     float w = 0.0f;
     if (tid < BLK) {
       const int jj = J * BLK + tid;
@@ -279,13 +279,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2), 
   };
 
   auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, const float *wvs, int J, bool windowed, float lse2,
-                       float a_x, float do_x, float c0) {
+                       float a_x, float do_x, float c0) __attribute__((always_inline)) {
     const bool hp = __builtin_amdgcn_readfirstlane((int)(windowed ? hp_st : hp_lt)) != 0;
     const bool masked = windowed || J == I || J * BLK < p0;
     const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
     const unsigned span = (unsigned)(iq - lo);
     const bool any = iq >= lo;
-#pragma unroll
+#pragma unroll 1
     for (int s = 0; s < UNITS; ++s) {
       f32x16 sacc, gacc;
 #pragma unroll
@@ -345,7 +345,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2), 
     if (tid < BLK) wv_s[0][tid] = w0;
   }
   __syncthreads();
-  auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *k_cur, const uint16_t *v_cur, int par) {
+  auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *k_cur, const uint16_t *v_cur,
+                  int par) __attribute__((always_inline)) {
     float wn = 0.0f;
     const bool more = t + 1 < n_all;
     if (more) {
@@ -354,8 +355,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2), 
       sg.stage(k_lane, k_fill, Jn);
       sg.stage(v_lane, v_fill, Jn);
     }
-    if (t < n_st) tile_body(k_cur, v_cur, wv_s[par], tile_of(t), true, lse2_st, a_st, do_st, c0_st);
-    else tile_body(k_cur, v_cur, wv_s[par], tile_of(t), false, lse2_lt, a_lt, do_lt, c0_lt);
+    const bool win = t < n_st;
+    tile_body(k_cur, v_cur, wv_s[par], tile_of(t), win, win ? lse2_st : lse2_lt, win ? a_st : a_lt,
+              win ? do_st : do_lt, win ? c0_st : c0_lt);
     if (more && tid < BLK) wv_s[par ^ 1][tid] = wn;
     __syncthreads();
   };
@@ -468,7 +470,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   struct RowC { float l2, dox, ax, dz, c0; };
   // per-row constants of query block Iq for one branch (pad rows: probability forced to zero)
-  auto row_consts = [&](int Iq, bool windowed) -> RowC {
+  auto row_consts = [&](int Iq, bool windowed) __attribute__((always_inline)) -> RowC {
     RowC r{1.0e30f, 0.0f, 0.0f, 0.0f, 0.0f};
     if (tid < BLK) {
       const int i = Iq * BLK + tid;
@@ -484,7 +486,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     return r;
   };
-  auto put_consts = [&](int par, const RowC &r) {
+  auto put_consts = [&](int par, const RowC &r) __attribute__((always_inline)) {
     if (tid < BLK) {
       rc_s[par][0][tid] = r.l2;
       rc_s[par][1][tid] = r.dox;
@@ -494,14 +496,15 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
-  auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, float wvx, float &u) {
+  auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, float wvx,
+                       float &u) __attribute__((always_inline)) {
     const bool masked = windowed || Iq == J || Iq * BLK < p0 || J * BLK < p0 || (Iq + 1) * BLK > p.L;
     // visible <=> key valid and lo_i <= i <= hi_i
     const int lo_i = max(j, p0);
     const int hi_i = windowed ? min(p.L - 1, j + p.w - 1) : p.L - 1;
     const unsigned span = (unsigned)(hi_i - lo_i);
     const bool any = key_ok && hi_i >= lo_i;
-#pragma unroll
+#pragma unroll 1
     for (int s = 0; s < UNITS; ++s) {
       f32x16 sacc, gacc;
       const int r0 = 32 * s + 4 * lh;  // this lane's rows of the unit: r0 + 8g + (0..3)
@@ -590,7 +593,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     put_consts(0, row_consts(I0, 0 < n_st));
   }
   __syncthreads();
-  auto step = [&](int t, uint16_t *q_fill, uint16_t *g_fill, const uint16_t *q_cur, const uint16_t *g_cur, int par) {
+  auto step = [&](int t, uint16_t *q_fill, uint16_t *g_fill, const uint16_t *q_cur, const uint16_t *g_cur,
+                  int par) __attribute__((always_inline)) {
     RowC rn{1.0e30f, 0.0f, 0.0f, 0.0f, 0.0f};
     const bool more = t + 1 < n_all;
     if (more) {
@@ -605,8 +609,11 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int src = e + 64 + tid;
       if (tid < 64 && src < n_lt) ring[src & (kListRing - 1)] = my_items[src];
     }
-    if (t < n_st) tile_body(q_cur, g_cur, par, tile_of(t), true, wv_st, u_st);
-    else tile_body(q_cur, g_cur, par, tile_of(t), false, wv_lt, u_lt);
+    const bool win = t < n_st;
+    float u = 0.0f;
+    tile_body(q_cur, g_cur, par, tile_of(t), win, win ? wv_st : wv_lt, u);
+    u_st += win ? u : 0.0f;
+    u_lt += win ? 0.0f : u;
     if (more) put_consts(par ^ 1, rn);
     __syncthreads();
   };
