@@ -66,7 +66,8 @@ def main():
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "dense"], default=None,
+    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense"],
+                    default=None,
                     help="profiling aid: run only this stage --steps times (after the others ran once) "
                          "and print its average time; the headline line is not produced")
     args = ap.parse_args()
@@ -124,6 +125,12 @@ def main():
               "fwd": lambda: B.attn_fwd(p_nosave, Q, K, V, vl, sel, gw, gb, out=fo_nosave),
               "fwd_save": lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo),
               "bwd": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd),
+              "bwd_gate": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
+                                             stages=B.BWD_GATE),
+              "bwd_dq": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
+                                           stages=B.BWD_DQ),
+              "bwd_dkv": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
+                                            stages=B.BWD_DKV),
               "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense)}[args.stage]
         for _ in range(args.warmup):
             fn()
@@ -150,7 +157,7 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
-    # ---- stage times with HIP events on the launch stream (separate passes) ----
+    # ---- per-kernel times with HIP events on the launch stream (separate passes) ----
     def timed(fn, reps):
         ev0 = torch.cuda.Event(enable_timing=True)
         ev1 = torch.cuda.Event(enable_timing=True)
@@ -164,40 +171,59 @@ def main():
         return ev0.elapsed_time(ev1) / reps
 
     reps = max(3, args.steps)
-    ms_select = timed(lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel), reps)
-    ms_fwd = timed(lambda: B.attn_fwd(p_nosave, Q, K, V, vl, sel, gw, gb, out=fo_nosave), reps)
-    ms_fwd_save = timed(lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo), reps)
-    ms_bwd = timed(lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd), reps)
+    bwd = lambda st: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd, stages=st)
+    ms = {
+        "select": timed(lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel), reps),
+        "fwd": timed(lambda: B.attn_fwd(p_nosave, Q, K, V, vl, sel, gw, gb, out=fo_nosave), reps),
+        "fwd_saving_for_bwd": timed(lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo), reps),
+        "bwd_gate": timed(lambda: bwd(B.BWD_GATE), reps),
+        "bwd_inverse_list": timed(lambda: bwd(B.BWD_INVERSE), reps),
+        "bwd_dq": timed(lambda: bwd(B.BWD_DQ), reps),
+        "bwd_dkv": timed(lambda: bwd(B.BWD_DKV), reps),
+        "bwd": timed(lambda: bwd(B.BWD_ALL), reps),
+    }
     ms_dense = None
     if not args.no_dense:
-        dense_reps = max(2, reps // 4)
-        ms_dense = timed(lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense), dense_reps)
+        ms_dense = timed(lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense), max(2, reps // 4))
 
-    # ---- algorithmic work ----
+    # ---- algorithmic work (pairs from the selection lists; bytes = tensors touched once) ----
     sel_h = sel.cpu().numpy()
     nnz_lt, nnz_st, nnz_dense = algorithmic_pairs(w, x.valid_len, sel_h)
+    pairs = nnz_lt + nnz_st
     tokens = int(x.valid_len.sum())
     sz = 4 if w.dtype == "fp32" else 2
-    flops_fwd = 4.0 * w.d * (nnz_lt + nnz_st)
-    flops_dense = 4.0 * w.d * nnz_dense
-    bytes_fwd = 4.0 * w.B * w.H * w.L * w.d * sz            # Q,K,V read once + O written once
-    t_fwd = ms_fwd * 1e-3
-    tflops = flops_fwd / t_fwd / 1e12
-    gbs = bytes_fwd / t_fwd / 1e9
+    tensor = float(w.B) * w.H * w.L * w.d
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
-    t_mfma = flops_fwd / (mfma_peak * 1e12)
-    t_hbm = bytes_fwd / (HBM_PEAK_GBS * 1e9)
-    if t_mfma >= t_hbm:
-        roof = {"bound": "mfma", "achieved": round(tflops, 3), "peak": mfma_peak, "unit": "TFLOP/s",
-                "frac": round(tflops / mfma_peak, 4), "traffic": None}
-    else:
-        roof = {"bound": "hbm", "achieved": round(gbs, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                "frac": round(gbs / HBM_PEAK_GBS, 4), "traffic": None}
-    roof["kernel"] = "blossom_attn_fwd"
-    roof["avg_launch_ms"] = round(ms_fwd, 4)
-    roof["algorithmic_gflop"] = round(flops_fwd / 1e9, 2)
-    roof["algorithmic_mb"] = round(bytes_fwd / 1e6, 1)
+    # kernel -> (flops, bytes): contractions each kernel has to produce per unmasked pair (2d flops
+    # each) and tensors it has to read or write once
+    work = {
+        "fwd": (4.0 * w.d * pairs, 4 * tensor * sz),                                  # QK^T, PV | Q,K,V,O
+        "fwd_saving_for_bwd": (4.0 * w.d * pairs, 4 * tensor * sz + 2 * tensor * 4),  # + o_lt, o_st fp32
+        "bwd_dq": (6.0 * w.d * pairs, 5 * tensor * sz),                               # S, dP, dQ | Q,K,V,dO,dQ
+        "bwd_dkv": (8.0 * w.d * pairs, 6 * tensor * sz),                              # S, dP, dV, dK | Q,K,V,dO,dK,dV
+        "bwd_gate": (0.0, tensor * (2 * sz + 8)),                                     # dO, V, o_lt, o_st
+        "select": (0.0, 2 * tensor * sz),                                             # Q, K
+    }
 
+    def roofline(kernel):
+        flops, nbytes = work[kernel]
+        t = ms[kernel] * 1e-3
+        t_mfma = flops / (mfma_peak * 1e12)
+        t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+        if t_mfma >= t_hbm:
+            a = flops / t / 1e12
+            r = {"bound": "mfma", "achieved": round(a, 2), "peak": mfma_peak, "unit": "TFLOP/s",
+                 "frac": round(a / mfma_peak, 4)}
+        else:
+            a = nbytes / t / 1e9
+            r = {"bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+                 "frac": round(a / HBM_PEAK_GBS, 4)}
+        r.update({"traffic": None, "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
+                  "algorithmic_gflop": round(flops / 1e9, 2), "algorithmic_mb": round(nbytes / 1e6, 1)})
+        return r
+
+    step_kernels = ["select", "fwd_saving_for_bwd", "bwd_gate", "bwd_dq", "bwd_dkv"]
+    dominant = max(step_kernels, key=lambda k_: ms[k_])
     out = {
         "metric": "sparse-attn fwd+bwd tokens/sec (select + forward + backward per step)",
         "value": round(tokens / (ms_per_step * 1e-3), 1),
@@ -213,34 +239,44 @@ def main():
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} b={w.block} k={w.topk} "
                                f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}",
-                   "tokens_per_step": tokens},
-        "stages_ms": {"select": round(ms_select, 4), "fwd": round(ms_fwd, 4),
-                      "fwd_saving_for_bwd": round(ms_fwd_save, 4), "bwd": round(ms_bwd, 4)},
-        "fwd_tokens_per_s": round(tokens / ((ms_select + ms_fwd) * 1e-3), 1),
-        "fwd_kernel_tokens_per_s": round(tokens / t_fwd, 1),
-        "roofline": roof,
+                   "tokens_per_step": tokens, "unmasked_pairs_lt": nnz_lt, "unmasked_pairs_st": nnz_st},
+        "kernels_ms": {k_: round(v, 4) for k_, v in ms.items()},
+        "fwd_tokens_per_s": round(tokens / ((ms["select"] + ms["fwd"]) * 1e-3), 1),
+        "roofline": roofline(dominant),
+        "roofline_fwd": roofline("fwd"),
+        "roofline_all": {k_: roofline(k_)["frac"] for k_ in ("fwd", "fwd_saving_for_bwd", "bwd_dq", "bwd_dkv",
+                                                              "bwd_gate", "select")},
     }
     if ms_dense is not None:
+        flops_dense = 4.0 * w.d * nnz_dense
         out["dense_causal"] = {"ms": round(ms_dense, 4), "tokens_per_s": round(tokens / (ms_dense * 1e-3), 1),
-                               "tflops": round(flops_dense / (ms_dense * 1e-3) / 1e12, 3),
-                               "sparse_fwd_speedup": round(ms_dense / (ms_select + ms_fwd), 3)}
+                               "tflops": round(flops_dense / (ms_dense * 1e-3) / 1e12, 2),
+                               "sparse_fwd_speedup": round(ms_dense / (ms["select"] + ms["fwd"]), 3)}
 
     # ---- CPU oracle on a bounded sample of the same workload (reported, not a target) ----
     if not args.no_cpu_baseline:
         import oracle
         threads = oracle.num_threads()
         total_pairs = w.B * w.H
-        n_pairs = min(total_pairs, 2 * threads)
-        pairs = np.linspace(0, total_pairs - 1, n_pairs).astype(np.int32)
-        t0 = time.perf_counter()
-        sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk, bh_list=pairs)
-        sel_ref = np.where(sel_ref == -2, -1, sel_ref)
-        oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk, w.window,
-                        bh_list=pairs)
-        oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block, w.topk,
-                        w.window, bh_list=pairs)
-        cpu_s = time.perf_counter() - t0
-        sample_tokens = float(sum(int(x.valid_len[int(bh) // w.H]) for bh in pairs)) / w.H
+
+        def run_oracle(n_pairs):
+            prs = np.linspace(0, total_pairs - 1, n_pairs).astype(np.int32)
+            t0 = time.perf_counter()
+            sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk, bh_list=prs)
+            sel_ref = np.where(sel_ref == -2, -1, sel_ref)
+            oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk, w.window,
+                            bh_list=prs)
+            oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block, w.topk,
+                            w.window, bh_list=prs)
+            dt_ = time.perf_counter() - t0
+            toks = float(sum(int(x.valid_len[int(bh) // w.H]) for bh in prs)) / w.H
+            return dt_, toks
+
+        n_pairs = min(total_pairs, threads)
+        cpu_s, sample_tokens = run_oracle(n_pairs)
+        if cpu_s < 8.0 and n_pairs < total_pairs:  # aim at about 15 s of CPU work
+            n_pairs = min(total_pairs, max(n_pairs + 1, int(n_pairs * 15.0 / max(cpu_s, 1e-3))))
+            cpu_s, sample_tokens = run_oracle(n_pairs)
         out["cpu_baseline"] = {"value": round(sample_tokens / cpu_s, 2), "unit": "tokens/s",
                                "cores": threads, "kind": "oracle",
                                "sample": f"{n_pairs} of {total_pairs} (row, head) pairs, select+fwd+bwd, "

@@ -137,6 +137,26 @@ int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, cons
                      void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The passes of blossom_attn_bwd one at a time, for profilers and benchmarks that need one
+ * kernel per timed region.  Same arguments, workspace and checks as blossom_attn_bwd (of which
+ * it is the general form: blossom_attn_bwd == all four bits); `stages` is a bit set:
+ *   BLOSSOM_BWD_GATE     gate backward per row (Eq. 18-19) and reduction of d_gate_w, d_gate_b
+ *   BLOSSOM_BWD_INVERSE  inverse selection list (key block -> query blocks that selected it)
+ *   BLOSSOM_BWD_DQ       dQ
+ *   BLOSSOM_BWD_DKV      dK and dV
+ * A pass reads what earlier passes left in the workspace: DQ needs GATE; DKV needs GATE and
+ * INVERSE, from calls with the same arguments and workspace.  Other bits are ignored.
+ */
+enum { BLOSSOM_BWD_GATE = 1, BLOSSOM_BWD_INVERSE = 2, BLOSSOM_BWD_DQ = 4, BLOSSOM_BWD_DKV = 8 };
+int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *K, const void *V,
+                            const int32_t *valid_len, const int32_t *sel,
+                            const float *gate_w, const float *gate_b,
+                            const void *o_lt, const void *o_st, const float *lse_lt, const float *lse_st,
+                            const void *dO,
+                            void *dQ, void *dK, void *dV, float *d_gate_w, float *d_gate_b,
+                            void *ws, size_t ws_bytes, void *hip_stream, unsigned stages);
+
+/*
  * Comparison kernel: dense causal attention over the valid suffix (Eq. 1 with the causal
  * mask), built in the same tile style.  topk, window, stis_mode and save_for_bwd are ignored.
  *   O out [B,H,L,d];  lse out fp32 [B,H,L] or NULL

@@ -18,7 +18,8 @@ F32, BF16 = 0, 1
 WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
 EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_attn_fwd", "blossom_attn_bwd",
-           "blossom_dense_causal_fwd", "blossom_strerror", "blossom_version")
+           "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_strerror", "blossom_version")
+BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
 
 
 class BlossomParams(ctypes.Structure):
@@ -59,6 +60,8 @@ def lib() -> ctypes.CDLL:
         L.blossom_attn_bwd.restype = ctypes.c_int
         L.blossom_attn_bwd.argtypes = [pp, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, fp, fp, vp, vp, vp, vp,
                                        fp, fp, vp, ctypes.c_size_t, vp]
+        L.blossom_attn_bwd_stages.restype = ctypes.c_int
+        L.blossom_attn_bwd_stages.argtypes = L.blossom_attn_bwd.argtypes + [ctypes.c_uint]
         L.blossom_dense_causal_fwd.restype = ctypes.c_int
         L.blossom_dense_causal_fwd.argtypes = [pp, vp, vp, vp, i32p, vp, fp, vp, ctypes.c_size_t, vp]
         L.blossom_strerror.restype = ctypes.c_char_p
@@ -207,7 +210,7 @@ class BwdOut:
 
 
 def attn_bwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b, fwd: FwdOut, dO,
-             out: BwdOut | None = None, ws=None, stream=None) -> BwdOut:
+             out: BwdOut | None = None, ws=None, stream=None, stages: int = BWD_ALL) -> BwdOut:
     import torch
     shp = (p.B, p.H, p.L, p.d)
     dt = _torch_dtype(p)
@@ -238,11 +241,13 @@ def attn_bwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b, fwd: FwdOut, dO
     _check_tensor(out.d_gate_b, (p.H,), torch.float32, "d_gate_b")
     ws, nbytes = _workspace(p, WS_BWD, ws, Q.device)
     cp = p.c()
-    rc = lib().blossom_attn_bwd(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len), _ptr(sel),
-                                _ptr(gate_w), _ptr(gate_b), _ptr(fwd.o_lt), _ptr(fwd.o_st),
-                                _ptr(fwd.lse_lt), _ptr(fwd.lse_st), _ptr(dO), _ptr(out.dQ), _ptr(out.dK),
-                                _ptr(out.dV), _ptr(out.d_gate_w), _ptr(out.d_gate_b), _ptr(ws), nbytes,
-                                _stream(stream))
+    args = (ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len), _ptr(sel), _ptr(gate_w), _ptr(gate_b),
+            _ptr(fwd.o_lt), _ptr(fwd.o_st), _ptr(fwd.lse_lt), _ptr(fwd.lse_st), _ptr(dO), _ptr(out.dQ),
+            _ptr(out.dK), _ptr(out.dV), _ptr(out.d_gate_w), _ptr(out.d_gate_b), _ptr(ws), nbytes, _stream(stream))
+    if stages == BWD_ALL:
+        rc = lib().blossom_attn_bwd(*args)
+    else:
+        rc = lib().blossom_attn_bwd_stages(*args, stages)
     if rc:
         raise BlossomError(rc, "blossom_attn_bwd")
     return out

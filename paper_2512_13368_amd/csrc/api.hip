@@ -110,11 +110,12 @@ int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, cons
   return launch_status();
 }
 
-int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, const void *V,
-                     const int32_t *valid_len, const int32_t *sel, const float *gate_w,
-                     const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
-                     const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
-                     float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream)
+int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *K, const void *V,
+                            const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                            const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                            const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
+                            float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream,
+                            unsigned stages)
 {
   KParams kp;
   int rc = check_params(p, &kp);
@@ -132,8 +133,18 @@ int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, cons
   a.gate_w = gate_w; a.gate_b = gate_b; a.o_lt = o_lt; a.o_st = o_st;
   a.lse_lt = lse_lt; a.lse_st = lse_st; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV;
   a.d_gate_w = d_gate_w; a.d_gate_b = d_gate_b; a.ws = ws;
-  launch_bwd(kp, p->dtype, a, (hipStream_t)hip_stream);
+  launch_bwd(kp, p->dtype, a, stages & kBwdStageAll, (hipStream_t)hip_stream);
   return launch_status();
+}
+
+int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, const void *V,
+                     const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                     const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                     const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
+                     float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream)
+{
+  return blossom_attn_bwd_stages(p, Q, K, V, valid_len, sel, gate_w, gate_b, o_lt, o_st, lse_lt, lse_st, dO, dQ,
+                                 dK, dV, d_gate_w, d_gate_b, ws, ws_bytes, hip_stream, kBwdStageAll);
 }
 
 int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,

@@ -762,40 +762,45 @@ BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws)
 size_t bwd_workspace_bytes(const KParams &p, int dtype) { return bwd_carve(p, dtype, nullptr).total; }
 
 template <typename T, int D>
-static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st)
+static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, hipStream_t st)
 {
   const BwdWorkspace w = bwd_carve(p, dtype, a.ws);
   const unsigned BH = (unsigned)(p.B * p.H);
   const bool mfma = bwd_mfma_supported(p, dtype);
 
-  hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(256), 0, st,
-                     (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
-                     a.gate_b, w.rowstat, w.partial, (const T *)a.V, w.rowB, w.rowC, p);
-  hipLaunchKernelGGL(bwd_gate_reduce1_kernel, dim3((unsigned)p.H, kGateSlices), dim3(256), 0, st, w.partial,
-                     w.stage2, w.nchunk, p);
-  hipLaunchKernelGGL(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
-                     a.d_gate_b, p);
-  hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64), 0, st, a.sel, w.offs, w.items, p);
+  if (stages & kBwdStageGate) {
+    hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(256), 0, st,
+                       (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
+                       a.gate_b, w.rowstat, w.partial, (const T *)a.V, w.rowB, w.rowC, p);
+    hipLaunchKernelGGL(bwd_gate_reduce1_kernel, dim3((unsigned)p.H, kGateSlices), dim3(256), 0, st, w.partial,
+                       w.stage2, w.nchunk, p);
+    hipLaunchKernelGGL(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
+                       a.d_gate_b, p);
+  }
+  if (stages & kBwdStageInverse)
+    hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64), 0, st, a.sel, w.offs, w.items, p);
   if (mfma) {
-    launch_bwd_mfma(p, a, w, st);
+    launch_bwd_mfma(p, a, w, stages, st);
     return;
   }
-  hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64), 0, st, (const T *)a.Q,
-                     (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st,
-                     (const T *)a.dO, w.rowstat, (T *)a.dQ, p);
-  hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D>), dim3(BH * p.NB, 2), dim3(64), 0, st, (const T *)a.Q,
-                     (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
-                     (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
+  if (stages & kBwdStageDQ)
+    hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64), 0, st, (const T *)a.Q,
+                       (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st,
+                       (const T *)a.dO, w.rowstat, (T *)a.dQ, p);
+  if (stages & kBwdStageDKV)
+    hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D>), dim3(BH * p.NB, 2), dim3(64), 0, st, (const T *)a.Q,
+                       (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
+                       (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
 }
 
-void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st)
+void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, hipStream_t st)
 {
   if (dtype == 0) {
-    if (p.d == 32) launch_bwd_t<float, 32>(p, dtype, a, st);
-    else launch_bwd_t<float, 64>(p, dtype, a, st);
+    if (p.d == 32) launch_bwd_t<float, 32>(p, dtype, a, stages, st);
+    else launch_bwd_t<float, 64>(p, dtype, a, stages, st);
   } else {
-    if (p.d == 32) launch_bwd_t<bf16_t, 32>(p, dtype, a, st);
-    else launch_bwd_t<bf16_t, 64>(p, dtype, a, st);
+    if (p.d == 32) launch_bwd_t<bf16_t, 32>(p, dtype, a, stages, st);
+    else launch_bwd_t<bf16_t, 64>(p, dtype, a, stages, st);
   }
 }
 

@@ -56,7 +56,8 @@ struct BwdWorkspace {
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
 BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws);
 size_t bwd_workspace_bytes(const KParams &p, int dtype);
-void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, hipStream_t st);
+enum : unsigned { kBwdStageGate = 1u, kBwdStageInverse = 2u, kBwdStageDQ = 4u, kBwdStageDKV = 8u, kBwdStageAll = 15u };
+void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, hipStream_t st);
 
 // mfma_fwd.hip: matrix-core forward for bf16, d = 64, b in {32, 64}
 bool fwd_mfma_supported(const KParams &p, int dtype);
@@ -64,6 +65,6 @@ void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st);
 
 // mfma_bwd.hip: matrix-core dQ and dK/dV for bf16, d = 64, b in {32, 64}
 bool bwd_mfma_supported(const KParams &p, int dtype);
-void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, hipStream_t st);
+void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st);
 
 }  // namespace blossom

@@ -643,22 +643,23 @@ bool bwd_mfma_supported(const KParams &p, int dtype)
   return (long)(p.w - 1) / p.b + 2 + p.k <= kMaxTilesQ;
 }
 
-void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, hipStream_t st)
+void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st)
 {
+  const bool do_dq = stages & kBwdStageDQ, do_dkv = stages & kBwdStageDKV;
   const unsigned grid = (unsigned)(p.B * p.H * p.NB);
   auto u16 = [](const void *x) { return reinterpret_cast<const uint16_t *>(x); };
   if (p.b == 32) {
-    hipLaunchKernelGGL((bwd_dq_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
+    if (do_dq) hipLaunchKernelGGL((bwd_dq_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
                        a.valid_len, a.sel, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC,
                        (uint16_t *)a.dQ, p);
-    hipLaunchKernelGGL((bwd_dkv_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
+    if (do_dkv) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
                        a.valid_len, a.gate_w, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC, w.offs,
                        w.items, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
   } else {
-    hipLaunchKernelGGL((bwd_dq_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
+    if (do_dq) hipLaunchKernelGGL((bwd_dq_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
                        a.valid_len, a.sel, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC,
                        (uint16_t *)a.dQ, p);
-    hipLaunchKernelGGL((bwd_dkv_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
+    if (do_dkv) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
                        a.valid_len, a.gate_w, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC, w.offs,
                        w.items, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
   }

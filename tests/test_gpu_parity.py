@@ -195,3 +195,21 @@ def test_selection_only_large_and_invariances():
     sel = B.select_blocks(params(w), dv.Q, dv.K, dv.vl)
     torch.cuda.synchronize()
     np.testing.assert_array_equal(sel.cpu().numpy(), oracle.select_blocks(x.Q, x.K, x.valid_len, 8, 3))
+
+
+def test_backward_passes_one_at_a_time_equal_the_full_call():
+    for w in (WORKLOADS["cfg1"], with_shape(WORKLOADS["cfg3"], B=3)):
+        x = make_inputs(w, want_dO=True)
+        dv = Dev(x)
+        p = params(w, save_for_bwd=1)
+        sel = B.select_blocks(p, dv.Q, dv.K, dv.vl)
+        f = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
+        full = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO)
+        ws = torch.empty(B.workspace_bytes(p, B.WS_BWD), dtype=torch.uint8, device="cuda")
+        parts = None
+        for st in (B.BWD_GATE, B.BWD_INVERSE, B.BWD_DQ, B.BWD_DKV):
+            parts = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO, out=parts, ws=ws, stages=st)
+        torch.cuda.synchronize()
+        for a, b_ in ((full.dQ, parts.dQ), (full.dK, parts.dK), (full.dV, parts.dV),
+                      (full.d_gate_w, parts.d_gate_w), (full.d_gate_b, parts.d_gate_b)):
+            assert torch.equal(a, b_)
