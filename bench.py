@@ -24,6 +24,14 @@ if ROOT not in sys.path:
 
 import numpy as np
 
+# HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
+# counters read for a plain copy of known size (FETCH_SIZE x2.000, WRITE_SIZE x1.000); the commands and the
+# raw readings are in profiles/cfg4_hbm_traffic.txt.  Other workloads: not measured (null).
+MEASURED_TRAFFIC_BYTES = {
+    ("cfg4", "fwd"): 562903345, ("cfg4", "fwd_saving_for_bwd"): 1208543493, ("cfg4", "bwd_gate"): 855178113,
+    ("cfg4", "bwd_dq"): 805316926, ("cfg4", "bwd_dkv"): 1130622172, ("cfg4", "select"): 276971581,
+}
+
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
 FP32_VALU_PEAK_TFLOPS = 157.3   # 256 CU x 4 SIMD x 64 FLOP/clk x 2.4 GHz
@@ -66,7 +74,8 @@ def main():
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense"],
+    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense",
+                                        "copy"],
                     default=None,
                     help="profiling aid: run only this stage --steps times (after the others ran once) "
                          "and print its average time; the headline line is not produced")
@@ -131,7 +140,9 @@ def main():
                                            stages=B.BWD_DQ),
               "bwd_dkv": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
                                             stages=B.BWD_DKV),
-              "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense)}[args.stage]
+              "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense),
+              # a plain device copy of one [B,H,L,d] tensor: calibrates the HBM byte counters
+              "copy": lambda: O_dense.copy_(Q)}[args.stage]
         for _ in range(args.warmup):
             fn()
         torch.cuda.synchronize()
@@ -218,7 +229,7 @@ def main():
             a = nbytes / t / 1e9
             r = {"bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                  "frac": round(a / HBM_PEAK_GBS, 4)}
-        r.update({"traffic": None, "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
+        r.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kernel)), "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
                   "algorithmic_gflop": round(flops / 1e9, 2), "algorithmic_mb": round(nbytes / 1e6, 1)})
         return r
 
