@@ -103,12 +103,28 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   const int bh = (int)(vid / p.NB);
   const int I = p.NB - 1 - (int)(vid % p.NB);
   const int h = bh % p.H;
-  const int n = clamp_len(valid_len[bh / p.H], p.L);
-  const int p0 = p.L - n;
   const int q0 = I * BLK + 32 * wv;  // first query row of this wavefront
   const int iq = q0 + lq;            // this lane's query row
-  const bool q_ok = iq < p.L && iq >= p0;
   const size_t head = (size_t)bh * p.L * D;
+
+  // ---- everything the prologue needs from memory is requested before anything is waited for ----
+  const int n_raw = valid_len[bh / p.H];
+  uint4 qraw[4];
+  {
+    const uint16_t *qrow = Q + head + (size_t)min(iq, p.L - 1) * D;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) qraw[kk] = *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh);
+  }
+  const int *my_sel = dense ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
+  const int sel0 = (!dense && lane < p.k) ? my_sel[lane] : -1;  // first 64 entries of the selection row
+  constexpr int GATE_PER = 2 * D / (2 * BLK);  // gate weights fetched per thread
+  float gate_mine[GATE_PER];
+#pragma unroll
+  for (int c = 0; c < GATE_PER; ++c) gate_mine[c] = dense ? 0.0f : gate_w[(size_t)h * 2 * D + c * 2 * BLK + tid];
+
+  const int n = clamp_len(n_raw, p.L);
+  const int p0 = p.L - n;
+  const bool q_ok = iq < p.L && iq >= p0;
 
   if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query in the block: zero outputs
     if (iq < p.L) {
@@ -129,72 +145,18 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     return;
   }
 
-  // Q^T operand: lane (query lq, half lh) holds c*Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk,
-  // c = scale*log2(e), rounded to bf16: the matrix cores then produce base-2 exponents directly.
-  const float c2 = p.scale * kLog2e;
-  bf16x8 qf[4];
-  {
-    const uint16_t *qrow = Q + head + (size_t)min(iq, p.L - 1) * D;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk) {
-      const uint4 raw = *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh);
-      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
-#pragma unroll
-      for (int e = 0; e < 4; ++e) {
-        qf[kk][2 * e] = (__bf16)(__uint_as_float(w[e] << 16) * c2);
-        qf[kk][2 * e + 1] = (__bf16)(__uint_as_float(w[e] & 0xFFFF0000u) * c2);
-      }
-    }
-  }
-
-  if (!dense)
-    for (int c = tid; c < 2 * D; c += BLK * 2) gate_s[c] = gate_w[(size_t)h * 2 * D + c];
-
-  // ---- tile list: window blocks J_lo..I, then the selection list up to its first -1 ----
-  // Every wavefront reads the whole selection row with one vector load per 64 entries and
-  // derives the counts from ballots (no chain of dependent scalar loads); the list itself is
-  // parked in LDS so that walking it never waits on the vector-memory counter, which also
-  // tracks the tile prefetches in flight.
+  // window blocks J_lo..I come first in the walk; they depend on the valid length only
   const int J_first = p0 / BLK;
-  int J_lo, n_st, n_all;
-  bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
+  int J_lo, n_st;
   if (dense) {
     J_lo = J_first;
     n_st = 0;
-    n_all = I - J_first + 1;
   } else {
-    const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
     const int lowpos = I * BLK - (p.w - 1);
     J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
     J_lo = max(J_lo, J_first);
     n_st = I - J_lo + 1;
-    if (wv == 0)
-      for (int t = lane; t < n_st; t += 64) tiles[t] = J_lo + t;
-    int n_lt = 0;
-    bool open = true;
-    for (int e0 = 0; e0 < p.k; e0 += 64) {
-      const int e = e0 + lane;
-      const int J = e < p.k ? my_sel[e] : -1;
-      const bool ok = J >= 0 && J < p.NB;
-      const unsigned long long okm = __ballot(ok);
-      const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);  // entries before the first -1
-      if (open) {
-        const bool mine = lane < lead;
-        if (wv == 0 && mine) tiles[n_st + e] = J;
-        // a full earlier block already brings a whole block of keys; only a partial first block may not
-        const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
-        if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
-        n_lt += lead;
-        open = lead == 64;
-      }
-    }
-    n_all = n_st + n_lt;
   }
-  __syncthreads();
-  auto tile_of = [&](int t) -> int {
-    if (dense) return J_first + t;
-    return __builtin_amdgcn_readfirstlane(tiles[t]);
-  };
 
   // ---- staging: each wavefront moves 4 x 1 KB of K and of V per tile ----
   // LDS position of 16-byte chunk c of row r:  r*128 + ((c ^ swz(r)) * 16),
@@ -224,6 +186,69 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
       }
     }
   };
+
+  // the first tiles are on their way while the rest of the prologue runs
+  const int first_J = dense ? J_first : J_lo;
+  const bool second_known = dense ? (I > J_first) : (n_st > 1);  // tile 1 is first_J + 1
+  stage(k_lane, Ks0, first_J);
+  stage(v_lane, Vs0, first_J);
+  if (second_known) stage(k_lane, Ks1, first_J + 1);
+
+  // Q^T operand: lane (query lq, half lh) holds c*Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk,
+  // c = scale*log2(e), rounded to bf16: the matrix cores then produce base-2 exponents directly.
+  const float c2 = p.scale * kLog2e;
+  bf16x8 qf[4];
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk) {
+    const uint32_t w[4] = {qraw[kk].x, qraw[kk].y, qraw[kk].z, qraw[kk].w};
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      qf[kk][2 * e] = (__bf16)(__uint_as_float(w[e] << 16) * c2);
+      qf[kk][2 * e + 1] = (__bf16)(__uint_as_float(w[e] & 0xFFFF0000u) * c2);
+    }
+  }
+  if (!dense)
+#pragma unroll
+    for (int c = 0; c < GATE_PER; ++c) gate_s[c * 2 * BLK + tid] = gate_mine[c];
+
+  // ---- tile list: window blocks J_lo..I, then the selection list up to its first -1 ----
+  // Every wavefront reads the whole selection row with one vector load per 64 entries and
+  // derives the counts from ballots (no chain of dependent scalar loads); the list itself is
+  // parked in LDS so that walking it never waits on the vector-memory counter, which also
+  // tracks the tile prefetches in flight.
+  int n_all;
+  bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
+  if (dense) {
+    n_all = I - J_first + 1;
+  } else {
+    if (wv == 0)
+      for (int t = lane; t < n_st; t += 64) tiles[t] = J_lo + t;
+    int n_lt = 0;
+    bool open = true;
+    for (int e0 = 0; e0 < p.k; e0 += 64) {
+      const int e = e0 + lane;
+      const int J = e0 == 0 ? sel0 : (e < p.k ? my_sel[e] : -1);
+      const bool ok = J >= 0 && J < p.NB;
+      const unsigned long long okm = __ballot(ok);
+      const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);  // entries before the first -1
+      if (open) {
+        const bool mine = lane < lead;
+        if (wv == 0 && mine) tiles[n_st + e] = J;
+        // a full earlier block already brings a whole block of keys; only a partial first block may not
+        const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
+        if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
+        n_lt += lead;
+        open = lead == 64;
+      }
+    }
+    n_all = n_st + n_lt;
+  }
+  __syncthreads();
+  auto tile_of = [&](int t) -> int {
+    if (dense) return J_first + t;
+    return __builtin_amdgcn_readfirstlane(tiles[t]);
+  };
+  if (!second_known && n_all > 1) stage(k_lane, Ks1, tile_of(1));
 
   // ---- per-lane LDS read offsets (elements) ----
   int koff[4];
@@ -420,9 +445,6 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   bool st_open = !dense;
   reset();
   f32x16 sA[UNITS], sB[UNITS];
-  stage(k_lane, Ks0, tile_of(0));
-  stage(v_lane, Vs0, tile_of(0));
-  if (n_all > 1) stage(k_lane, Ks1, tile_of(1));
   __syncthreads();
   qk(Ks0, sA);
   __syncthreads();  // Ks0 may be overwritten from here on
