@@ -18,7 +18,8 @@ SOURCES = {
     "generic.hip": [],
     # accumulators of the matrix instructions stay in VGPRs: the online softmax rescales them
     # with VALU instructions, and AGPR placement costs a register copy per element per tile
-    "mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    # (the forward kernel also reuses its bf16 staging rows as fp32 exchange space between wavefronts)
+    "mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-strict-aliasing"],
     "mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 

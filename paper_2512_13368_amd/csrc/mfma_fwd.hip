@@ -1,86 +1,67 @@
 // Fused forward on the matrix cores for bf16, d = 64, block size 32 or 64 (Eq. 1 under the two
 // branch masks, Eq. 16-19), plus the same-style dense causal comparison.
 //
-// Work split: one workgroup per (row, head, query block); one wavefront per 32 query rows.
-// K/V tiles of the short-term window and of the selected blocks are gathered by the selection
-// list with direct global->LDS loads (16 bytes per lane, whole 128-byte rows per 8 lanes),
-// double buffered, XOR-swizzled so that the operand reads below are bank-conflict free, and
-// shared by the workgroup's wavefronts.
+// Work split: one workgroup per (row, head, query block), BLK/32 wavefronts.  Every wavefront
+// works on ALL query rows of the block but only on "its" 32 key rows of every K/V tile (keys
+// 32*wv .. 32*wv+31 of the block): it stages those rows itself with direct global->LDS loads
+// (16 bytes per lane, whole 128-byte rows per 8 lanes, XOR-swizzled so that the operand reads
+// are bank-conflict free), and nobody else reads them.  The tile loop therefore has no
+// workgroup barrier at all; a wavefront only waits for its own loads.  Each K fragment read
+// from LDS serves all query groups, each V fragment too.  At the end of a branch the wavefronts
+// hold partial (reference, row sum, output) triples over disjoint key subsets; they are merged
+// through LDS once per branch, after which wavefront wv owns the finished rows 32*wv .. +31.
 //
-// Per 32-key unit a wavefront computes S^T = K Q^T with four v_mfma_f32_32x32x16_bf16 (keys
-// are the M dimension, so every lane owns ONE query column and 16 of its logits: row maximum
-// and row sum are in-lane reductions plus one exchange with lane^32), applies the online
-// softmax in fp32, and feeds P^T straight from the accumulator registers (converted to bf16)
-// as the B operand of O^T += V^T P^T (four more MFMAs).  The key order inside a contraction
-// slab is whatever the accumulator layout dictates; V^T is read from LDS with the transposing
-// ds_read_b64_tr_b16 in exactly that order, so P never moves between lanes.
-//
-// Pipeline: the logits of tile t+1 are issued to the matrix cores in the same straight-line
-// region as the exponentials of tile t and its P V products, so MFMA and VALU work of one
-// wavefront can overlap; K therefore runs one tile ahead of V in LDS.
+// Per tile and 32-query group a wavefront computes S^T = K Q^T with four
+// v_mfma_f32_32x32x16_bf16 (keys are the M dimension, so every lane owns ONE query column and
+// 16 of its logits: row maximum and row sum are in-lane reductions plus one exchange with
+// lane^32), applies the online softmax in fp32, and feeds P^T straight from the accumulator
+// registers (converted to bf16) as the B operand of O^T += V^T P^T (four more MFMAs).  The key
+// order inside a contraction slab is whatever the accumulator layout dictates; V^T is read
+// from LDS with the transposing ds_read_b64_tr_b16 in exactly that order, so P never moves
+// between lanes.
 //
 // Softmax bookkeeping: Q is pre-multiplied by scale*log2(e) (rounded to bf16 once), and the
-// logits accumulator of a tile starts at minus the row's current reference m_ref instead of
-// zero, so the MFMA result is directly the exponent s*c - m_ref and each probability costs one
-// v_exp_f32.  m_ref is only moved when a row's tile maximum exceeds 2^8 above it (then the
-// tile's exponents, the running sum and the output accumulators are shifted), or on the first
-// visible key of a branch; probabilities therefore stay below 2^8, far inside bf16 range.
-#include "common.h"
+// logits of a tile are started by one extra matrix instruction that broadcasts minus the row's
+// current reference m_ref (an exact three-term bf16 split), so the MFMA result is directly the
+// exponent s*c - m_ref and each probability costs one v_exp_f32, with no per-element VALU
+// initialisation.  The common tile takes its exponentials speculatively against the current
+// references and is accepted when every lane's probabilities sum to at most 2^12; only a
+// branch's first visible key, or a maximum that ran more than 2^8 above the reference, sends
+// the tile through the slow path (row maxima, shift of the tile's exponents, the running sum
+// and the output accumulators, exponentials again).  Row sums are plain fp32 adds: the packed
+// dot-product instructions execute on the matrix pipeline and would stall the MFMAs.
 #include "launch.h"
+#include "mfma_common.h"
 
 namespace blossom {
 
+using namespace mfma;
+
 namespace {
 
-typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
-typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
-typedef short s16x4 __attribute__((ext_vector_type(4)));
-typedef short s16x8 __attribute__((ext_vector_type(8)));
-typedef float f32x16 __attribute__((ext_vector_type(16)));
-typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr int D = 64;
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kNegInf = -__builtin_huge_valf();
 constexpr float kRaise = 8.0f;  // log2 units by which the maximum must grow before it is raised
 constexpr int kMaxTiles = 96;   // window blocks + selected blocks one query block may walk (host-checked)
 constexpr int kFewKeys = 32;    // rows seeing fewer keys than this get two-term bf16 probabilities
+constexpr float kSumLimit = 4096.0f;  // a lane's 16 probabilities of a tile may sum to this (16 * 2^kRaise)
 
-typedef __attribute__((address_space(3))) s16x4 lds_s16x4;
-typedef __attribute__((address_space(3))) void lds_void;
-typedef const __attribute__((address_space(1))) void glb_void;
-
-// Maps the hardware workgroup id (dealt round-robin over the 8 XCDs) to a virtual id such that
-// each XCD works through a contiguous range: all query blocks of a head then share one L2.
-__device__ __forceinline__ unsigned xcd_remap(unsigned pid, unsigned total)
-{
-  constexpr unsigned X = 8;
-  const unsigned per = (total + X - 1) / X;  // ids of a "tall" XCD
-  const unsigned tall = total % X ? total % X : X;
-  const unsigned xcd = pid % X, local = pid / X;
-  return xcd < tall ? xcd * per + local : tall * per + (xcd - tall) * (per - 1) + local;
-}
+// s_waitcnt immediate that waits until at most n vector-memory operations are outstanding and
+// leaves the other counters alone (gfx9 encoding: vmcnt in bits 3:0 and 15:14, expcnt 6:4,
+// lgkmcnt 11:8).
+constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >> 4) << 14); }
 
 }  // namespace
 
 template <int BLK>
-__global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__restrict__ Q,
-                                                           const uint16_t *__restrict__ K,
-                                                           const uint16_t *__restrict__ V,
-                                                           const int *__restrict__ valid_len,
-                                                           const int *__restrict__ sel,
-                                                           const float *__restrict__ gate_w,
-                                                           const float *__restrict__ gate_b,
-                                                           uint16_t *__restrict__ O,
-                                                           float *__restrict__ o_lt_out,
-                                                           float *__restrict__ o_st_out,
-                                                           float *__restrict__ lse_lt_out,
-                                                           float *__restrict__ lse_st_out, int dense,
-                                                           KParams p)
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_mfma_kernel(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int *__restrict__ valid_len, const int *__restrict__ sel, const float *__restrict__ gate_w,
+    const float *__restrict__ gate_b, uint16_t *__restrict__ O, float *__restrict__ o_lt_out,
+    float *__restrict__ o_st_out, float *__restrict__ lse_lt_out, float *__restrict__ lse_st_out, int dense,
+    KParams p)
 {
-  constexpr int UNITS = BLK / 32;  // 32-key units per tile
-  constexpr int TILE = BLK * D;    // bf16 elements of one staged tile (rows of 128 bytes, swizzled)
+  constexpr int NQ = BLK / 32;   // 32-query groups per wavefront == wavefronts per workgroup
+  constexpr int TILE = BLK * D;  // bf16 elements of one staged tile (rows of 128 bytes, swizzled)
+  constexpr int HALF = 32 * D;   // elements of the 32 rows one wavefront stages and reads
   // Four separate arrays (not one indexed by parity): the compiler can then prove that a
   // prefetch in flight into one buffer does not alias the operand reads of another, and does
   // not wait for the prefetch before those reads.
@@ -88,8 +69,9 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
-  __shared__ int tiles[kMaxTiles];  // key blocks in processing order: window blocks, then selected blocks
-  __shared__ float gate_s[2 * D];   // this head's gate weights, fetched at the start, used at the very end
+  __shared__ int tiles[kMaxTiles];    // key blocks in processing order: window blocks, then selected blocks
+  __shared__ float gate_s[2 * D];     // this head's gate weights, fetched at the start, used at the very end
+  __shared__ float xch_s[NQ][2][64];  // branch merge: reference and partial row sum handed to the partner
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -103,32 +85,41 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
   const int bh = (int)(vid / p.NB);
   const int I = p.NB - 1 - (int)(vid % p.NB);
   const int h = bh % p.H;
-  const int q0 = I * BLK + 32 * wv;  // first query row of this wavefront
-  const int iq = q0 + lq;            // this lane's query row
   const size_t head = (size_t)bh * p.L * D;
+  // Local query group g covers rows I*BLK + 32*(g ^ wv) + lq: group 0 is always the one this
+  // wavefront finishes and stores, group 1 the one it hands to its partner.
+  int qbase[NQ], iq[NQ];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) {
+    qbase[g] = I * BLK + 32 * (g ^ wv);
+    iq[g] = qbase[g] + lq;
+  }
 
   // ---- everything the prologue needs from memory is requested before anything is waited for ----
   const int n_raw = valid_len[bh / p.H];
-  uint4 qraw[4];
-  {
-    const uint16_t *qrow = Q + head + (size_t)min(iq, p.L - 1) * D;
+  uint4 qraw[NQ][4];
 #pragma unroll
-    for (int kk = 0; kk < 4; ++kk) qraw[kk] = *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh);
+  for (int g = 0; g < NQ; ++g) {
+    const uint16_t *qrow = Q + head + (size_t)min(iq[g], p.L - 1) * D;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) qraw[g][kk] = *reinterpret_cast<const uint4 *>(qrow + 16 * kk + 8 * lh);
   }
   const int *my_sel = dense ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
   const int sel0 = (!dense && lane < p.k) ? my_sel[lane] : -1;  // first 64 entries of the selection row
-  constexpr int GATE_PER = 2 * D / (2 * BLK);  // gate weights fetched per thread
+  constexpr int GATE_PER = 2 * D / (2 * BLK);                    // gate weights fetched per thread
   float gate_mine[GATE_PER];
 #pragma unroll
   for (int c = 0; c < GATE_PER; ++c) gate_mine[c] = dense ? 0.0f : gate_w[(size_t)h * 2 * D + c * 2 * BLK + tid];
 
   const int n = clamp_len(n_raw, p.L);
   const int p0 = p.L - n;
-  const bool q_ok = iq < p.L && iq >= p0;
+  bool q_ok[NQ];
+#pragma unroll
+  for (int g = 0; g < NQ; ++g) q_ok[g] = iq[g] < p.L && iq[g] >= p0;
 
   if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query in the block: zero outputs
-    if (iq < p.L) {
-      const size_t ro = head + (size_t)iq * D + 32 * lh;
+    if (iq[0] < p.L) {
+      const size_t ro = head + (size_t)iq[0] * D + 32 * lh;
 #pragma unroll
       for (int c = 0; c < 32; c += 8) *reinterpret_cast<uint4 *>(O + ro + c) = make_uint4(0u, 0u, 0u, 0u);
       if (o_lt_out)
@@ -138,8 +129,8 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
           *reinterpret_cast<float4 *>(o_st_out + ro + c) = make_float4(0.f, 0.f, 0.f, 0.f);
         }
       if (lh == 0) {
-        if (lse_lt_out) lse_lt_out[(size_t)bh * p.L + iq] = 0.0f;
-        if (lse_st_out) lse_st_out[(size_t)bh * p.L + iq] = 0.0f;
+        if (lse_lt_out) lse_lt_out[(size_t)bh * p.L + iq[0]] = 0.0f;
+        if (lse_st_out) lse_st_out[(size_t)bh * p.L + iq[0]] = 0.0f;
       }
     }
     return;
@@ -158,55 +149,60 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     n_st = I - J_lo + 1;
   }
 
-  // ---- staging: each wavefront moves 4 x 1 KB of K and of V per tile ----
+  // ---- staging: each wavefront moves its 32 rows (4 x 1 KB) of K and of V per tile ----
   // LDS position of 16-byte chunk c of row r:  r*128 + ((c ^ swz(r)) * 16),
   //   swzK(r) = r & 7 (8 rows x one chunk column = 8 distinct positions for the row-per-lane reads)
   //   swzV(r) = 2*(r & 3) (4 rows x two chunk columns = 8 distinct positions for the transposing reads)
-  const uint16_t *Kh = K + head;
-  const uint16_t *Vh = V + head;
+  // A tile's rows are contiguous in memory, and the LDS copy keeps the 128-byte row pitch, so
+  // one uniform base (SGPRs) + one per-lane byte offset + the same immediate for the global
+  // and the LDS side addresses all four 8-row slices.
+  const char *Kh = reinterpret_cast<const char *>(K + head);
+  const char *Vh = reinterpret_cast<const char *>(V + head);
   const int ld_row = 32 * wv + (lane >> 3);  // + 8*u
-  const int ld_ck = ((lane & 7) ^ (lane >> 3)) * 8;
-  const int ld_cv = ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8;
-  const uint16_t *k_lane = Kh + ld_row * D + ld_ck;  // this lane's chunk inside block 0
-  const uint16_t *v_lane = Vh + ld_row * D + ld_cv;
+  const unsigned k_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (lane >> 3)) * 8) * 2u;            // bytes
+  const unsigned v_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8) * 2u;  // bytes
   const bool ragged = p.L % BLK != 0;
-  auto stage = [&](const uint16_t *src_lane, uint16_t *dst_tile, int J) {
+  auto stage = [&](const char *src_head, unsigned lane_off, uint16_t *dst_tile, int J) __attribute__((always_inline)) {
+    const char *src = src_head + (size_t)J * (TILE * 2);  // uniform
+    lds_void *dst = (lds_void *)(dst_tile + 32 * wv * D);
     if (!ragged || J != p.NB - 1) {
-      const uint16_t *src = src_lane + (size_t)J * TILE;  // lane pointer + uniform tile offset
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        __builtin_amdgcn_global_load_lds((glb_void *)(src + 8 * u * D),
-                                         (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 1024, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 2048, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 3072, 0);
     } else {  // last, partial block: rows past the end are clamped (they are causally masked anyway)
+      // (the empty asm hides that J is a constant here: the clamped per-lane offsets would
+      // otherwise be computed ahead of the loop and held in registers throughout)
+      asm volatile("" : "+s"(J));
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int over = max(0, J * BLK + ld_row + 8 * u - (p.L - 1));
-        const uint16_t *src = src_lane + (size_t)J * TILE + (8 * u - over) * D;
-        __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+        const unsigned off = lane_off + (unsigned)((8 * u - over) * D * 2);
+        __builtin_amdgcn_global_load_lds((glb_void *)(src + off), (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
       }
     }
   };
 
-  // the first tiles are on their way while the rest of the prologue runs
+  // the first tile is on its way while the rest of the prologue runs
   const int first_J = dense ? J_first : J_lo;
-  const bool second_known = dense ? (I > J_first) : (n_st > 1);  // tile 1 is first_J + 1
-  stage(k_lane, Ks0, first_J);
-  stage(v_lane, Vs0, first_J);
-  if (second_known) stage(k_lane, Ks1, first_J + 1);
+  stage(Kh, k_lane, Ks0, first_J);
+  stage(Vh, v_lane, Vs0, first_J);
 
   // Q^T operand: lane (query lq, half lh) holds c*Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk,
   // c = scale*log2(e), rounded to bf16: the matrix cores then produce base-2 exponents directly.
   const float c2 = p.scale * kLog2e;
-  bf16x8 qf[4];
+  bf16x8 qf[NQ][4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) {
-    const uint32_t w[4] = {qraw[kk].x, qraw[kk].y, qraw[kk].z, qraw[kk].w};
+  for (int g = 0; g < NQ; ++g)
 #pragma unroll
-    for (int e = 0; e < 4; ++e) {
-      qf[kk][2 * e] = (__bf16)(__uint_as_float(w[e] << 16) * c2);
-      qf[kk][2 * e + 1] = (__bf16)(__uint_as_float(w[e] & 0xFFFF0000u) * c2);
+    for (int kk = 0; kk < 4; ++kk) {
+      const uint32_t w[4] = {qraw[g][kk].x, qraw[g][kk].y, qraw[g][kk].z, qraw[g][kk].w};
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        qf[g][kk][2 * e] = (__bf16)(bf_lo(w[e]) * c2);
+        qf[g][kk][2 * e + 1] = (__bf16)(bf_hi(w[e]) * c2);
+      }
     }
-  }
   if (!dense)
 #pragma unroll
     for (int c = 0; c < GATE_PER; ++c) gate_s[c * 2 * BLK + tid] = gate_mine[c];
@@ -248,243 +244,303 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     if (dense) return J_first + t;
     return __builtin_amdgcn_readfirstlane(tiles[t]);
   };
-  if (!second_known && n_all > 1) stage(k_lane, Ks1, tile_of(1));
 
-  // ---- per-lane LDS read offsets (elements) ----
+  // ---- per-lane LDS read offsets (elements) inside this wavefront's 32 rows ----
   int koff[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) koff[kk] = lq * D + (((2 * kk + lh) ^ (lq & 7)) * 8);
+  for (int kk = 0; kk < 4; ++kk) koff[kk] = wv * HALF + lq * D + (((2 * kk + lh) ^ (lq & 7)) * 8);
   const int r16 = lane & 15;
   int voff[2];
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
-    voff[mb] = (4 * lh + (r16 >> 2)) * D +
+    voff[mb] = wv * HALF + (4 * lh + (r16 >> 2)) * D +
                (((4 * mb + 2 * ((lane >> 4) & 1) + ((r16 & 3) >> 1)) ^ (2 * (r16 >> 2))) * 8) + 4 * (r16 & 1);
 
-  // Per-row softmax state.  m_ref: reference exponent (log2 units) the accumulators are relative
-  // to; fresh: nothing accumulated yet in this branch; l_run: this lane's part of the row sum.
-  f32x16 oacc[2];
-  float m_ref = 0.0f, l_run;
-  bool fresh;
-  auto reset = [&]() {
-    fresh = true;
-    l_run = 0.0f;
+  // Per-row softmax state of each query group.  m_ref: reference exponent (log2 units) the
+  // accumulators are relative to; fresh: no visible key met yet in this branch; l_run: this
+  // lane's part of the row sum.  Rows that are padding never become valid: they are not
+  // "fresh" either, so they never ask for the slow path below (their outputs are zeroed).
+  f32x16 oacc[NQ][2];
+  float m_ref[NQ], l_run[NQ];
+  bool fresh[NQ];
+  // -m_ref as an operand: the logits of a tile are started by one extra matrix instruction
+  // ones[key][0..2] x (hi, mid, lo of -m_ref)[0..2][query], a three-term bf16 split that
+  // represents the fp32 value exactly, so no per-element VALU initialisation is needed.
+  bf16x8 mneg[NQ];
+  bf16x8 ones_k;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.0f; oacc[1][i] = 0.0f; }
+  for (int e = 0; e < 8; ++e) ones_k[e] = (__bf16)((lh == 0 && e < 3) ? 1.0f : 0.0f);
+  auto set_ref = [&](int g, float m) __attribute__((always_inline)) {
+    m_ref[g] = m;
+    const float x = -m;
+    const __bf16 hi = (__bf16)x;
+    const float r1 = x - (float)hi;
+    const __bf16 mid = (__bf16)r1;
+    const __bf16 lo = (__bf16)(r1 - (float)mid);
+    const __bf16 zero = (__bf16)0.0f;
+    mneg[g] = bf16x8{lh == 0 ? hi : zero, lh == 0 ? mid : zero, lh == 0 ? lo : zero, zero, zero, zero, zero, zero};
   };
-  auto finish = [&]() -> float {  // normalise the running state into oacc, return lse (natural log)
-    const float l_tot = l_run + __shfl_xor(l_run, 32);
-    const bool ok = q_ok && l_tot > 0.0f;
-    const float inv = ok ? 1.0f / l_tot : 0.0f;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { oacc[0][i] *= inv; oacc[1][i] *= inv; }
-    return ok ? (m_ref + __log2f(l_tot)) * kLn2 : 0.0f;
-  };
-  // exponents of one tile: sacc = c*K Q^T - m_ref
-  auto qk = [&](const uint16_t *ks, f32x16 (&sacc)[UNITS]) {
-    const float init = -m_ref;
+  for (int g = 0; g < NQ; ++g) set_ref(g, 0.0f);
+  auto reset = [&]() __attribute__((always_inline)) {
 #pragma unroll
-    for (int s = 0; s < UNITS; ++s)
+    for (int g = 0; g < NQ; ++g) {
+      fresh[g] = q_ok[g];
+      l_run[g] = 0.0f;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) sacc[s][i] = init;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-      for (int s = 0; s < UNITS; ++s) {
-        const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + 32 * s * D + koff[kk]);
-        sacc[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[kk], sacc[s], 0, 0, 0);
-      }
+      for (int i = 0; i < 16; ++i) { oacc[g][0][i] = 0.0f; oacc[g][1][i] = 0.0f; }
+    }
   };
 
   // Rows that see only a few keys have large probabilities, and rounding those to bf16 would
   // leave a relative error of 2^-9 in the saved branch outputs, which backward amplifies
-  // through D = dO_x.o_x.  Wavefronts that may hold such rows (fewer than kFewKeys keys) feed
-  // P to the matrix cores as a two-term bf16 sum (hi + lo); everyone else uses one term.
-  bool hp_st, hp_lt;
+  // through D = dO_x.o_x.  Blocks that may hold such rows (fewer than kFewKeys keys) feed P to
+  // the matrix cores as a two-term bf16 sum (hi + lo); everyone else uses one term.
+  int hp_st, hp_lt;  // uniform
   if (dense) {
-    hp_st = false;
-    hp_lt = q0 - p0 + 1 < kFewKeys;
+    hp_st = 0;
+    hp_lt = I * BLK - p0 + 1 < kFewKeys;
   } else {
-    hp_st = p.w < kFewKeys || q0 - p0 + 1 < kFewKeys;
-    hp_lt = lt_few;
+    hp_st = p.w < kFewKeys || I * BLK - p0 + 1 < kFewKeys;
+    hp_lt = __builtin_amdgcn_readfirstlane((int)lt_few);
   }
 
   // ---- per-tile pieces ----
-  // prep: mask the exponents of tile J and move the row reference if needed (see file header).
-  auto prep = [&](int J, bool windowed, f32x16 (&sacc)[UNITS]) {
-    if (windowed || J == I || J * BLK < p0) {
-      // visible <=> lo <= key <= iq with lo = max(p0, iq - w + 1); per lane this is one range
-      // test on the element's compile-time key offset
-      const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
-      const int base = J * BLK + 4 * lh;
-      const unsigned span = (unsigned)(iq - lo);  // wraps to huge when iq < lo: handled by q-validity below
-      const bool any = iq >= lo;
+  // visible <=> lo <= key <= iq with lo = max(p0, iq - w + 1); per lane this is one range test
+  // on the element's compile-time key offset
+  auto mask = [&](int J, bool windowed, int g, f32x16 &s) __attribute__((always_inline)) {
+    // (The query row is rebuilt from the lane id inside a volatile asm: everything derived
+    // below would otherwise be loop invariant, get hoisted, and sit in registers or spill
+    // slots across the whole walk.)
+    int ql;
+    asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(ql));
+    const int q = qbase[g] + (ql & 31);
+    const int lh = ql >> 5;
+    asm volatile("" : "+s"(J));
+    const int lo = windowed ? max(p0, q - p.w + 1) : p0;
+    const int base = J * BLK + 32 * wv + 4 * lh;
+    const unsigned span = (unsigned)(q - lo);  // wraps to huge when q < lo: handled by `any`
+    const bool any = q >= lo;
 #pragma unroll
-      for (int s = 0; s < UNITS; ++s)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = base + 32 * s + 8 * (i >> 2) + (i & 3);
-          const bool vis = any & ((unsigned)(key - lo) <= span);
-          sacc[s][i] = vis ? sacc[s][i] : kNegInf;
-        }
+    for (int i = 0; i < 16; ++i) {
+      const int key = base + 8 * (i >> 2) + (i & 3);
+      const bool vis = any & ((unsigned)(key - lo) <= span);
+      s[i] = vis ? s[i] : kNegInf;
     }
+  };
+  auto row_max = [&](const f32x16 &s) __attribute__((always_inline)) -> float {
     float m4[4];
 #pragma unroll
-    for (int c = 0; c < 4; ++c) m4[c] = sacc[0][c];
+    for (int c = 0; c < 4; ++c) m4[c] = s[c];
 #pragma unroll
-    for (int s = 0; s < UNITS; ++s)
-#pragma unroll
-      for (int i = (s == 0 ? 4 : 0); i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], sacc[s][i]);
+    for (int i = 4; i < 16; ++i) m4[i & 3] = fmaxf(m4[i & 3], s[i]);
     float mx = fmaxf(fmaxf(m4[0], m4[1]), fmaxf(m4[2], m4[3]));
-    {  // other half of the row lives in lane^32
-      const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
-      mx = fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
-    }
-    // move the reference: first visible key of the branch, or the tile maximum ran away upwards
-    const bool upd = fresh ? mx != kNegInf : mx > kRaise;
-    if (__any(upd)) {
-      const float dlt = upd ? mx : 0.0f;
-      const float alpha = (upd && !fresh) ? __builtin_amdgcn_exp2f(-dlt) : 1.0f;
-      l_run *= alpha;
+    // the other half of the wavefront's keys for this query lives in lane^32
+    const u32x2 sw = __builtin_amdgcn_permlane32_swap(__float_as_uint(mx), __float_as_uint(mx), false, false);
+    return fmaxf(__uint_as_float(sw[0]), __uint_as_float(sw[1]));
+  };
+  // Slow path of the reference bookkeeping: moves the reference of group g to the tile maximum
+  // where a row meets its first visible key or where the maximum ran away upwards, and shifts
+  // the tile's exponents, the running sum and the output accumulators accordingly.
+  auto move_ref = [&](int g, f32x16 &s) __attribute__((always_inline)) {
+    const float mx = row_max(s);
+    const bool upd = fresh[g] ? mx != kNegInf : mx > kRaise;
+    const float dlt = upd ? mx : 0.0f;
+    const float alpha = (upd && !fresh[g]) ? __builtin_amdgcn_exp2f(-dlt) : 1.0f;
+    l_run[g] *= alpha;
 #pragma unroll
-      for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
+    for (int i = 0; i < 16; ++i) { oacc[g][0][i] *= alpha; oacc[g][1][i] *= alpha; }
 #pragma unroll
-      for (int s = 0; s < UNITS; ++s)
-#pragma unroll
-        for (int i = 0; i < 16; ++i) sacc[s][i] -= dlt;
-      m_ref += dlt;
-      fresh = fresh && !upd;
-    }
+    for (int i = 0; i < 16; ++i) s[i] -= dlt;
+    set_ref(g, m_ref[g] + dlt);
+    fresh[g] = fresh[g] && !upd;
   };
 
-  const bf16x2 ones = {(__bf16)1.0f, (__bf16)1.0f};
-  // exponentials of one 32-key unit: sacc <- p (fp32), pf <- bf16(p), l_run += sum of bf16(p)
-  auto expo = [&](f32x16 &sacc, bf16x8 (&pf)[2]) {
+  // exponentials of one group: pf <- bf16(2^s), returns this lane's sum of the probabilities.
+  // (Plain fp32 adds: the packed dot-product instructions would do the bf16 sum in one step,
+  // but they execute on the matrix pipeline and stall the MFMAs of every wavefront of the SIMD.)
+  auto expo = [&](const f32x16 &s, bf16x8 (&pf)[2]) __attribute__((always_inline)) -> float {
+    float sum_a = 0.0f, sum_b = 0.0f;
 #pragma unroll
     for (int i = 0; i < 16; i += 2) {
-      const float pa = __builtin_amdgcn_exp2f(sacc[i]);
-      const float pb = __builtin_amdgcn_exp2f(sacc[i + 1]);
-      sacc[i] = pa;
-      sacc[i + 1] = pb;
-      const bf16x2 pk = {(__bf16)pa, (__bf16)pb};
-      pf[i >> 3][i & 7] = pk[0];
-      pf[i >> 3][(i & 7) + 1] = pk[1];
-      l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);  // sums what the MFMA will see
+      const float pa = __builtin_amdgcn_exp2f(s[i]);
+      const float pb = __builtin_amdgcn_exp2f(s[i + 1]);
+      pf[i >> 3][i & 7] = (__bf16)pa;
+      pf[i >> 3][(i & 7) + 1] = (__bf16)pb;
+      sum_a += pa;
+      sum_b += pb;
     }
+    return sum_a + sum_b;
   };
-  // V^T operands of one unit: [t][mb], keys in accumulator order
-  auto load_v = [&](const uint16_t *vs, int s, bf16x8 (&vf)[2][2]) {
+  // second bf16 term of P (what the first term's rounding lost); the row sum already holds it
+  auto expo_lo = [&](const f32x16 &s, const bf16x8 (&pf)[2], bf16x8 (&pl)[2]) __attribute__((always_inline)) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      pl[i >> 3][i & 7] = (__bf16)(__builtin_amdgcn_exp2f(s[i]) - (float)pf[i >> 3][i & 7]);
+  };
+  // V^T operands of the wavefront's 32 keys: [t][mb], keys in accumulator order
+  auto load_v = [&](const uint16_t *vs, bf16x8 (&vf)[2][2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb) {
-        const uint16_t *a0 = vs + (32 * s + 16 * t) * D + voff[mb];
+        const uint16_t *a0 = vs + 16 * t * D + voff[mb];
         const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0));
         const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a0 + 8 * D));
         vf[t][mb] = __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
       }
   };
-  auto pv = [&](const bf16x8 (&vf)[2][2], const bf16x8 (&pf)[2]) {
+  auto pv = [&](int g, const bf16x8 (&vf)[2][2], const bf16x8 (&pf)[2]) __attribute__((always_inline)) {
 #pragma unroll
     for (int t = 0; t < 2; ++t)
 #pragma unroll
       for (int mb = 0; mb < 2; ++mb)
-        oacc[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][mb], pf[t], oacc[mb], 0, 0, 0);
+        oacc[g][mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(vf[t][mb], pf[t], oacc[g][mb], 0, 0, 0);
   };
 
-  // One tile: logits of the next tile (K from ks_next), exponentials of this one and P V.
-  auto tile_body = [&](const uint16_t *vs, const uint16_t *ks_next, bool windowed,
-                       f32x16 (&sacc)[UNITS], f32x16 (&snext)[UNITS]) {
-    const bool hp = __builtin_amdgcn_readfirstlane((int)(windowed ? hp_st : hp_lt)) != 0;
-    bf16x8 kf[UNITS][4];
+  // One tile (this wavefront's 32 keys of block J against every query group).
+  //
+  // The common case costs no bookkeeping beyond the exponentials: they are taken against the
+  // current references, and the tile is accepted if every lane's sum of probabilities stays
+  // below 2^12 (so no probability can exceed it) and no row is still waiting for its first
+  // key.  Otherwise the slow path finds the row maxima, moves the references and takes the
+  // exponentials again; it raises a reference whenever a probability would exceed 2^kRaise,
+  // which also guarantees that the retaken tile passes.
+  auto tile = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
+    const bool hp = (windowed ? hp_st : hp_lt) != 0;
+    // The empty asm makes the read offsets look freshly computed: buffer base + offset is then
+    // formed next to each read, where it folds into the instruction's immediate, instead of
+    // being kept in one register per (buffer, fragment) across the whole loop.
+    asm volatile("" : "+v"(koff[0]), "+v"(koff[1]), "+v"(koff[2]), "+v"(koff[3]), "+v"(voff[0]), "+v"(voff[1]));
+    // block-level visibility of the 32 keys for the 32 queries of each group (uniform): tiles
+    // whose keys every query sees skip the mask arithmetic
+    const int k_lo = J * BLK + 32 * wv, k_hi = k_lo + 31;
+    bool full[NQ], all_full = true;
 #pragma unroll
-    for (int s = 0; s < UNITS; ++s)
-#pragma unroll
-      for (int kk = 0; kk < 4; ++kk)
-        kf[s][kk] = *reinterpret_cast<const bf16x8 *>(ks_next + 32 * s * D + koff[kk]);
-    bf16x8 vf[2][2];
-    load_v(vs, 0, vf);
-    const float init = -m_ref;
-#pragma unroll
-    for (int s = 0; s < UNITS; ++s)
-#pragma unroll
-      for (int i = 0; i < 16; ++i) snext[s][i] = init;
-#pragma unroll
-    for (int kk = 0; kk < 4; ++kk)
-#pragma unroll
-      for (int s = 0; s < UNITS; ++s)
-        snext[s] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[s][kk], qf[kk], snext[s], 0, 0, 0);
-    bf16x8 pf[UNITS][2];
-#pragma unroll
-    for (int s = 0; s < UNITS; ++s) {
-      expo(sacc[s], pf[s]);
-      pv(vf, pf[s]);
-      if (s + 1 < UNITS) load_v(vs, s + 1, vf);
+    for (int g = 0; g < NQ; ++g) {
+      const int q_lo = qbase[g], q_hi = qbase[g] + 31;
+      full[g] = k_hi <= q_lo && k_lo >= p0 && (!windowed || k_lo >= q_hi - p.w + 1);
+      all_full = all_full && full[g];
     }
-    if (hp) {  // second bf16 term of P
+    f32x16 s[NQ];
+    const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-      for (int s = 0; s < UNITS; ++s) {
+    for (int g = 0; g < NQ; ++g) s[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones_k, mneg[g], zero16, 0, 0, 0);
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {  // each K fragment serves every query group
+      const bf16x8 kf = *reinterpret_cast<const bf16x8 *>(ks + koff[kk]);
+#pragma unroll
+      for (int g = 0; g < NQ; ++g) s[g] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf, qf[g][kk], s[g], 0, 0, 0);
+    }
+    if (!all_full) {
+#pragma unroll
+      for (int g = 0; g < NQ; ++g)
+        if (!full[g]) mask(J, windowed, g, s[g]);
+    }
+    bf16x8 vf[2][2];
+    load_v(vs, vf);
+    bf16x8 pf[NQ][2];
+#pragma unroll
+    for (int g = 0; g < NQ; ++g) {  // the P V products of one group run under the exponentials of the next
+      float tsum = expo(s[g], pf[g]);
+      if (__any(fresh[g] || !(tsum <= kSumLimit))) {
+        move_ref(g, s[g]);
+        tsum = expo(s[g], pf[g]);
+      }
+      l_run[g] += tsum;
+      pv(g, vf, pf[g]);
+    }
+    if (hp) {
+#pragma unroll
+      for (int g = 0; g < NQ; ++g) {
         bf16x8 pl[2];
-#pragma unroll
-        for (int i = 0; i < 16; i += 2) {
-          const bf16x2 pk = {(__bf16)(sacc[s][i] - (float)pf[s][i >> 3][i & 7]),
-                             (__bf16)(sacc[s][i + 1] - (float)pf[s][i >> 3][(i & 7) + 1])};
-          pl[i >> 3][i & 7] = pk[0];
-          pl[i >> 3][(i & 7) + 1] = pk[1];
-          l_run = __builtin_amdgcn_fdot2_f32_bf16(pk, ones, l_run, false);
-        }
-        load_v(vs, s, vf);
-        pv(vf, pl);
+        expo_lo(s[g], pf[g], pl);
+        pv(g, vf, pl);
       }
     }
   };
 
-  // ---- pipeline over the tile list: K runs one tile ahead of V ----
-  f32x16 ost[2];  // normalised short-term output, parked while the long-term branch runs
+  // Closes a branch.  With two wavefronts each holds, for every query, a partial result over
+  // its own key rows; the partial for the partner's queries (group 1) goes through LDS (staging
+  // rows kx/vx of this wavefront, free at this point), the partner's partial for this
+  // wavefront's queries comes back the same way, and both are brought to a common reference.
+  // Leaves the normalised output of group 0 in oacc[0] and returns its lse (natural log).
+  auto close_branch = [&](uint16_t *kx, uint16_t *vx) __attribute__((always_inline)) -> float {
+    if constexpr (NQ == 2) {
+      float *mine_a = reinterpret_cast<float *>(kx + wv * HALF);  // 16 registers x 64 lanes each
+      float *mine_b = reinterpret_cast<float *>(vx + wv * HALF);
+      const float *part_a = reinterpret_cast<const float *>(kx + (wv ^ 1) * HALF);
+      const float *part_b = reinterpret_cast<const float *>(vx + (wv ^ 1) * HALF);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        mine_a[i * 64 + lane] = oacc[NQ - 1][0][i];
+        mine_b[i * 64 + lane] = oacc[NQ - 1][1][i];
+      }
+      xch_s[wv][0][lane] = fresh[NQ - 1] ? kNegInf : m_ref[NQ - 1];
+      xch_s[wv][1][lane] = l_run[NQ - 1];
+      __syncthreads();
+      const float m_b = xch_s[wv ^ 1][0][lane];
+      const float l_b = xch_s[wv ^ 1][1][lane];
+      const float m_a = fresh[0] ? kNegInf : m_ref[0];
+      const float m = fmaxf(m_a, m_b);
+      const float fa = m_a == kNegInf ? 0.0f : __builtin_amdgcn_exp2f(m_a - m);
+      const float fb = m_b == kNegInf ? 0.0f : __builtin_amdgcn_exp2f(m_b - m);
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        oacc[0][0][i] = oacc[0][0][i] * fa + part_a[i * 64 + lane] * fb;
+        oacc[0][1][i] = oacc[0][1][i] * fa + part_b[i * 64 + lane] * fb;
+      }
+      l_run[0] = l_run[0] * fa + l_b * fb;
+      set_ref(0, m == kNegInf ? 0.0f : m);
+      __syncthreads();  // the partner has read this wavefront's rows: they may be refilled
+    }
+    const float l_tot = l_run[0] + __shfl_xor(l_run[0], 32);
+    const bool ok = q_ok[0] && l_tot > 0.0f;
+    const float inv = ok ? 1.0f / l_tot : 0.0f;
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { oacc[0][0][i] *= inv; oacc[0][1][i] *= inv; }
+    return ok ? (m_ref[0] + __log2f(l_tot)) * kLn2 : 0.0f;
+  };
+
+  // ---- walk over the tile list ----
+  f32x16 ost[2];  // normalised short-term output of group 0, parked while the long-term branch runs
   float lse_st = 0.0f;
   bool st_open = !dense;
   reset();
-  f32x16 sA[UNITS], sB[UNITS];
-  __syncthreads();
-  qk(Ks0, sA);
-  __syncthreads();  // Ks0 may be overwritten from here on
-  auto close_st = [&]() {
-    lse_st = finish();
-    ost[0] = oacc[0];
-    ost[1] = oacc[1];
+  auto close_st = [&](uint16_t *kx, uint16_t *vx) __attribute__((always_inline)) {
+    lse_st = close_branch(kx, vx);
+    ost[0] = oacc[0][0];
+    ost[1] = oacc[0][1];
     reset();
     st_open = false;
   };
-  if (st_open && n_st == 0) close_st();
-  prep(tile_of(0), 0 < n_st, sA);
-
-  // step t: prefetch K(t+2) and V(t+1); exponentials and P V of tile t; logits, mask and
-  // maximum of tile t+1 (the latter overlap the last P V products)
-  auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *v_cur, const uint16_t *k_next,
-                  f32x16 (&scur)[UNITS], f32x16 (&snext)[UNITS]) {
-    if (t + 2 < n_all) stage(k_lane, k_fill, tile_of(t + 2));
-    if (t + 1 < n_all) stage(v_lane, v_fill, tile_of(t + 1));
-    tile_body(v_cur, k_next, t < n_st, scur, snext);
-    if (st_open && t + 1 >= n_st) close_st();  // the window tiles are done: close the short-term branch
-    if (t + 1 < n_all) prep(tile_of(t + 1), t + 1 < n_st, snext);
-    __syncthreads();
+  // step t: prefetch tile t+1 into the other buffer pair, wait for this wavefront's own loads
+  // of tile t (the 8 just issued stay in flight), process tile t
+  int J_cur = first_J;
+  auto step = [&](int t, uint16_t *k_cur, uint16_t *v_cur, uint16_t *k_nxt, uint16_t *v_nxt) __attribute__((always_inline)) {
+    int J_nxt = 0;
+    if (t + 1 < n_all) {
+      J_nxt = tile_of(t + 1);
+      stage(Kh, k_lane, k_nxt, J_nxt);
+      stage(Vh, v_lane, v_nxt, J_nxt);
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+    } else {
+      __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+    }
+    tile(k_cur, v_cur, J_cur, t < n_st);
+    J_cur = J_nxt;
+    if (st_open && t + 1 >= n_st) close_st(k_cur, v_cur);  // the window tiles are done
   };
   for (int t = 0; t < n_all; t += 2) {
-    step(t, Ks0, Vs1, Vs0, Ks1, sA, sB);
-    if (t + 1 < n_all) step(t + 1, Ks1, Vs0, Vs1, Ks0, sB, sA);
+    step(t, Ks0, Vs0, Ks1, Vs1);
+    if (t + 1 < n_all) step(t + 1, Ks1, Vs1, Ks0, Vs0);
   }
-  if (st_open) {  // no usable selection entry at all
-    lse_st = finish();
-    ost[0] = oacc[0];
-    ost[1] = oacc[1];
-    reset();
-  }
-  const float lse_lt = finish();
+  const float lse_lt = close_branch(Ks0, Vs0);
 
-  // ---- epilogue: gate (Eq. 18-19) and stores ----
-  if (iq >= p.L) return;
-  const size_t rowoff = head + (size_t)iq * D;
-  const size_t lrow = (size_t)bh * p.L + iq;
+  // ---- epilogue: gate (Eq. 18-19) and stores of this wavefront's own 32 rows ----
+  if (iq[0] >= p.L) return;
+  const size_t rowoff = head + (size_t)iq[0] * D;
+  const size_t lrow = (size_t)bh * p.L + iq[0];
   if (dense) {
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
@@ -492,8 +548,8 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
       for (int g = 0; g < 4; ++g) {
         const int d0 = 32 * mb + 8 * g + 4 * lh;
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(oacc[mb][4 * g]) | ((uint32_t)f32_to_bf16(oacc[mb][4 * g + 1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(oacc[mb][4 * g + 2]) | ((uint32_t)f32_to_bf16(oacc[mb][4 * g + 3]) << 16);
+        pk.x = (uint32_t)f32_to_bf16(oacc[0][mb][4 * g]) | ((uint32_t)f32_to_bf16(oacc[0][mb][4 * g + 1]) << 16);
+        pk.y = (uint32_t)f32_to_bf16(oacc[0][mb][4 * g + 2]) | ((uint32_t)f32_to_bf16(oacc[0][mb][4 * g + 3]) << 16);
         *reinterpret_cast<uint2 *>(O + rowoff + d0) = pk;
       }
     if (lh == 0 && lse_lt_out) lse_lt_out[lrow] = lse_lt;
@@ -509,10 +565,10 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
       const int d0 = 32 * mb + 8 * g + 4 * lh;
       const float4 a = *reinterpret_cast<const float4 *>(wl + d0);
       const float4 b = *reinterpret_cast<const float4 *>(ws + d0);
-      z = fmaf(a.x, oacc[mb][4 * g], z);
-      z = fmaf(a.y, oacc[mb][4 * g + 1], z);
-      z = fmaf(a.z, oacc[mb][4 * g + 2], z);
-      z = fmaf(a.w, oacc[mb][4 * g + 3], z);
+      z = fmaf(a.x, oacc[0][mb][4 * g], z);
+      z = fmaf(a.y, oacc[0][mb][4 * g + 1], z);
+      z = fmaf(a.z, oacc[0][mb][4 * g + 2], z);
+      z = fmaf(a.w, oacc[0][mb][4 * g + 3], z);
       z = fmaf(b.x, ost[mb][4 * g], z);
       z = fmaf(b.y, ost[mb][4 * g + 1], z);
       z = fmaf(b.z, ost[mb][4 * g + 2], z);
@@ -520,7 +576,7 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
     }
   z += __shfl_xor(z, 32);
   z += gate_b ? gate_b[h] : 0.0f;
-  const float alpha = q_ok ? 1.0f / (1.0f + __expf(-z)) : 0.0f;
+  const float alpha = q_ok[0] ? 1.0f / (1.0f + __expf(-z)) : 0.0f;
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
@@ -529,14 +585,14 @@ __global__ __launch_bounds__(BLK * 2) void fwd_mfma_kernel(const uint16_t *__res
       float o4[4];
 #pragma unroll
       for (int e = 0; e < 4; ++e)
-        o4[e] = alpha * oacc[mb][4 * g + e] + (1.0f - alpha) * ost[mb][4 * g + e];
+        o4[e] = alpha * oacc[0][mb][4 * g + e] + (1.0f - alpha) * ost[mb][4 * g + e];
       uint2 pk;
       pk.x = (uint32_t)f32_to_bf16(o4[0]) | ((uint32_t)f32_to_bf16(o4[1]) << 16);
       pk.y = (uint32_t)f32_to_bf16(o4[2]) | ((uint32_t)f32_to_bf16(o4[3]) << 16);
       *reinterpret_cast<uint2 *>(O + rowoff + d0) = pk;
       if (o_lt_out) {
         *reinterpret_cast<float4 *>(o_lt_out + rowoff + d0) =
-            make_float4(oacc[mb][4 * g], oacc[mb][4 * g + 1], oacc[mb][4 * g + 2], oacc[mb][4 * g + 3]);
+            make_float4(oacc[0][mb][4 * g], oacc[0][mb][4 * g + 1], oacc[0][mb][4 * g + 2], oacc[0][mb][4 * g + 3]);
         *reinterpret_cast<float4 *>(o_st_out + rowoff + d0) =
             make_float4(ost[mb][4 * g], ost[mb][4 * g + 1], ost[mb][4 * g + 2], ost[mb][4 * g + 3]);
       }
