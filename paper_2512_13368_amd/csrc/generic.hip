@@ -8,6 +8,7 @@
 // the phases are merged with wavefront shuffles at the end.  All accumulation is fp32.
 #include "common.h"
 #include "launch.h"
+#include "mfma_common.h"
 
 namespace blossom {
 
@@ -260,9 +261,12 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float *__restrict__
                                                        const float *__restrict__ gate_b,
                                                        float4 *__restrict__ rowstat,
                                                        float *__restrict__ partial,
-                                                       const T *__restrict__ V,
-                                                       float4 *__restrict__ rowB,
-                                                       float2 *__restrict__ rowC, KParams p)
+                                                       const float *__restrict__ lse_lt,
+                                                       const float *__restrict__ lse_st,
+                                                       uint16_t *__restrict__ g_lt,
+                                                       uint16_t *__restrict__ g_st,
+                                                       uint4 *__restrict__ rowI_lt,
+                                                       uint4 *__restrict__ rowI_st, KParams p)
 {
   constexpr int LPR = D / 4;        // lanes per row
   constexpr int RPW = 64 / LPR;     // rows per wavefront step
@@ -291,23 +295,19 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float *__restrict__
     const bool inb = i < p.L;
     const bool valid = inb && i >= p0;
     float g[4] = {0.f, 0.f, 0.f, 0.f}, ol[4] = {0.f, 0.f, 0.f, 0.f}, os[4] = {0.f, 0.f, 0.f, 0.f};
-    float v[4] = {0.f, 0.f, 0.f, 0.f};
     if (valid) {
       const size_t ro = head + (size_t)i * D + c4;
       load4(dO + ro, g);
       load4(o_lt + ro, ol);
       load4(o_st + ro, os);
-      if (rowC) load4(V + ro, v);
     }
-    float a_ll = 0.f, a_ss = 0.f, w_l = 0.f, w_s = 0.f, v_l = 0.f, v_s = 0.f;
+    float a_ll = 0.f, a_ss = 0.f, w_l = 0.f, w_s = 0.f;
 #pragma unroll
     for (int e = 0; e < 4; ++e) {
       a_ll = fmaf(g[e], ol[e], a_ll);
       a_ss = fmaf(g[e], os[e], a_ss);
       w_l = fmaf(wl[e], ol[e], w_l);
       w_s = fmaf(ws[e], os[e], w_s);
-      v_l = fmaf(wl[e], v[e], v_l);
-      v_s = fmaf(ws[e], v[e], v_s);
     }
 #pragma unroll
     for (int off = 1; off < LPR; off <<= 1) {
@@ -315,26 +315,51 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float *__restrict__
       a_ss += __shfl_xor(a_ss, off);
       w_l += __shfl_xor(w_l, off);
       w_s += __shfl_xor(w_s, off);
-      v_l += __shfl_xor(v_l, off);
-      v_s += __shfl_xor(v_s, off);
     }
     float4 st = make_float4(0.f, 0.f, 0.f, 0.f);
-    float4 rb = make_float4(0.f, 0.f, 0.f, 0.f);
-    float2 rc = make_float2(0.f, 0.f);
-    float dz = 0.0f;
+    float dz = 0.0f, alpha = 0.0f;
     if (valid) {
       const float z = bias + w_l + w_s;
-      const float alpha = 1.0f / (1.0f + __expf(-z));
+      alpha = 1.0f / (1.0f + __expf(-z));
       dz = (a_ll - a_ss) * alpha * (1.0f - alpha);
       st = make_float4(alpha, dz, alpha * a_ll + dz * w_l, (1.0f - alpha) * a_ss + dz * w_s);
-      rb = make_float4(a_ll, a_ss, w_l, w_s);
-      rc = make_float2(v_l, v_s);
     }
-    if (inb && sub == 0) {
-      rowstat[(size_t)bh * p.L + i] = st;
-      if (rowB) {
-        rowB[(size_t)bh * p.L + i] = rb;
-        rowC[(size_t)bh * p.L + i] = rc;
+    if (inb && sub == 0) rowstat[(size_t)bh * p.L + i] = st;
+    if (g_lt) {
+      // Matrix-core path: the upstream gradient of each branch, dO_x = a_x*dO + dz*Wg_x, rounded
+      // to bf16 once, and the row constant c_x = dO_x.o_x taken with the SAME rounded values, so
+      // that P*(dO_x.v - c_x) is the exact softmax backward of the rounded gradient (rows with a
+      // single key still cancel to zero).  -lse*log2(e) and -c_x are left as three-term bf16
+      // splits, the form in which one matrix instruction broadcasts them into an accumulator.
+      uint16_t gl[4], gs[4];
+      float c_l = 0.0f, c_s = 0.0f;
+#pragma unroll
+      for (int e = 0; e < 4; ++e) {
+        gl[e] = f32_to_bf16(fmaf(alpha, g[e], dz * wl[e]));
+        gs[e] = f32_to_bf16(fmaf(1.0f - alpha, g[e], dz * ws[e]));
+        c_l = fmaf(bf16_to_f32(gl[e]), ol[e], c_l);
+        c_s = fmaf(bf16_to_f32(gs[e]), os[e], c_s);
+      }
+#pragma unroll
+      for (int off = 1; off < LPR; off <<= 1) {
+        c_l += __shfl_xor(c_l, off);
+        c_s += __shfl_xor(c_s, off);
+      }
+      if (inb) {
+        const size_t ro = head + (size_t)i * D + c4;
+        *reinterpret_cast<uint2 *>(g_lt + ro) =
+            make_uint2((uint32_t)gl[0] | ((uint32_t)gl[1] << 16), (uint32_t)gl[2] | ((uint32_t)gl[3] << 16));
+        *reinterpret_cast<uint2 *>(g_st + ro) =
+            make_uint2((uint32_t)gs[0] | ((uint32_t)gs[1] << 16), (uint32_t)gs[2] | ((uint32_t)gs[3] << 16));
+        if (sub == 0) {
+          const size_t r = (size_t)bh * p.L + i;
+          // pad rows: an exponent of -1e30 makes every probability of the row zero
+          const uint2 l_l = mfma::split3(valid ? -lse_lt[r] * 1.4426950408889634f : -1.0e30f);
+          const uint2 l_s = mfma::split3(valid ? -lse_st[r] * 1.4426950408889634f : -1.0e30f);
+          const uint2 k_l = mfma::split3(-c_l), k_s = mfma::split3(-c_s);
+          rowI_lt[r] = make_uint4(l_l.x, l_l.y, k_l.x, k_l.y);
+          rowI_st[r] = make_uint4(l_s.x, l_s.y, k_s.x, k_s.y);
+        }
       }
     }
 #pragma unroll
@@ -519,16 +544,22 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
 // =============================================================================================
 constexpr int kMaxNBInv = 4096;
 
-__global__ __launch_bounds__(64) void inverse_list_kernel(const int *__restrict__ sel, int *__restrict__ offs,
+__global__ __launch_bounds__(64) void inverse_list_kernel(const int *__restrict__ sel,
+                                                          const int *__restrict__ valid_len, int *__restrict__ offs,
                                                           int *__restrict__ items, KParams p)
 {
   __shared__ int cnt[kMaxNBInv + 64];
+  __shared__ unsigned char few[kMaxNBInv + 64];  // query block whose selected past blocks hold few valid keys
   const int lane = threadIdx.x;
   const int bh = blockIdx.x;
   const int *s = sel + (size_t)bh * p.NB * p.k;
   int *o = offs + (size_t)bh * (p.NB + 1);
   int *it = items + (size_t)bh * p.NB * p.k;
-  for (int J = lane; J <= p.NB; J += 64) cnt[J] = 0;
+  const int p0 = p.L - clamp_len(valid_len[bh / p.H], p.L);
+  for (int J = lane; J <= p.NB; J += 64) {
+    cnt[J] = 0;
+    few[J] = 1;
+  }
   __syncthreads();
   for (int e0 = 0; e0 < p.k; e0 += 64) {
     const int e = e0 + lane;
@@ -536,6 +567,9 @@ __global__ __launch_bounds__(64) void inverse_list_kernel(const int *__restrict_
     for (int I = 0; I < p.NB; ++I) {
       const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
       if (J >= 0 && J <= I) atomicAdd(&cnt[J], 1);
+      // an earlier block with at least kInvFewKeys valid keys gives every row of I that many keys
+      const int vcount = min((J + 1) * p.b, p.L) - max(J * p.b, p0);
+      if (__ballot(J >= 0 && J < I && vcount >= kInvFewKeys) != 0ull && lane == 0) few[I] = 0;
     }
   }
   __syncthreads();
@@ -562,7 +596,7 @@ __global__ __launch_bounds__(64) void inverse_list_kernel(const int *__restrict_
 #pragma unroll 8
     for (int I = 0; I < p.NB; ++I) {
       const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
-      if (J >= 0 && J <= I) it[atomicAdd(&cnt[J], 1)] = I;
+      if (J >= 0 && J <= I) it[atomicAdd(&cnt[J], 1)] = I | ((int)few[I] << kInvFewShift);
     }
   }
 }
@@ -691,7 +725,7 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     const int *o = offs + (size_t)bh * (p.NB + 1);
     const int *it = items + (size_t)bh * p.NB * p.k;
     const int e_lo = o[J], e_hi = o[J + 1];
-    for (int e = e_lo; e < e_hi; ++e) tile(it[e], false);
+    for (int e = e_lo; e < e_hi; ++e) tile(it[e] & kInvBlockMask, false);
   }
   for (int off = b; off < 64; off <<= 1) {
 #pragma unroll
@@ -750,10 +784,14 @@ BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws)
   w.stage2 = reinterpret_cast<float *>(base + off);
   off = align256(off + (size_t)p.H * kGateSlices * (2 * p.d + 1) * sizeof(float));
   if (bwd_mfma_supported(p, dtype)) {
-    w.rowB = reinterpret_cast<float4 *>(base + off);
-    off = align256(off + BH * p.L * sizeof(float4));
-    w.rowC = reinterpret_cast<float2 *>(base + off);
-    off = align256(off + BH * p.L * sizeof(float2));
+    w.g_lt = reinterpret_cast<uint16_t *>(base + off);
+    off = align256(off + BH * p.L * p.d * sizeof(uint16_t));
+    w.g_st = reinterpret_cast<uint16_t *>(base + off);
+    off = align256(off + BH * p.L * p.d * sizeof(uint16_t));
+    w.rowI_lt = reinterpret_cast<uint4 *>(base + off);
+    off = align256(off + BH * p.L * sizeof(uint4));
+    w.rowI_st = reinterpret_cast<uint4 *>(base + off);
+    off = align256(off + BH * p.L * sizeof(uint4));
   }
   w.total = off;
   return w;
@@ -771,14 +809,14 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
   if (stages & kBwdStageGate) {
     hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(256), 0, st,
                        (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
-                       a.gate_b, w.rowstat, w.partial, (const T *)a.V, w.rowB, w.rowC, p);
+                       a.gate_b, w.rowstat, w.partial, a.lse_lt, a.lse_st, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, p);
     hipLaunchKernelGGL(bwd_gate_reduce1_kernel, dim3((unsigned)p.H, kGateSlices), dim3(256), 0, st, w.partial,
                        w.stage2, w.nchunk, p);
     hipLaunchKernelGGL(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
                        a.d_gate_b, p);
   }
   if (stages & kBwdStageInverse)
-    hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64), 0, st, a.sel, w.offs, w.items, p);
+    hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64), 0, st, a.sel, a.valid_len, w.offs, w.items, p);
   if (mfma) {
     launch_bwd_mfma(p, a, w, stages, st);
     return;

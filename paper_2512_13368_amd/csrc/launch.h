@@ -43,11 +43,14 @@ void launch_select(const KParams &p, int dtype, const void *Q, const void *K, co
 struct BwdWorkspace {
   float4 *rowstat;   // [B*H*L] (alpha, dz, D_lt, D_st)
   int *offs;         // [B*H,(NB+1)] inverse selection list: offsets
-  int *items;        // [B*H,NB*k]   inverse selection list: query blocks, ascending per key block
+  int *items;        // [B*H,NB*k]   inverse selection list: query blocks, ascending per key block;
+                     //              bit kInvFewShift marks a query block whose long-term rows may see few keys
   float *partial;    // [B*H*nchunk,(2d+1)] partial gate-weight gradients
   float *stage2;     // [H,slices,(2d+1)] second reduction level
-  float4 *rowB;      // [B*H*L] (dO.o_lt, dO.o_st, Wg_lt.o_lt, Wg_st.o_st), matrix-core path only
-  float2 *rowC;      // [B*H*L] (Wg_lt.v, Wg_st.v), matrix-core path only
+  // matrix-core path only: per-branch upstream gradient dO_x = a_x*dO + dz*Wg_x in bf16, and per
+  // row the three-term bf16 splits of (-lse_x*log2(e), -dO_x.o_x) as (hi|mid<<16, lo) pairs
+  uint16_t *g_lt, *g_st;      // [B*H*L,d]
+  uint4 *rowI_lt, *rowI_st;   // [B*H*L]
   int nchunk;
   size_t total;
 };
@@ -56,6 +59,11 @@ struct BwdWorkspace {
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
 BwdWorkspace bwd_carve(const KParams &p, int dtype, void *ws);
 size_t bwd_workspace_bytes(const KParams &p, int dtype);
+// inverse selection list entries: query block index, plus a flag for blocks whose selected past
+// blocks hold fewer than kInvFewKeys valid keys (their rows carry large probabilities)
+constexpr int kInvFewKeys = 32;
+constexpr int kInvFewShift = 30;
+constexpr int kInvBlockMask = (1 << kInvFewShift) - 1;
 enum : unsigned { kBwdStageGate = 1u, kBwdStageInverse = 2u, kBwdStageDQ = 4u, kBwdStageDKV = 8u, kBwdStageAll = 15u };
 void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, hipStream_t st);
 

@@ -3,17 +3,23 @@
 // the selection held fixed.
 //
 // The upstream gradient of branch x is dO_x = a_x*dO + dz*Wg_x (a_lt = alpha, a_st = 1-alpha;
-// gate backward).  It is never materialised: rounding it to bf16 for the matrix cores would
-// break the exact cancellation dS = P*(dO_x.v - dO_x.o) = 0 that rows with one key rely on.
-// Everything the matrix cores see is an input tensor (Q, K, V, dO) or a probability; the gate
-// enters through per-row and per-key scalars that the per-row pass leaves in the workspace:
-//   dS_ij = P_ij * ( a_x[i]*(dO_i.v_j - dO_i.o_x,i) + dz[i]*(Wg_x.v_j - Wg_x.o_x,i) )
-//   dV_j  = sum_i (a_x[i] P_ij) dO_i  +  Wg_x * sum_i dz[i] P_ij
-// Accumulators start at minus a per-row constant, so the MFMA result is directly what the
-// next step needs: the exponent S'' = c*q.k - lse*log2(e) (Q or K pre-multiplied by
-// c = scale*log2(e)) and dO_i.v_j - dO_i.o_x,i.  Probabilities and dS leave the accumulator
+// gate backward).  The per-row pass rounds it to bf16 ONCE and derives the row constant
+// c_x = dO_x.o_x from the same rounded values; then
+//   dS_ij = P_ij * (dO_x,i.v_j - c_x,i),   dV_j = sum_i P_ij dO_x,i,   dK_j = sum_i dS_ij q_i,
+//   dQ_i = sum_j dS_ij k_j
+// is the exact softmax backward of the rounded gradient: the cancellation that rows with one
+// or two keys rely on (dO_x.v_j = c_x when P = 1) survives, and the kernels are left with one
+// exponential, one multiply and the bf16 conversions per score.
+//
+// Accumulators start at minus a per-row constant, so the MFMA result is directly what the next
+// step needs: the exponent S'' = c*q.k - lse*log2(e) (Q or K pre-multiplied by c =
+// scale*log2(e)) and dO_x,i.v_j - c_x,i.  The constants arrive as three-term bf16 splits and
+// are broadcast into the accumulator by one extra matrix instruction (ones x split), so no
+// per-element VALU initialisation is needed.  Probabilities and dS leave the accumulator
 // registers as the B operand of the next product without moving between lanes; the matching
-// A operands (K^T, Q^T, dO^T) come from LDS through the transposing ds_read_b64_tr_b16.
+// A operands (K^T, Q^T, dO_x^T) come from LDS through the transposing ds_read_b64_tr_b16.
+// Query blocks whose rows may see only a few keys (large probabilities) feed P and dS as
+// two-term bf16 sums.
 #include "launch.h"
 #include "mfma_common.h"
 
@@ -144,30 +150,41 @@ __device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x
 
 constexpr int kMaxTilesQ = 96;  // window blocks + selected blocks of one query block (host-checked)
 constexpr int kFewKeys = 32;    // rows seeing fewer keys than this get two-term bf16 operands
-constexpr float kBigProb = 0.03125f;  // a_x*P above this triggers the two-term operand in dK/dV
+
+// ones[.][0..2] in the half of the wavefront that holds contraction slots 0..7: multiplied with a
+// three-term split it broadcasts the split's value along the other dimension of the tile
+__device__ __forceinline__ bf16x8 ones3(int lh)
+{
+  bf16x8 o;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) o[e] = (__bf16)((lh == 0 && e < 3) ? 1.0f : 0.0f);
+  return o;
+}
+
+// a packed split (hi | mid << 16, lo) as an MFMA operand (slots 0..2; lanes of the other half
+// meet zeros of ones3 and may hold anything finite)
+__device__ __forceinline__ bf16x8 split_operand(uint32_t x, uint32_t y)
+{
+  const uint4 raw = make_uint4(x, y, 0u, 0u);
+  return __builtin_bit_cast(bf16x8, raw);
+}
 
 }  // namespace
 
 // =============================================================================================
 // dQ: one workgroup per (row, head, query block), one wavefront per 32 query rows.
-//   per 32-key unit:  S''^T = K (cQ)^T - lse2     (keys x queries, lane owns a query column)
-//                     G^T   = V dO^T - dO.o_x
-//                     dS^T  = 2^S'' * (a_x*G^T + dz*(wv_x[key] - wo_x))  -> bf16 -> B operand
+//   per 32-key unit:  S''^T = K (cQ)^T - lse2       (keys x queries, lane owns a query column)
+//                     G^T   = V dO_x^T - c_x
+//                     dS^T  = 2^S'' * G^T  -> bf16 -> B operand
 //                     dQ^T += K^T dS^T      (K^T through the transposing LDS read)
 // =============================================================================================
 template <int BLK>
-__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(const uint16_t *__restrict__ Q,
-                                                              const uint16_t *__restrict__ K,
-                                                              const uint16_t *__restrict__ V,
-                                                              const int *__restrict__ valid_len,
-                                                              const int *__restrict__ sel,
-                                                              const float *__restrict__ lse_lt,
-                                                              const float *__restrict__ lse_st,
-                                                              const uint16_t *__restrict__ dO,
-                                                              const float4 *__restrict__ rowstat,
-                                                              const float4 *__restrict__ rowB,
-                                                              const float2 *__restrict__ rowC,
-                                                              uint16_t *__restrict__ dQ, KParams p)
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int *__restrict__ valid_len, const int *__restrict__ sel, const uint16_t *__restrict__ g_lt,
+    const uint16_t *__restrict__ g_st, const uint4 *__restrict__ rowI_lt, const uint4 *__restrict__ rowI_st,
+    const uint16_t *__restrict__ dO, const float4 *__restrict__ rowstat, const float *__restrict__ gate_w,
+    const float *__restrict__ o_lt, const float *__restrict__ o_st, uint16_t *__restrict__ dQ, KParams p)
 {
   constexpr int UNITS = BLK / 32;
   constexpr int TILE = BLK * D;
@@ -175,7 +192,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
-  __shared__ __attribute__((aligned(16))) float wv_s[2][BLK];  // Wg_x.v_j of the staged key tiles
   __shared__ int tiles[kMaxTilesQ];
 
   const int tid = threadIdx.x;
@@ -192,8 +208,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const bool q_ok = iq < p.L && iq >= p0;
   const size_t head = (size_t)bh * p.L * D;
   const size_t rowoff = head + (size_t)min(iq, p.L - 1) * D;
-  const size_t lbase = (size_t)bh * p.L;
-  const size_t lrow = lbase + min(iq, p.L - 1);
+  const size_t lrow = (size_t)bh * p.L + min(iq, p.L - 1);
 
   f32x16 dq[2];
 #pragma unroll
@@ -204,25 +219,15 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 
   const float c2 = p.scale * kLog2e;
-  bf16x8 qf[4], gf[4];
+  bf16x8 qf[4], gf[4], gf_next[4];
   load_frags(Q + rowoff, lh, c2, qf);
-  load_frags(dO + rowoff, lh, 1.0f, gf);
-  // per-row constants; pad lanes get a huge lse so that every probability of their column is zero
-  float lse2_lt = 1.0e30f, lse2_st = 1.0e30f;
-  float a_lt = 0.0f, a_st = 0.0f, dz = 0.0f, do_lt = 0.0f, do_st = 0.0f, c0_lt = 0.0f, c0_st = 0.0f;
-  if (q_ok) {
-    const float4 st = rowstat[lrow];
-    const float4 rb = rowB[lrow];
-    lse2_lt = lse_lt[lrow] * kLog2e;
-    lse2_st = lse_st[lrow] * kLog2e;
-    a_lt = st.x;
-    a_st = 1.0f - st.x;
-    dz = st.y;
-    do_lt = rb.x;
-    do_st = rb.y;
-    c0_lt = -dz * rb.z;
-    c0_st = -dz * rb.w;
-  }
+  load_frags(g_st + rowoff, lh, 1.0f, gf);       // the walk starts with the window tiles
+  load_frags(g_lt + rowoff, lh, 1.0f, gf_next);
+  // per-row constants (pad rows carry an exponent of -1e30: every probability of the column is zero)
+  const uint4 ri_st = rowI_st[lrow];
+  const uint4 ri_lt = rowI_lt[lrow];
+  bf16x8 l2n = split_operand(ri_st.x, ri_st.y), c1n = split_operand(ri_st.z, ri_st.w);
+  const bf16x8 ones = ones3(lh);
 
   // ---- tile list: window blocks, then the selection list up to its first -1 ----
   const int J_first = p0 / BLK;
@@ -254,9 +259,50 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
   // Rows with only a few keys: dq is a sum of a few large dS*k terms that nearly cancel, so the
   // bf16 rounding of dS would dominate it.  Such wavefronts feed dS as a two-term bf16 sum.
-  const bool hp_st = p.w < kFewKeys || q0 - p0 + 1 < kFewKeys;
-  const bool hp_lt = lt_few;
+  const int hp_st = __builtin_amdgcn_readfirstlane((int)(p.w < kFewKeys || q0 - p0 + 1 < kFewKeys));
+  const int hp_lt = __builtin_amdgcn_readfirstlane((int)lt_few);
   const int n_all = n_st + n_lt;
+  // For those rows the bf16 rounding of dO_x itself would show as well (dS is large, and the
+  // small projections dO_x.(v_j - o) lose relative accuracy): the residual dO_x - bf16(dO_x) is
+  // rebuilt from dO, alpha, dz and the gate weights exactly as the per-row pass formed it, and
+  // enters as a second B operand; the row constant gains the matching residual.o_x.
+  bf16x8 gl[4], gl_next[4];
+  uint32_t c1_st_x = ri_st.z, c1_st_y = ri_st.w, c1_lt_x = ri_lt.z, c1_lt_y = ri_lt.w;
+#pragma unroll
+  for (int kk = 0; kk < 4; ++kk)
+#pragma unroll
+    for (int e = 0; e < 8; ++e) { gl[kk][e] = (__bf16)0.0f; gl_next[kk][e] = (__bf16)0.0f; }
+  if (hp_st | hp_lt) {
+    const float4 st = rowstat[lrow];
+    const float *wrow = gate_w + (size_t)(bh % p.H) * 2 * D;
+    float corr_st = 0.0f, corr_lt = 0.0f;
+#pragma unroll
+    for (int kk = 0; kk < 4; ++kk) {
+      const uint4 raw = *reinterpret_cast<const uint4 *>(dO + rowoff + 16 * kk + 8 * lh);
+      const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int dd = 16 * kk + 8 * lh + e;
+        const float g = (e & 1) ? bf_hi(w[e >> 1]) : bf_lo(w[e >> 1]);
+        const float full_l = fmaf(st.x, g, st.y * wrow[dd]);
+        const float full_s = fmaf(1.0f - st.x, g, st.y * wrow[D + dd]);
+        const __bf16 lo_l = (__bf16)(full_l - bf16_to_f32(f32_to_bf16(full_l)));
+        const __bf16 lo_s = (__bf16)(full_s - bf16_to_f32(f32_to_bf16(full_s)));
+        gl_next[kk][e] = lo_l;
+        gl[kk][e] = lo_s;
+        corr_lt = fmaf((float)lo_l, o_lt[rowoff + dd], corr_lt);
+        corr_st = fmaf((float)lo_s, o_st[rowoff + dd], corr_st);
+      }
+    }
+    corr_lt += __shfl_xor(corr_lt, 32);
+    corr_st += __shfl_xor(corr_st, 32);
+    const uint2 ns = split3(unsplit3(ri_st.z, ri_st.w) - corr_st);
+    const uint2 nl = split3(unsplit3(ri_lt.z, ri_lt.w) - corr_lt);
+    if (q_ok) {
+      c1_st_x = ns.x; c1_st_y = ns.y; c1_lt_x = nl.x; c1_lt_y = nl.y;
+    }
+  }
+  c1n = split_operand(c1_st_x, c1_st_y);
   __syncthreads();
   auto tile_of = [&](int t) -> int { return __builtin_amdgcn_readfirstlane(tiles[t]); };
 
@@ -265,35 +311,27 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const uint16_t *k_lane = K + head + sg.ld_row * D + Stager<BLK>::lane_col(lane);
   const uint16_t *v_lane = V + head + sg.ld_row * D + Stager<BLK>::lane_col(lane);
   const ReadOffsets ro = read_offsets(lane);
-  // Wg_x.v_j of key tile J for the branch the tile belongs to (0 past the end)
-  auto key_const = [&](int J, bool windowed) __attribute__((always_inline)) -> float {
-    float w = 0.0f;
-    if (tid < BLK) {
-      const int jj = J * BLK + tid;
-      if (jj < p.L) {
-        const float2 rc = rowC[lbase + jj];
-        w = windowed ? rc.y : rc.x;
-      }
-    }
-    return w;
-  };
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
-  auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, const float *wvs, int J, bool windowed, float lse2,
-                       float a_x, float do_x, float c0) __attribute__((always_inline)) {
-    const bool hp = __builtin_amdgcn_readfirstlane((int)(windowed ? hp_st : hp_lt)) != 0;
+  auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
+    const bool hp = (windowed ? hp_st : hp_lt) != 0;
     const bool masked = windowed || J == I || J * BLK < p0;
     const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
     const unsigned span = (unsigned)(iq - lo);
     const bool any = iq >= lo;
 #pragma unroll 1
     for (int s = 0; s < UNITS; ++s) {
-      f32x16 sacc, gacc;
-#pragma unroll
-      for (int i = 0; i < 16; ++i) { sacc[i] = -lse2; gacc[i] = -do_x; }
+      f32x16 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, l2n, zero16, 0, 0, 0);
+      f32x16 gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, c1n, zero16, 0, 0, 0);
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(ks, 32 * s * D + ro.row[kk]), qf[kk], sacc, 0, 0, 0);
         gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 32 * s * D + ro.row[kk]), gf[kk], gacc, 0, 0, 0);
+      }
+      if (hp) {
+#pragma unroll
+        for (int kk = 0; kk < 4; ++kk)
+          gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 32 * s * D + ro.row[kk]), gl[kk], gacc, 0, 0, 0);
       }
       if (masked) {
         const int base = J * BLK + 32 * s + 4 * lh;
@@ -305,16 +343,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 w4 = *reinterpret_cast<const float4 *>(wvs + 32 * s + 8 * g + 4 * lh);
-        const float w[4] = {w4.x, w4.y, w4.z, w4.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * g + e;
-          const float pr = __builtin_amdgcn_exp2f(sacc[i]);
-          sacc[i] = pr * fmaf(a_x, gacc[i], fmaf(dz, w[e], c0));
-        }
-      }
+      for (int i = 0; i < 16; ++i) sacc[i] = __builtin_amdgcn_exp2f(sacc[i]) * gacc[i];  // dS
       bf16x8 dsf[2];
       to_operand(sacc, dsf);
 #pragma unroll
@@ -341,29 +370,30 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int J0 = tile_of(0);
     sg.stage(k_lane, Ks0, J0);
     sg.stage(v_lane, Vs0, J0);
-    const float w0 = key_const(J0, 0 < n_st);
-    if (tid < BLK) wv_s[0][tid] = w0;
   }
   __syncthreads();
-  auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *k_cur, const uint16_t *v_cur,
-                  int par) __attribute__((always_inline)) {
-    float wn = 0.0f;
-    const bool more = t + 1 < n_all;
-    if (more) {
+  auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *k_cur, const uint16_t *v_cur)
+                  __attribute__((always_inline)) {
+    if (t + 1 < n_all) {
       const int Jn = tile_of(t + 1);
-      wn = key_const(Jn, t + 1 < n_st);
       sg.stage(k_lane, k_fill, Jn);
       sg.stage(v_lane, v_fill, Jn);
     }
-    const bool win = t < n_st;
-    tile_body(k_cur, v_cur, wv_s[par], tile_of(t), win, win ? lse2_st : lse2_lt, win ? a_st : a_lt,
-              win ? do_st : do_lt, win ? c0_st : c0_lt);
-    if (more && tid < BLK) wv_s[par ^ 1][tid] = wn;
+    if (t == n_st) {  // the long-term tiles start: switch to that branch's gradient and constants
+#pragma unroll
+      for (int kk = 0; kk < 4; ++kk) {
+        gf[kk] = gf_next[kk];
+        gl[kk] = gl_next[kk];
+      }
+      l2n = split_operand(ri_lt.x, ri_lt.y);
+      c1n = split_operand(c1_lt_x, c1_lt_y);
+    }
+    tile_body(k_cur, v_cur, tile_of(t), t < n_st);
     __syncthreads();
   };
   for (int t = 0; t < n_all; t += 2) {
-    step(t, Ks1, Vs1, Ks0, Vs0, 0);
-    if (t + 1 < n_all) step(t + 1, Ks0, Vs0, Ks1, Vs1, 1);
+    step(t, Ks1, Vs1, Ks0, Vs0);
+    if (t + 1 < n_all) step(t + 1, Ks0, Vs0, Ks1, Vs1);
   }
   if (iq < p.L) store_row_bf16(dQ + rowoff, lh, dq, p.scale, q_ok);
 }
@@ -372,29 +402,20 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // dK, dV: one workgroup per (row, head, key block), one wavefront per 32 key rows; walks the
 // query blocks whose window reaches the key block, then those that selected it (inverse list).
 //   per 32-query unit:  S'' = Q (cK)^T - lse2[i]   (queries x keys, lane owns a key column)
-//                       G   = dO V^T - dO.o_x[i]
-//                       P = 2^S'',  dS = P*(a_x[i]*G + dz[i]*(wv_x[key] - wo_x[i]))
-//                       dV^T += dO^T (a_x P),  u += dz[i]*P,  dK^T += Q^T dS
-//   epilogue:           dV_j += Wg_lt*u_lt + Wg_st*u_st
+//                       G   = dO_x V^T - c_x[i]
+//                       P = 2^S'',  dS = P*G
+//                       dV^T += dO_x^T P,  dK^T += Q^T dS
 // =============================================================================================
 constexpr int kListRing = 128;
 
 template <int BLK>
-__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(const uint16_t *__restrict__ Q,
-                                                               const uint16_t *__restrict__ K,
-                                                               const uint16_t *__restrict__ V,
-                                                               const int *__restrict__ valid_len,
-                                                               const float *__restrict__ gate_w,
-                                                               const float *__restrict__ lse_lt,
-                                                               const float *__restrict__ lse_st,
-                                                               const uint16_t *__restrict__ dO,
-                                                               const float4 *__restrict__ rowstat,
-                                                               const float4 *__restrict__ rowB,
-                                                               const float2 *__restrict__ rowC,
-                                                               const int *__restrict__ offs,
-                                                               const int *__restrict__ items,
-                                                               uint16_t *__restrict__ dK,
-                                                               uint16_t *__restrict__ dV, KParams p)
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int *__restrict__ valid_len, const uint16_t *__restrict__ g_lt, const uint16_t *__restrict__ g_st,
+    const uint4 *__restrict__ rowI_lt, const uint4 *__restrict__ rowI_st, const int *__restrict__ offs,
+    const int *__restrict__ items, const uint16_t *__restrict__ dO, const float4 *__restrict__ rowstat,
+    const float *__restrict__ gate_w, const float *__restrict__ o_lt, const float *__restrict__ o_st,
+    uint16_t *__restrict__ dK, uint16_t *__restrict__ dV, KParams p)
 {
   constexpr int UNITS = BLK / 32;
   constexpr int TILE = BLK * D;
@@ -403,9 +424,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(1024))) uint16_t Qs1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Gs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Gs1[TILE];
-  // per-row constants of the staged query tile: lse2, dO.o_x, a_x, dz, -dz*wo_x
-  __shared__ __attribute__((aligned(16))) float rc_s[2][5][BLK];
-  __shared__ float gate_s[2 * D];
+  // per-row constants of the staged query tile: splits of -lse2 (x, y) and of -c_x (z, w)
+  __shared__ __attribute__((aligned(16))) uint4 rc_s[2][BLK];
   __shared__ int ring[kListRing];  // query blocks of the long-term part of the walk, refilled in halves
 
   const int tid = threadIdx.x;
@@ -414,7 +434,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int lq = lane & 31, lh = lane >> 5;
   const unsigned vid = xcd_remap(blockIdx.x, (unsigned)(p.B * p.H * p.NB));
   const int bh = (int)(vid / p.NB);
-  const int h = bh % p.H;
   const int J = (int)(vid % p.NB);  // early key blocks are selected by more query blocks: start them first
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
@@ -434,18 +453,11 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     return;
   }
-  for (int c = tid; c < 2 * D; c += NT) gate_s[c] = gate_w[(size_t)h * 2 * D + c];
   const float c2 = p.scale * kLog2e;
   bf16x8 kf[4], vf[4];
   load_frags(K + rowoff, lh, c2, kf);
   load_frags(V + rowoff, lh, 1.0f, vf);
-  float wv_lt = 0.0f, wv_st = 0.0f;
-  if (key_ok) {
-    const float2 rc = rowC[lbase + j];
-    wv_lt = rc.x;
-    wv_st = rc.y;
-  }
-  float u_lt = 0.0f, u_st = 0.0f;  // sum_i dz[i] P_ij of the two branches (this lane's rows)
+  const bf16x8 ones = ones3(lh);
 
   // ---- walk: window part I = J..I_hi, then the inverse selection list ----
   const long last_q = (long)J * BLK + (BLK - 1) + (p.w - 1);
@@ -457,7 +469,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int *my_items = items + (size_t)bh * p.NB * p.k + e_lo;
   for (int e = tid; e < min(n_lt, kListRing); e += NT) ring[e] = my_items[e];
   __syncthreads();
-  auto tile_of = [&](int t) -> int {  // query block of step t
+  // query block of step t, with the few-keys flag of the list entries in bit kInvFewShift
+  auto entry_of = [&](int t) -> int {
     return t < n_st ? J + t : __builtin_amdgcn_readfirstlane(ring[(t - n_st) & (kListRing - 1)]);
   };
 
@@ -465,39 +478,24 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   sg.init(wv, lane, p.L, p.NB);
   const int lcol = Stager<BLK>::lane_col(lane);
   const uint16_t *q_lane = Q + head + sg.ld_row * D + lcol;
-  const uint16_t *g_lane = dO + head + sg.ld_row * D + lcol;
+  const uint16_t *gl_lane = g_lt + head + sg.ld_row * D + lcol;
+  const uint16_t *gs_lane = g_st + head + sg.ld_row * D + lcol;
   const ReadOffsets ro = read_offsets(lane);
+  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+  const uint4 pad_consts = make_uint4(0x0000f149u, 0u, 0u, 0u);  // -1e30 as (hi, 0, 0): probability zero
 
-  struct RowC { float l2, dox, ax, dz, c0; };
-  // per-row constants of query block Iq for one branch (pad rows: probability forced to zero)
-  auto row_consts = [&](int Iq, bool windowed) __attribute__((always_inline)) -> RowC {
-    RowC r{1.0e30f, 0.0f, 0.0f, 0.0f, 0.0f};
+  // per-row constants of query block Iq for one branch (rows past the end: probability zero)
+  auto row_consts = [&](int Iq, bool windowed) __attribute__((always_inline)) -> uint4 {
+    uint4 r = pad_consts;
     if (tid < BLK) {
       const int i = Iq * BLK + tid;
-      if (i < p.L && i >= p0) {
-        const float4 st = rowstat[lbase + i];
-        const float4 rb = rowB[lbase + i];
-        r.l2 = (windowed ? lse_st[lbase + i] : lse_lt[lbase + i]) * kLog2e;
-        r.dox = windowed ? rb.y : rb.x;
-        r.ax = windowed ? 1.0f - st.x : st.x;
-        r.dz = st.y;
-        r.c0 = -st.y * (windowed ? rb.w : rb.z);
-      }
+      if (i < p.L) r = (windowed ? rowI_st : rowI_lt)[lbase + i];
     }
     return r;
   };
-  auto put_consts = [&](int par, const RowC &r) __attribute__((always_inline)) {
-    if (tid < BLK) {
-      rc_s[par][0][tid] = r.l2;
-      rc_s[par][1][tid] = r.dox;
-      rc_s[par][2][tid] = r.ax;
-      rc_s[par][3][tid] = r.dz;
-      rc_s[par][4][tid] = r.c0;
-    }
-  };
 
-  auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, float wvx,
-                       float &u) __attribute__((always_inline)) {
+  auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, bool hp)
+                       __attribute__((always_inline)) {
     const bool masked = windowed || Iq == J || Iq * BLK < p0 || J * BLK < p0 || (Iq + 1) * BLK > p.L;
     // visible <=> key valid and lo_i <= i <= hi_i
     const int lo_i = max(j, p0);
@@ -506,15 +504,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const bool any = key_ok && hi_i >= lo_i;
 #pragma unroll 1
     for (int s = 0; s < UNITS; ++s) {
-      f32x16 sacc, gacc;
-      const int r0 = 32 * s + 4 * lh;  // this lane's rows of the unit: r0 + 8g + (0..3)
-#pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 a = *reinterpret_cast<const float4 *>(&rc_s[par][0][r0 + 8 * g]);
-        const float4 b = *reinterpret_cast<const float4 *>(&rc_s[par][1][r0 + 8 * g]);
-        sacc[4 * g] = -a.x; sacc[4 * g + 1] = -a.y; sacc[4 * g + 2] = -a.z; sacc[4 * g + 3] = -a.w;
-        gacc[4 * g] = -b.x; gacc[4 * g + 1] = -b.y; gacc[4 * g + 2] = -b.z; gacc[4 * g + 3] = -b.w;
-      }
+      const uint4 rc = rc_s[par][32 * s + lq];  // this lane's row of the unit
+      f32x16 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(split_operand(rc.x, rc.y), ones, zero16, 0, 0, 0);
+      f32x16 gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(split_operand(rc.z, rc.w), ones, zero16, 0, 0, 0);
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(qs, 32 * s * D + ro.row[kk]), kf[kk], sacc, 0, 0, 0);
@@ -530,21 +522,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         }
       }
 #pragma unroll
-      for (int g = 0; g < 4; ++g) {
-        const float4 ax4 = *reinterpret_cast<const float4 *>(&rc_s[par][2][r0 + 8 * g]);
-        const float4 dz4 = *reinterpret_cast<const float4 *>(&rc_s[par][3][r0 + 8 * g]);
-        const float4 c04 = *reinterpret_cast<const float4 *>(&rc_s[par][4][r0 + 8 * g]);
-        const float ax[4] = {ax4.x, ax4.y, ax4.z, ax4.w};
-        const float dzr[4] = {dz4.x, dz4.y, dz4.z, dz4.w};
-        const float c0[4] = {c04.x, c04.y, c04.z, c04.w};
-#pragma unroll
-        for (int e = 0; e < 4; ++e) {
-          const int i = 4 * g + e;
-          const float pr = __builtin_amdgcn_exp2f(sacc[i]);
-          gacc[i] = pr * fmaf(ax[e], gacc[i], fmaf(dzr[e], wvx, c0[e]));  // dS
-          u = fmaf(dzr[e], pr, u);
-          sacc[i] = ax[e] * pr;                                            // a_x P
-        }
+      for (int i = 0; i < 16; ++i) {
+        sacc[i] = __builtin_amdgcn_exp2f(sacc[i]);  // P
+        gacc[i] *= sacc[i];                         // dS
       }
       bf16x8 pf[2], dsf[2];
       to_operand(sacc, pf);
@@ -558,14 +538,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
           dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
                                                            dk[mb], 0, 0, 0);
         }
-      // A probability that is not small (a row with few keys, or a peaked row) multiplies a dO
-      // of ordinary size: its bf16 rounding error, 2^-9*P*|dO|, would show in dV, whose other
-      // terms are small.  Units holding such a probability add the rounding residuals as a
-      // second bf16 term.
-      float pmax = sacc[0];
-#pragma unroll
-      for (int i = 1; i < 16; ++i) pmax = fmaxf(pmax, sacc[i]);
-      if (__any(pmax > kBigProb)) {
+      if (hp) {  // rows with few keys: large P and dS, add the rounding residuals as a second bf16 term
 #pragma unroll
         for (int i = 0; i < 16; ++i) {
           sacc[i] -= (float)pf[i >> 3][i & 7];
@@ -586,22 +559,28 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
+  int ent_cur = entry_of(0);
   {
-    const int I0 = tile_of(0);
+    const int I0 = ent_cur & kInvBlockMask;
+    const bool win0 = 0 < n_st;
     sg.stage(q_lane, Qs0, I0);
-    sg.stage(g_lane, Gs0, I0);
-    put_consts(0, row_consts(I0, 0 < n_st));
+    sg.stage(win0 ? gs_lane : gl_lane, Gs0, I0);
+    const uint4 r0 = row_consts(I0, win0);
+    if (tid < BLK) rc_s[0][tid] = r0;
   }
   __syncthreads();
   auto step = [&](int t, uint16_t *q_fill, uint16_t *g_fill, const uint16_t *q_cur, const uint16_t *g_cur,
                   int par) __attribute__((always_inline)) {
-    RowC rn{1.0e30f, 0.0f, 0.0f, 0.0f, 0.0f};
+    uint4 rn = pad_consts;
     const bool more = t + 1 < n_all;
+    int ent_nxt = 0;
     if (more) {
-      const int In = tile_of(t + 1);
-      rn = row_consts(In, t + 1 < n_st);
+      ent_nxt = entry_of(t + 1);
+      const int In = ent_nxt & kInvBlockMask;
+      const bool win_n = t + 1 < n_st;
+      rn = row_consts(In, win_n);
       sg.stage(q_lane, q_fill, In);
-      sg.stage(g_lane, g_fill, In);
+      sg.stage(win_n ? gs_lane : gl_lane, g_fill, In);
     }
     // refill the half of the ring that was consumed 64 steps ago
     const int e = t - n_st;
@@ -610,27 +589,81 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       if (tid < 64 && src < n_lt) ring[src & (kListRing - 1)] = my_items[src];
     }
     const bool win = t < n_st;
-    float u = 0.0f;
-    tile_body(q_cur, g_cur, par, tile_of(t), win, win ? wv_st : wv_lt, u);
-    u_st += win ? u : 0.0f;
-    u_lt += win ? 0.0f : u;
-    if (more) put_consts(par ^ 1, rn);
+    const int Iq = ent_cur & kInvBlockMask;
+    // rows that may see fewer than kFewKeys keys: the first valid rows of a window (or a very
+    // short window), or a query block flagged by the inverse list
+    const bool hp = win ? (p.w < kFewKeys || Iq * BLK - p0 + 1 < kFewKeys) : (ent_cur >> kInvFewShift) != 0;
+    tile_body(q_cur, g_cur, par, Iq, win, hp);
+    if (more && tid < BLK) rc_s[par ^ 1][tid] = rn;
+    ent_cur = ent_nxt;
     __syncthreads();
   };
   for (int t = 0; t < n_all; t += 2) {
     step(t, Qs1, Gs1, Qs0, Gs0, 0);
     if (t + 1 < n_all) step(t + 1, Qs0, Gs0, Qs1, Gs1, 1);
   }
-  // rank-one part of dV: Wg_x * sum_i dz[i] P_ij (the other half of the rows sits in lane^32)
-  u_lt += __shfl_xor(u_lt, 32);
-  u_st += __shfl_xor(u_st, 32);
+
+  // ---- residual passes over the query blocks with few-key rows ----
+  // There the probabilities are near one, dV holds single terms P*dO_x of full size and dS
+  // projections of dO_x that are small against its norm, so the bf16 rounding of dO_x itself
+  // would show.  Everything above is linear in dO_x: the tile is simply walked a second time
+  // with the residual dO_x - bf16(dO_x) in place of dO_x and residual.o_x in place of c_x.  The
+  // residual tile is rebuilt in LDS from dO, alpha, dz and the gate weights exactly as the
+  // per-row pass formed dO_x.  (Rare: the first blocks of a row, or top-k below three.)
+  auto residual_pass = [&](int Iq, bool windowed) __attribute__((always_inline)) {
+    sg.stage(q_lane, Qs0, Iq);
+    {
+      // thread -> (row, half of d): 32 residuals each, written as four swizzled 16-byte chunks
+      const int r = tid >> 1, hf = tid & 1;
+      const int i = Iq * BLK + r;
+      const bool in = i < p.L;
+      const size_t ro = head + (size_t)min(i, p.L - 1) * D + 32 * hf;
+      const float4 st = rowstat[lbase + min(i, p.L - 1)];
+      const float ax = windowed ? 1.0f - st.x : st.x;
+      const float *wrow = gate_w + (size_t)(bh % p.H) * 2 * D + (windowed ? D : 0) + 32 * hf;
+      const float *orow = (windowed ? o_st : o_lt) + ro;
+      float corr = 0.0f;
 #pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
+      for (int c = 0; c < 4; ++c) {
+        const uint4 raw = *reinterpret_cast<const uint4 *>(dO + ro + 8 * c);
+        const uint32_t w[4] = {raw.x, raw.y, raw.z, raw.w};
+        uint32_t out[4];
 #pragma unroll
-    for (int i = 0; i < 16; ++i) {
-      const int dd = 32 * mb + 8 * (i >> 2) + 4 * lh + (i & 3);
-      dv[mb][i] += gate_s[dd] * u_lt + gate_s[D + dd] * u_st;
+        for (int e = 0; e < 8; ++e) {
+          const float g = (e & 1) ? bf_hi(w[e >> 1]) : bf_lo(w[e >> 1]);
+          const float full = fmaf(ax, g, st.y * wrow[8 * c + e]);
+          const uint16_t lo = in ? f32_to_bf16(full - bf16_to_f32(f32_to_bf16(full))) : (uint16_t)0;
+          corr = fmaf(bf16_to_f32(lo), orow[8 * c + e], corr);
+          if (e & 1) out[e >> 1] |= (uint32_t)lo << 16; else out[e >> 1] = lo;
+        }
+        const int chunk = (4 * hf + c) ^ swz(r);
+        *reinterpret_cast<uint4 *>(Gs0 + r * D + chunk * 8) = make_uint4(out[0], out[1], out[2], out[3]);
+      }
+      corr += __shfl_xor(corr, 1);
+      if (hf == 0) {
+        const uint4 base = in ? (windowed ? rowI_st : rowI_lt)[lbase + i] : pad_consts;
+        const uint2 k = split3(-corr);
+        rc_s[0][r] = make_uint4(base.x, base.y, k.x, k.y);
+      }
     }
+    __syncthreads();  // (waits for the staged Q rows of every wavefront as well)
+    tile_body(Qs0, Gs0, 0, Iq, windowed, false);
+    __syncthreads();
+  };
+  if (p.w < kFewKeys || J * BLK - p0 + 1 < kFewKeys) {  // the window part: a prefix of the walk
+#pragma unroll 1
+    for (int t = 0; t < n_st; ++t) {
+      const int Iq = J + t;
+      if (!(p.w < kFewKeys || Iq * BLK - p0 + 1 < kFewKeys)) break;
+      residual_pass(Iq, true);
+    }
+  }
+#pragma unroll 1
+  for (int e = 0; e < n_lt; ++e) {  // flagged entries of the inverse list
+    const int ent = __builtin_amdgcn_readfirstlane(my_items[e]);
+    if ((ent >> kInvFewShift) != 0) residual_pass(ent & kInvBlockMask, false);
+  }
+
   if (j < p.L) {
     store_row_bf16(dK + rowoff, lh, dk, p.scale, key_ok);
     store_row_bf16(dV + rowoff, lh, dv, 1.0f, key_ok);
@@ -650,18 +683,18 @@ void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, 
   auto u16 = [](const void *x) { return reinterpret_cast<const uint16_t *>(x); };
   if (p.b == 32) {
     if (do_dq) hipLaunchKernelGGL((bwd_dq_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.sel, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC,
-                       (uint16_t *)a.dQ, p);
+                       a.valid_len, a.sel, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, u16(a.dO), w.rowstat, a.gate_w,
+                       (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dQ, p);
     if (do_dkv) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.gate_w, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC, w.offs,
-                       w.items, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
+                       a.valid_len, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, w.offs, w.items, u16(a.dO), w.rowstat,
+                       a.gate_w, (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
   } else {
     if (do_dq) hipLaunchKernelGGL((bwd_dq_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.sel, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC,
-                       (uint16_t *)a.dQ, p);
+                       a.valid_len, a.sel, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, u16(a.dO), w.rowstat, a.gate_w,
+                       (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dQ, p);
     if (do_dkv) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.gate_w, a.lse_lt, a.lse_st, u16(a.dO), w.rowstat, w.rowB, w.rowC, w.offs,
-                       w.items, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
+                       a.valid_len, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, w.offs, w.items, u16(a.dO), w.rowstat,
+                       a.gate_w, (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
   }
 }
 

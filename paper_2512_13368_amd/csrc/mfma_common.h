@@ -46,5 +46,17 @@ __device__ __forceinline__ int swz(int r) { return ((r & 3) << 1) | ((r >> 2) & 
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }
 
+// x as hi + mid + lo with bf16 terms (exact for fp32 x), packed (hi | mid << 16, lo): the form
+// in which one matrix instruction broadcasts a per-row constant into an accumulator
+__device__ __forceinline__ uint2 split3(float x)
+{
+  const uint16_t hi = f32_to_bf16(x);
+  const float r1 = x - bf16_to_f32(hi);
+  const uint16_t mid = f32_to_bf16(r1);
+  const uint16_t lo = f32_to_bf16(r1 - bf16_to_f32(mid));
+  return make_uint2((uint32_t)hi | ((uint32_t)mid << 16), (uint32_t)lo);
+}
+__device__ __forceinline__ float unsplit3(uint32_t x, uint32_t y) { return (bf_lo(x) + bf_hi(x)) + bf_lo(y); }
+
 }  // namespace mfma
 }  // namespace blossom
