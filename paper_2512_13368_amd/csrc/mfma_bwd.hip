@@ -29,10 +29,12 @@ using namespace mfma;
 
 namespace {
 
-// Per-lane LDS element offsets of the two operand read patterns for a tile staged with swz().
+// Per-lane LDS BYTE offsets of the two operand read patterns for a tile staged with swz().
+// Kept in bytes and passed through an empty asm by the kernels, so that "tile base + offset +
+// constant" is formed next to each read and the constant folds into the instruction's immediate.
 struct ReadOffsets {
-  int row[4];  // row-per-lane 16-byte reads: slab kk; add 32*unit*D
-  int tr[2];   // transposing 8-byte reads: M-block mb; add (32*unit + 16*t + 8*x)*D
+  int row[4];  // row-per-lane 16-byte reads: slab kk; add 2*32*unit*D
+  int tr[2];   // transposing 8-byte reads: M-block mb; add 2*(32*unit + 16*t + 8*x)*D
 };
 
 __device__ __forceinline__ ReadOffsets read_offsets(int lane)
@@ -40,20 +42,24 @@ __device__ __forceinline__ ReadOffsets read_offsets(int lane)
   ReadOffsets o;
   const int lq = lane & 31, lh = lane >> 5, r16 = lane & 15, g1 = (lane >> 4) & 1;
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) o.row[kk] = lq * D + (((2 * kk + lh) ^ swz(lq)) * 8);
+  for (int kk = 0; kk < 4; ++kk) o.row[kk] = 2 * (lq * D + (((2 * kk + lh) ^ swz(lq)) * 8));
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
-    o.tr[mb] = (4 * lh + (r16 >> 2)) * D +
-               (((4 * mb + 2 * g1 + ((r16 & 3) >> 1)) ^ (2 * (r16 >> 2) + lh)) * 8) + 4 * (r16 & 1);
+    o.tr[mb] = 2 * ((4 * lh + (r16 >> 2)) * D +
+                    (((4 * mb + 2 * g1 + ((r16 & 3) >> 1)) ^ (2 * (r16 >> 2) + lh)) * 8) + 4 * (r16 & 1));
   return o;
 }
 
 // Direct global->LDS staging of one tile (BLK rows x 128 bytes): each wavefront moves 4 x 1 KB.
+// A tile's rows are contiguous in memory and the LDS copy keeps the 128-byte row pitch, so one
+// uniform base (SGPRs), one per-lane byte offset and the same immediate on the global and the
+// LDS side address the four 8-row slices.
 template <int BLK>
 struct Stager {
-  int wv, ld_row, over_base;
+  int wv, ld_row;
   bool ragged;
   int L, NB;
+  unsigned lane_off;  // bytes: (ld_row, chunk) of this lane inside a tile
   __device__ __forceinline__ void init(int wv_, int lane, int L_, int NB_)
   {
     wv = wv_;
@@ -61,39 +67,42 @@ struct Stager {
     NB = NB_;
     ld_row = 32 * wv + (lane >> 3);
     ragged = L % BLK != 0;
+    // LDS chunk position lane&7 holds chunk (lane&7)^swz(row)
+    lane_off = (unsigned)(ld_row * D + ((lane & 7) ^ (2 * ((lane >> 3) & 3) + ((lane >> 5) & 1))) * 8) * 2u;
   }
-  // column (elements) of the chunk this lane fetches: LDS chunk position lane&7 holds chunk (lane&7)^swz(row)
-  __device__ __forceinline__ static int lane_col(int lane) { return ((lane & 7) ^ (2 * ((lane >> 3) & 3) + ((lane >> 5) & 1))) * 8; }
-  // src_lane = head + ld_row*D + lane_col
-  __device__ __forceinline__ void stage(const uint16_t *src_lane, uint16_t *dst_tile, int blk) const
+  // src_head: first element of the (row, head) slice of the tensor
+  __device__ __forceinline__ void stage(const uint16_t *src_head, uint16_t *dst_tile, int blk) const
   {
     constexpr int TILE = BLK * D;
+    const char *src = reinterpret_cast<const char *>(src_head) + (size_t)blk * (TILE * 2);  // uniform
+    lds_void *dst = (lds_void *)(dst_tile + 32 * wv * D);
     if (!ragged || blk != NB - 1) {
-      const uint16_t *src = src_lane + (size_t)blk * TILE;
-#pragma unroll
-      for (int u = 0; u < 4; ++u)
-        __builtin_amdgcn_global_load_lds((glb_void *)(src + 8 * u * D), (lds_void *)(dst_tile + (32 * wv + 8 * u) * D),
-                                         16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 1024, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 2048, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 3072, 0);
     } else {  // last, partial block: rows past the end are clamped (always masked)
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int over = max(0, blk * BLK + ld_row + 8 * u - (L - 1));
-        const uint16_t *src = src_lane + (size_t)blk * TILE + (8 * u - over) * D;
-        __builtin_amdgcn_global_load_lds((glb_void *)src, (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
+        const unsigned off = lane_off + (unsigned)((8 * u - over) * D * 2);
+        __builtin_amdgcn_global_load_lds((glb_void *)(src + off), (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
       }
     }
   }
 };
 
+// off: byte offset inside the tile
 __device__ __forceinline__ bf16x8 lds_row(const uint16_t *tile, int off)
 {
-  return *reinterpret_cast<const bf16x8 *>(tile + off);
+  return *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const char *>(tile) + off);
 }
 
 __device__ __forceinline__ bf16x8 lds_tr(const uint16_t *tile, int off)
 {
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + off));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(tile + off + 8 * D));
+  const char *a = reinterpret_cast<const char *>(tile) + off;
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 2 * 8 * D));
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
@@ -308,30 +317,31 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   Stager<BLK> sg;
   sg.init(wv, lane, p.L, p.NB);
-  const uint16_t *k_lane = K + head + sg.ld_row * D + Stager<BLK>::lane_col(lane);
-  const uint16_t *v_lane = V + head + sg.ld_row * D + Stager<BLK>::lane_col(lane);
-  const ReadOffsets ro = read_offsets(lane);
+  const uint16_t *k_lane = K + head;  // (row, head) slices; the stager adds block and lane offsets
+  const uint16_t *v_lane = V + head;
+  ReadOffsets ro = read_offsets(lane);
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
+    asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]));
     const bool hp = (windowed ? hp_st : hp_lt) != 0;
     const bool masked = windowed || J == I || J * BLK < p0;
     const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
     const unsigned span = (unsigned)(iq - lo);
     const bool any = iq >= lo;
-#pragma unroll 1
+#pragma unroll
     for (int s = 0; s < UNITS; ++s) {
       f32x16 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, l2n, zero16, 0, 0, 0);
       f32x16 gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, c1n, zero16, 0, 0, 0);
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(ks, 32 * s * D + ro.row[kk]), qf[kk], sacc, 0, 0, 0);
-        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 32 * s * D + ro.row[kk]), gf[kk], gacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(ks, 2 * 32 * s * D + ro.row[kk]), qf[kk], sacc, 0, 0, 0);
+        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 2 * 32 * s * D + ro.row[kk]), gf[kk], gacc, 0, 0, 0);
       }
       if (hp) {
 #pragma unroll
         for (int kk = 0; kk < 4; ++kk)
-          gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 32 * s * D + ro.row[kk]), gl[kk], gacc, 0, 0, 0);
+          gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 2 * 32 * s * D + ro.row[kk]), gl[kk], gacc, 0, 0, 0);
       }
       if (masked) {
         const int base = J * BLK + 32 * s + 4 * lh;
@@ -350,7 +360,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-          dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+          dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
                                                            dq[mb], 0, 0, 0);
       if (hp) {
 #pragma unroll
@@ -360,7 +370,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int mb = 0; mb < 2; ++mb)
-            dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+            dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
                                                              dq[mb], 0, 0, 0);
       }
     }
@@ -476,11 +486,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   Stager<BLK> sg;
   sg.init(wv, lane, p.L, p.NB);
-  const int lcol = Stager<BLK>::lane_col(lane);
-  const uint16_t *q_lane = Q + head + sg.ld_row * D + lcol;
-  const uint16_t *gl_lane = g_lt + head + sg.ld_row * D + lcol;
-  const uint16_t *gs_lane = g_st + head + sg.ld_row * D + lcol;
-  const ReadOffsets ro = read_offsets(lane);
+  const uint16_t *q_lane = Q + head;  // (row, head) slices; the stager adds block and lane offsets
+  const uint16_t *gl_lane = g_lt + head;
+  const uint16_t *gs_lane = g_st + head;
+  ReadOffsets ro = read_offsets(lane);
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
   const uint4 pad_consts = make_uint4(0x0000f149u, 0u, 0u, 0u);  // -1e30 as (hi, 0, 0): probability zero
 
@@ -496,21 +505,22 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, bool hp)
                        __attribute__((always_inline)) {
+    asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]));
     const bool masked = windowed || Iq == J || Iq * BLK < p0 || J * BLK < p0 || (Iq + 1) * BLK > p.L;
     // visible <=> key valid and lo_i <= i <= hi_i
     const int lo_i = max(j, p0);
     const int hi_i = windowed ? min(p.L - 1, j + p.w - 1) : p.L - 1;
     const unsigned span = (unsigned)(hi_i - lo_i);
     const bool any = key_ok && hi_i >= lo_i;
-#pragma unroll 1
+#pragma unroll
     for (int s = 0; s < UNITS; ++s) {
       const uint4 rc = rc_s[par][32 * s + lq];  // this lane's row of the unit
       f32x16 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(split_operand(rc.x, rc.y), ones, zero16, 0, 0, 0);
       f32x16 gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(split_operand(rc.z, rc.w), ones, zero16, 0, 0, 0);
 #pragma unroll
       for (int kk = 0; kk < 4; ++kk) {
-        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(qs, 32 * s * D + ro.row[kk]), kf[kk], sacc, 0, 0, 0);
-        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(gsm, 32 * s * D + ro.row[kk]), vf[kk], gacc, 0, 0, 0);
+        sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(qs, 2 * 32 * s * D + ro.row[kk]), kf[kk], sacc, 0, 0, 0);
+        gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(gsm, 2 * 32 * s * D + ro.row[kk]), vf[kk], gacc, 0, 0, 0);
       }
       if (masked) {
         const int base = Iq * BLK + 32 * s + 4 * lh;
@@ -533,9 +543,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
-          dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, (32 * s + 16 * t) * D + ro.tr[mb]), pf[t],
+          dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), pf[t],
                                                            dv[mb], 0, 0, 0);
-          dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+          dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
                                                            dk[mb], 0, 0, 0);
         }
       if (hp) {  // rows with few keys: large P and dS, add the rounding residuals as a second bf16 term
@@ -550,9 +560,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int mb = 0; mb < 2; ++mb) {
-            dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, (32 * s + 16 * t) * D + ro.tr[mb]), pf[t],
+            dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), pf[t],
                                                              dv[mb], 0, 0, 0);
-            dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+            dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
                                                              dk[mb], 0, 0, 0);
           }
       }
