@@ -73,7 +73,7 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
                                                         int *__restrict__ sel, KParams p)
 {
   __shared__ float qs[D];
-  __shared__ float sc[kMaxNB];
+  extern __shared__ float sc[];  // NB scores (sized at launch: a static worst-case array would cap the occupancy)
   const int lane = threadIdx.x;
   const int I = blockIdx.x % p.NB;
   const int bh = blockIdx.x / p.NB;
@@ -135,7 +135,8 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, cons
   const unsigned grid = (unsigned)((tasks + per_wg - 1) / per_wg);
   hipLaunchKernelGGL((pool_kernel<T, D>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
                      valid_len, qsum, kmeanT, p);
-  hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64), 0, st,
+  hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64),
+                     (size_t)p.NB * sizeof(float), st,
                      qsum, kmeanT, valid_len, sel, p);
 }
 
