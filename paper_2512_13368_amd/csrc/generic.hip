@@ -537,66 +537,88 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
 // =============================================================================================
 // Backward, step 3: inverse selection list.  For each key block J of a (row, head): the
 // ascending list of query blocks I whose selection holds J.  offs [B*H,(NB+1)], items [B*H,NB*k].
-// One wavefront per (row, head).  Counting and filling use LDS integer atomics, one selection
+// One workgroup of W wavefronts per (row, head); wavefront w owns a contiguous range of query
+// blocks and its own counters.  Counting and filling use LDS integer atomics, one selection
 // row per wavefront instruction: a row lists distinct blocks, and the LDS executes one
-// wavefront's instructions in order, so each list comes out ascending in I and the result is
-// deterministic.
+// wavefront's instructions in order, so inside a wavefront's range each list comes out
+// ascending in I; the ranges are laid out one after the other per key block (the scan hands
+// each wavefront its base), so the whole list is ascending and the result is deterministic.
 // =============================================================================================
 constexpr int kMaxNBInv = 4096;
+constexpr int kInvWaves = 4;      // wavefronts per (row, head) when the counters fit
+constexpr int kInvWavesMaxNB = 2048;
 
-__global__ __launch_bounds__(64) void inverse_list_kernel(const int *__restrict__ sel,
-                                                          const int *__restrict__ valid_len, int *__restrict__ offs,
-                                                          int *__restrict__ items, KParams p)
+__global__ __launch_bounds__(64 * kInvWaves) void inverse_list_kernel(const int *__restrict__ sel,
+                                                                      const int *__restrict__ valid_len,
+                                                                      int *__restrict__ offs, int *__restrict__ items,
+                                                                      KParams p)
 {
-  __shared__ int cnt[kMaxNBInv + 64];
-  __shared__ unsigned char few[kMaxNBInv + 64];  // query block whose selected past blocks hold few valid keys
-  const int lane = threadIdx.x;
+  extern __shared__ int inv_lds[];  // cnt[W][NB+1], then few[NB+1] bytes
+  const int W = blockDim.x >> 6;
+  const int stride = p.NB + 1;
+  int *cnt = inv_lds;
+  unsigned char *few = reinterpret_cast<unsigned char *>(inv_lds + W * stride);  // query block whose selected
+                                                                                  // past blocks hold few valid keys
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wv = tid >> 6;
   const int bh = blockIdx.x;
   const int *s = sel + (size_t)bh * p.NB * p.k;
   int *o = offs + (size_t)bh * (p.NB + 1);
   int *it = items + (size_t)bh * p.NB * p.k;
   const int p0 = p.L - clamp_len(valid_len[bh / p.H], p.L);
-  for (int J = lane; J <= p.NB; J += 64) {
-    cnt[J] = 0;
-    few[J] = 1;
-  }
+  const int per = (p.NB + W - 1) / W;
+  const int I_lo = wv * per, I_hi = min(p.NB, I_lo + per);
+  int *mine = cnt + wv * stride;
+  for (int x = tid; x < W * stride; x += blockDim.x) cnt[x] = 0;
+  for (int J = tid; J <= p.NB; J += blockDim.x) few[J] = 1;
   __syncthreads();
   for (int e0 = 0; e0 < p.k; e0 += 64) {
     const int e = e0 + lane;
 #pragma unroll 8
-    for (int I = 0; I < p.NB; ++I) {
+    for (int I = I_lo; I < I_hi; ++I) {
       const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
-      if (J >= 0 && J <= I) atomicAdd(&cnt[J], 1);
+      if (J >= 0 && J <= I) atomicAdd(&mine[J], 1);
       // an earlier block with at least kInvFewKeys valid keys gives every row of I that many keys
       const int vcount = min((J + 1) * p.b, p.L) - max(J * p.b, p0);
       if (__ballot(J >= 0 && J < I && vcount >= kInvFewKeys) != 0ull && lane == 0) few[I] = 0;
     }
   }
   __syncthreads();
-  // exclusive scan of cnt[0..NB) in chunks of 64; cnt[NB] receives the total
-  int carry = 0;
-  for (int J0 = 0; J0 <= p.NB; J0 += 64) {
-    const int J = J0 + lane;
-    const int c = J < p.NB ? cnt[J] : 0;
-    int incl = c;
+  // exclusive scan over (key block, wavefront) in chunks of 64 key blocks; o[NB] receives the total
+  if (wv == 0) {
+    int carry = 0;
+    for (int J0 = 0; J0 <= p.NB; J0 += 64) {
+      const int J = J0 + lane;
+      int c = 0;
+      if (J < p.NB)
+        for (int w = 0; w < W; ++w) c += cnt[w * stride + J];
+      int incl = c;
 #pragma unroll
-    for (int off = 1; off < 64; off <<= 1) {
-      const int up = __shfl_up(incl, off);
-      if (lane >= off) incl += up;
+      for (int off = 1; off < 64; off <<= 1) {
+        const int up = __shfl_up(incl, off);
+        if (lane >= off) incl += up;
+      }
+      if (J <= p.NB) {
+        int base = carry + incl - c;
+        o[J] = base;
+        if (J < p.NB)
+          for (int w = 0; w < W; ++w) {
+            const int cw = cnt[w * stride + J];
+            cnt[w * stride + J] = base;
+            base += cw;
+          }
+      }
+      carry += __shfl(incl, 63);
     }
-    if (J <= p.NB) {
-      cnt[J] = carry + incl - c;
-      o[J] = carry + incl - c;
-    }
-    carry += __shfl(incl, 63);
   }
   __syncthreads();
   for (int e0 = 0; e0 < p.k; e0 += 64) {
     const int e = e0 + lane;
 #pragma unroll 8
-    for (int I = 0; I < p.NB; ++I) {
+    for (int I = I_lo; I < I_hi; ++I) {
       const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
-      if (J >= 0 && J <= I) it[atomicAdd(&cnt[J], 1)] = I | ((int)few[I] << kInvFewShift);
+      if (J >= 0 && J <= I) it[atomicAdd(&mine[J], 1)] = I | ((int)few[I] << kInvFewShift);
     }
   }
 }
@@ -815,8 +837,12 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     hipLaunchKernelGGL(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
                        a.d_gate_b, p);
   }
-  if (stages & kBwdStageInverse)
-    hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64), 0, st, a.sel, a.valid_len, w.offs, w.items, p);
+  if (stages & kBwdStageInverse) {
+    const int W = p.NB <= kInvWavesMaxNB ? kInvWaves : 1;
+    const size_t lds = (size_t)W * (p.NB + 1) * sizeof(int) + (size_t)(p.NB + 1 + 3) / 4 * 4;
+    hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64 * W), lds, st, a.sel, a.valid_len, w.offs, w.items,
+                       p);
+  }
   if (mfma) {
     launch_bwd_mfma(p, a, w, stages, st);
     return;
