@@ -34,7 +34,8 @@ namespace {
 // constant" is formed next to each read and the constant folds into the instruction's immediate.
 struct ReadOffsets {
   int row[4];  // row-per-lane 16-byte reads: slab kk; add 2*32*unit*D
-  int tr[2];   // transposing 8-byte reads: M-block mb; add 2*(32*unit + 16*t + 8*x)*D
+  int tr[2];   // transposing 8-byte reads: M-block mb; add 2*(32*unit + 16*t)*D
+  int tr8[2];  // the same for the read 8 rows further down (row bit 3 set: another swizzle)
 };
 
 __device__ __forceinline__ ReadOffsets read_offsets(int lane)
@@ -45,8 +46,12 @@ __device__ __forceinline__ ReadOffsets read_offsets(int lane)
   for (int kk = 0; kk < 4; ++kk) o.row[kk] = 2 * (lq * D + (((2 * kk + lh) ^ swz(lq)) * 8));
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
-    o.tr[mb] = 2 * ((4 * lh + (r16 >> 2)) * D +
-                    (((4 * mb + 2 * g1 + ((r16 & 3) >> 1)) ^ (2 * (r16 >> 2) + lh)) * 8) + 4 * (r16 & 1));
+  {
+    const int row = 4 * lh + (r16 >> 2);  // rows row and row + 8 of a 16-row contraction slab
+    const int chunk = 4 * mb + 2 * g1 + ((r16 & 3) >> 1);
+    o.tr[mb] = 2 * (row * D + ((chunk ^ swz(row)) * 8) + 4 * (r16 & 1));
+    o.tr8[mb] = 2 * ((row + 8) * D + ((chunk ^ swz(row + 8)) * 8) + 4 * (r16 & 1));
+  }
   return o;
 }
 
@@ -59,7 +64,8 @@ struct Stager {
   int wv, ld_row;
   bool ragged;
   int L, NB;
-  unsigned lane_off;  // bytes: (ld_row, chunk) of this lane inside a tile
+  unsigned lane_off;  // bytes: (ld_row, chunk) of this lane inside a tile, 8-row slices 0 and 2
+  unsigned lane_odd;  // the same for slices 1 and 3 (row bit 3 set: another swizzle)
   __device__ __forceinline__ void init(int wv_, int lane, int L_, int NB_)
   {
     wv = wv_;
@@ -68,7 +74,8 @@ struct Stager {
     ld_row = 32 * wv + (lane >> 3);
     ragged = L % BLK != 0;
     // LDS chunk position lane&7 holds chunk (lane&7)^swz(row)
-    lane_off = (unsigned)(ld_row * D + ((lane & 7) ^ (2 * ((lane >> 3) & 3) + ((lane >> 5) & 1))) * 8) * 2u;
+    lane_off = (unsigned)(ld_row * D + ((lane & 7) ^ swz(ld_row)) * 8) * 2u;
+    lane_odd = (unsigned)(ld_row * D + ((lane & 7) ^ swz(ld_row + 8)) * 8) * 2u;
   }
   // src_head: first element of the (row, head) slice of the tensor
   __device__ __forceinline__ void stage(const uint16_t *src_head, uint16_t *dst_tile, int blk) const
@@ -78,14 +85,14 @@ struct Stager {
     lds_void *dst = (lds_void *)(dst_tile + 32 * wv * D);
     if (!ragged || blk != NB - 1) {
       __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 1024, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_odd), dst, 16, 1024, 0);
       __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 2048, 0);
-      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 3072, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_odd), dst, 16, 3072, 0);
     } else {  // last, partial block: rows past the end are clamped (always masked)
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int over = max(0, blk * BLK + ld_row + 8 * u - (L - 1));
-        const unsigned off = lane_off + (unsigned)((8 * u - over) * D * 2);
+        const unsigned off = ((u & 1) ? lane_odd : lane_off) + (unsigned)((8 * u - over) * D * 2);
         __builtin_amdgcn_global_load_lds((glb_void *)(src + off), (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
       }
     }
@@ -98,11 +105,11 @@ __device__ __forceinline__ bf16x8 lds_row(const uint16_t *tile, int off)
   return *reinterpret_cast<const bf16x8 *>(reinterpret_cast<const char *>(tile) + off);
 }
 
-__device__ __forceinline__ bf16x8 lds_tr(const uint16_t *tile, int off)
+__device__ __forceinline__ bf16x8 lds_tr(const uint16_t *tile, int off, int off8)
 {
-  const char *a = reinterpret_cast<const char *>(tile) + off;
-  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a));
-  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + 2 * 8 * D));
+  const char *a = reinterpret_cast<const char *>(tile);
+  const s16x4 lo = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + off));
+  const s16x4 hi = __builtin_amdgcn_ds_read_tr16_b64_v4i16((lds_s16x4 *)(a + off8));
   return __builtin_bit_cast(bf16x8, __builtin_shufflevector(lo, hi, 0, 1, 2, 3, 4, 5, 6, 7));
 }
 
@@ -323,7 +330,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
-    asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]));
+    asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
     const bool hp = (windowed ? hp_st : hp_lt) != 0;
     const bool masked = windowed || J == I || J * BLK < p0;
     const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
@@ -360,7 +367,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb)
-          dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+          dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, 2 * (32 * s + 16 * t) * D + ro.tr[mb], 2 * (32 * s + 16 * t) * D + ro.tr8[mb]), dsf[t],
                                                            dq[mb], 0, 0, 0);
       if (hp) {
 #pragma unroll
@@ -370,7 +377,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int mb = 0; mb < 2; ++mb)
-            dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+            dq[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(ks, 2 * (32 * s + 16 * t) * D + ro.tr[mb], 2 * (32 * s + 16 * t) * D + ro.tr8[mb]), dsf[t],
                                                              dq[mb], 0, 0, 0);
       }
     }
@@ -505,7 +512,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, bool hp)
                        __attribute__((always_inline)) {
-    asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]));
+    asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
     const bool masked = windowed || Iq == J || Iq * BLK < p0 || J * BLK < p0 || (Iq + 1) * BLK > p.L;
     // visible <=> key valid and lo_i <= i <= hi_i
     const int lo_i = max(j, p0);
@@ -543,9 +550,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       for (int t = 0; t < 2; ++t)
 #pragma unroll
         for (int mb = 0; mb < 2; ++mb) {
-          dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), pf[t],
+          dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, 2 * (32 * s + 16 * t) * D + ro.tr[mb], 2 * (32 * s + 16 * t) * D + ro.tr8[mb]), pf[t],
                                                            dv[mb], 0, 0, 0);
-          dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+          dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, 2 * (32 * s + 16 * t) * D + ro.tr[mb], 2 * (32 * s + 16 * t) * D + ro.tr8[mb]), dsf[t],
                                                            dk[mb], 0, 0, 0);
         }
       if (hp) {  // rows with few keys: large P and dS, add the rounding residuals as a second bf16 term
@@ -560,9 +567,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         for (int t = 0; t < 2; ++t)
 #pragma unroll
           for (int mb = 0; mb < 2; ++mb) {
-            dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), pf[t],
+            dv[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(gsm, 2 * (32 * s + 16 * t) * D + ro.tr[mb], 2 * (32 * s + 16 * t) * D + ro.tr8[mb]), pf[t],
                                                              dv[mb], 0, 0, 0);
-            dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, 2 * (32 * s + 16 * t) * D + ro.tr[mb]), dsf[t],
+            dk[mb] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_tr(qs, 2 * (32 * s + 16 * t) * D + ro.tr[mb], 2 * (32 * s + 16 * t) * D + ro.tr8[mb]), dsf[t],
                                                              dk[mb], 0, 0, 0);
           }
       }

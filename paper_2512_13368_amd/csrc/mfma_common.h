@@ -34,13 +34,16 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned pid, unsigned total)
 }
 
 // A staged tile is BLK rows of 128 bytes; 16-byte chunk c of row r sits at chunk position
-// c ^ swz(r).  This swizzle serves both operand read patterns without bank conflicts:
-//  - row-per-lane 16-byte reads (8 consecutive rows, one chunk column): swz is a bijection of
-//    r mod 8, so the 8 lanes of a 128-byte LDS cycle hit 8 distinct positions;
+// c ^ swz(r).  Measured on gfx950: the LDS serves 16 lanes x 16 bytes per cycle over 64 banks
+// (rows of 128 bytes alternate between the two bank halves), and the lanes of one cycle of a
+// 16-byte read run over bits 1-3 of the lane index (bit 4 tied to them, bit 0 free).  The
+// swizzle serves both operand read patterns without bank conflicts:
+//  - row-per-lane 16-byte reads (lane = row, one chunk column): swz is injective over row bits
+//    1-3 for fixed bits 0 and 4 (position bits: b2, b0 ^ b3, b1);
 //  - transposing 8-byte reads (4 consecutive rows r0..r0+3, r0 % 4 == 0, two adjacent chunk
 //    columns c0, c0+1 with c0 even): positions (c0 ^ swz) and (c0 ^ swz ^ 1) over the four rows
-//    are 8 distinct values because swz(r) = 2*(r%4) + (r/4)%2 differs in bits 1-2 between rows.
-__device__ __forceinline__ int swz(int r) { return ((r & 3) << 1) | ((r >> 2) & 1); }
+//    are 8 distinct values because swz differs in bits 1-2 between rows with equal bits 2-3.
+__device__ __forceinline__ int swz(int r) { return (((r & 3) << 1) | ((r >> 2) & 1)) ^ (((r >> 3) & 1) << 1); }
 
 // bf16 pair -> two floats and back (round to nearest even through the hardware conversion)
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }

@@ -151,7 +151,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // ---- staging: each wavefront moves its 32 rows (4 x 1 KB) of K and of V per tile ----
   // LDS position of 16-byte chunk c of row r:  r*128 + ((c ^ swz(r)) * 16),
-  //   swzK(r) = r & 7 (8 rows x one chunk column = 8 distinct positions for the row-per-lane reads)
+  //   swzK(r) = (r >> 1) & 7 for the row-per-lane 16-byte reads.  Measured on gfx950: the LDS serves
+  //             16 lanes x 16 bytes per cycle over 64 banks, rows of 128 bytes alternate between the
+  //             two bank halves, and a cycle's lanes run over bits 1-3 of the lane index (bit 4
+  //             tied to them, bit 0 free): positions must be distinct over row bits 1-3.
   //   swzV(r) = 2*(r & 3) (4 rows x two chunk columns = 8 distinct positions for the transposing reads)
   // A tile's rows are contiguous in memory, and the LDS copy keeps the 128-byte row pitch, so
   // one uniform base (SGPRs) + one per-lane byte offset + the same immediate for the global
@@ -159,17 +162,19 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const char *Kh = reinterpret_cast<const char *>(K + head);
   const char *Vh = reinterpret_cast<const char *>(V + head);
   const int ld_row = 32 * wv + (lane >> 3);  // + 8*u
-  const unsigned k_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (lane >> 3)) * 8) * 2u;            // bytes
+  // rows 8u .. 8u+7 of a slice: swzK = (lane >> 4) | ((u & 1) << 2), so odd slices use k_lane ^ 64
+  const unsigned k_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (lane >> 4)) * 8) * 2u;            // bytes
   const unsigned v_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8) * 2u;  // bytes
   const bool ragged = p.L % BLK != 0;
-  auto stage = [&](const char *src_head, unsigned lane_off, uint16_t *dst_tile, int J) __attribute__((always_inline)) {
+  auto stage = [&](const char *src_head, unsigned lane_off, unsigned odd_xor, uint16_t *dst_tile, int J) __attribute__((always_inline)) {
     const char *src = src_head + (size_t)J * (TILE * 2);  // uniform
     lds_void *dst = (lds_void *)(dst_tile + 32 * wv * D);
     if (!ragged || J != p.NB - 1) {
+      const unsigned lane_odd = lane_off ^ odd_xor;  // odd 8-row slices (K only: their swizzle differs)
       __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 1024, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_odd), dst, 16, 1024, 0);
       __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 2048, 0);
-      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 3072, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_odd), dst, 16, 3072, 0);
     } else {  // last, partial block: rows past the end are clamped (they are causally masked anyway)
       // (the empty asm hides that J is a constant here: the clamped per-lane offsets would
       // otherwise be computed ahead of the loop and held in registers throughout)
@@ -177,7 +182,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
       for (int u = 0; u < 4; ++u) {
         const int over = max(0, J * BLK + ld_row + 8 * u - (p.L - 1));
-        const unsigned off = lane_off + (unsigned)((8 * u - over) * D * 2);
+        const unsigned off = ((u & 1) ? lane_off ^ odd_xor : lane_off) + (unsigned)((8 * u - over) * D * 2);
         __builtin_amdgcn_global_load_lds((glb_void *)(src + off), (lds_void *)(dst_tile + (32 * wv + 8 * u) * D), 16, 0, 0);
       }
     }
@@ -185,8 +190,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // the first tile is on its way while the rest of the prologue runs
   const int first_J = dense ? J_first : J_lo;
-  stage(Kh, k_lane, Ks0, first_J);
-  stage(Vh, v_lane, Vs0, first_J);
+  stage(Kh, k_lane, 64u, Ks0, first_J);
+  stage(Vh, v_lane, 0u, Vs0, first_J);
 
   // Q^T operand: lane (query lq, half lh) holds c*Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk,
   // c = scale*log2(e), rounded to bf16: the matrix cores then produce base-2 exponents directly.
@@ -248,7 +253,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ---- per-lane LDS read offsets (elements) inside this wavefront's 32 rows ----
   int koff[4];
 #pragma unroll
-  for (int kk = 0; kk < 4; ++kk) koff[kk] = wv * HALF + lq * D + (((2 * kk + lh) ^ (lq & 7)) * 8);
+  for (int kk = 0; kk < 4; ++kk) koff[kk] = wv * HALF + lq * D + (((2 * kk + lh) ^ ((lq >> 1) & 7)) * 8);
   const int r16 = lane & 15;
   int voff[2];
 #pragma unroll
@@ -521,8 +526,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     int J_nxt = 0;
     if (t + 1 < n_all) {
       J_nxt = tile_of(t + 1);
-      stage(Kh, k_lane, k_nxt, J_nxt);
-      stage(Vh, v_lane, v_nxt, J_nxt);
+      stage(Kh, k_lane, 64u, k_nxt, J_nxt);
+      stage(Vh, v_lane, 0u, v_nxt, J_nxt);
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
     } else {
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
