@@ -28,8 +28,8 @@ import numpy as np
 # counters read for a plain copy of known size (FETCH_SIZE x2.000, WRITE_SIZE x1.000); the commands and the
 # raw readings are in profiles/cfg4_hbm_traffic.txt.  Other workloads: not measured (null).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg4", "fwd"): 562903345, ("cfg4", "fwd_saving_for_bwd"): 1208543493, ("cfg4", "bwd_gate"): 855178113,
-    ("cfg4", "bwd_dq"): 805316926, ("cfg4", "bwd_dkv"): 1130622172, ("cfg4", "select"): 276971581,
+    ("cfg4", "fwd"): 563411663, ("cfg4", "fwd_saving_for_bwd"): 1223953232, ("cfg4", "bwd_gate"): 1006286142,
+    ("cfg4", "bwd_dq"): 930666002, ("cfg4", "bwd_dkv"): 1145904236, ("cfg4", "select"): 276949308,
 }
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
@@ -212,7 +212,7 @@ def main():
         "fwd_saving_for_bwd": (4.0 * w.d * pairs, 4 * tensor * sz + 2 * tensor * 4),  # + o_lt, o_st fp32
         "bwd_dq": (6.0 * w.d * pairs, 5 * tensor * sz),                               # S, dP, dQ | Q,K,V,dO,dQ
         "bwd_dkv": (8.0 * w.d * pairs, 6 * tensor * sz),                              # S, dP, dV, dK | Q,K,V,dO,dK,dV
-        "bwd_gate": (0.0, tensor * (2 * sz + 8)),                                     # dO, V, o_lt, o_st
+        "bwd_gate": (0.0, tensor * (sz + 8)),                                         # dO, o_lt, o_st
         "select": (0.0, 2 * tensor * sz),                                             # Q, K
     }
 
