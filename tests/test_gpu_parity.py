@@ -139,6 +139,20 @@ def test_shape_matrix(dtype, d, b):
     run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
 
 
+@pytest.mark.parametrize("b,topk,window", [(64, 1, 5), (64, 2, 40), (32, 1, 200), (32, 2, 7), (64, 3, 20)])
+def test_matrix_core_few_key_rows(b, topk, window):
+    # bf16 d=64 (the matrix-core kernels) where rows see only a few keys far beyond the first blocks:
+    # top-k of one or two (every query block's long-term rows may have few keys), windows shorter than
+    # 32 (every short-term row has few keys).  Exercises the two-term operands and the residual passes of
+    # the backward kernels on most tiles, and the inverse list's few-keys flag.
+    L = 5 * b + b // 2 + 3
+    w = with_shape(WORKLOADS["cfg4"], name=f"few-{b}-{topk}-{window}", B=3, H=2, L=L, d=64, block=b, topk=topk,
+                   window=window, len_lo=1, len_hi=L, seed=500 + b + topk + window)
+    x = make_inputs(w, want_dO=True)
+    x.valid_len[:] = [L, L - b - 5, 2 * b + 1]
+    run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
+
+
 def test_edge_cases():
     base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
     x = make_inputs(base, want_dO=True)
