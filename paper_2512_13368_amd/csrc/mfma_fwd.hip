@@ -543,21 +543,61 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float lse_lt = close_branch(Ks0, Vs0);
 
   // ---- epilogue: gate (Eq. 18-19) and stores of this wavefront's own 32 rows ----
-  if (iq[0] >= p.L) return;
-  const size_t rowoff = head + (size_t)iq[0] * D;
-  const size_t lrow = (size_t)bh * p.L + iq[0];
-  if (dense) {
+  // A lane holds 4 consecutive channels of ONE row per accumulator quad; stored directly, an
+  // instruction would touch 32 rows with 16 or 32 bytes each.  The tiles go through this
+  // wavefront's staging rows instead (free now, XOR-swizzled against bank conflicts) and leave
+  // as whole rows: 256 contiguous bytes per 16 lanes (fp32), 128 per 8 lanes (bf16).
+  const int row0 = qbase[0];  // first of the 32 rows
+  int el = lane;  // opaque copy: keeps the store addressing out of the registers of the tile loop
+  asm volatile("" : "+v"(el));
+  const int elq = el & 31, elh = el >> 5;
+  auto store_f32_rows = [&](float *dst, const f32x16 (&acc)[2], uint16_t *piece_a, uint16_t *piece_b)
+                            __attribute__((always_inline)) {
+    float *pa = reinterpret_cast<float *>(piece_a + wv * HALF);  // rows 0..15, 256 bytes each
+    float *pb = reinterpret_cast<float *>(piece_b + wv * HALF);  // rows 16..31
+    float *mine = elq < 16 ? pa : pb;
+    const int rl = elq & 15;
 #pragma unroll
     for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
-        const int d0 = 32 * mb + 8 * g + 4 * lh;
-        uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(oacc[0][mb][4 * g]) | ((uint32_t)f32_to_bf16(oacc[0][mb][4 * g + 1]) << 16);
-        pk.y = (uint32_t)f32_to_bf16(oacc[0][mb][4 * g + 2]) | ((uint32_t)f32_to_bf16(oacc[0][mb][4 * g + 3]) << 16);
-        *reinterpret_cast<uint2 *>(O + rowoff + d0) = pk;
+        const int chunk = 8 * mb + 2 * g + elh;  // 16-byte chunk of the row
+        *reinterpret_cast<float4 *>(mine + rl * 64 + ((chunk ^ rl) * 4)) =
+            make_float4(acc[mb][4 * g], acc[mb][4 * g + 1], acc[mb][4 * g + 2], acc[mb][4 * g + 3]);
       }
-    if (lh == 0 && lse_lt_out) lse_lt_out[lrow] = lse_lt;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) {
+      const int rr = 4 * (i & 3) + (el >> 4), c = el & 15;
+      const float4 v = *reinterpret_cast<const float4 *>((i < 4 ? pa : pb) + rr * 64 + ((c ^ rr) * 4));
+      const int grow = row0 + 16 * (i >> 2) + rr;
+      if (grow < p.L) *reinterpret_cast<float4 *>(dst + head + (size_t)grow * D + 4 * c) = v;
+    }
+  };
+  // o4(mb, g, e): the value of channel 32*mb + 8*g + 4*lh + e of this lane's row
+  auto store_bf16_rows = [&](uint16_t *dst, auto o4, uint16_t *piece) __attribute__((always_inline)) {
+    uint16_t *pt = piece + wv * HALF;  // 32 rows of 128 bytes
+#pragma unroll
+    for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+      for (int g = 0; g < 4; ++g) {
+        uint2 pk;
+        pk.x = (uint32_t)f32_to_bf16(o4(mb, g, 0)) | ((uint32_t)f32_to_bf16(o4(mb, g, 1)) << 16);
+        pk.y = (uint32_t)f32_to_bf16(o4(mb, g, 2)) | ((uint32_t)f32_to_bf16(o4(mb, g, 3)) << 16);
+        const int chunk = 4 * mb + g;  // 16-byte chunk (8 channels); this lane fills half lh of it
+        *reinterpret_cast<uint2 *>(pt + elq * D + ((chunk ^ (elq & 7)) * 8) + 4 * elh) = pk;
+      }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int rr = 8 * i + (el >> 3), c = el & 7;
+      const uint4 v = *reinterpret_cast<const uint4 *>(pt + rr * D + ((c ^ (rr & 7)) * 8));
+      const int grow = row0 + rr;
+      if (grow < p.L) *reinterpret_cast<uint4 *>(dst + head + (size_t)grow * D + 8 * c) = v;
+    }
+  };
+  const size_t lrow = (size_t)bh * p.L + iq[0];
+  if (dense) {
+    store_bf16_rows(O, [&](int mb, int g, int e) { return oacc[0][mb][4 * g + e]; }, Ks0);
+    if (iq[0] < p.L && lh == 0 && lse_lt_out) lse_lt_out[lrow] = lse_lt;
     return;
   }
   const float *wl = gate_s;
@@ -582,27 +622,14 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   z += __shfl_xor(z, 32);
   z += gate_b ? gate_b[h] : 0.0f;
   const float alpha = q_ok[0] ? 1.0f / (1.0f + __expf(-z)) : 0.0f;
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = 32 * mb + 8 * g + 4 * lh;
-      float o4[4];
-#pragma unroll
-      for (int e = 0; e < 4; ++e)
-        o4[e] = alpha * oacc[0][mb][4 * g + e] + (1.0f - alpha) * ost[mb][4 * g + e];
-      uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(o4[0]) | ((uint32_t)f32_to_bf16(o4[1]) << 16);
-      pk.y = (uint32_t)f32_to_bf16(o4[2]) | ((uint32_t)f32_to_bf16(o4[3]) << 16);
-      *reinterpret_cast<uint2 *>(O + rowoff + d0) = pk;
-      if (o_lt_out) {
-        *reinterpret_cast<float4 *>(o_lt_out + rowoff + d0) =
-            make_float4(oacc[0][mb][4 * g], oacc[0][mb][4 * g + 1], oacc[0][mb][4 * g + 2], oacc[0][mb][4 * g + 3]);
-        *reinterpret_cast<float4 *>(o_st_out + rowoff + d0) =
-            make_float4(ost[mb][4 * g], ost[mb][4 * g + 1], ost[mb][4 * g + 2], ost[mb][4 * g + 3]);
-      }
-    }
-  if (lh == 0) {
+  if (o_lt_out) {
+    store_f32_rows(o_lt_out, oacc[0], Ks0, Ks1);
+    store_f32_rows(o_st_out, ost, Vs0, Vs1);
+  }
+  store_bf16_rows(O, [&](int mb, int g, int e) {
+    return alpha * oacc[0][mb][4 * g + e] + (1.0f - alpha) * ost[mb][4 * g + e];
+  }, Ks0);
+  if (iq[0] < p.L && lh == 0) {
     if (lse_lt_out) lse_lt_out[lrow] = lse_lt;
     if (lse_st_out) lse_st_out[lrow] = lse_st;
   }
