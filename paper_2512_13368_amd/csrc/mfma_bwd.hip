@@ -13,9 +13,13 @@
 //
 // Accumulators start at minus a per-row constant, so the MFMA result is directly what the next
 // step needs: the exponent S'' = c*q.k - lse*log2(e) (Q or K pre-multiplied by c =
-// scale*log2(e)) and dO_x,i.v_j - c_x,i.  The constants arrive as three-term bf16 splits and
-// are broadcast into the accumulator by one extra matrix instruction (ones x split), so no
-// per-element VALU initialisation is needed.  Probabilities and dS leave the accumulator
+// scale*log2(e)) and dO_x,i.v_j - c_x,i.  The constants arrive as three-term bf16 splits (exact).
+// dK/dV, where they change with every query tile, broadcasts them into the accumulator by one
+// extra matrix instruction (ones x split); dQ, where a lane keeps its row for the whole walk,
+// holds them as two 16-register blocks that the first matrix instruction of each product
+// takes as its C operand.  Either way no per-element VALU initialisation is needed.  (Reading
+// the dK/dV constants from LDS straight into a C block was measured slower: that kernel's LDS
+// pipe is as busy as its matrix pipe.)  Probabilities and dS leave the accumulator
 // registers as the B operand of the next product without moving between lanes; the matching
 // A operands (K^T, Q^T, dO_x^T) come from LDS through the transposing ds_read_b64_tr_b16.
 // Query blocks whose rows may see only a few keys (large probabilities) feed P and dS as
@@ -242,8 +246,16 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // per-row constants (pad rows carry an exponent of -1e30: every probability of the column is zero)
   const uint4 ri_st = rowI_st[lrow];
   const uint4 ri_lt = rowI_lt[lrow];
-  bf16x8 l2n = split_operand(ri_st.x, ri_st.y), c1n = split_operand(ri_st.z, ri_st.w);
-  const bf16x8 ones = ones3(lh);
+  // s_init, g_init: -lse2[i] and -c_x[i] of this lane's row in every accumulator slot.  The
+  // first matrix instruction of each product takes them as its C operand, so the logits and
+  // dP - c_x leave the matrix cores with the row terms already applied.
+  f32x16 s_init, g_init;
+  auto set_init = [&](uint32_t sx, uint32_t sy, uint32_t cx, uint32_t cy) __attribute__((always_inline)) {
+    const float a = unsplit3(sx, sy), b = unsplit3(cx, cy);
+#pragma unroll
+    for (int i = 0; i < 16; ++i) { s_init[i] = a; g_init[i] = b; }
+    asm volatile("" : "+v"(s_init), "+v"(g_init));  // register blocks, not one value copied at each use
+  };
 
   // ---- tile list: window blocks, then the selection list up to its first -1 ----
   const int J_first = p0 / BLK;
@@ -318,7 +330,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       c1_st_x = ns.x; c1_st_y = ns.y; c1_lt_x = nl.x; c1_lt_y = nl.y;
     }
   }
-  c1n = split_operand(c1_st_x, c1_st_y);
+  set_init(ri_st.x, ri_st.y, c1_st_x, c1_st_y);
   __syncthreads();
   auto tile_of = [&](int t) -> int { return __builtin_amdgcn_readfirstlane(tiles[t]); };
 
@@ -327,7 +339,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const uint16_t *k_lane = K + head;  // (row, head) slices; the stager adds block and lane offsets
   const uint16_t *v_lane = V + head;
   ReadOffsets ro = read_offsets(lane);
-  const f32x16 zero16 = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
 
   auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
     asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
@@ -338,10 +349,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const bool any = iq >= lo;
 #pragma unroll
     for (int s = 0; s < UNITS; ++s) {
-      f32x16 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, l2n, zero16, 0, 0, 0);
-      f32x16 gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(ones, c1n, zero16, 0, 0, 0);
+      f32x16 sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(ks, 2 * 32 * s * D + ro.row[0]), qf[0], s_init, 0, 0, 0);
+      f32x16 gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 2 * 32 * s * D + ro.row[0]), gf[0], g_init, 0, 0, 0);
 #pragma unroll
-      for (int kk = 0; kk < 4; ++kk) {
+      for (int kk = 1; kk < 4; ++kk) {
         sacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(ks, 2 * 32 * s * D + ro.row[kk]), qf[kk], sacc, 0, 0, 0);
         gacc = __builtin_amdgcn_mfma_f32_32x32x16_bf16(lds_row(vs, 2 * 32 * s * D + ro.row[kk]), gf[kk], gacc, 0, 0, 0);
       }
@@ -402,8 +413,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         gf[kk] = gf_next[kk];
         gl[kk] = gl_next[kk];
       }
-      l2n = split_operand(ri_lt.x, ri_lt.y);
-      c1n = split_operand(c1_lt_x, c1_lt_y);
+      set_init(ri_lt.x, ri_lt.y, c1_lt_x, c1_lt_y);
     }
     tile_body(k_cur, v_cur, tile_of(t), t < n_st);
     __syncthreads();
