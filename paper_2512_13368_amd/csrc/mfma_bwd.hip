@@ -168,7 +168,6 @@ __device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x
     }
 }
 
-constexpr int kMaxTilesQ = 96;  // window blocks + selected blocks of one query block (host-checked)
 constexpr int kFewKeys = 32;    // rows seeing fewer keys than this get two-term bf16 operands
 
 // ones[.][0..2] in the half of the wavefront that holds contraction slots 0..7: multiplied with a
@@ -212,7 +211,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
-  __shared__ int tiles[kMaxTilesQ];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -265,10 +263,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int n_st = I - J_lo + 1;
   int n_lt = 0;
   bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
+  const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
   {
-    const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
-    if (wv == 0)
-      for (int t = lane; t < n_st; t += 64) tiles[t] = J_lo + t;
     bool open = true;
     for (int e0 = 0; e0 < p.k; e0 += 64) {
       const int e = e0 + lane;
@@ -277,7 +273,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);
       if (open) {
         const bool mine = lane < lead;
-        if (wv == 0 && mine) tiles[n_st + e] = J;
         const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
         if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
         n_lt += lead;
@@ -332,7 +327,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
   set_init(ri_st.x, ri_st.y, c1_st_x, c1_st_y);
   __syncthreads();
-  auto tile_of = [&](int t) -> int { return __builtin_amdgcn_readfirstlane(tiles[t]); };
+  // Block id of tile t: window blocks by arithmetic, selected blocks by a scalar load from the
+  // selection row (uniform address), issued a whole tile before its value is needed.
+  auto tile_of = [&](int t) -> int {
+    const int e = __builtin_amdgcn_readfirstlane(t - n_st);
+    typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
+    return e < 0 ? J_lo + t : ((const_int_ptr)my_sel)[e];
+  };
 
   Stager<BLK> sg;
   sg.init(wv, lane, p.L, p.NB);
@@ -394,18 +395,17 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
-  {
-    const int J0 = tile_of(0);
-    sg.stage(k_lane, Ks0, J0);
-    sg.stage(v_lane, Vs0, J0);
-  }
+  int J_cur = tile_of(0);
+  int J_nxt = tile_of(min(1, n_all - 1));
+  sg.stage(k_lane, Ks0, J_cur);
+  sg.stage(v_lane, Vs0, J_cur);
   __syncthreads();
   auto step = [&](int t, uint16_t *k_fill, uint16_t *v_fill, const uint16_t *k_cur, const uint16_t *v_cur)
                   __attribute__((always_inline)) {
+    const int J_after = tile_of(min(t + 2, n_all - 1));  // consumed at the end of this step
     if (t + 1 < n_all) {
-      const int Jn = tile_of(t + 1);
-      sg.stage(k_lane, k_fill, Jn);
-      sg.stage(v_lane, v_fill, Jn);
+      sg.stage(k_lane, k_fill, J_nxt);
+      sg.stage(v_lane, v_fill, J_nxt);
     }
     if (t == n_st) {  // the long-term tiles start: switch to that branch's gradient and constants
 #pragma unroll
@@ -415,7 +415,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
       set_init(ri_lt.x, ri_lt.y, c1_lt_x, c1_lt_y);
     }
-    tile_body(k_cur, v_cur, tile_of(t), t < n_st);
+    tile_body(k_cur, v_cur, J_cur, t < n_st);
+    J_cur = J_nxt;
+    J_nxt = J_after;
     __syncthreads();
   };
   for (int t = 0; t < n_all; t += 2) {
@@ -433,7 +435,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 //                       P = 2^S'',  dS = P*G
 //                       dV^T += dO_x^T P,  dK^T += Q^T dS
 // =============================================================================================
-constexpr int kListRing = 128;
 
 template <int BLK>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
@@ -446,14 +447,12 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 {
   constexpr int UNITS = BLK / 32;
   constexpr int TILE = BLK * D;
-  constexpr int NT = BLK * 2;
   __shared__ __attribute__((aligned(1024))) uint16_t Qs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Qs1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Gs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Gs1[TILE];
   // per-row constants of the staged query tile: splits of -lse2 (x, y) and of -c_x (z, w)
   __shared__ __attribute__((aligned(16))) uint4 rc_s[2][BLK];
-  __shared__ int ring[kListRing];  // query blocks of the long-term part of the walk, refilled in halves
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
@@ -494,11 +493,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int n_lt = offs[(size_t)bh * (p.NB + 1) + J + 1] - e_lo;
   const int n_all = n_st + n_lt;
   const int *my_items = items + (size_t)bh * p.NB * p.k + e_lo;
-  for (int e = tid; e < min(n_lt, kListRing); e += NT) ring[e] = my_items[e];
-  __syncthreads();
-  // query block of step t, with the few-keys flag of the list entries in bit kInvFewShift
+  // Query block of step t, with the few-keys flag of the list entries in bit kInvFewShift:
+  // window blocks by arithmetic, list entries by a scalar load (uniform address), issued a
+  // whole tile before the value is needed.
   auto entry_of = [&](int t) -> int {
-    return t < n_st ? J + t : __builtin_amdgcn_readfirstlane(ring[(t - n_st) & (kListRing - 1)]);
+    const int e = __builtin_amdgcn_readfirstlane(t - n_st);
+    typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
+    return e < 0 ? J + t : ((const_int_ptr)my_items)[e];
   };
 
   Stager<BLK> sg;
@@ -587,6 +588,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   };
 
   int ent_cur = entry_of(0);
+  int ent_nxt = entry_of(min(1, n_all - 1));
   {
     const int I0 = ent_cur & kInvBlockMask;
     const bool win0 = 0 < n_st;
@@ -600,20 +602,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
                   int par) __attribute__((always_inline)) {
     uint4 rn = pad_consts;
     const bool more = t + 1 < n_all;
-    int ent_nxt = 0;
+    const int ent_after = entry_of(min(t + 2, n_all - 1));  // consumed at the end of this step
     if (more) {
-      ent_nxt = entry_of(t + 1);
       const int In = ent_nxt & kInvBlockMask;
       const bool win_n = t + 1 < n_st;
       rn = row_consts(In, win_n);
       sg.stage(q_lane, q_fill, In);
       sg.stage(win_n ? gs_lane : gl_lane, g_fill, In);
-    }
-    // refill the half of the ring that was consumed 64 steps ago
-    const int e = t - n_st;
-    if (e >= 64 && (e & 63) == 0) {
-      const int src = e + 64 + tid;
-      if (tid < 64 && src < n_lt) ring[src & (kListRing - 1)] = my_items[src];
     }
     const bool win = t < n_st;
     const int Iq = ent_cur & kInvBlockMask;
@@ -623,6 +618,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     tile_body(q_cur, g_cur, par, Iq, win, hp);
     if (more && tid < BLK) rc_s[par ^ 1][tid] = rn;
     ent_cur = ent_nxt;
+    ent_nxt = ent_after;
     __syncthreads();
   };
   for (int t = 0; t < n_all; t += 2) {
@@ -699,8 +695,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool bwd_mfma_supported(const KParams &p, int dtype)
 {
-  if (dtype != 1 || p.d != 64 || (p.b != 32 && p.b != 64)) return false;
-  return (long)(p.w - 1) / p.b + 2 + p.k <= kMaxTilesQ;
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64);
 }
 
 void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st)

@@ -40,7 +40,6 @@ using namespace mfma;
 namespace {
 
 constexpr float kRaise = 8.0f;  // log2 units by which the maximum must grow before it is raised
-constexpr int kMaxTiles = 96;   // window blocks + selected blocks one query block may walk (host-checked)
 constexpr int kFewKeys = 32;    // rows seeing fewer keys than this get two-term bf16 probabilities
 constexpr float kSumLimit = 4096.0f;  // a lane's 16 probabilities of a tile may sum to this (16 * 2^kRaise)
 
@@ -69,7 +68,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
-  __shared__ int tiles[kMaxTiles];    // key blocks in processing order: window blocks, then selected blocks
   __shared__ float gate_s[2 * D];     // this head's gate weights, fetched at the start, used at the very end
   __shared__ float xch_s[NQ][2][64];  // branch merge: reference and partial row sum handed to the partner
 
@@ -214,16 +212,14 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // ---- tile list: window blocks J_lo..I, then the selection list up to its first -1 ----
   // Every wavefront reads the whole selection row with one vector load per 64 entries and
-  // derives the counts from ballots (no chain of dependent scalar loads); the list itself is
-  // parked in LDS so that walking it never waits on the vector-memory counter, which also
-  // tracks the tile prefetches in flight.
+  // derives the counts from ballots (no chain of dependent scalar loads).  The walk itself
+  // fetches one entry per tile with a scalar load (see tile_raw): those do not touch the
+  // vector-memory counter, which tracks the tile prefetches in flight.
   int n_all;
   bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
   if (dense) {
     n_all = I - J_first + 1;
   } else {
-    if (wv == 0)
-      for (int t = lane; t < n_st; t += 64) tiles[t] = J_lo + t;
     int n_lt = 0;
     bool open = true;
     for (int e0 = 0; e0 < p.k; e0 += 64) {
@@ -234,7 +230,6 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);  // entries before the first -1
       if (open) {
         const bool mine = lane < lead;
-        if (wv == 0 && mine) tiles[n_st + e] = J;
         // a full earlier block already brings a whole block of keys; only a partial first block may not
         const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
         if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
@@ -245,9 +240,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     n_all = n_st + n_lt;
   }
   __syncthreads();
-  auto tile_of = [&](int t) -> int {
+  // Block id of tile t: window blocks by arithmetic, selected blocks by a scalar load from the
+  // selection row (uniform address), issued a whole tile before its value is needed.
+  auto tile_raw = [&](int t) -> int {
     if (dense) return J_first + t;
-    return __builtin_amdgcn_readfirstlane(tiles[t]);
+    const int e = __builtin_amdgcn_readfirstlane(t - n_st);
+    typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
+    return e < 0 ? J_lo + t : ((const_int_ptr)my_sel)[e];
   };
 
   // ---- per-lane LDS read offsets (elements) inside this wavefront's 32 rows ----
@@ -522,10 +521,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // step t: prefetch tile t+1 into the other buffer pair, wait for this wavefront's own loads
   // of tile t (the 8 just issued stay in flight), process tile t
   int J_cur = first_J;
+  int J_nxt = __builtin_amdgcn_readfirstlane(tile_raw(min(1, n_all - 1)));
   auto step = [&](int t, uint16_t *k_cur, uint16_t *v_cur, uint16_t *k_nxt, uint16_t *v_nxt) __attribute__((always_inline)) {
-    int J_nxt = 0;
+    const int J_after = tile_raw(min(t + 2, n_all - 1));  // consumed at the end of this step
     if (t + 1 < n_all) {
-      J_nxt = tile_of(t + 1);
       stage(Kh, k_lane, 64u, k_nxt, J_nxt);
       stage(Vh, v_lane, 0u, v_nxt, J_nxt);
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
@@ -534,6 +533,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     tile(k_cur, v_cur, J_cur, t < n_st);
     J_cur = J_nxt;
+    J_nxt = __builtin_amdgcn_readfirstlane(J_after);
     if (st_open && t + 1 >= n_st) close_st(k_cur, v_cur);  // the window tiles are done
   };
   for (int t = 0; t < n_all; t += 2) {
@@ -637,9 +637,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool fwd_mfma_supported(const KParams &p, int dtype)
 {
-  if (dtype != 1 || p.d != 64 || (p.b != 32 && p.b != 64)) return false;
-  // window blocks (at most (w-1)/b + 2) plus selected blocks must fit the in-LDS tile list
-  return (long)(p.w - 1) / p.b + 2 + p.k <= kMaxTiles;
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64);
 }
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)

@@ -153,6 +153,27 @@ def test_matrix_core_few_key_rows(b, topk, window):
     run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
 
 
+def test_matrix_core_long_walks():
+    # bf16 d=64 b=32 with more than a hundred tiles per query block.  First a window wider than the
+    # sequence plus a top-k that keeps every block: both branches are dense causal attention (forward;
+    # in that limit the gradient rms is set by thousands of late rows with tiny gradients, which makes
+    # the rms-floored tolerance a 5-sigma test for the first rows, so backward is checked on the second
+    # case).  Then window tiles and selected tiles each above 64 entries: the selection row is read in
+    # two chunks, and the walk is longer than any of the workloads'.
+    L = 32 * 104 + 5
+    w = with_shape(WORKLOADS["cfg3"], name="long-dense-limit", B=1, H=2, L=L, d=64, block=32, topk=105,
+                   window=L, len_lo=L, len_hi=L, seed=611)
+    x2, sel, f, _ = run_case(w, x=make_inputs(w, want_dO=True), backward=False, check_dense=True, gate_scale=0.4)
+    dv = Dev(x2)
+    Od, _ = B.dense_causal_fwd(params(w), dv.Q, dv.K, dv.V, dv.vl)
+    torch.cuda.synchronize()
+    assert_close(host(f.o_lt), host(Od), 2e-2, "o_lt vs dense kernel")
+    assert_close(host(f.o_st), host(Od), 2e-2, "o_st vs dense kernel")
+    w = with_shape(WORKLOADS["cfg3"], name="long-mixed", B=2, H=1, L=L, d=64, block=32, topk=70,
+                   window=32 * 66, len_lo=L - 700, len_hi=L, seed=612)
+    run_case(w, backward=True, gate_scale=0.4)
+
+
 def test_edge_cases():
     base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
     x = make_inputs(base, want_dO=True)
