@@ -544,7 +544,6 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
 // ascending in I; the ranges are laid out one after the other per key block (the scan hands
 // each wavefront its base), so the whole list is ascending and the result is deterministic.
 // =============================================================================================
-constexpr int kMaxNBInv = 4096;
 constexpr int kInvWaves = 4;      // wavefronts per (row, head) when the counters fit
 constexpr int kInvWavesMaxNB = 2048;
 

@@ -64,8 +64,6 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, cons
 // scores are parked in LDS; a candidate is selected iff fewer than `take` candidates beat it
 // under (score descending, index ascending); ballots and prefix popcounts emit the list in
 // ascending order.
-constexpr int kMaxNB = 4096;
-
 template <int D>
 __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict__ qsum,
                                                         const float *__restrict__ kmeanT,
