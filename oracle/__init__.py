@@ -47,14 +47,14 @@ def lib() -> ctypes.CDLL:
         L.oracle_select_blocks.restype = _c_int
         L.oracle_select_blocks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
         L.oracle_build_masks.restype = _c_int
-        L.oracle_build_masks.argtypes = [_c_int] * 5 + [_vp, _vp, _vp]
+        L.oracle_build_masks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp]
         L.oracle_masked_attention.restype = _c_int
         L.oracle_masked_attention.argtypes = [_c_int, _c_int, _vp, _vp, _vp, _vp, _c_dbl, _vp, _vp]
         L.oracle_attn_fwd.restype = _c_int
-        L.oracle_attn_fwd.argtypes = ([_c_int] * 7 + [_c_dbl, _c_int] + [_vp] * 7 + [_vp, _c_int]
+        L.oracle_attn_fwd.argtypes = ([_c_int] * 8 + [_c_dbl, _c_int] + [_vp] * 7 + [_vp, _c_int]
                                       + [_vp] * 7)
         L.oracle_attn_bwd.restype = _c_int
-        L.oracle_attn_bwd.argtypes = ([_c_int] * 7 + [_c_dbl, _c_int] + [_vp] * 8 + [_vp, _c_int]
+        L.oracle_attn_bwd.argtypes = ([_c_int] * 8 + [_c_dbl, _c_int] + [_vp] * 8 + [_vp, _c_int]
                                       + [_vp] * 5)
         L.oracle_dense_causal_fwd.restype = _c_int
         L.oracle_dense_causal_fwd.argtypes = ([_c_int] * 4 + [_c_dbl, _c_int] + [_vp] * 4
@@ -106,14 +106,17 @@ def select_blocks(Q, K, valid_len, block, topk, bh_list=None, want_scores=False)
     return (sel, scores) if want_scores else sel
 
 
-def build_masks(L, block, topk, window, n_valid, sel_bh):
-    """The two materialised masks of one (row, head): uint8 [L,L] each."""
+def build_masks(L, block, topk, window, n_valid, sel_bh, stis_block=0):
+    """The two materialised masks of one (row, head): uint8 [L,L] each.
+
+    stis_block = 0: the short-term mask is the causal local window; >= 1: the causal form of all
+    three terms of Eq. 15 with that mask block size."""
     s = np.ascontiguousarray(sel_bh, dtype=np.int32)
     NB = -(-L // block)
     assert s.shape == (NB, topk)
     M_lt = np.zeros((L, L), dtype=np.uint8)
     M_st = np.zeros((L, L), dtype=np.uint8)
-    _check(lib().oracle_build_masks(L, block, topk, window, int(n_valid), _p(s), _p(M_lt), _p(M_st)),
+    _check(lib().oracle_build_masks(L, block, topk, window, int(stis_block), int(n_valid), _p(s), _p(M_lt), _p(M_st)),
            "build_masks")
     return M_lt, M_st
 
@@ -145,7 +148,7 @@ class Fwd:
 
 
 def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale=None,
-             bh_list=None, f64=False) -> Fwd:
+             bh_list=None, f64=False, stis_block=0) -> Fwd:
     Q = _in(Q, f64)
     K = _in(K, f64)
     V = _in(V, f64)
@@ -163,7 +166,7 @@ def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale
     z = lambda *s: np.zeros(s, dtype=np.float64)
     out = Fwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L), z(n_bh, L), z(n_bh, L), 0, 0)
     nnz = np.zeros(2, dtype=np.int64)
-    rc = lib().oracle_attn_fwd(B, H, L, d, block, topk, window, float(scale), int(f64),
+    rc = lib().oracle_attn_fwd(B, H, L, d, block, topk, window, int(stis_block), float(scale), int(f64),
                                _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(bh), n_bh,
                                _p(out.O), _p(out.o_lt), _p(out.o_st), _p(out.lse_lt), _p(out.lse_st),
                                _p(out.alpha), _p(nnz))
@@ -182,7 +185,7 @@ class Bwd:
 
 
 def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, scale=None,
-             bh_list=None, f64=False) -> Bwd:
+             bh_list=None, f64=False, stis_block=0) -> Bwd:
     Q = _in(Q, f64)
     K = _in(K, f64)
     V = _in(V, f64)
@@ -198,7 +201,7 @@ def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, s
     bh, n_bh = _bh(bh_list, B, H)
     z = lambda *s: np.zeros(s, dtype=np.float64)
     out = Bwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(H, 2 * d), z(H))
-    rc = lib().oracle_attn_bwd(B, H, L, d, block, topk, window, float(scale), int(f64),
+    rc = lib().oracle_attn_bwd(B, H, L, d, block, topk, window, int(stis_block), float(scale), int(f64),
                                _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(dO),
                                _p(bh), n_bh, _p(out.dQ), _p(out.dK), _p(out.dV),
                                _p(out.d_gate_w), _p(out.d_gate_b))

@@ -25,8 +25,12 @@
  *      least one valid key, ordered by (score descending, index ascending).
  *   4. Long-term branch: softmax attention (Eq. 1) over the keys of the
  *      selected blocks (Eq. 14, 16), causal inside the own block.
- *   5. Short-term branch: softmax attention under the causal half of the
- *      local-window term of Eq. 15: 0 <= i-j < w (Eq. 17).
+ *   5. Short-term branch: softmax attention (Eq. 17) under a causal mask taken
+ *      from Eq. 15.  stis_blk = 0: the local-window term only, 0 <= i-j < w.
+ *      stis_blk >= 1: all three terms of Eq. 15 with mask block size stis_blk,
+ *      each intersected with j <= i: the window, every key whose block lies
+ *      2^r blocks (r = 0, 1, ...) before the query's block, and the keys in
+ *      the last stis_blk positions of the sequence.
  *   6. Gate (Eq. 18-19): alpha = sigmoid(Wg . [o_lt ; o_st] + bg) per
  *      (position, head); O = alpha*o_lt + (1-alpha)*o_st.
  *   7. Backward: the chain rule through steps 4-6 with the selection frozen.
@@ -44,7 +48,9 @@
  * Parity status: every function here is pinned by tests/test_oracle_*.py
  * (dense special case against a library attention routine, forced gates,
  * brute-force subset enumeration, hand-computed integer fixture, finite
- * differences, invariances).  Absolute outputs for random inputs have no
+ * differences, invariances; the full short-term mask by the distance counts
+ * behind Appendix D Table 4, closed-form row counts, its block structure and
+ * its dense-causal limit).  Absolute outputs for random inputs have no
  * printed reference in the paper: beyond those pins they are "parity unpinned".
  */
 #include <math.h>
@@ -170,9 +176,11 @@ int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
 }
 
 /* ------------------------------------------------------------------------- */
-/* The two masks, materialised (Eq. 14 as a mask; Eq. 15 first case, causal). */
+/* The two masks, materialised (Eq. 14 as a mask; Eq. 15, causal).             */
 /* ------------------------------------------------------------------------- */
-static void build_masks_one(int L, int b, int k, int w, int n_valid, const int32_t *sel,
+static int is_power_of_two(int x) { return x >= 1 && (x & (x - 1)) == 0; }
+
+static void build_masks_one(int L, int b, int k, int w, int stis_blk, int n_valid, const int32_t *sel,
                             uint8_t *M_lt, uint8_t *M_st)
 {
     const int p0 = L - n_valid;
@@ -187,7 +195,12 @@ static void build_masks_one(int L, int b, int k, int w, int n_valid, const int32
                         if (si[e] == bj) lt = 1;
                 }
                 const int dist = i - j;
-                if (dist >= 0 && dist < w) st = 1;
+                if (dist >= 0 && dist < w) st = 1;                        /* Eq. 15, first case  */
+                if (stis_blk >= 1 && dist >= 0) {
+                    const int bq = i / stis_blk, bk = j / stis_blk;
+                    if (is_power_of_two(bq - bk)) st = 1;                 /* second case         */
+                    if (j >= L - stis_blk) st = 1;                        /* third case          */
+                }
             }
             M_lt[(size_t)i * L + j] = lt;
             M_st[(size_t)i * L + j] = st;
@@ -195,12 +208,12 @@ static void build_masks_one(int L, int b, int k, int w, int n_valid, const int32
     }
 }
 
-int oracle_build_masks(int L, int b, int k, int w, int n_valid, const int32_t *sel_bh,
+int oracle_build_masks(int L, int b, int k, int w, int stis_blk, int n_valid, const int32_t *sel_bh,
                        uint8_t *M_lt, uint8_t *M_st)
 {
     if (n_valid < 0) n_valid = 0;
     if (n_valid > L) n_valid = L;
-    build_masks_one(L, b, k, w, n_valid, sel_bh, M_lt, M_st);
+    build_masks_one(L, b, k, w, stis_blk, n_valid, sel_bh, M_lt, M_st);
     return 0;
 }
 
@@ -287,7 +300,7 @@ static double load1(const void *src, int is_f64, size_t idx)
 /*   O, o_lt, o_st [n_bh,L,d]; lse_lt, lse_st, alpha [n_bh,L]; any may be NULL */
 /*   nnz [2]: number of unmasked (i,j) pairs in the two branches, summed.      */
 /* ------------------------------------------------------------------------- */
-int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, double scale,
+int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, int stis_blk, double scale,
                     int in_f64, const void *Q, const void *K, const void *V,
                     const int32_t *valid_len, const int32_t *sel,
                     const void *gate_w, const void *gate_b,
@@ -325,7 +338,7 @@ int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, double scal
             widen(Q, in_f64, (size_t)bh * Ld, Ld, q);
             widen(K, in_f64, (size_t)bh * Ld, Ld, key);
             widen(V, in_f64, (size_t)bh * Ld, Ld, v);
-            build_masks_one(L, b, k, w, n, sel + (size_t)bh * NB * k, M_lt, M_st);
+            build_masks_one(L, b, k, w, stis_blk, n, sel + (size_t)bh * NB * k, M_lt, M_st);
             long long c_lt = 0, c_st = 0;
             masked_attention(L, d, q, key, v, M_lt, scale, ol, ll, &c_lt);
             masked_attention(L, d, q, key, v, M_st, scale, os, ls, &c_st);
@@ -401,7 +414,7 @@ static void masked_attention_bwd(int L, int d, const double *q, const double *ke
  * dQ, dK, dV [n_bh,L,d] compact; d_gate_w [H,2d], d_gate_b [H] are summed over
  * the listed pairs only, in list order.
  */
-int oracle_attn_bwd(int B, int H, int L, int d, int b, int k, int w, double scale,
+int oracle_attn_bwd(int B, int H, int L, int d, int b, int k, int w, int stis_blk, double scale,
                     int in_f64, const void *Q, const void *K, const void *V,
                     const int32_t *valid_len, const int32_t *sel,
                     const void *gate_w, const void *gate_b, const void *dO,
@@ -448,7 +461,7 @@ int oracle_attn_bwd(int B, int H, int L, int d, int b, int k, int w, double scal
             widen(K, in_f64, (size_t)bh * Ld, Ld, key);
             widen(V, in_f64, (size_t)bh * Ld, Ld, v);
             widen(dO, in_f64, (size_t)bh * Ld, Ld, g);
-            build_masks_one(L, b, k, w, n, sel + (size_t)bh * NB * k, M_lt, M_st);
+            build_masks_one(L, b, k, w, stis_blk, n, sel + (size_t)bh * NB * k, M_lt, M_st);
             masked_attention(L, d, q, key, v, M_lt, scale, ol, ll, NULL);
             masked_attention(L, d, q, key, v, M_st, scale, os, ls, NULL);
             double *gp = gpart + (size_t)it * G;
