@@ -8,7 +8,9 @@
  *     scored against the query (Eq. 10), the top-k blocks are kept (Eq. 13) and
  *     attention runs over the keys of the kept blocks only (Eq. 14, 16);
  *   - short-term branch (STIS, Sec. 3.5): attention under a local mask
- *     (Eq. 15, 17); this library implements the causal local-window term;
+ *     (Eq. 15, 17), always intersected with the causal mask j <= i:
+ *     stis_mode 0 is the local-window term alone, stis_mode 1 the whole of
+ *     Eq. 15 (window, whole blocks at power-of-two block distances, last block);
  *   - learnable gate (Sec. 3.6, Eq. 18-19): a sigmoid of a linear map of both
  *     branch outputs blends them.
  *
@@ -52,7 +54,7 @@ enum {
   BLOSSOM_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   BLOSSOM_ERR_SHAPE = -2,       /* B, H or L < 1, or L/b too large (NB > 4096)                 */
   BLOSSOM_ERR_UNSUPPORTED = -3, /* d not in {32,64}, b not in {8,16,32,64}, dtype, stis_mode   */
-  BLOSSOM_ERR_PARAM = -4,       /* topk < 1, window < 1, softmax_scale < 0 or not finite       */
+  BLOSSOM_ERR_PARAM = -4,       /* topk < 1, window < 1, stis_block < 0, bad softmax_scale      */
   BLOSSOM_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned                     */
   BLOSSOM_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than blossom_workspace_bytes()    */
   BLOSSOM_ERR_LAUNCH = -7       /* a kernel launch failed (hipGetLastError)                    */
@@ -68,8 +70,12 @@ typedef struct {
   int32_t window;         /* w: query i sees keys j with 0 <= i-j < w in the short-term branch  */
   int32_t dtype;          /* BLOSSOM_F32 or BLOSSOM_BF16 (fp32 accumulation either way)         */
   float softmax_scale;    /* logits are softmax_scale * q.k ; 0.0f means 1/sqrt(d) (Eq. 1)      */
-  int32_t stis_mode;      /* 0 = causal local window.  Other values: BLOSSOM_ERR_UNSUPPORTED    */
+  int32_t stis_mode;      /* 0 = causal local window; 1 = causal form of Eq. 15 (see stis_block) */
   int32_t save_for_bwd;   /* fwd only: 1 = also write o_lt, o_st, lse_lt, lse_st                */
+  int32_t stis_block;     /* stis_mode 1: mask block size blk of Eq. 15 (>= 1); 0 means `block`.
+                             With b_q = i / blk, b_k = j / blk query i sees key j <= i iff
+                             i - j < window, or b_q - b_k = 2^r for an integer r >= 0, or
+                             j >= L - blk.  Ignored when stis_mode is 0.                         */
 } blossom_params;
 
 /* Bytes of device workspace an entry point needs (host call, no HIP).  `which` is a

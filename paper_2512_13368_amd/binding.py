@@ -26,7 +26,8 @@ class BlossomParams(ctypes.Structure):
     _fields_ = [("B", ctypes.c_int32), ("H", ctypes.c_int32), ("L", ctypes.c_int32), ("d", ctypes.c_int32),
                 ("block", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
-                ("stis_mode", ctypes.c_int32), ("save_for_bwd", ctypes.c_int32)]
+                ("stis_mode", ctypes.c_int32), ("save_for_bwd", ctypes.c_int32),
+                ("stis_block", ctypes.c_int32)]
 
 
 class BlossomError(RuntimeError):
@@ -93,6 +94,7 @@ class Params:
     softmax_scale: float = 0.0
     stis_mode: int = 0
     save_for_bwd: int = 0
+    stis_block: int = 0
 
     @property
     def NB(self) -> int:
@@ -100,7 +102,7 @@ class Params:
 
     def c(self) -> BlossomParams:
         return BlossomParams(self.B, self.H, self.L, self.d, self.block, self.topk, self.window,
-                             self.dtype, self.softmax_scale, self.stis_mode, self.save_for_bwd)
+                             self.dtype, self.softmax_scale, self.stis_mode, self.save_for_bwd, self.stis_block)
 
 
 def workspace_bytes(p: Params, which: int) -> int:

@@ -20,8 +20,9 @@ int check_params(const blossom_params *p, KParams *kp)
   if (p->d != 32 && p->d != 64) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->block != 8 && p->block != 16 && p->block != 32 && p->block != 64) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->dtype != BLOSSOM_F32 && p->dtype != BLOSSOM_BF16) return BLOSSOM_ERR_UNSUPPORTED;
-  if (p->stis_mode != 0) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->stis_mode != 0 && p->stis_mode != 1) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->topk < 1 || p->window < 1) return BLOSSOM_ERR_PARAM;
+  if (p->stis_mode == 1 && p->stis_block < 0) return BLOSSOM_ERR_PARAM;
   if (!std::isfinite(p->softmax_scale) || p->softmax_scale < 0.0f) return BLOSSOM_ERR_PARAM;
   const long NB = ((long)p->L + p->block - 1) / p->block;
   if (NB > 4096) return BLOSSOM_ERR_SHAPE;
@@ -30,6 +31,8 @@ int check_params(const blossom_params *p, KParams *kp)
   kp->B = p->B; kp->H = p->H; kp->L = p->L; kp->d = p->d;
   kp->b = p->block; kp->k = p->topk; kp->w = p->window; kp->NB = (int)NB;
   kp->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->d);
+  kp->sblk = p->stis_mode == 1 ? (p->stis_block > 0 ? p->stis_block : p->block) : 0;
+  kp->last_lo = kp->sblk > 0 ? p->L - kp->sblk : 0x3FFFFFFF;
   return BLOSSOM_OK;
 }
 
@@ -154,7 +157,7 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
   blossom_params q;
   if (!p) return BLOSSOM_ERR_NULL;
   q = *p;
-  q.topk = 1; q.window = 1; q.stis_mode = 0; q.save_for_bwd = 0;  // ignored fields
+  q.topk = 1; q.window = 1; q.stis_mode = 0; q.stis_block = 0; q.save_for_bwd = 0;  // ignored fields
   KParams kp;
   int rc = check_params(&q, &kp);
   if (rc) return rc;
@@ -177,7 +180,7 @@ const char *blossom_strerror(int code)
     case BLOSSOM_ERR_NULL: return "a required pointer is NULL";
     case BLOSSOM_ERR_SHAPE: return "bad shape: B, H, L must be >= 1 and ceil(L/block) <= 4096";
     case BLOSSOM_ERR_UNSUPPORTED: return "unsupported d, block, dtype or stis_mode";
-    case BLOSSOM_ERR_PARAM: return "bad parameter: topk >= 1, window >= 1, finite softmax_scale >= 0";
+    case BLOSSOM_ERR_PARAM: return "bad parameter: topk >= 1, window >= 1, stis_block >= 0, finite softmax_scale >= 0";
     case BLOSSOM_ERR_ALIGN: return "tensor or workspace pointer not 16-byte aligned";
     case BLOSSOM_ERR_WORKSPACE: return "workspace missing or too small";
     case BLOSSOM_ERR_LAUNCH: return "kernel launch failed";

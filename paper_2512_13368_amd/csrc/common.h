@@ -14,7 +14,35 @@ struct KParams {
   int w;        // short-term window
   int NB;       // ceil(L / b)
   float scale;  // softmax scale (already resolved, > 0)
+  int sblk;     // mask block size of the full short-term mask (Eq. 15); 0 = local window only
+  int last_lo;  // first of the last sblk positions (L - sblk); INT_MAX/2 when sblk == 0
 };
+
+// ---- short-term mask, Eq. 15 in its causal form (callers guarantee j <= i, both valid) ----
+__host__ __device__ __forceinline__ bool is_pow2(int x) { return x >= 1 && (x & (x - 1)) == 0; }
+// does [lo, hi] hold a power of two (>= 1)?
+__host__ __device__ __forceinline__ bool holds_pow2(int lo, int hi)
+{
+  if (hi < 1) return false;
+  int top = 1;
+  while (top <= hi / 2) top *= 2;  // largest power of two <= hi
+  return top >= lo;
+}
+__device__ __forceinline__ bool st_visible(const KParams &p, int i, int j)
+{
+  if (i - j < p.w) return true;
+  if (p.sblk == 0) return false;
+  return j >= p.last_lo || is_pow2(i / p.sblk - j / p.sblk);
+}
+// may any query of block I (size b) see any key of block J <= I through the second or third case?
+__device__ __forceinline__ bool st_block_reach(const KParams &p, int I, int J)
+{
+  if (p.sblk == 0) return false;
+  const int q_lo = I * p.b, q_hi = min(I * p.b + p.b - 1, p.L - 1);
+  const int k_lo = J * p.b, k_hi = min(J * p.b + p.b - 1, p.L - 1);
+  if (k_hi >= p.last_lo) return true;
+  return holds_pow2(q_lo / p.sblk - k_hi / p.sblk, q_hi / p.sblk - k_lo / p.sblk);
+}
 
 struct bf16_t {
   uint16_t bits;

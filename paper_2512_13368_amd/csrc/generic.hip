@@ -131,7 +131,7 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
     __syncthreads();
     for (int jj = phase; jj < b; jj += nph) {
       const int j = J * b + jj;
-      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || i - j < p.w);
+      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || st_visible(p, i, j));
       if (vis) {
         float s = 0.0f;
 #pragma unroll
@@ -198,9 +198,14 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
     return;
   }
 
-  // ---- short-term branch: causal window ----
+  // ---- short-term branch: causal window, plus the blocks the other cases of Eq. 15 reach ----
   reset();
-  for (int J = first_window_block(I, b, p.w, J_first); J <= I; ++J) tile(J, true);
+  {
+    const int J_win = first_window_block(I, b, p.w, J_first);
+    for (int J = J_first; J < J_win; ++J)
+      if (st_block_reach(p, I, J)) tile(J, true);
+    for (int J = J_win; J <= I; ++J) tile(J, true);
+  }
   const float lse_st = finish();
   float z = gate_b ? gate_b[h] : 0.0f;
   if (phase == 0) {
@@ -500,7 +505,7 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
     __syncthreads();
     for (int jj = phase; jj < b; jj += nph) {
       const int j = J * b + jj;
-      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || i - j < p.w);
+      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || st_visible(p, i, j));
       if (vis) {
         float s = 0.0f, gv = 0.0f;
 #pragma unroll
@@ -516,7 +521,12 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
     }
   };
 
-  for (int J = first_window_block(I, b, p.w, J_first); J <= I; ++J) tile(J, true);
+  {
+    const int J_win = first_window_block(I, b, p.w, J_first);
+    for (int J = J_first; J < J_win; ++J)
+      if (st_block_reach(p, I, J)) tile(J, true);
+    for (int J = J_win; J <= I; ++J) tile(J, true);
+  }
   const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
   for (int e = 0; e < p.k; ++e) {
     const int J = my_sel[e];
@@ -714,7 +724,7 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     __syncthreads();
     for (int ii = phase; ii < b; ii += nph) {
       const int i = I * b + ii;
-      const bool vis = key_ok && i < p.L && i >= p0 && j <= i && (!windowed || i - j < p.w);
+      const bool vis = key_ok && i < p.L && i >= p0 && j <= i && (!windowed || st_visible(p, i, j));
       if (vis) {
         float s = 0.0f;
 #pragma unroll
@@ -735,11 +745,14 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     }
   };
 
-  // short-term branch: query blocks whose window reaches this key block
+  // short-term branch: query blocks whose window reaches this key block, then those that
+  // reach it through the other cases of Eq. 15
   {
     const long last_q = (long)J * b + (b - 1) + (p.w - 1);
     const int I_hi = (int)min((long)(p.NB - 1), last_q / b);
     for (int I = J; I <= I_hi; ++I) tile(I, true);
+    for (int I = I_hi + 1; I < p.NB; ++I)
+      if (st_block_reach(p, I, J)) tile(I, true);
   }
   // long-term branch: query blocks that selected this key block
   {

@@ -637,7 +637,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool fwd_mfma_supported(const KParams &p, int dtype)
 {
-  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64);
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && p.sblk == 0;
 }
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)

@@ -39,6 +39,7 @@ class Workload:
     qkv_scaled: bool    # True: Q,K,V ~ N(0,1)/sqrt(d); False: N(0,1)
     seed: int
     backward: bool = False
+    stis_block: int = 0  # 0: the short-term mask is the causal window; >= 1: all of Eq. 15 with this mask block size
 
     @property
     def NB(self) -> int:

@@ -12,7 +12,8 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 def params(w: Workload, **kw) -> B.Params:
     return B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window,
-                    B.F32 if w.dtype == "fp32" else B.BF16, **kw)
+                    B.F32 if w.dtype == "fp32" else B.BF16, stis_mode=int(w.stis_block > 0),
+                    stis_block=w.stis_block, **kw)
 
 
 def to_dev(a: np.ndarray, dtype: str):

@@ -43,7 +43,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
     bh = None if pairs is None else np.asarray(pairs, np.int32)
     take = (lambda t: host(t).reshape(w.B * w.H, *t.shape[2:])[bh if bh is not None else slice(None)])
     fr = oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk,
-                         w.window, bh_list=bh)
+                         w.window, bh_list=bh, stis_block=w.stis_block)
     assert_close(take(f.o_lt), fr.o_lt, tol, "o_lt")
     assert_close(take(f.o_st), fr.o_st, tol, "o_st")
     assert_close(take(f.O), fr.O, tol, "O")
@@ -63,7 +63,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
 
     if backward:
         gr = oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block,
-                             w.topk, w.window, bh_list=bh)
+                             w.topk, w.window, bh_list=bh, stis_block=w.stis_block)
         assert_close(take(g.dQ), gr.dQ, tol, "dQ")
         assert_close(take(g.dK), gr.dK, tol, "dK")
         assert_close(take(g.dV), gr.dV, tol, "dV")
@@ -201,6 +201,24 @@ def test_seeded_random_shapes():
         x.valid_len[:] = [L, int(rng.integers(0, L + 1)), int(rng.integers(0, L + 1)), min(L, 1 + int(rng.integers(0, b)))]
         same = w.topk >= w.NB and w.window >= L  # both branches are dense causal attention
         run_case(w, x=x, backward=True, check_dense=(case % 4 == 0), gate_scale=0.4, branches_coincide=same)
+
+
+@pytest.mark.parametrize("dtype,d,b,sblk,window,L", [
+    ("fp32", 32, 8, 1, 8, 200),      # the paper's own setting: mask block 1, window 8
+    ("fp32", 64, 16, 4, 6, 131),     # mask blocks smaller than the tiles, ragged tail
+    ("fp32", 32, 16, 16, 20, 150),   # mask block = tile
+    ("bf16", 32, 32, 8, 3, 300),
+    ("bf16", 64, 16, 64, 5, 333),    # mask blocks larger than the tiles
+    ("fp32", 64, 8, 200, 2, 90),     # one mask block: the short-term branch is dense causal attention
+])
+def test_full_short_term_mask(dtype, d, b, sblk, window, L):
+    # stis_mode 1: window + whole blocks at power-of-two block distances + last block (Eq. 15, causal)
+    w = with_shape(WORKLOADS["cfg1"], name=f"stis-{dtype}-{d}-{b}-{sblk}", B=3, H=2, L=L, d=d, block=b, topk=3,
+                   window=window, dtype=dtype, len_lo=1, len_hi=L, qkv_scaled=(dtype == "bf16"), seed=900 + d + b + sblk,
+                   stis_block=sblk)
+    x = make_inputs(w, want_dO=True)
+    x.valid_len[:] = [L, L - b - 3, max(1, L // 3)]
+    run_case(w, x=x, backward=True, gate_scale=0.4)
 
 
 def test_edge_cases():
