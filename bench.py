@@ -50,7 +50,24 @@ def algorithmic_pairs(w, valid_len, sel):
         if n == 0:
             continue
         i = np.arange(p0, L)
-        st += int(np.minimum(win, i - p0 + 1).sum()) * w.H
+        if w.stis_block == 0:
+            st += int(np.minimum(win, i - p0 + 1).sum()) * w.H
+        else:
+            # all of Eq. 15, causal: the window and the last-block term are suffixes of [p0, i]; the
+            # blocks at power-of-two block distances lie below them and are disjoint
+            sb = w.stis_block
+            lo = np.maximum(p0, i - win + 1)
+            lo = np.where(i >= L - sb, np.minimum(lo, max(p0, L - sb)), lo)
+            cnt = i - lo + 1
+            bq = i // sb
+            e2 = 0
+            while (1 << e2) <= int(bq.max()):
+                bk = bq - (1 << e2)
+                k_lo = np.maximum(bk * sb, p0)
+                k_hi = np.minimum(np.minimum((bk + 1) * sb - 1, L - 1), lo - 1)
+                cnt = cnt + np.where(bk >= 0, np.clip(k_hi - k_lo + 1, 0, None), 0)
+                e2 += 1
+            st += int(cnt.sum()) * w.H
         dense += n * (n + 1) // 2 * w.H
         vcount = np.clip(blk_hi - np.maximum(blk_lo, p0), 0, None)          # valid positions per block
         first = np.maximum(blk_lo, p0)
@@ -73,6 +90,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--stis-block", type=int, default=0,
+                    help="0: short-term mask = causal window (default); N >= 1: all of Eq. 15 with mask block N")
     ap.add_argument("--no-dense", action="store_true")
     ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense",
                                         "copy"],
@@ -88,9 +107,11 @@ def main():
 
     import torch
     from paper_2512_13368_amd import binding as B
-    from paper_2512_13368_amd.inputs import WORKLOADS, bf16_bits, make_inputs
+    from paper_2512_13368_amd.inputs import WORKLOADS, bf16_bits, make_inputs, with_shape
 
     w = WORKLOADS[args.workload]
+    if args.stis_block:
+        w = with_shape(w, stis_block=args.stis_block)
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     x = make_inputs(w, want_dO=True)
@@ -105,8 +126,9 @@ def main():
     gw = torch.from_numpy(x.gate_w).to(dev)
     gb = torch.from_numpy(x.gate_b).to(dev)
     dt = B.F32 if w.dtype == "fp32" else B.BF16
-    p = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=1)
-    p_nosave = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=0)
+    stis = dict(stis_mode=int(w.stis_block > 0), stis_block=w.stis_block)
+    p = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=1, **stis)
+    p_nosave = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=0, **stis)
 
     # all buffers are allocated once, outside the timed region
     tdt = torch.float32 if w.dtype == "fp32" else torch.bfloat16
@@ -229,7 +251,7 @@ def main():
             a = nbytes / t / 1e9
             r = {"bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
                  "frac": round(a / HBM_PEAK_GBS, 4)}
-        r.update({"traffic": MEASURED_TRAFFIC_BYTES.get((w.name, kernel)), "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
+        r.update({"traffic": None if w.stis_block else MEASURED_TRAFFIC_BYTES.get((w.name, kernel)), "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
                   "algorithmic_gflop": round(flops / 1e9, 2), "algorithmic_mb": round(nbytes / 1e6, 1)})
         return r
 
@@ -249,7 +271,8 @@ def main():
         "dtype": w.dtype if w.dtype == "bf16" else "f32",
         "data": "synthetic",
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} b={w.block} k={w.topk} "
-                               f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}",
+                               f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}"
+                               + (f", short-term mask = all of Eq. 15 with mask block {w.stis_block}" if w.stis_block else ""),
                    "tokens_per_step": tokens, "unmasked_pairs_lt": nnz_lt, "unmasked_pairs_st": nnz_st},
         "kernels_ms": {k_: round(v, 4) for k_, v in ms.items()},
         "fwd_tokens_per_s": round(tokens / ((ms["select"] + ms["fwd"]) * 1e-3), 1),
@@ -276,9 +299,9 @@ def main():
             sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk, bh_list=prs)
             sel_ref = np.where(sel_ref == -2, -1, sel_ref)
             oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk, w.window,
-                            bh_list=prs)
+                            bh_list=prs, stis_block=w.stis_block)
             oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block, w.topk,
-                            w.window, bh_list=prs)
+                            w.window, bh_list=prs, stis_block=w.stis_block)
             dt_ = time.perf_counter() - t0
             toks = float(sum(int(x.valid_len[int(bh) // w.H]) for bh in prs)) / w.H
             return dt_, toks

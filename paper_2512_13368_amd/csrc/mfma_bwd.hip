@@ -197,7 +197,7 @@ __device__ __forceinline__ bf16x8 split_operand(uint32_t x, uint32_t y)
 //                     dS^T  = 2^S'' * G^T  -> bf16 -> B operand
 //                     dQ^T += K^T dS^T      (K^T through the transposing LDS read)
 // =============================================================================================
-template <int BLK>
+template <int BLK, bool EQ15>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const int *__restrict__ sel, const uint16_t *__restrict__ g_lt,
@@ -260,7 +260,16 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int lowpos = I * BLK - (p.w - 1);
   int J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
   J_lo = max(J_lo, J_first);
-  const int n_st = I - J_lo + 1;
+  // With the full short-term mask (Eq. 15, mask block = BLK) the blocks I - 2^r below the window
+  // range follow the window blocks: r = r0 .. r0 + n_pow - 1.
+  const int n_win = I - J_lo + 1;
+  int n_st = n_win, r0 = 0;
+  if (EQ15 && I > J_first) {
+    const int d_win = I - J_lo;                                      // largest block distance inside the window range
+    r0 = d_win == 0 ? 0 : 32 - __builtin_clz((unsigned)d_win);       // smallest r with 2^r > d_win
+    const int r_max = 31 - __builtin_clz((unsigned)(I - J_first));   // largest r with I - 2^r >= J_first
+    n_st += max(0, r_max - r0 + 1);
+  }
   int n_lt = 0;
   bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
   const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
@@ -332,7 +341,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto tile_of = [&](int t) -> int {
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    return e < 0 ? J_lo + t : ((const_int_ptr)my_sel)[e];
+    if (e >= 0) return ((const_int_ptr)my_sel)[e];
+    if (!EQ15) return J_lo + t;
+    return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
   };
 
   Stager<BLK> sg;
@@ -341,11 +352,15 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const uint16_t *v_lane = V + head;
   ReadOffsets ro = read_offsets(lane);
 
-  auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
+  auto tile_body = [&](const uint16_t *ks, const uint16_t *vs, int J, bool short_term) __attribute__((always_inline)) {
     asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
-    const bool hp = (windowed ? hp_st : hp_lt) != 0;
+    const bool hp = (short_term ? hp_st : hp_lt) != 0;
+    // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
+    const bool windowed = short_term && !(EQ15 && is_pow2(I - J));
     const bool masked = windowed || J == I || J * BLK < p0;
-    const int lo = windowed ? max(p0, iq - p.w + 1) : p0;
+    int wlo = iq - p.w + 1;
+    if (EQ15 && iq >= p.last_lo) wlo = min(wlo, p.last_lo);  // third case of Eq. 15: the last block is visible to its own rows
+    const int lo = windowed ? max(p0, wlo) : p0;
     const unsigned span = (unsigned)(iq - lo);
     const bool any = iq >= lo;
 #pragma unroll
@@ -436,7 +451,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 //                       dV^T += dO_x^T P,  dK^T += Q^T dS
 // =============================================================================================
 
-template <int BLK>
+template <int BLK, bool EQ15>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const uint16_t *__restrict__ g_lt, const uint16_t *__restrict__ g_st,
@@ -488,7 +503,16 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // ---- walk: window part I = J..I_hi, then the inverse selection list ----
   const long last_q = (long)J * BLK + (BLK - 1) + (p.w - 1);
   const int I_hi = (int)min((long)(p.NB - 1), last_q / BLK);
-  const int n_st = I_hi - J + 1;
+  // With the full short-term mask (Eq. 15, mask block = BLK) the query blocks J + 2^r above the
+  // window range follow: r = r0 .. r0 + n_pow - 1.
+  const int n_win = I_hi - J + 1;
+  int n_st = n_win, r0 = 0;
+  if (EQ15 && p.NB - 1 > J) {
+    const int d_win = I_hi - J;                                       // largest block distance inside the window range
+    r0 = d_win == 0 ? 0 : 32 - __builtin_clz((unsigned)d_win);        // smallest r with 2^r > d_win
+    const int r_max = 31 - __builtin_clz((unsigned)(p.NB - 1 - J));   // largest r with J + 2^r <= NB - 1
+    n_st += max(0, r_max - r0 + 1);
+  }
   const int e_lo = offs[(size_t)bh * (p.NB + 1) + J];
   const int n_lt = offs[(size_t)bh * (p.NB + 1) + J + 1] - e_lo;
   const int n_all = n_st + n_lt;
@@ -499,7 +523,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto entry_of = [&](int t) -> int {
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    return e < 0 ? J + t : ((const_int_ptr)my_items)[e];
+    if (e >= 0) return ((const_int_ptr)my_items)[e];
+    if (!EQ15) return J + t;
+    return t < n_win ? J + t : J + (1 << (r0 + t - n_win));
   };
 
   Stager<BLK> sg;
@@ -521,13 +547,16 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     return r;
   };
 
-  auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool windowed, bool hp)
+  auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool short_term, bool hp)
                        __attribute__((always_inline)) {
+    // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
+    const bool windowed = short_term && !(EQ15 && is_pow2(Iq - J));
     asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
     const bool masked = windowed || Iq == J || Iq * BLK < p0 || J * BLK < p0 || (Iq + 1) * BLK > p.L;
     // visible <=> key valid and lo_i <= i <= hi_i
     const int lo_i = max(j, p0);
-    const int hi_i = windowed ? min(p.L - 1, j + p.w - 1) : p.L - 1;
+    // (third case of Eq. 15: a key among the last block's positions is visible to every later row)
+    const int hi_i = windowed && !(EQ15 && j >= p.last_lo) ? min(p.L - 1, j + p.w - 1) : p.L - 1;
     const unsigned span = (unsigned)(hi_i - lo_i);
     const bool any = key_ok && hi_i >= lo_i;
 #pragma unroll
@@ -676,7 +705,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   if (p.w < kFewKeys || J * BLK - p0 + 1 < kFewKeys) {  // the window part: a prefix of the walk
 #pragma unroll 1
     for (int t = 0; t < n_st; ++t) {
-      const int Iq = J + t;
+      const int Iq = entry_of(t);
       if (!(p.w < kFewKeys || Iq * BLK - p0 + 1 < kFewKeys)) break;
       residual_pass(Iq, true);
     }
@@ -695,7 +724,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool bwd_mfma_supported(const KParams &p, int dtype)
 {
-  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && p.sblk == 0;
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || p.sblk == p.b);
 }
 
 void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st)
@@ -703,20 +732,23 @@ void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, 
   const bool do_dq = stages & kBwdStageDQ, do_dkv = stages & kBwdStageDKV;
   const unsigned grid = (unsigned)(p.B * p.H * p.NB);
   auto u16 = [](const void *x) { return reinterpret_cast<const uint16_t *>(x); };
+  auto go_dq = [&](auto kernel, unsigned threads) {
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, u16(a.Q), u16(a.K), u16(a.V), a.valid_len, a.sel,
+                       w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, u16(a.dO), w.rowstat, a.gate_w, (const float *)a.o_lt,
+                       (const float *)a.o_st, (uint16_t *)a.dQ, p);
+  };
+  auto go_dkv = [&](auto kernel, unsigned threads) {
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, u16(a.Q), u16(a.K), u16(a.V), a.valid_len, w.g_lt,
+                       w.g_st, w.rowI_lt, w.rowI_st, w.offs, w.items, u16(a.dO), w.rowstat, a.gate_w,
+                       (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
+  };
+  const bool eq15 = p.sblk != 0;
   if (p.b == 32) {
-    if (do_dq) hipLaunchKernelGGL((bwd_dq_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.sel, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, u16(a.dO), w.rowstat, a.gate_w,
-                       (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dQ, p);
-    if (do_dkv) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, w.offs, w.items, u16(a.dO), w.rowstat,
-                       a.gate_w, (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
+    if (do_dq) { if (eq15) go_dq(bwd_dq_mfma_kernel<32, true>, 64); else go_dq(bwd_dq_mfma_kernel<32, false>, 64); }
+    if (do_dkv) { if (eq15) go_dkv(bwd_dkv_mfma_kernel<32, true>, 64); else go_dkv(bwd_dkv_mfma_kernel<32, false>, 64); }
   } else {
-    if (do_dq) hipLaunchKernelGGL((bwd_dq_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.sel, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, u16(a.dO), w.rowstat, a.gate_w,
-                       (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dQ, p);
-    if (do_dkv) hipLaunchKernelGGL((bwd_dkv_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, w.offs, w.items, u16(a.dO), w.rowstat,
-                       a.gate_w, (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
+    if (do_dq) { if (eq15) go_dq(bwd_dq_mfma_kernel<64, true>, 128); else go_dq(bwd_dq_mfma_kernel<64, false>, 128); }
+    if (do_dkv) { if (eq15) go_dkv(bwd_dkv_mfma_kernel<64, true>, 128); else go_dkv(bwd_dkv_mfma_kernel<64, false>, 128); }
   }
 }
 

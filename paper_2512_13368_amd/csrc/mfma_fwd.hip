@@ -50,7 +50,9 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >>
 
 }  // namespace
 
-template <int BLK>
+// EQ15: the short-term mask is all of Eq. 15 with mask block BLK (compile-time, so that the plain
+// causal window compiles to exactly the code it had without it)
+template <int BLK, bool EQ15>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const int *__restrict__ sel, const float *__restrict__ gate_w,
@@ -136,15 +138,25 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // window blocks J_lo..I come first in the walk; they depend on the valid length only
   const int J_first = p0 / BLK;
-  int J_lo, n_st;
+  // With the full short-term mask (Eq. 15, mask block = BLK) the blocks I - 2^r below the window
+  // range follow: r = r0 .. r0 + n_pow - 1.
+  int J_lo, n_win, n_st, r0 = 0;
   if (dense) {
     J_lo = J_first;
+    n_win = 0;
     n_st = 0;
   } else {
     const int lowpos = I * BLK - (p.w - 1);
     J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
     J_lo = max(J_lo, J_first);
-    n_st = I - J_lo + 1;
+    n_win = I - J_lo + 1;
+    n_st = n_win;
+    if (EQ15 && I > J_first) {
+      const int d_win = I - J_lo;                                       // largest block distance inside the window range
+      r0 = d_win == 0 ? 0 : 32 - __builtin_clz((unsigned)d_win);        // smallest r with 2^r > d_win
+      const int r_max = 31 - __builtin_clz((unsigned)(I - J_first));  // largest r with I - 2^r >= J_first
+      n_st += max(0, r_max - r0 + 1);
+    }
   }
 
   // ---- staging: each wavefront moves its 32 rows (4 x 1 KB) of K and of V per tile ----
@@ -246,7 +258,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if (dense) return J_first + t;
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    return e < 0 ? J_lo + t : ((const_int_ptr)my_sel)[e];
+    if (e >= 0) return ((const_int_ptr)my_sel)[e];
+    if (!EQ15) return J_lo + t;
+    return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
   };
 
   // ---- per-lane LDS read offsets (elements) inside this wavefront's 32 rows ----
@@ -321,7 +335,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     const int q = qbase[g] + (ql & 31);
     const int lh = ql >> 5;
     asm volatile("" : "+s"(J));
-    const int lo = windowed ? max(p0, q - p.w + 1) : p0;
+    int wlo = q - p.w + 1;
+    if (EQ15 && q >= p.last_lo) wlo = min(wlo, p.last_lo);  // third case of Eq. 15: the last block is visible to its own rows
+    const int lo = windowed ? max(p0, wlo) : p0;
     const int base = J * BLK + 32 * wv + 4 * lh;
     const unsigned span = (unsigned)(q - lo);  // wraps to huge when q < lo: handled by `any`
     const bool any = q >= lo;
@@ -410,8 +426,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // key.  Otherwise the slow path finds the row maxima, moves the references and takes the
   // exponentials again; it raises a reference whenever a probability would exceed 2^kRaise,
   // which also guarantees that the retaken tile passes.
-  auto tile = [&](const uint16_t *ks, const uint16_t *vs, int J, bool windowed) __attribute__((always_inline)) {
-    const bool hp = (windowed ? hp_st : hp_lt) != 0;
+  auto tile = [&](const uint16_t *ks, const uint16_t *vs, int J, bool short_term) __attribute__((always_inline)) {
+    const bool hp = (short_term ? hp_st : hp_lt) != 0;
+    // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
+    const bool windowed = short_term && !(EQ15 && is_pow2(I - J));
     // The empty asm makes the read offsets look freshly computed: buffer base + offset is then
     // formed next to each read, where it folds into the instruction's immediate, instead of
     // being kept in one register per (buffer, fragment) across the whole loop.
@@ -637,21 +655,23 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool fwd_mfma_supported(const KParams &p, int dtype)
 {
-  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && p.sblk == 0;
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || p.sblk == p.b);
 }
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
   const unsigned grid = (unsigned)(p.B * p.H * p.NB);
   auto u16 = [](const void *x) { return reinterpret_cast<const uint16_t *>(x); };
+  auto go = [&](auto kernel, unsigned threads) {
+    hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, u16(a.Q), u16(a.K), u16(a.V), a.valid_len, a.sel,
+                       a.gate_w, a.gate_b, (uint16_t *)a.O, (float *)a.o_lt, (float *)a.o_st, a.lse_lt, a.lse_st,
+                       a.dense, p);
+  };
+  const bool eq15 = p.sblk != 0 && !a.dense;
   if (p.b == 32) {
-    hipLaunchKernelGGL((fwd_mfma_kernel<32>), dim3(grid), dim3(64), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.sel, a.gate_w, a.gate_b, (uint16_t *)a.O, (float *)a.o_lt,
-                       (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
+    if (eq15) go(fwd_mfma_kernel<32, true>, 64); else go(fwd_mfma_kernel<32, false>, 64);
   } else {
-    hipLaunchKernelGGL((fwd_mfma_kernel<64>), dim3(grid), dim3(128), 0, st, u16(a.Q), u16(a.K), u16(a.V),
-                       a.valid_len, a.sel, a.gate_w, a.gate_b, (uint16_t *)a.O, (float *)a.o_lt,
-                       (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
+    if (eq15) go(fwd_mfma_kernel<64, true>, 128); else go(fwd_mfma_kernel<64, false>, 128);
   }
 }
 

@@ -126,6 +126,12 @@ def test_cfg4_full_size_sampled():
     run_case(w, pairs=pick_pairs(w, 3), backward=False)
 
 
+def test_cfg4_full_size_sampled_full_short_term_mask():
+    # cfg4 at full size with all of Eq. 15 (mask block = tile): seven more key blocks per query block
+    w = with_shape(WORKLOADS["cfg4"], name="cfg4-eq15", stis_block=64)
+    run_case(w, pairs=pick_pairs(w, 2), backward=True)
+
+
 def test_cfg5_full_size_sampled():
     w = WORKLOADS["cfg5"]
     run_case(w, pairs=pick_pairs(w, 8), backward=True)
@@ -191,15 +197,16 @@ def test_seeded_random_shapes():
         d = 64 if mfma else int(rng.choice([32, 64]))
         b = int(rng.choice([32, 64])) if mfma else int(rng.choice([8, 16, 32, 64]))
         nb = int(rng.integers(1, 13))
-        L = max(1, nb * b - int(rng.integers(0, b)))
+        L = max(2, nb * b - int(rng.integers(0, b)))  # (one key per row would make dQ, dK identically zero)
         topk = int(rng.choice([1, 2, 3, nb, nb + 3]))
         window = int(rng.choice([1, 2, b - 1, b, b + 1, 2 * b + 5, L, L + 7]))
+        sblk = int(rng.choice([0, 0, b, 1, 3, 2 * b]))  # a third of the draws use all of Eq. 15
         w = with_shape(WORKLOADS["cfg1"], name=f"rnd{case}", B=4, H=2, L=L, d=d, block=b, topk=max(1, topk),
                        window=max(1, window), dtype=dtype, len_lo=0, len_hi=L, qkv_scaled=(dtype == "bf16"),
-                       seed=7000 + case)
+                       seed=7000 + case, stis_block=sblk)
         x = make_inputs(w, want_dO=True)
         x.valid_len[:] = [L, int(rng.integers(0, L + 1)), int(rng.integers(0, L + 1)), min(L, 1 + int(rng.integers(0, b)))]
-        same = w.topk >= w.NB and w.window >= L  # both branches are dense causal attention
+        same = w.topk >= w.NB and (w.window >= L or sblk >= L)  # both branches are dense causal attention
         run_case(w, x=x, backward=True, check_dense=(case % 4 == 0), gate_scale=0.4, branches_coincide=same)
 
 
@@ -210,6 +217,11 @@ def test_seeded_random_shapes():
     ("bf16", 32, 32, 8, 3, 300),
     ("bf16", 64, 16, 64, 5, 333),    # mask blocks larger than the tiles
     ("fp32", 64, 8, 200, 2, 90),     # one mask block: the short-term branch is dense causal attention
+    ("bf16", 64, 32, 32, 40, 647),   # the matrix-core kernels: mask block = tile
+    ("bf16", 64, 64, 64, 128, 1157),
+    ("bf16", 64, 64, 64, 5, 577),    # short window: few-key rows in the band tiles
+    ("bf16", 64, 32, 32, 1, 1024),   # no ragged tail: the last block term covers a whole tile
+    ("bf16", 64, 64, 32, 70, 700),   # bf16 d=64 with a mask block that is not the tile: scalar kernels
 ])
 def test_full_short_term_mask(dtype, d, b, sblk, window, L):
     # stis_mode 1: window + whole blocks at power-of-two block distances + last block (Eq. 15, causal)
