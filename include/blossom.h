@@ -75,7 +75,8 @@ typedef struct {
   int32_t stis_block;     /* stis_mode 1: mask block size blk of Eq. 15 (>= 1); 0 means `block`.
                              With b_q = i / blk, b_k = j / blk query i sees key j <= i iff
                              i - j < window, or b_q - b_k = 2^r for an integer r >= 0, or
-                             j >= L - blk.  Ignored when stis_mode is 0.                         */
+                             j >= L - blk.  Ignored when stis_mode is 0.  (bf16, d = 64,
+                             block 32 or 64 run on the matrix cores when blk == block.)          */
 } blossom_params;
 
 /* Bytes of device workspace an entry point needs (host call, no HIP).  `which` is a
