@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--shape", default="",
+                    help="overrides of the workload's fields, e.g. B=32,H=8,L=2000,len_lo=2000,len_hi=2000 "
+                         "(the efficiency-study shapes of the paper's Appendix B); the JSON line names them")
     ap.add_argument("--stis-block", type=int, default=0,
                     help="0: short-term mask = causal window (default); N >= 1: all of Eq. 15 with mask block N")
     ap.add_argument("--no-dense", action="store_true")
@@ -112,6 +115,9 @@ def main():
     w = WORKLOADS[args.workload]
     if args.stis_block:
         w = with_shape(w, stis_block=args.stis_block)
+    if args.shape:
+        kv = dict(t.split("=") for t in args.shape.split(","))
+        w = with_shape(w, name=w.name + "*", **{k_: int(v_) for k_, v_ in kv.items()})
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     x = make_inputs(w, want_dO=True)
