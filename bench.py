@@ -96,7 +96,7 @@ def main():
     ap.add_argument("--stis-block", type=int, default=0,
                     help="0: short-term mask = causal window (default); N >= 1: all of Eq. 15 with mask block N")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense",
+    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense", "serve",
                                         "copy"],
                     default=None,
                     help="profiling aid: run only this stage --steps times (after the others ran once) "
@@ -135,6 +135,7 @@ def main():
     stis = dict(stis_mode=int(w.stis_block > 0), stis_block=w.stis_block)
     p = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=1, **stis)
     p_nosave = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=0, **stis)
+    p_serve = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=0, last_block_only=1, **stis)
 
     # all buffers are allocated once, outside the timed region
     tdt = torch.float32 if w.dtype == "fp32" else torch.bfloat16
@@ -169,6 +170,9 @@ def main():
               "bwd_dkv": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
                                             stages=B.BWD_DKV),
               "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense),
+              # serving: selection and forward of the last query block only (the scored position)
+              "serve": lambda: (B.select_blocks(p_serve, Q, K, vl, sel=sel, ws=ws_sel),
+                                B.attn_fwd(p_serve, Q, K, V, vl, sel, gw, gb, out=fo_nosave)),
               # a plain device copy of one [B,H,L,d] tensor: calibrates the HBM byte counters
               "copy": lambda: O_dense.copy_(Q)}[args.stage]
         for _ in range(args.warmup):

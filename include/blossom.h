@@ -53,7 +53,8 @@ enum {
   BLOSSOM_OK = 0,
   BLOSSOM_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   BLOSSOM_ERR_SHAPE = -2,       /* B, H or L < 1, or L/b too large (NB > 4096)                 */
-  BLOSSOM_ERR_UNSUPPORTED = -3, /* d not in {32,64}, b not in {8,16,32,64}, dtype, stis_mode   */
+  BLOSSOM_ERR_UNSUPPORTED = -3, /* d not in {32,64}, b not in {8,16,32,64}, dtype, stis_mode;   
+                                   backward with last_block_only                               */
   BLOSSOM_ERR_PARAM = -4,       /* topk < 1, window < 1, stis_block < 0, bad softmax_scale      */
   BLOSSOM_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned                     */
   BLOSSOM_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than blossom_workspace_bytes()    */
@@ -77,6 +78,12 @@ typedef struct {
                              i - j < window, or b_q - b_k = 2^r for an integer r >= 0, or
                              j >= L - blk.  Ignored when stis_mode is 0.  (bf16, d = 64,
                              block 32 or 64 run on the matrix cores when blk == block.)          */
+  int32_t last_block_only; /* 1: serving mode (Appendix C: only the representation of the last
+                             position is scored).  blossom_select_blocks writes only the
+                             selection row of the last query block, blossom_attn_fwd only the
+                             rows of that block (O, and the saved tensors if asked for);
+                             everything else in those buffers is left untouched.  Backward
+                             calls return BLOSSOM_ERR_UNSUPPORTED.  0: all query blocks.          */
 } blossom_params;
 
 /* Bytes of device workspace an entry point needs (host call, no HIP).  `which` is a

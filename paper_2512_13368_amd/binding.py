@@ -27,7 +27,7 @@ class BlossomParams(ctypes.Structure):
                 ("block", ctypes.c_int32), ("topk", ctypes.c_int32), ("window", ctypes.c_int32),
                 ("dtype", ctypes.c_int32), ("softmax_scale", ctypes.c_float),
                 ("stis_mode", ctypes.c_int32), ("save_for_bwd", ctypes.c_int32),
-                ("stis_block", ctypes.c_int32)]
+                ("stis_block", ctypes.c_int32), ("last_block_only", ctypes.c_int32)]
 
 
 class BlossomError(RuntimeError):
@@ -95,6 +95,7 @@ class Params:
     stis_mode: int = 0
     save_for_bwd: int = 0
     stis_block: int = 0
+    last_block_only: int = 0
 
     @property
     def NB(self) -> int:
@@ -102,7 +103,8 @@ class Params:
 
     def c(self) -> BlossomParams:
         return BlossomParams(self.B, self.H, self.L, self.d, self.block, self.topk, self.window,
-                             self.dtype, self.softmax_scale, self.stis_mode, self.save_for_bwd, self.stis_block)
+                             self.dtype, self.softmax_scale, self.stis_mode, self.save_for_bwd, self.stis_block,
+                             self.last_block_only)
 
 
 def workspace_bytes(p: Params, which: int) -> int:

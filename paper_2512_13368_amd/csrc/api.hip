@@ -33,6 +33,7 @@ int check_params(const blossom_params *p, KParams *kp)
   kp->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->d);
   kp->sblk = p->stis_mode == 1 ? (p->stis_block > 0 ? p->stis_block : p->block) : 0;
   kp->last_lo = kp->sblk > 0 ? p->L - kp->sblk : 0x3FFFFFFF;
+  kp->nq = p->last_block_only ? 1 : (int)NB;
   return BLOSSOM_OK;
 }
 
@@ -123,6 +124,7 @@ int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *
   KParams kp;
   int rc = check_params(p, &kp);
   if (rc) return rc;
+  if (p->last_block_only) return BLOSSOM_ERR_UNSUPPORTED;  // serving mode has no backward
   if (!Q || !K || !V || !valid_len || !sel || !gate_w || !o_lt || !o_st || !lse_lt || !lse_st ||
       !dO || !dQ || !dK || !dV || !d_gate_w)
     return BLOSSOM_ERR_NULL;
@@ -158,6 +160,7 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
   if (!p) return BLOSSOM_ERR_NULL;
   q = *p;
   q.topk = 1; q.window = 1; q.stis_mode = 0; q.stis_block = 0; q.save_for_bwd = 0;  // ignored fields
+  q.last_block_only = 0;
   KParams kp;
   int rc = check_params(&q, &kp);
   if (rc) return rc;
@@ -179,7 +182,7 @@ const char *blossom_strerror(int code)
     case BLOSSOM_OK: return "ok";
     case BLOSSOM_ERR_NULL: return "a required pointer is NULL";
     case BLOSSOM_ERR_SHAPE: return "bad shape: B, H, L must be >= 1 and ceil(L/block) <= 4096";
-    case BLOSSOM_ERR_UNSUPPORTED: return "unsupported d, block, dtype or stis_mode";
+    case BLOSSOM_ERR_UNSUPPORTED: return "unsupported d, block, dtype or stis_mode, or backward in serving mode";
     case BLOSSOM_ERR_PARAM: return "bad parameter: topk >= 1, window >= 1, stis_block >= 0, finite softmax_scale >= 0";
     case BLOSSOM_ERR_ALIGN: return "tensor or workspace pointer not 16-byte aligned";
     case BLOSSOM_ERR_WORKSPACE: return "workspace missing or too small";

@@ -16,6 +16,7 @@ struct KParams {
   float scale;  // softmax scale (already resolved, > 0)
   int sblk;     // mask block size of the full short-term mask (Eq. 15); 0 = local window only
   int last_lo;  // first of the last sblk positions (L - sblk); INT_MAX/2 when sblk == 0
+  int nq;       // query blocks walked by select and forward: NB, or 1 (the last one) in serving mode
 };
 
 // ---- short-term mask, Eq. 15 in its causal form (callers guarantee j <= i, both valid) ----

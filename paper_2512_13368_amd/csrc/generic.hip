@@ -86,8 +86,8 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
   const int nph = 64 / b;
   const int row = lane % b;
   const int phase = lane / b;
-  const int bh = blockIdx.x / p.NB;
-  const int I = p.NB - 1 - (int)(blockIdx.x % p.NB);  // late (long) blocks first
+  const int bh = blockIdx.x / p.nq;
+  const int I = p.NB - 1 - (int)(blockIdx.x % p.nq);  // late (long) blocks first
   const int h = bh % p.H;
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
@@ -780,7 +780,7 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
 template <typename T, int D>
 static void launch_fwd_t(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
-  hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64), 0, st,
+  hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64), 0, st,
                      (const T *)a.Q, (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w,
                      a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
 }

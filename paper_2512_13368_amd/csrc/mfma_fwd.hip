@@ -81,9 +81,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31;  // query column (and key row of the K operand, d row of the V^T operand)
   const int lh = lane >> 5;  // which half of each 16-wide contraction slab
-  const unsigned vid = xcd_remap(blockIdx.x, (unsigned)(p.B * p.H * p.NB));
-  const int bh = (int)(vid / p.NB);
-  const int I = p.NB - 1 - (int)(vid % p.NB);
+  const unsigned vid = xcd_remap(blockIdx.x, (unsigned)(p.B * p.H * p.nq));
+  const int bh = (int)(vid / p.nq);
+  const int I = p.NB - 1 - (int)(vid % p.nq);
   const int h = bh % p.H;
   const size_t head = (size_t)bh * p.L * D;
   // Local query group g covers rows I*BLK + 32*(g ^ wv) + lq: group 0 is always the one this
@@ -660,7 +660,7 @@ bool fwd_mfma_supported(const KParams &p, int dtype)
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
-  const unsigned grid = (unsigned)(p.B * p.H * p.NB);
+  const unsigned grid = (unsigned)(p.B * p.H * p.nq);
   auto u16 = [](const void *x) { return reinterpret_cast<const uint16_t *>(x); };
   auto go = [&](auto kernel, unsigned threads) {
     hipLaunchKernelGGL(kernel, dim3(grid), dim3(threads), 0, st, u16(a.Q), u16(a.K), u16(a.V), a.valid_len, a.sel,

@@ -31,6 +31,7 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, cons
   const long rem = which ? task - n_bhj : task;
   const int bh = (int)(rem / p.NB);
   const int J = (int)(rem % p.NB);
+  if (!which && J < p.NB - p.nq) return;  // serving mode: only the last query block is pooled
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
   const int lo = max(J * p.b, p0);
@@ -73,8 +74,8 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
   __shared__ float qs[D];
   extern __shared__ float sc[];  // NB scores (sized at launch: a static worst-case array would cap the occupancy)
   const int lane = threadIdx.x;
-  const int I = blockIdx.x % p.NB;
-  const int bh = blockIdx.x / p.NB;
+  const int I = p.NB - p.nq + (int)(blockIdx.x % p.nq);
+  const int bh = blockIdx.x / p.nq;
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
   int *out = sel + ((size_t)bh * p.NB + I) * p.k;
@@ -133,7 +134,7 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, cons
   const unsigned grid = (unsigned)((tasks + per_wg - 1) / per_wg);
   hipLaunchKernelGGL((pool_kernel<T, D>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
                      valid_len, qsum, kmeanT, p);
-  hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.NB)), dim3(64),
+  hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
                      (size_t)p.NB * sizeof(float), st,
                      qsum, kmeanT, valid_len, sel, p);
 }

@@ -93,6 +93,7 @@ def test_validation_codes_fwd_bwd_dense(lib):
     assert bwd(ws=None) == -6
     assert bwd(n=8) == -6
     assert bwd(p=_p(topk=0).c()) == -4
+    assert bwd(p=_p(last_block_only=1).c()) == -3                   # serving mode has no backward
     dense = lambda **k: lib.blossom_dense_causal_fwd(ctypes.byref(k.get("p", cp)), k.get("Q", a), a, a, a,
                                                      k.get("O", a), None, None, 0, None)
     assert dense(Q=None) == -1

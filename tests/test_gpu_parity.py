@@ -233,6 +233,42 @@ def test_full_short_term_mask(dtype, d, b, sblk, window, L):
     run_case(w, x=x, backward=True, gate_scale=0.4)
 
 
+@pytest.mark.parametrize("name,shape", [
+    ("cfg1", dict()),                                                          # scalar kernels, fp32
+    ("cfg3", dict(B=3, L=32 * 9 + 11, len_lo=40, len_hi=32 * 9 + 11)),          # matrix cores, ragged last block
+    ("cfg4", dict(B=2, H=2, L=64 * 6, len_lo=100, len_hi=64 * 6)),              # matrix cores, b = 64
+    ("cfg4", dict(B=2, H=2, L=64 * 5 + 3, len_lo=64 * 5 + 3, len_hi=64 * 5 + 3, stis_block=64)),
+])
+def test_serving_mode_last_block_only(name, shape):
+    # last_block_only: selection row and output rows of the last query block equal the full run's, and
+    # nothing else in the buffers is written
+    w = with_shape(WORKLOADS[name], name=name + "-serve", **shape)
+    x = make_inputs(w)
+    dv = Dev(x)
+    p_all = params(w)
+    p_last = params(w, last_block_only=1)
+    sel_all = B.select_blocks(p_all, dv.Q, dv.K, dv.vl)
+    f_all = B.attn_fwd(p_all, dv.Q, dv.K, dv.V, dv.vl, sel_all, dv.gw, dv.gb)
+    sel = torch.full_like(sel_all, -7)
+    B.select_blocks(p_last, dv.Q, dv.K, dv.vl, sel=sel)
+    O = torch.full_like(f_all.O, 3.0)
+    B.attn_fwd(p_last, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, out=B.FwdOut(O))
+    torch.cuda.synchronize()
+    lo = (w.NB - 1) * w.block
+    assert torch.equal(sel[:, :, -1], sel_all[:, :, -1]) and bool((sel[:, :, :-1] == -7).all())
+    assert torch.equal(O[:, :, lo:], f_all.O[:, :, lo:]) and bool((O[:, :, :lo] == 3.0).all())
+    # and the last block agrees with the oracle
+    sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk)
+    np.testing.assert_array_equal(sel[:, :, -1].cpu().numpy(), sel_ref[:, :, -1])
+    fr = oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk, w.window,
+                         stis_block=w.stis_block)
+    assert_close(host(O[:, :, lo:]).reshape(w.B * w.H, w.L - lo, w.d), fr.O[:, lo:], TOL[w.dtype], "O (last block)")
+    with pytest.raises(B.BlossomError):  # no backward in serving mode
+        f = B.attn_fwd(params(w, save_for_bwd=1), dv.Q, dv.K, dv.V, dv.vl, sel_all, dv.gw, dv.gb)
+        B.attn_bwd(params(w, save_for_bwd=1, last_block_only=1), dv.Q, dv.K, dv.V, dv.vl, sel_all, dv.gw, dv.gb, f,
+                   torch.zeros_like(f.O))
+
+
 def test_edge_cases():
     base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
     x = make_inputs(base, want_dO=True)
