@@ -30,6 +30,12 @@
 // the tile through the slow path (row maxima, shift of the tile's exponents, the running sum
 // and the output accumulators, exponentials again).  Row sums are plain fp32 adds: the packed
 // dot-product instructions execute on the matrix pipeline and would stall the MFMAs.
+//
+// The walk: the short-term branch first (window blocks by arithmetic; with the full mask of
+// Eq. 15, compile-time variant EQ15 with mask block = BLK, also the blocks 2^r before the query
+// block, and tiles at power-of-two distances are unmasked), then the long-term branch, whose
+// block ids come from one scalar load per tile out of the selection row, issued a tile ahead.
+// Outputs leave through the wavefront's staging rows so that every store covers whole rows.
 #include "launch.h"
 #include "mfma_common.h"
 
