@@ -269,6 +269,19 @@ def test_serving_mode_last_block_only(name, shape):
                    torch.zeros_like(f.O))
 
 
+@pytest.mark.parametrize("b", [32, 64])
+def test_matrix_core_sharp_softmax(b):
+    # logits eight times the usual spread (queries scaled by a power of two, so they stay bf16 values):
+    # probabilities of a tile exceed the forward's acceptance bound again and again, so its softmax
+    # reference has to move many times per row; backward sees probabilities close to one everywhere
+    L = 9 * b + 5
+    w = with_shape(WORKLOADS["cfg3"], name=f"sharp-{b}", B=2, H=2, L=L, d=64, block=b, topk=4, window=b + 9,
+                   len_lo=L - 70, len_hi=L, seed=1200 + b)
+    x = make_inputs(w, want_dO=True)
+    x.Q *= np.float32(8.0)
+    run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
+
+
 def test_edge_cases():
     base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
     x = make_inputs(base, want_dO=True)
