@@ -404,13 +404,21 @@ __global__ __launch_bounds__(256) void bwd_gate_reduce1_kernel(const float *__re
   const int N = p.B * nchunk;  // partial rows of this head, ordered by (batch row, chunk)
   const int per = (N + kGateSlices - 1) / kGateSlices;
   const int lo = sl * per, hi = min(N, lo + per);
+  // one thread per output column; four independent running sums keep four loads in flight, and
+  // are added in a fixed order at the end
   for (int c = threadIdx.x; c < G; c += blockDim.x) {
-    float acc = 0.0f;
-    for (int nn = lo; nn < hi; ++nn) {
+    float acc[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+    auto at = [&](int nn) -> float {
       const int r = nn / nchunk, ch = nn % nchunk;
-      acc += partial[(((size_t)r * p.H + h) * nchunk + ch) * G + c];
+      return partial[(((size_t)r * p.H + h) * nchunk + ch) * G + c];
+    };
+    int nn = lo;
+    for (; nn + 4 <= hi; nn += 4) {
+      const float v0 = at(nn), v1 = at(nn + 1), v2 = at(nn + 2), v3 = at(nn + 3);
+      acc[0] += v0; acc[1] += v1; acc[2] += v2; acc[3] += v3;
     }
-    stage2[((size_t)h * kGateSlices + sl) * G + c] = acc;
+    for (; nn < hi; ++nn) acc[0] += at(nn);
+    stage2[((size_t)h * kGateSlices + sl) * G + c] = (acc[0] + acc[1]) + (acc[2] + acc[3]);
   }
 }
 
