@@ -104,7 +104,8 @@ def main():
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(the path shards over (row, head) pairs with no exchange in forward; see DESIGN.md).",
+              "(every (row, head) pair is independent in selection, forward and backward: rows shard over GPUs "
+              "with no exchange in forward and one small all-reduce of the gate gradients in backward).",
               file=sys.stderr)
         sys.exit(2)
 
