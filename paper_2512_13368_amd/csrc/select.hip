@@ -61,10 +61,20 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, cons
 }
 
 // ---- scoring + top-k ----------------------------------------------------------------------
-// One wavefront per (row, head, query block I).  Lane-strided candidates J_first <= J < I;
-// scores are parked in LDS; a candidate is selected iff fewer than `take` candidates beat it
-// under (score descending, index ascending); ballots and prefix popcounts emit the list in
-// ascending order.
+// One wavefront per (row, head, query block I).  Lane-strided candidates J_first <= J < I.
+// Each score becomes one 64-bit key in LDS: an order-preserving integer image of the fp32 score
+// (with -0 folded onto +0, so that equal scores give equal images) above NB-1-J, so that
+// "beats" under (score descending, index ascending) is a single unsigned comparison of unique
+// keys.  A candidate is selected iff fewer than `take` candidates beat it; ballots and prefix
+// popcounts emit the list in ascending order.
+__device__ __forceinline__ unsigned long long rank_key(float score, int J, int NB)
+{
+  unsigned u = __float_as_uint(score);
+  if (u == 0x80000000u) u = 0u;                       // -0 ties with +0
+  u = (u & 0x80000000u) ? ~u : (u | 0x80000000u);     // monotone in the score
+  return ((unsigned long long)u << 32) | (unsigned)(NB - 1 - J);
+}
+
 template <int D>
 __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict__ qsum,
                                                         const float *__restrict__ kmeanT,
@@ -72,7 +82,7 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
                                                         int *__restrict__ sel, KParams p)
 {
   __shared__ float qs[D];
-  extern __shared__ float sc[];  // NB scores (sized at launch: a static worst-case array would cap the occupancy)
+  extern __shared__ unsigned long long key_s[];  // NB keys (sized at launch: a static worst-case array would cap the occupancy)
   const int lane = threadIdx.x;
   const int I = p.NB - p.nq + (int)(blockIdx.x % p.nq);
   const int bh = blockIdx.x / p.nq;
@@ -94,7 +104,7 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
     float acc = 0.0f;
 #pragma unroll 8
     for (int c = 0; c < D; ++c) acc = __fmaf_rn(qs[c], km[(size_t)c * p.NB + J], acc);
-    sc[J] = acc;
+    key_s[J] = rank_key(acc, J, p.NB);
   }
   __syncthreads();
   int base = 0;
@@ -102,12 +112,9 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
     const int J = J0 + lane;
     bool chosen = false;
     if (J < I) {
-      const float s = sc[J];
+      const unsigned long long mine = key_s[J];
       int rank = 0;
-      for (int Jo = J_first; Jo < I; ++Jo) {
-        const float so = sc[Jo];
-        rank += (so > s || (so == s && Jo < J)) ? 1 : 0;
-      }
+      for (int Jo = J_first; Jo < I; ++Jo) rank += key_s[Jo] > mine ? 1 : 0;
       chosen = rank < take;
     }
     const unsigned long long mask = __ballot(chosen);
@@ -135,7 +142,7 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, cons
   hipLaunchKernelGGL((pool_kernel<T, D>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
                      valid_len, qsum, kmeanT, p);
   hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
-                     (size_t)p.NB * sizeof(float), st,
+                     (size_t)p.NB * sizeof(unsigned long long), st,
                      qsum, kmeanT, valid_len, sel, p);
 }
 

@@ -282,6 +282,32 @@ def test_matrix_core_sharp_softmax(b):
     run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
 
 
+def test_selection_ties():
+    # equal scores: planted duplicate key blocks (bit-identical scores, the lower index must win), and
+    # zero scores from two different causes (a zero key block, and a key block orthogonal to the query sum)
+    w = with_shape(WORKLOADS["cfg1"], name="dup", B=2, H=2, L=80, d=32, block=8, topk=3, len_lo=70, len_hi=80, seed=3)
+    for dtype in ("fp32", "bf16"):
+        wd = with_shape(w, dtype=dtype)
+        xd = make_inputs(wd)
+        xd.K[:, :, 32:40] = xd.K[:, :, 16:24]
+        xd.K[:, :, 48:56] = xd.K[:, :, 16:24]
+        xd.K[:, :, 56:64] = xd.K[:, :, 16:24]
+        dv = Dev(xd)
+        sel = B.select_blocks(params(wd), dv.Q, dv.K, dv.vl)
+        np.testing.assert_array_equal(sel.cpu().numpy(), oracle.select_blocks(xd.Q, xd.K, xd.valid_len, 8, 3))
+    wz = with_shape(WORKLOADS["cfg1"], name="zeros", B=1, H=1, L=24, d=32, block=8, topk=2, len_lo=24, len_hi=24)
+    xz = make_inputs(wz)
+    xz.Q[:] = 0.0
+    xz.K[:] = 0.0
+    xz.Q[0, 0, 16:24, 0] = -1.0
+    xz.K[0, 0, 8:16, 1] = 1.0
+    sel_ref, sc = oracle.select_blocks(xz.Q, xz.K, xz.valid_len, 8, 2, want_scores=True)
+    assert sc[0, 2, 0] == 0.0 and sc[0, 2, 1] == 0.0
+    dv = Dev(xz)
+    np.testing.assert_array_equal(B.select_blocks(params(wz), dv.Q, dv.K, dv.vl).cpu().numpy(), sel_ref)
+    assert [int(t) for t in sel_ref[0, 0, 2]] == [0, 2]
+
+
 def test_edge_cases():
     base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
     x = make_inputs(base, want_dO=True)

@@ -49,8 +49,9 @@ def test_hand_computed_integer_case(oracle):
 
 
 def test_signed_zero_scores_tie(oracle):
-    # block 0 keys are all zero -> its score is -0.0 for a negative Qsum, block 1 gives
-    # +0.0 through an orthogonal key; they must compare equal and index 0 wins.
+    # block 0 keys are all zero, block 1 is orthogonal to the query sum: both scores are zero (the
+    # products are -0 and +0; the fused-multiply-add chain starts from +0, so both sums are +0),
+    # they compare equal and index 0 wins.
     L, d, b = 12, 2, 4
     Q = np.zeros((1, 1, L, d), np.float32)
     K = np.zeros((1, 1, L, d), np.float32)
