@@ -90,6 +90,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step (select + forward + backward) in a HIP graph once and time its replays")
     ap.add_argument("--shape", default="",
                     help="overrides of the workload's fields, e.g. B=32,H=8,L=2000,len_lo=2000,len_hi=2000 "
                          "(the efficiency-study shapes of the paper's Appendix B); the JSON line names them")
@@ -192,11 +194,27 @@ def main():
     for _ in range(args.warmup):
         step()
     torch.cuda.synchronize()
+    run_step = step
+    if args.graph:
+        # the library allocates nothing and never synchronises: the step is captured as it is
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        run_step = graph.replay
+        run_step()
+        torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps ----
     t0 = time.perf_counter()
     for _ in range(args.steps):
-        step()
+        run_step()
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
@@ -284,7 +302,8 @@ def main():
         "config": {"workload": f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} b={w.block} k={w.topk} "
                                f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}"
                                + (f", short-term mask = all of Eq. 15 with mask block {w.stis_block}" if w.stis_block else ""),
-                   "tokens_per_step": tokens, "unmasked_pairs_lt": nnz_lt, "unmasked_pairs_st": nnz_st},
+                   "tokens_per_step": tokens, "unmasked_pairs_lt": nnz_lt, "unmasked_pairs_st": nnz_st,
+                   "launch": "hip graph replay" if args.graph else "stream"},
         "kernels_ms": {k_: round(v, 4) for k_, v in ms.items()},
         "fwd_tokens_per_s": round(tokens / ((ms["select"] + ms["fwd"]) * 1e-3), 1),
         "roofline": roofline(dominant),

@@ -382,3 +382,48 @@ def test_backward_passes_one_at_a_time_equal_the_full_call():
         for a, b_ in ((full.dQ, parts.dQ), (full.dK, parts.dK), (full.dV, parts.dV),
                       (full.d_gate_w, parts.d_gate_w), (full.d_gate_b, parts.d_gate_b)):
             assert torch.equal(a, b_)
+
+
+def test_step_under_a_hip_graph():
+    # The library allocates nothing, clears nothing with memset nodes and never synchronises, so a whole
+    # training step can be captured once and replayed: every replay (with new inputs copied into the
+    # captured buffers, and eager work between the replays) must reproduce the eager results bit for bit.
+    for w in (WORKLOADS["cfg1"], with_shape(WORKLOADS["cfg3"], B=2, H=2, L=32 * 7 + 9, len_lo=50, len_hi=32 * 7 + 9)):
+        p = params(w, save_for_bwd=1)
+        xs = [make_inputs(with_shape(w, seed=w.seed + 31 * i), want_dO=True) for i in range(3)]
+        dv = Dev(xs[0])
+        ws_sel = torch.empty(max(1, B.workspace_bytes(p, B.WS_SELECT)), dtype=torch.uint8, device="cuda")
+        ws_bwd = torch.empty(max(1, B.workspace_bytes(p, B.WS_BWD)), dtype=torch.uint8, device="cuda")
+        sel = B.select_blocks(p, dv.Q, dv.K, dv.vl, ws=ws_sel)
+        f = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
+        g = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO, ws=ws_bwd)
+        torch.cuda.synchronize()
+
+        def step():
+            B.select_blocks(p, dv.Q, dv.K, dv.vl, sel=sel, ws=ws_sel)
+            B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, out=f)
+            B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO, out=g, ws=ws_bwd)
+
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.stream(side):
+            step()  # warm-up on the capture stream
+            side.synchronize()
+            with torch.cuda.graph(graph, stream=side):
+                step()
+        torch.cuda.current_stream().wait_stream(side)
+        torch.cuda.synchronize()
+        for x in xs[::-1] + xs:
+            fresh = Dev(x)
+            for dst, src in ((dv.Q, fresh.Q), (dv.K, fresh.K), (dv.V, fresh.V), (dv.dO, fresh.dO), (dv.vl, fresh.vl)):
+                dst.copy_(src)
+            step()  # eager
+            torch.cuda.synchronize()
+            want = [t.clone() for t in (sel, f.O, f.o_lt, f.o_st, f.lse_lt, f.lse_st, g.dQ, g.dK, g.dV, g.d_gate_w, g.d_gate_b)]
+            for t in (sel, f.O, f.o_lt, f.o_st, f.lse_lt, f.lse_st, g.dQ, g.dK, g.dV, g.d_gate_w, g.d_gate_b):
+                t.fill_(1)  # eager work between the replays, and proof that the replay rewrites everything
+            graph.replay()
+            torch.cuda.synchronize()
+            for a, b_ in zip(want, (sel, f.O, f.o_lt, f.o_st, f.lse_lt, f.lse_st, g.dQ, g.dK, g.dV, g.d_gate_w, g.d_gate_b)):
+                assert torch.equal(a, b_)
