@@ -90,6 +90,9 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--input-sets", type=int, default=3,
+                    help="independent seeded input sets the timed steps rotate over, so that a small workload is not "
+                         "served from the 256 MB last-level cache (one set with --stage and --graph)")
     ap.add_argument("--graph", action="store_true",
                     help="capture the step (select + forward + backward) in a HIP graph once and time its replays")
     ap.add_argument("--shape", default="",
@@ -123,15 +126,17 @@ def main():
         w = with_shape(w, name=w.name + "*", **{k_: int(v_) for k_, v_ in kv.items()})
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
-    x = make_inputs(w, want_dO=True)
+    n_sets = 1 if (args.stage or args.graph) else max(1, args.input_sets)
+    xs = [make_inputs(w, input_set=i, want_dO=True) for i in range(n_sets)]
+    x = xs[0]  # the per-kernel passes, the pair counts and the CPU baseline use the first set
 
     def up(a):
         if w.dtype == "bf16":
             return torch.from_numpy(bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
         return torch.from_numpy(a).to(dev)
 
-    Q, K, V, dO = up(x.Q), up(x.K), up(x.V), up(x.dO)
-    vl = torch.from_numpy(x.valid_len).to(dev)
+    sets = [(up(xi.Q), up(xi.K), up(xi.V), up(xi.dO), torch.from_numpy(xi.valid_len).to(dev)) for xi in xs]
+    Q, K, V, dO, vl = sets[0]
     gw = torch.from_numpy(x.gate_w).to(dev)
     gb = torch.from_numpy(x.gate_b).to(dev)
     dt = B.F32 if w.dtype == "fp32" else B.BF16
@@ -155,10 +160,11 @@ def main():
     ws_bwd = torch.empty(max(1, B.workspace_bytes(p, B.WS_BWD)), dtype=torch.uint8, device=dev)
     O_dense = mk()
 
-    def step():
-        B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel)
-        B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo)
-        B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd)
+    def step(i=0):
+        Qi, Ki, Vi, dOi, vli = sets[i % n_sets]
+        B.select_blocks(p, Qi, Ki, vli, sel=sel, ws=ws_sel)
+        B.attn_fwd(p, Qi, Ki, Vi, vli, sel, gw, gb, out=fo)
+        B.attn_bwd(p, Qi, Ki, Vi, vli, sel, gw, gb, fo, dOi, out=bo, ws=ws_bwd)
 
     if args.stage:
         step()  # every buffer a later stage reads is filled once
@@ -191,8 +197,8 @@ def main():
                           "avg_ms": round(e0.elapsed_time(e1) / args.steps, 4)}))
         return
 
-    for _ in range(args.warmup):
-        step()
+    for i in range(args.warmup):
+        step(i)
     torch.cuda.synchronize()
     run_step = step
     if args.graph:
@@ -207,14 +213,14 @@ def main():
                 step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
-        run_step = graph.replay
-        run_step()
+        run_step = lambda i: graph.replay()
+        run_step(0)
         torch.cuda.synchronize()
 
     # ---- timed region: exactly K steps ----
     t0 = time.perf_counter()
-    for _ in range(args.steps):
-        run_step()
+    for i in range(args.steps):
+        run_step(i)
     torch.cuda.synchronize()
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
@@ -253,6 +259,7 @@ def main():
     nnz_lt, nnz_st, nnz_dense = algorithmic_pairs(w, x.valid_len, sel_h)
     pairs = nnz_lt + nnz_st
     tokens = int(x.valid_len.sum())
+    tokens_timed = sum(int(xs[i % n_sets].valid_len.sum()) for i in range(args.steps))  # over the timed steps
     sz = 4 if w.dtype == "fp32" else 2
     tensor = float(w.B) * w.H * w.L * w.d
     mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
@@ -288,7 +295,7 @@ def main():
     dominant = max(step_kernels, key=lambda k_: ms[k_])
     out = {
         "metric": "sparse-attn fwd+bwd tokens/sec (select + forward + backward per step)",
-        "value": round(tokens / (ms_per_step * 1e-3), 1),
+        "value": round(tokens_timed / (wall), 1),
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
@@ -303,7 +310,7 @@ def main():
                                f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}"
                                + (f", short-term mask = all of Eq. 15 with mask block {w.stis_block}" if w.stis_block else ""),
                    "tokens_per_step": tokens, "unmasked_pairs_lt": nnz_lt, "unmasked_pairs_st": nnz_st,
-                   "launch": "hip graph replay" if args.graph else "stream"},
+                   "launch": "hip graph replay" if args.graph else "stream", "input_sets": n_sets},
         "kernels_ms": {k_: round(v, 4) for k_, v in ms.items()},
         "fwd_tokens_per_s": round(tokens / ((ms["select"] + ms["fwd"]) * 1e-3), 1),
         "roofline": roofline(dominant),
@@ -341,8 +348,16 @@ def main():
         if cpu_s < 8.0 and n_pairs < total_pairs:  # aim at about 15 s of CPU work
             n_pairs = min(total_pairs, max(n_pairs + 1, int(n_pairs * 15.0 / max(cpu_s, 1e-3))))
             cpu_s, sample_tokens = run_oracle(n_pairs)
+        cpu_model = "unknown"
+        try:
+            for line in open("/proc/cpuinfo"):
+                if line.startswith("model name"):
+                    cpu_model = line.split(":", 1)[1].strip()
+                    break
+        except OSError:
+            pass
         out["cpu_baseline"] = {"value": round(sample_tokens / cpu_s, 2), "unit": "tokens/s",
-                               "cores": threads, "kind": "oracle",
+                               "cores": threads, "cpu": cpu_model, "kind": "oracle",
                                "sample": f"{n_pairs} of {total_pairs} (row, head) pairs, select+fwd+bwd, "
                                          f"{cpu_s:.1f} s; tokens counted as pairs/H * valid_len"}
     print(json.dumps(out))
