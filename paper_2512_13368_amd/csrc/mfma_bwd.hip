@@ -18,8 +18,8 @@
 // extra matrix instruction (ones x split); dQ, where a lane keeps its row for the whole walk,
 // holds them as two 16-register blocks that the first matrix instruction of each product
 // takes as its C operand.  Either way no per-element VALU initialisation is needed.  (Reading
-// the dK/dV constants from LDS straight into a C block was measured slower: that kernel's LDS
-// pipe is as busy as its matrix pipe.)  Probabilities and dS leave the accumulator
+// the dK/dV constants from LDS straight into a C block was measured slower: that kernel
+// already issues 25 LDS reads per 18 matrix instructions.)  Probabilities and dS leave the accumulator
 // registers as the B operand of the next product without moving between lanes; the matching
 // A operands (K^T, Q^T, dO_x^T) come from LDS through the transposing ds_read_b64_tr_b16.
 // Query blocks whose rows may see only a few keys (large probabilities) feed P and dS as
