@@ -308,6 +308,14 @@ def test_selection_ties():
     assert [int(t) for t in sel_ref[0, 0, 2]] == [0, 2]
 
 
+def test_many_blocks_backward():
+    # more than 2048 blocks per row: the inverse selection list then runs with one wavefront per (row, head)
+    # and its counters no longer fit four-fold in LDS; scalar kernels, fp32
+    w = with_shape(WORKLOADS["cfg1"], name="many-blocks", B=1, H=2, L=8 * 2100 + 3, d=32, block=8, topk=4, window=11,
+                   len_lo=8 * 2100 - 50, len_hi=8 * 2100 + 3, seed=77)
+    run_case(w, backward=True, gate_scale=0.4)
+
+
 def test_edge_cases():
     base = with_shape(WORKLOADS["cfg1"], name="edge", B=5, H=2, L=50, seed=301)
     x = make_inputs(base, want_dO=True)
