@@ -329,6 +329,14 @@ def test_edge_cases():
     torch.cuda.synchronize()
     assert_close(host(f.o_lt), host(Od), 1e-5, "o_lt vs dense kernel")
     assert_close(host(f.o_st), host(Od), 1e-5, "o_st vs dense kernel")
+    # every row empty: all outputs and gradients are zero, nothing faults (both kernel families)
+    for wz in (with_shape(base, name="all-empty", B=2), with_shape(WORKLOADS["cfg3"], name="all-empty-mc", B=2, H=2, L=32 * 5 + 7)):
+        xz = make_inputs(wz, want_dO=True)
+        xz.valid_len[:] = 0
+        _, selz, fz, gz = run_case(wz, x=xz, backward=True, check_dense=True)
+        assert int((selz != -1).sum()) == 0
+        for t in (fz.O, fz.o_lt, fz.o_st, gz.dQ, gz.dK, gz.dV, gz.d_gate_w, gz.d_gate_b):
+            assert float(t.float().abs().max()) == 0.0
     # k = 1 (own block only), w = 1 (self only), k larger than the number of blocks
     run_case(with_shape(base, name="k1w1", topk=1, window=1), backward=True)
     run_case(with_shape(base, name="kbig", topk=12, window=200), backward=True)
