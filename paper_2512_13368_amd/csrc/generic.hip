@@ -65,7 +65,7 @@ __device__ __forceinline__ int first_window_block(int I, int b, int w, int J_fir
 // Forward
 // =============================================================================================
 template <typename T, int D>
-__global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 32 ? 4 : 2))) void fwd_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                          const T *__restrict__ V,
                                                          const int *__restrict__ valid_len,
                                                          const int *__restrict__ sel,
@@ -77,12 +77,15 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
                                                          float *__restrict__ lse_st_out, int dense,
                                                          KParams p)
 {
-  __shared__ float Ks[64][D + 1];
-  __shared__ float Vs[64][D + 1];
-  __shared__ float Os[64][D + 1];  // short-term output of each row, parked during the long-term pass
-
+  // three tiles of b rows (sized at launch: with small blocks a fixed 64-row layout would cap the
+  // number of resident wavefronts): K, V, and the short-term output of each row, parked during
+  // the long-term pass
+  extern __shared__ float fwd_lds[];
   const int lane = threadIdx.x;
   const int b = p.b;
+  float (*Ks)[D + 1] = reinterpret_cast<float (*)[D + 1]>(fwd_lds);
+  float (*Vs)[D + 1] = Ks + b;
+  float (*Os)[D + 1] = Vs + b;
   const int nph = 64 / b;
   const int row = lane % b;
   const int phase = lane / b;
@@ -133,10 +136,10 @@ __global__ __launch_bounds__(64) void fwd_generic_kernel(const T *__restrict__ Q
       const int j = J * b + jj;
       const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || st_visible(p, i, j));
       if (vis) {
-        float s = 0.0f;
+        float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // four independent chains
 #pragma unroll
-        for (int c = 0; c < D; ++c) s = fmaf(q[c], Ks[jj][c], s);
-        s *= p.scale;
+        for (int c = 0; c < D; ++c) s4[c & 3] = fmaf(q[c], Ks[jj][c], s4[c & 3]);
+        const float s = ((s4[0] + s4[1]) + (s4[2] + s4[3])) * p.scale;
         if (s > m) {
           const float corr = __expf(m - s);
           l *= corr;
@@ -441,7 +444,7 @@ __global__ __launch_bounds__(256) void bwd_gate_reduce2_kernel(const float *__re
 //   dP_ij = dO_x[i].v_j = a_x[i]*(dO[i].v_j) + dz[i]*(gate_w_x.v_j)
 // =============================================================================================
 template <typename T, int D>
-__global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 32 ? 3 : 1))) void bwd_dq_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                             const T *__restrict__ V,
                                                             const int *__restrict__ valid_len,
                                                             const int *__restrict__ sel,
@@ -452,12 +455,13 @@ __global__ __launch_bounds__(64) void bwd_dq_generic_kernel(const T *__restrict_
                                                             const float4 *__restrict__ rowstat,
                                                             T *__restrict__ dQ, KParams p)
 {
-  __shared__ float Ks[64][D + 1];
-  __shared__ float Vs[64][D + 1];
-  __shared__ float wv[64];  // gate_w_x . v_j of the staged tile
+  extern __shared__ float dq_lds[];  // K and V tiles of b rows (sized at launch)
+  __shared__ float wv[64];           // gate_w_x . v_j of the staged tile
 
   const int lane = threadIdx.x;
   const int b = p.b;
+  float (*Ks)[D + 1] = reinterpret_cast<float (*)[D + 1]>(dq_lds);
+  float (*Vs)[D + 1] = Ks + b;
   const int nph = 64 / b;
   const int row = lane % b;
   const int phase = lane / b;
@@ -641,10 +645,11 @@ __global__ __launch_bounds__(64 * kInvWaves) void inverse_list_kernel(const int 
 }
 
 // =============================================================================================
-// Backward, step 4: dK / dV (key-block stationary).  blockIdx.y = 0 computes dV, 1 computes dK.
+// Backward, step 4: dK / dV (key-block stationary), one launch each (WANT_DK): the dV pass needs
+// neither the V row nor the dP product, so it runs with fewer registers and more wavefronts.
 // A lane owns one key row and one phase of the query tile.
 // =============================================================================================
-template <typename T, int D>
+template <typename T, int D, bool WANT_DK>
 __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                              const T *__restrict__ V,
                                                              const int *__restrict__ valid_len,
@@ -658,19 +663,20 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
                                                              T *__restrict__ dK, T *__restrict__ dV,
                                                              KParams p)
 {
-  __shared__ float Qs[64][D + 1];
-  __shared__ float Gs[64][D + 1];  // dO_x rows of the staged query tile
+  extern __shared__ float dkv_lds[];  // Q and dO_x tiles of b rows (sized at launch)
   __shared__ float lse_s[64];
   __shared__ float Dx_s[64];
 
   const int lane = threadIdx.x;
   const int b = p.b;
+  float (*Qs)[D + 1] = reinterpret_cast<float (*)[D + 1]>(dkv_lds);
+  float (*Gs)[D + 1] = Qs + b;  // dO_x rows of the staged query tile
   const int nph = 64 / b;
   const int jj = lane % b;
   const int phase = lane / b;
   const int bh = blockIdx.x / p.NB;
   const int J = (int)(blockIdx.x % p.NB);
-  const bool want_dk = blockIdx.y == 1;
+  constexpr bool want_dk = WANT_DK;
   const int h = bh % p.H;
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
@@ -734,14 +740,16 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
       const int i = I * b + ii;
       const bool vis = key_ok && i < p.L && i >= p0 && j <= i && (!windowed || st_visible(p, i, j));
       if (vis) {
-        float s = 0.0f;
+        float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // four independent chains
 #pragma unroll
-        for (int c = 0; c < D; ++c) s = fmaf(Qs[ii][c], kr[c], s);
+        for (int c = 0; c < D; ++c) s4[c & 3] = fmaf(Qs[ii][c], kr[c], s4[c & 3]);
+        const float s = (s4[0] + s4[1]) + (s4[2] + s4[3]);
         const float pj = __expf(s * p.scale - lse_s[ii]);
         if (want_dk) {
-          float dP = 0.0f;
+          float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-          for (int c = 0; c < D; ++c) dP = fmaf(Gs[ii][c], vr[c], dP);
+          for (int c = 0; c < D; ++c) d4[c & 3] = fmaf(Gs[ii][c], vr[c], d4[c & 3]);
+          const float dP = (d4[0] + d4[1]) + (d4[2] + d4[3]);
           const float dS = pj * (dP - Dx_s[ii]);
 #pragma unroll
           for (int c = 0; c < D; ++c) acc[c] = fmaf(dS, Qs[ii][c], acc[c]);
@@ -788,7 +796,8 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
 template <typename T, int D>
 static void launch_fwd_t(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
-  hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64), 0, st,
+  hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
+                     3 * (size_t)p.b * (D + 1) * sizeof(float), st,
                      (const T *)a.Q, (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w,
                      a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
 }
@@ -868,13 +877,20 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     return;
   }
   if (stages & kBwdStageDQ)
-    hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64), 0, st, (const T *)a.Q,
+    hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64),
+                       2 * (size_t)p.b * (D + 1) * sizeof(float), st, (const T *)a.Q,
                        (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st,
                        (const T *)a.dO, w.rowstat, (T *)a.dQ, p);
   if (stages & kBwdStageDKV)
-    hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D>), dim3(BH * p.NB, 2), dim3(64), 0, st, (const T *)a.Q,
+  {
+    const size_t lds = 2 * (size_t)p.b * (D + 1) * sizeof(float);
+    hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D, false>), dim3(BH * p.NB), dim3(64), lds, st, (const T *)a.Q,
                        (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
                        (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
+    hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D, true>), dim3(BH * p.NB), dim3(64), lds, st, (const T *)a.Q,
+                       (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
+                       (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
+  }
 }
 
 void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, hipStream_t st)
