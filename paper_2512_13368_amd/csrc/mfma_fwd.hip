@@ -59,7 +59,7 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >>
 // EQ15: the short-term mask is all of Eq. 15 with mask block BLK (compile-time, so that the plain
 // causal window compiles to exactly the code it had without it)
 template <int BLK, bool EQ15>
-__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void fwd_mfma_kernel(
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 32 ? 3 : 2, BLK == 32 ? 3 : 2))) void fwd_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const int *__restrict__ sel, const float *__restrict__ gate_w,
     const float *__restrict__ gate_b, uint16_t *__restrict__ O, float *__restrict__ o_lt_out,
@@ -75,7 +75,12 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   __shared__ __attribute__((aligned(1024))) uint16_t Ks0[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
   __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
+  // The 32-row kernel (one wavefront per workgroup, short tiles) is bound by latency, so it trades
+  // the second V buffer for a third wavefront per SIMD (12.5 KB of LDS and 168 registers per
+  // workgroup): a tile's V is requested at the start of its own step, ahead of the next K tile,
+  // and waited for after the QK products.
+  constexpr bool V1 = BLK == 32;
+  __shared__ __attribute__((aligned(1024))) uint16_t Vs1[V1 ? 8 : TILE];
   __shared__ float gate_s[2 * D];     // this head's gate weights, fetched at the start, used at the very end
   __shared__ float xch_s[NQ][2][64];  // branch merge: reference and partial row sum handed to the partner
 
@@ -207,7 +212,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // the first tile is on its way while the rest of the prologue runs
   const int first_J = dense ? J_first : J_lo;
   stage(Kh, k_lane, 64u, Ks0, first_J);
-  stage(Vh, v_lane, 0u, Vs0, first_J);
+  if (!V1) stage(Vh, v_lane, 0u, Vs0, first_J);
 
   // Q^T operand: lane (query lq, half lh) holds c*Q[iq][16*kk + 8*lh .. +7] for the 4 slabs kk,
   // c = scale*log2(e), rounded to bf16: the matrix cores then produce base-2 exponents directly.
@@ -432,7 +437,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   // key.  Otherwise the slow path finds the row maxima, moves the references and takes the
   // exponentials again; it raises a reference whenever a probability would exceed 2^kRaise,
   // which also guarantees that the retaken tile passes.
-  auto tile = [&](const uint16_t *ks, const uint16_t *vs, int J, bool short_term) __attribute__((always_inline)) {
+  auto tile = [&](const uint16_t *ks, const uint16_t *vs, int J, bool short_term, bool last) __attribute__((always_inline)) {
     const bool hp = (short_term ? hp_st : hp_lt) != 0;
     // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
     const bool windowed = short_term && !(EQ15 && is_pow2(I - J));
@@ -466,6 +471,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
         if (!full[g]) mask(J, windowed, g, s[g]);
     }
     bf16x8 vf[2][2];
+    if (V1) {  // this tile's V (4 loads) was requested ahead of the next K tile (4 loads, absent after the last tile)
+      if (last) __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
+      else __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+    }
     load_v(vs, vf);
     bf16x8 pf[NQ][2];
 #pragma unroll
@@ -543,19 +552,30 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     st_open = false;
   };
   // step t: prefetch tile t+1 into the other buffer pair, wait for this wavefront's own loads
-  // of tile t (the 8 just issued stay in flight), process tile t
+  // of tile t (the 8 just issued stay in flight), process tile t.  With one V buffer: request
+  // V of tile t, then K of tile t+1; K of tile t (requested a step ago) is there once at most
+  // those 8 are outstanding, V of tile t is waited for inside the tile.
   int J_cur = first_J;
   int J_nxt = __builtin_amdgcn_readfirstlane(tile_raw(min(1, n_all - 1)));
   auto step = [&](int t, uint16_t *k_cur, uint16_t *v_cur, uint16_t *k_nxt, uint16_t *v_nxt) __attribute__((always_inline)) {
     const int J_after = tile_raw(min(t + 2, n_all - 1));  // consumed at the end of this step
-    if (t + 1 < n_all) {
+    const bool last = t + 1 >= n_all;
+    if (V1) {
+      stage(Vh, v_lane, 0u, Vs0, J_cur);
+      if (!last) {
+        stage(Kh, k_lane, 64u, k_nxt, J_nxt);
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
+      } else {
+        __builtin_amdgcn_s_waitcnt(vmcnt_imm(4));
+      }
+    } else if (!last) {
       stage(Kh, k_lane, 64u, k_nxt, J_nxt);
       stage(Vh, v_lane, 0u, v_nxt, J_nxt);
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(8));
     } else {
       __builtin_amdgcn_s_waitcnt(vmcnt_imm(0));
     }
-    tile(k_cur, v_cur, J_cur, t < n_st);
+    tile(k_cur, V1 ? Vs0 : v_cur, J_cur, t < n_st, last);
     J_cur = J_nxt;
     J_nxt = __builtin_amdgcn_readfirstlane(J_after);
     if (st_open && t + 1 >= n_st) close_st(k_cur, v_cur);  // the window tiles are done
@@ -594,7 +614,9 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       const int rr = 4 * (i & 3) + (el >> 4), c = el & 15;
       const float4 v = *reinterpret_cast<const float4 *>((i < 4 ? pa : pb) + rr * 64 + ((c ^ rr) * 4));
       const int grow = row0 + 16 * (i >> 2) + rr;
-      if (grow < p.L) *reinterpret_cast<float4 *>(dst + head + (size_t)grow * D + 4 * c) = v;
+      typedef float f32x4_t __attribute__((ext_vector_type(4)));
+      const f32x4_t vv = {v.x, v.y, v.z, v.w};
+      if (grow < p.L) __builtin_nontemporal_store(vv, reinterpret_cast<f32x4_t *>(dst + head + (size_t)grow * D + 4 * c));
     }
   };
   // o4(mb, g, e): the value of channel 32*mb + 8*g + 4*lh + e of this lane's row
@@ -648,7 +670,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const float alpha = q_ok[0] ? 1.0f / (1.0f + __expf(-z)) : 0.0f;
   if (o_lt_out) {
     store_f32_rows(o_lt_out, oacc[0], Ks0, Ks1);
-    store_f32_rows(o_st_out, ost, Vs0, Vs1);
+    store_f32_rows(o_st_out, ost, Vs0, V1 ? Ks0 : Vs1);
   }
   store_bf16_rows(O, [&](int mb, int g, int e) {
     return alpha * oacc[0][mb][4 * g + e] + (1.0f - alpha) * ost[mb][4 * g + e];
