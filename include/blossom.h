@@ -53,8 +53,8 @@ enum {
   BLOSSOM_OK = 0,
   BLOSSOM_ERR_NULL = -1,        /* a required pointer is NULL                                  */
   BLOSSOM_ERR_SHAPE = -2,       /* B, H or L < 1, or L/b too large (NB > 4096)                 */
-  BLOSSOM_ERR_UNSUPPORTED = -3, /* d not in {32,64}, b not in {8,16,32,64}, dtype, stis_mode;   
-                                   backward with last_block_only                               */
+  BLOSSOM_ERR_UNSUPPORTED = -3, /* d or b not in {8,16,32,64}, dtype, stis_mode; backward with
+                                   last_block_only                                             */
   BLOSSOM_ERR_PARAM = -4,       /* topk < 1, window < 1, stis_block < 0, bad softmax_scale      */
   BLOSSOM_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned                     */
   BLOSSOM_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than blossom_workspace_bytes()    */

@@ -17,7 +17,7 @@ int check_params(const blossom_params *p, KParams *kp)
 {
   if (!p) return BLOSSOM_ERR_NULL;
   if (p->B < 1 || p->H < 1 || p->L < 1) return BLOSSOM_ERR_SHAPE;
-  if (p->d != 32 && p->d != 64) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->d != 8 && p->d != 16 && p->d != 32 && p->d != 64) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->block != 8 && p->block != 16 && p->block != 32 && p->block != 64) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->dtype != BLOSSOM_F32 && p->dtype != BLOSSOM_BF16) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->stis_mode != 0 && p->stis_mode != 1) return BLOSSOM_ERR_UNSUPPORTED;

@@ -65,7 +65,7 @@ __device__ __forceinline__ int first_window_block(int I, int b, int w, int J_fir
 // Forward
 // =============================================================================================
 template <typename T, int D>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 32 ? 4 : 2))) void fwd_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 : 2))) void fwd_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                          const T *__restrict__ V,
                                                          const int *__restrict__ valid_len,
                                                          const int *__restrict__ sel,
@@ -444,7 +444,7 @@ __global__ __launch_bounds__(256) void bwd_gate_reduce2_kernel(const float *__re
 //   dP_ij = dO_x[i].v_j = a_x[i]*(dO[i].v_j) + dz[i]*(gate_w_x.v_j)
 // =============================================================================================
 template <typename T, int D>
-__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D == 32 ? 3 : 1))) void bwd_dq_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+__global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 : 1))) void bwd_dq_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                             const T *__restrict__ V,
                                                             const int *__restrict__ valid_len,
                                                             const int *__restrict__ sel,
@@ -804,13 +804,11 @@ static void launch_fwd_t(const KParams &p, const FwdArgs &a, hipStream_t st)
 
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st)
 {
-  if (dtype == 0) {
-    if (p.d == 32) launch_fwd_t<float, 32>(p, a, st);
-    else launch_fwd_t<float, 64>(p, a, st);
-  } else {
-    if (p.d == 32) launch_fwd_t<bf16_t, 32>(p, a, st);
-    else launch_fwd_t<bf16_t, 64>(p, a, st);
-  }
+  with_head_dim(p.d, [&](auto dim) {
+    constexpr int D = decltype(dim)::value;
+    if (dtype == 0) launch_fwd_t<float, D>(p, a, st);
+    else launch_fwd_t<bf16_t, D>(p, a, st);
+  });
 }
 
 namespace {
@@ -895,13 +893,11 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
 
 void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, hipStream_t st)
 {
-  if (dtype == 0) {
-    if (p.d == 32) launch_bwd_t<float, 32>(p, dtype, a, stages, st);
-    else launch_bwd_t<float, 64>(p, dtype, a, stages, st);
-  } else {
-    if (p.d == 32) launch_bwd_t<bf16_t, 32>(p, dtype, a, stages, st);
-    else launch_bwd_t<bf16_t, 64>(p, dtype, a, stages, st);
-  }
+  with_head_dim(p.d, [&](auto dim) {
+    constexpr int D = decltype(dim)::value;
+    if (dtype == 0) launch_bwd_t<float, D>(p, dtype, a, stages, st);
+    else launch_bwd_t<bf16_t, D>(p, dtype, a, stages, st);
+  });
 }
 
 }  // namespace blossom

@@ -1,6 +1,8 @@
 // Host-side launch entry points of the kernel translation units (internal to the library).
 #pragma once
 
+#include <type_traits>
+
 #include <hip/hip_runtime.h>
 #include <stddef.h>
 
@@ -54,6 +56,19 @@ struct BwdWorkspace {
   int nchunk;
   size_t total;
 };
+
+// Calls f with the head dimension as a compile-time constant (d is one of 8, 16, 32, 64: checked
+// at the boundary).
+template <typename F>
+inline void with_head_dim(int d, F &&f)
+{
+  switch (d) {
+    case 8: f(std::integral_constant<int, 8>{}); break;
+    case 16: f(std::integral_constant<int, 16>{}); break;
+    case 32: f(std::integral_constant<int, 32>{}); break;
+    default: f(std::integral_constant<int, 64>{}); break;
+  }
+}
 
 // generic.hip: scalar-ALU kernels for every supported (dtype, d, b)
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);

@@ -151,13 +151,11 @@ size_t select_workspace_bytes(const KParams &p) { return 2 * (size_t)p.B * p.H *
 void launch_select(const KParams &p, int dtype, const void *Q, const void *K, const int *valid_len,
                    int *sel, void *ws, hipStream_t st)
 {
-  if (dtype == 0) {
-    if (p.d == 32) launch_select_t<float, 32>(p, Q, K, valid_len, sel, ws, st);
-    else launch_select_t<float, 64>(p, Q, K, valid_len, sel, ws, st);
-  } else {
-    if (p.d == 32) launch_select_t<bf16_t, 32>(p, Q, K, valid_len, sel, ws, st);
-    else launch_select_t<bf16_t, 64>(p, Q, K, valid_len, sel, ws, st);
-  }
+  with_head_dim(p.d, [&](auto dim) {
+    constexpr int D = decltype(dim)::value;
+    if (dtype == 0) launch_select_t<float, D>(p, Q, K, valid_len, sel, ws, st);
+    else launch_select_t<bf16_t, D>(p, Q, K, valid_len, sel, ws, st);
+  });
 }
 
 }  // namespace blossom

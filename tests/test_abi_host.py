@@ -84,7 +84,7 @@ def test_validation_codes_fwd_bwd_dense(lib):
     assert fwd(gw=None) == -1
     assert fwd(O=vp(4100)) == -5
     assert fwd(p=_p(save_for_bwd=1).c()) == -1                      # saved outputs required
-    assert fwd(p=_p(d=16).c()) == -3
+    assert fwd(p=_p(d=24).c()) == -3
     bwd = lambda **k: lib.blossom_attn_bwd(ctypes.byref(k.get("p", cp)), a, a, a, a, a, a, None, a, a, a, a,
                                            k.get("dO", a), a, a, a, k.get("dgw", a), None,
                                            k.get("ws", a), k.get("n", 1 << 30), None)

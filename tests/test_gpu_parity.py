@@ -342,6 +342,20 @@ def test_edge_cases():
     run_case(with_shape(base, name="kbig", topk=12, window=200), backward=True)
 
 
+@pytest.mark.parametrize("dtype,d,H,L,b,k,w,sblk", [
+    ("fp32", 8, 8, 100, 16, 4, 8, 1),     # the paper's own setting: hidden 64 over 8 heads, length 100 (App. E)
+    ("fp32", 16, 8, 200, 16, 4, 8, 1),    # ML-1M: hidden 128 over 8 heads, length 200
+    ("bf16", 8, 8, 200, 16, 4, 8, 0),
+    ("bf16", 16, 4, 333, 32, 3, 40, 0),
+    ("fp32", 8, 2, 77, 8, 2, 5, 4),
+    ("fp32", 16, 2, 500, 64, 5, 70, 0),
+])
+def test_small_head_dims(dtype, d, H, L, b, k, w, sblk):
+    wl = with_shape(WORKLOADS["cfg1"], name=f"d{d}-{dtype}", B=6, H=H, L=L, d=d, block=b, topk=k, window=w, dtype=dtype,
+                    len_lo=0, len_hi=L, qkv_scaled=(dtype == "bf16"), seed=1700 + d + L, stis_block=sblk)
+    run_case(wl, backward=True, check_dense=True, gate_scale=0.4)
+
+
 def test_forced_gate():
     w = WORKLOADS["cfg1"]
     x = make_inputs(w, want_dO=True)
