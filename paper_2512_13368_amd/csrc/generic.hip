@@ -59,12 +59,51 @@ __device__ __forceinline__ int first_window_block(int I, int b, int w, int J_fir
   return J > J_first ? J : J_first;
 }
 
+// Far part of the short-term mask when the mask block is smaller than the tile (Eq. 15, second and
+// third case, below the window tiles): the rows of a query block then see different, short runs of
+// keys, so each lane reads its own keys straight from memory instead of walking whole tiles.
+// Calls f(j) once for every key j in [p0, far_hi) at a power-of-two mask-block distance from
+// query i, or among the last sblk positions; the runs are dealt over the nph phases of the row.
+template <typename F>
+__device__ __forceinline__ void far_keys_of_row(const KParams &p, int i, int p0, int far_hi, int phase, int nph, F &&f)
+{
+  const int qb = i / p.sblk;
+  for (int r = phase; r < 31; r += nph) {
+    const int mb = qb - (1 << r);
+    if (mb < 0) break;
+    const int lo = max(mb * p.sblk, p0), hi = min(mb * p.sblk + p.sblk, far_hi);
+    for (int j = lo; j < hi; ++j) f(j);
+  }
+  if (phase == 0)
+    for (int j = max(p.last_lo, p0); j < far_hi; ++j)
+      if (!is_pow2(qb - j / p.sblk)) f(j);
+}
+// The same pairs from the key's side: f(i) for every query i in [far_lo, L) that sees key j that way.
+template <typename F>
+__device__ __forceinline__ void far_rows_of_key(const KParams &p, int j, int far_lo, int phase, int nph, F &&f)
+{
+  const int kb = j / p.sblk;
+  for (int r = phase; r < 31; r += nph) {
+    const long first = ((long)kb + (1L << r)) * p.sblk;
+    if (first >= p.L) break;
+    const int lo = max((int)first, far_lo), hi = min((int)first + p.sblk, p.L);
+    for (int i = lo; i < hi; ++i) f(i);
+  }
+  if (phase == 0 && j >= p.last_lo)
+    for (int i = far_lo; i < p.L; ++i)
+      if (!is_pow2(i / p.sblk - kb)) f(i);
+}
+// (host side: picks the instantiation)
+static inline bool far_by_rows(const KParams &p) { return p.sblk > 0 && p.sblk < p.b; }
+
 }  // namespace
 
 // =============================================================================================
 // Forward
 // =============================================================================================
-template <typename T, int D>
+// FAR: the far part of the short-term mask is gathered row by row (mask block smaller than the
+// tile); a separate instantiation, so that the plain kernels keep their register budget.
+template <typename T, int D, bool FAR>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 : 2))) void fwd_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                          const T *__restrict__ V,
                                                          const int *__restrict__ valid_len,
@@ -201,12 +240,44 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 
     return;
   }
 
-  // ---- short-term branch: causal window, plus the blocks the other cases of Eq. 15 reach ----
+  // ---- short-term branch: causal window, plus the keys the other cases of Eq. 15 reach ----
   reset();
   {
     const int J_win = first_window_block(I, b, p.w, J_first);
-    for (int J = J_first; J < J_win; ++J)
-      if (st_block_reach(p, I, J)) tile(J, true);
+    if constexpr (FAR) {
+      if (active)
+        far_keys_of_row(p, i, p0, J_win * b, phase, nph, [&](int j) {
+          const T *kp = Kh + (size_t)j * D, *vp = Vh + (size_t)j * D;
+          float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+          for (int c = 0; c < D; c += 4) {
+            float x[4];
+            load4(kp + c, x);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s4[e] = fmaf(q[c + e], x[e], s4[e]);
+          }
+          const float s = ((s4[0] + s4[1]) + (s4[2] + s4[3])) * p.scale;
+          if (s > m) {
+            const float corr = __expf(m - s);
+            l *= corr;
+#pragma unroll
+            for (int c = 0; c < D; ++c) acc[c] *= corr;
+            m = s;
+          }
+          const float pj = __expf(s - m);
+          l += pj;
+#pragma unroll
+          for (int c = 0; c < D; c += 4) {
+            float x[4];
+            load4(vp + c, x);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) acc[c + e] = fmaf(pj, x[e], acc[c + e]);
+          }
+        });
+    } else {
+      for (int J = J_first; J < J_win; ++J)
+        if (st_block_reach(p, I, J)) tile(J, true);
+    }
     for (int J = J_win; J <= I; ++J) tile(J, true);
   }
   const float lse_st = finish();
@@ -443,7 +514,7 @@ __global__ __launch_bounds__(256) void bwd_gate_reduce2_kernel(const float *__re
 // Backward, step 2: dQ (query-block stationary, same tile walk as the forward).
 //   dP_ij = dO_x[i].v_j = a_x[i]*(dO[i].v_j) + dz[i]*(gate_w_x.v_j)
 // =============================================================================================
-template <typename T, int D>
+template <typename T, int D, bool FAR>
 __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 : 1))) void bwd_dq_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                             const T *__restrict__ V,
                                                             const int *__restrict__ valid_len,
@@ -535,8 +606,41 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 
 
   {
     const int J_win = first_window_block(I, b, p.w, J_first);
-    for (int J = J_first; J < J_win; ++J)
-      if (st_block_reach(p, I, J)) tile(J, true);
+    if constexpr (FAR) {
+      const float *wx = gate_w + (size_t)h * 2 * D + D;
+      if (active)
+        far_keys_of_row(p, i, p0, J_win * b, phase, nph, [&](int j) {
+          const T *kp = Kh + (size_t)j * D, *vp = Vh + (size_t)j * D;
+          float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f}, g4[4] = {0.0f, 0.0f, 0.0f, 0.0f}, w4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+          for (int c = 0; c < D; c += 4) {
+            float kx[4], vx[4];
+            load4(kp + c, kx);
+            load4(vp + c, vx);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) {
+              s4[e] = fmaf(q[c + e], kx[e], s4[e]);
+              g4[e] = fmaf(g[c + e], vx[e], g4[e]);
+              w4[e] = fmaf(wx[c + e], vx[e], w4[e]);
+            }
+          }
+          const float sj = (s4[0] + s4[1]) + (s4[2] + s4[3]);
+          const float gv = (g4[0] + g4[1]) + (g4[2] + g4[3]);
+          const float wvj = (w4[0] + w4[1]) + (w4[2] + w4[3]);
+          const float pj = __expf(sj * p.scale - l_st);
+          const float dS = pj * ((1.0f - st.x) * gv + st.y * wvj - st.w);
+#pragma unroll
+          for (int c = 0; c < D; c += 4) {
+            float kx[4];
+            load4(kp + c, kx);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) dq[c + e] = fmaf(dS, kx[e], dq[c + e]);
+          }
+        });
+    } else {
+      for (int J = J_first; J < J_win; ++J)
+        if (st_block_reach(p, I, J)) tile(J, true);
+    }
     for (int J = J_win; J <= I; ++J) tile(J, true);
   }
   const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
@@ -649,7 +753,7 @@ __global__ __launch_bounds__(64 * kInvWaves) void inverse_list_kernel(const int 
 // neither the V row nor the dP product, so it runs with fewer registers and more wavefronts.
 // A lane owns one key row and one phase of the query tile.
 // =============================================================================================
-template <typename T, int D, bool WANT_DK>
+template <typename T, int D, bool WANT_DK, bool FAR>
 __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                              const T *__restrict__ V,
                                                              const int *__restrict__ valid_len,
@@ -767,8 +871,54 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     const long last_q = (long)J * b + (b - 1) + (p.w - 1);
     const int I_hi = (int)min((long)(p.NB - 1), last_q / b);
     for (int I = J; I <= I_hi; ++I) tile(I, true);
-    for (int I = I_hi + 1; I < p.NB; ++I)
-      if (st_block_reach(p, I, J)) tile(I, true);
+    if constexpr (FAR) {
+      const float *wx = gate_w + (size_t)h * 2 * D + D;
+      if (key_ok)
+        far_rows_of_key(p, j, (I_hi + 1) * b, phase, nph, [&](int i) {
+          const size_t r = (size_t)bh * p.L + i;
+          const float4 st = rowstat[r];
+          const float a_x = 1.0f - st.x;
+          const T *qp = Qh + (size_t)i * D, *gp = Gh + (size_t)i * D;
+          float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+          for (int c = 0; c < D; c += 4) {
+            float qx[4];
+            load4(qp + c, qx);
+#pragma unroll
+            for (int e = 0; e < 4; ++e) s4[e] = fmaf(qx[e], kr[c + e], s4[e]);
+          }
+          const float pj = __expf(((s4[0] + s4[1]) + (s4[2] + s4[3])) * p.scale - lse_st[r]);
+          if (want_dk) {
+            float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+#pragma unroll
+            for (int c = 0; c < D; c += 4) {
+              float gx[4];
+              load4(gp + c, gx);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) d4[e] = fmaf(a_x * gx[e] + st.y * wx[c + e], vr[c + e], d4[e]);
+            }
+            const float dS = pj * (((d4[0] + d4[1]) + (d4[2] + d4[3])) - st.w);
+#pragma unroll
+            for (int c = 0; c < D; c += 4) {
+              float qx[4];
+              load4(qp + c, qx);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[c + e] = fmaf(dS, qx[e], acc[c + e]);
+            }
+          } else {
+#pragma unroll
+            for (int c = 0; c < D; c += 4) {
+              float gx[4];
+              load4(gp + c, gx);
+#pragma unroll
+              for (int e = 0; e < 4; ++e) acc[c + e] = fmaf(pj, a_x * gx[e] + st.y * wx[c + e], acc[c + e]);
+            }
+          }
+        });
+    } else {
+      for (int I = I_hi + 1; I < p.NB; ++I)
+        if (st_block_reach(p, I, J)) tile(I, true);
+    }
   }
   // long-term branch: query blocks that selected this key block
   {
@@ -796,10 +946,14 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
 template <typename T, int D>
 static void launch_fwd_t(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
-  hipLaunchKernelGGL((fwd_generic_kernel<T, D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
-                     3 * (size_t)p.b * (D + 1) * sizeof(float), st,
-                     (const T *)a.Q, (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w,
-                     a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
+  auto go = [&](auto kernel) {
+    hipLaunchKernelGGL(kernel, dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
+                       3 * (size_t)p.b * (D + 1) * sizeof(float), st,
+                       (const T *)a.Q, (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w,
+                       a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st, a.lse_lt, a.lse_st, a.dense, p);
+  };
+  if (far_by_rows(p) && !a.dense) go(fwd_generic_kernel<T, D, true>);
+  else go(fwd_generic_kernel<T, D, false>);
 }
 
 void launch_fwd_generic(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st)
@@ -874,20 +1028,30 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     launch_bwd_mfma(p, a, w, stages, st);
     return;
   }
-  if (stages & kBwdStageDQ)
-    hipLaunchKernelGGL((bwd_dq_generic_kernel<T, D>), dim3(BH * p.NB), dim3(64),
-                       2 * (size_t)p.b * (D + 1) * sizeof(float), st, (const T *)a.Q,
-                       (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st,
-                       (const T *)a.dO, w.rowstat, (T *)a.dQ, p);
-  if (stages & kBwdStageDKV)
-  {
-    const size_t lds = 2 * (size_t)p.b * (D + 1) * sizeof(float);
-    hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D, false>), dim3(BH * p.NB), dim3(64), lds, st, (const T *)a.Q,
-                       (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
-                       (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
-    hipLaunchKernelGGL((bwd_dkv_generic_kernel<T, D, true>), dim3(BH * p.NB), dim3(64), lds, st, (const T *)a.Q,
-                       (const T *)a.K, (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st,
-                       (const T *)a.dO, w.rowstat, w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
+  const size_t lds = 2 * (size_t)p.b * (D + 1) * sizeof(float);  // two tiles of b rows
+  const bool far = far_by_rows(p);
+  if (stages & kBwdStageDQ) {
+    auto go = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, dim3(BH * p.NB), dim3(64), lds, st, (const T *)a.Q, (const T *)a.K,
+                         (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO,
+                         w.rowstat, (T *)a.dQ, p);
+    };
+    if (far) go(bwd_dq_generic_kernel<T, D, true>);
+    else go(bwd_dq_generic_kernel<T, D, false>);
+  }
+  if (stages & kBwdStageDKV) {
+    auto go = [&](auto kernel) {
+      hipLaunchKernelGGL(kernel, dim3(BH * p.NB), dim3(64), lds, st, (const T *)a.Q, (const T *)a.K,
+                         (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO, w.rowstat,
+                         w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
+    };
+    if (far) {
+      go(bwd_dkv_generic_kernel<T, D, false, true>);
+      go(bwd_dkv_generic_kernel<T, D, true, true>);
+    } else {
+      go(bwd_dkv_generic_kernel<T, D, false, false>);
+      go(bwd_dkv_generic_kernel<T, D, true, false>);
+    }
   }
 }
 
