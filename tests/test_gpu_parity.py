@@ -222,6 +222,9 @@ def test_seeded_random_shapes():
     ("bf16", 64, 64, 64, 5, 577),    # short window: few-key rows in the band tiles
     ("bf16", 64, 32, 32, 1, 1024),   # no ragged tail: the last block term covers a whole tile
     ("bf16", 64, 64, 32, 70, 700),   # bf16 d=64 with a mask block that is not the tile: scalar kernels
+    ("fp32", 32, 16, 4, 1, 131),     # window 1 and a short last block: last-block keys lie below the window tiles
+    ("fp32", 8, 16, 3, 2, 100),      # mask block that is no power of two and does not divide the tile
+    ("bf16", 16, 64, 1, 8, 1000),    # mask block 1 under a 64-row tile: 10 gathered runs per row
 ])
 def test_full_short_term_mask(dtype, d, b, sblk, window, L):
     # stis_mode 1: window + whole blocks at power-of-two block distances + last block (Eq. 15, causal)
