@@ -749,11 +749,12 @@ __global__ __launch_bounds__(64 * kInvWaves) void inverse_list_kernel(const int 
 }
 
 // =============================================================================================
-// Backward, step 4: dK / dV (key-block stationary), one launch each (WANT_DK): the dV pass needs
-// neither the V row nor the dP product, so it runs with fewer registers and more wavefronts.
+// Backward, step 4: dK / dV (key-block stationary).  MODE 0 computes dV, 1 dK, 2 both.  With
+// d >= 32 they are one launch each: the dV pass needs neither the V row nor the dP product, so it
+// runs with fewer registers and more wavefronts; with small d one pass holds both.
 // A lane owns one key row and one phase of the query tile.
 // =============================================================================================
-template <typename T, int D, bool WANT_DK, bool FAR>
+template <typename T, int D, int MODE, bool FAR>
 __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                              const T *__restrict__ V,
                                                              const int *__restrict__ valid_len,
@@ -780,7 +781,7 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
   const int phase = lane / b;
   const int bh = blockIdx.x / p.NB;
   const int J = (int)(blockIdx.x % p.NB);
-  constexpr bool want_dk = WANT_DK;
+  constexpr bool want_dk = MODE != 0, want_dv = MODE != 1;
   const int h = bh % p.H;
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
@@ -788,13 +789,16 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
   const bool in_range = j < p.L;
   const bool key_ok = in_range && j >= p0;
   const size_t head = (size_t)bh * p.L * D;
-  T *out = (want_dk ? dK : dV) + head + (size_t)j * D;
+  const size_t outoff = head + (size_t)j * D;
 
-  float acc[D];
+  float acck[D], accv[D];
 #pragma unroll
-  for (int c = 0; c < D; ++c) acc[c] = 0.0f;
+  for (int c = 0; c < D; ++c) { acck[c] = 0.0f; accv[c] = 0.0f; }
   if (min((J + 1) * b, p.L) <= p0) {  // no valid key in the block
-    if (phase == 0 && in_range) store_row<T, D>(out, acc);
+    if (phase == 0 && in_range) {
+      if (want_dk) store_row<T, D>(dK + outoff, acck);
+      if (want_dv) store_row<T, D>(dV + outoff, accv);
+    }
     return;
   }
   float kr[D], vr[D];
@@ -856,10 +860,11 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
           const float dP = (d4[0] + d4[1]) + (d4[2] + d4[3]);
           const float dS = pj * (dP - Dx_s[ii]);
 #pragma unroll
-          for (int c = 0; c < D; ++c) acc[c] = fmaf(dS, Qs[ii][c], acc[c]);
-        } else {
+          for (int c = 0; c < D; ++c) acck[c] = fmaf(dS, Qs[ii][c], acck[c]);
+        }
+        if (want_dv) {
 #pragma unroll
-          for (int c = 0; c < D; ++c) acc[c] = fmaf(pj, Gs[ii][c], acc[c]);
+          for (int c = 0; c < D; ++c) accv[c] = fmaf(pj, Gs[ii][c], accv[c]);
         }
       }
     }
@@ -888,30 +893,26 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
             for (int e = 0; e < 4; ++e) s4[e] = fmaf(qx[e], kr[c + e], s4[e]);
           }
           const float pj = __expf(((s4[0] + s4[1]) + (s4[2] + s4[3])) * p.scale - lse_st[r]);
-          if (want_dk) {
-            float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
+          float d4[4] = {0.0f, 0.0f, 0.0f, 0.0f};
 #pragma unroll
-            for (int c = 0; c < D; c += 4) {
-              float gx[4];
-              load4(gp + c, gx);
+          for (int c = 0; c < D; c += 4) {
+            float gx[4];
+            load4(gp + c, gx);
 #pragma unroll
-              for (int e = 0; e < 4; ++e) d4[e] = fmaf(a_x * gx[e] + st.y * wx[c + e], vr[c + e], d4[e]);
+            for (int e = 0; e < 4; ++e) {
+              const float gxe = a_x * gx[e] + st.y * wx[c + e];  // dO_st
+              if (want_dk) d4[e] = fmaf(gxe, vr[c + e], d4[e]);
+              if (want_dv) accv[c + e] = fmaf(pj, gxe, accv[c + e]);
             }
+          }
+          if (want_dk) {
             const float dS = pj * (((d4[0] + d4[1]) + (d4[2] + d4[3])) - st.w);
 #pragma unroll
             for (int c = 0; c < D; c += 4) {
               float qx[4];
               load4(qp + c, qx);
 #pragma unroll
-              for (int e = 0; e < 4; ++e) acc[c + e] = fmaf(dS, qx[e], acc[c + e]);
-            }
-          } else {
-#pragma unroll
-            for (int c = 0; c < D; c += 4) {
-              float gx[4];
-              load4(gp + c, gx);
-#pragma unroll
-              for (int e = 0; e < 4; ++e) acc[c + e] = fmaf(pj, a_x * gx[e] + st.y * wx[c + e], acc[c + e]);
+              for (int e = 0; e < 4; ++e) acck[c + e] = fmaf(dS, qx[e], acck[c + e]);
             }
           }
         });
@@ -929,14 +930,18 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
   }
   for (int off = b; off < 64; off <<= 1) {
 #pragma unroll
-    for (int c = 0; c < D; ++c) acc[c] += __shfl_xor(acc[c], off);
+    for (int c = 0; c < D; ++c) {
+      if (want_dk) acck[c] += __shfl_xor(acck[c], off);
+      if (want_dv) accv[c] += __shfl_xor(accv[c], off);
+    }
   }
   if (phase == 0 && in_range) {
     if (want_dk) {
 #pragma unroll
-      for (int c = 0; c < D; ++c) acc[c] *= p.scale;
+      for (int c = 0; c < D; ++c) acck[c] *= p.scale;
+      store_row<T, D>(dK + outoff, acck);
     }
-    store_row<T, D>(out, acc);
+    if (want_dv) store_row<T, D>(dV + outoff, accv);
   }
 }
 
@@ -1045,12 +1050,17 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
                          (const T *)a.V, a.valid_len, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO, w.rowstat,
                          w.offs, w.items, (T *)a.dK, (T *)a.dV, p);
     };
-    if (far) {
-      go(bwd_dkv_generic_kernel<T, D, false, true>);
-      go(bwd_dkv_generic_kernel<T, D, true, true>);
+    if constexpr (D <= 16) {
+      if (far) go(bwd_dkv_generic_kernel<T, D, 2, true>);
+      else go(bwd_dkv_generic_kernel<T, D, 2, false>);
     } else {
-      go(bwd_dkv_generic_kernel<T, D, false, false>);
-      go(bwd_dkv_generic_kernel<T, D, true, false>);
+      if (far) {
+        go(bwd_dkv_generic_kernel<T, D, 0, true>);
+        go(bwd_dkv_generic_kernel<T, D, 1, true>);
+      } else {
+        go(bwd_dkv_generic_kernel<T, D, 0, false>);
+        go(bwd_dkv_generic_kernel<T, D, 1, false>);
+      }
     }
   }
 }
