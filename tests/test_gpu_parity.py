@@ -241,6 +241,7 @@ def test_full_short_term_mask(dtype, d, b, sblk, window, L):
     ("cfg3", dict(B=3, L=32 * 9 + 11, len_lo=40, len_hi=32 * 9 + 11)),          # matrix cores, ragged last block
     ("cfg4", dict(B=2, H=2, L=64 * 6, len_lo=100, len_hi=64 * 6)),              # matrix cores, b = 64
     ("cfg4", dict(B=2, H=2, L=64 * 5 + 3, len_lo=64 * 5 + 3, len_hi=64 * 5 + 3, stis_block=64)),
+    ("cfg2", dict(B=5, H=8, d=8, L=197, len_lo=30, len_hi=197, topk=4, window=8, stis_block=1)),  # the paper's setting
 ])
 def test_serving_mode_last_block_only(name, shape):
     # last_block_only: selection row and output rows of the last query block equal the full run's, and
