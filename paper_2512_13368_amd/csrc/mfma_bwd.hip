@@ -168,6 +168,36 @@ __device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x
     }
 }
 
+// The same rows through LDS: the wavefront's 32 rows (this lane: row lane%32, channels
+// 32*mb + 8*g + 4*(lane/32) + e in acc[mb][4*g + e]) are written into its own 4 KB of staging rows
+// (free once the walk is over; chunks XOR-swizzled against bank conflicts) and leave as whole
+// 128-byte rows, 8 rows per store instruction.  Rows that are not kept are stored as zeros, rows
+// at or past rows_left not at all.
+__device__ __forceinline__ void store_rows_bf16(uint16_t *dst_row0, int rows_left, uint16_t *pt, const f32x16 (&acc)[2],
+                                                float scale, bool keep)
+{
+  int el;  // the lane id, rebuilt here so that none of the addressing below is computed ahead of the walk
+  asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(el));
+  const int elq = el & 31, elh = el >> 5;
+  const float sc = keep ? scale : 0.0f;
+#pragma unroll
+  for (int mb = 0; mb < 2; ++mb)
+#pragma unroll
+    for (int g = 0; g < 4; ++g) {
+      uint2 pk;
+      pk.x = (uint32_t)f32_to_bf16(acc[mb][4 * g] * sc) | ((uint32_t)f32_to_bf16(acc[mb][4 * g + 1] * sc) << 16);
+      pk.y = (uint32_t)f32_to_bf16(acc[mb][4 * g + 2] * sc) | ((uint32_t)f32_to_bf16(acc[mb][4 * g + 3] * sc) << 16);
+      const int chunk = 4 * mb + g;  // 16-byte chunk of the row; this lane fills half elh of it
+      *reinterpret_cast<uint2 *>(pt + elq * D + ((chunk ^ (elq & 7)) * 8) + 4 * elh) = pk;
+    }
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int rr = 8 * i + (el >> 3), c = el & 7;
+    const uint4 v = *reinterpret_cast<const uint4 *>(pt + rr * D + ((c ^ (rr & 7)) * 8));
+    if (rr < rows_left) *reinterpret_cast<uint4 *>(dst_row0 + (size_t)rr * D + 8 * c) = v;
+  }
+}
+
 constexpr int kFewKeys = 32;    // rows seeing fewer keys than this get two-term bf16 operands
 
 // ones[.][0..2] in the half of the wavefront that holds contraction slots 0..7: multiplied with a
@@ -439,7 +469,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     step(t, Ks1, Vs1, Ks0, Vs0);
     if (t + 1 < n_all) step(t + 1, Ks0, Vs0, Ks1, Vs1);
   }
-  if (iq < p.L) store_row_bf16(dQ + rowoff, lh, dq, p.scale, q_ok);
+  {  // (every wavefront is past the last barrier of the walk: the staging rows are free)
+    const int row0 = I * BLK + 32 * wv;
+    store_rows_bf16(dQ + head + (size_t)row0 * D, p.L - row0, Ks0 + wv * 32 * D, dq, p.scale, q_ok);
+  }
 }
 
 // =============================================================================================
@@ -716,9 +749,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     if ((ent >> kInvFewShift) != 0) residual_pass(ent & kInvBlockMask, false);
   }
 
-  if (j < p.L) {
-    store_row_bf16(dK + rowoff, lh, dk, p.scale, key_ok);
-    store_row_bf16(dV + rowoff, lh, dv, 1.0f, key_ok);
+  {  // (every wavefront is past the last barrier of the walk: the staging rows are free)
+    const int row0 = J * BLK + 32 * wv;
+    store_rows_bf16(dK + head + (size_t)row0 * D, p.L - row0, Qs0 + wv * 32 * D, dk, p.scale, key_ok);
+    store_rows_bf16(dV + head + (size_t)row0 * D, p.L - row0, Gs0 + wv * 32 * D, dv, 1.0f, key_ok);
   }
 }
 
