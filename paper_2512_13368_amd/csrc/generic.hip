@@ -6,6 +6,10 @@
 // one "phase" of the key (or query) tile: with block size b there are 64/b phases, each
 // walking every (64/b)-th row of a tile staged in LDS with its own online-softmax state;
 // the phases are merged with wavefront shuffles at the end.  All accumulation is fp32.
+// The head dimension (8, 16, 32, 64) is a template parameter; the LDS tiles hold b rows and are
+// sized at launch.  With the full short-term mask of Eq. 15 and a mask block smaller than b, the
+// far keys of each row (power-of-two distances, last block) are read straight from memory by the
+// row's own lanes instead of being walked tile by tile.
 #include "common.h"
 #include "launch.h"
 #include "mfma_common.h"
