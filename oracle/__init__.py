@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_num_threads.restype = _c_int
         L.oracle_select_blocks.restype = _c_int
         L.oracle_select_blocks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
+        L.oracle_select_blocks_cmp.restype = _c_int
+        L.oracle_select_blocks_cmp.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
         L.oracle_build_masks.restype = _c_int
         L.oracle_build_masks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp]
         L.oracle_masked_attention.restype = _c_int
@@ -103,6 +105,25 @@ def select_blocks(Q, K, valid_len, block, topk, bh_list=None, want_scores=False)
     rc = lib().oracle_select_blocks(B, H, L, d, block, topk, _p(Q), _p(K), _p(vl), _p(bh), n_bh,
                                     _p(sel), _p(scores))
     _check(rc, "select_blocks")
+    return (sel, scores) if want_scores else sel
+
+
+def select_blocks_cmp(Q, Kcmp, valid_len, block, topk, bh_list=None, want_scores=False):
+    """Steps 2-3 with caller-supplied compressed keys (Eq. 9 with the caller's phi): Q [B,H,L,d],
+    Kcmp [B,H,NB,d] float32.  Same returns as select_blocks."""
+    Q = _in(Q, False)
+    Kcmp = _in(Kcmp, False)
+    B, H, L, d = Q.shape
+    NB = -(-L // block)
+    assert Kcmp.shape == (B, H, NB, d)
+    vl = np.ascontiguousarray(valid_len, dtype=np.int32)
+    assert vl.shape == (B,)
+    bh, n_bh = _bh(bh_list, B, H)
+    sel = np.full((B, H, NB, topk), -2, dtype=np.int32)
+    scores = np.zeros((n_bh, NB, NB), dtype=np.float32) if want_scores else None
+    rc = lib().oracle_select_blocks_cmp(B, H, L, d, block, topk, _p(Q), _p(Kcmp), _p(vl), _p(bh), n_bh,
+                                        _p(sel), _p(scores))
+    _check(rc, "select_blocks_cmp")
     return (sel, scores) if want_scores else sel
 
 

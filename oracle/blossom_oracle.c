@@ -76,7 +76,9 @@ int oracle_num_threads(void)
 /* ------------------------------------------------------------------------- */
 /* Steps 1-3: pooling, scoring, top-k (fp32 canonical recipe), one (row, head) */
 /* ------------------------------------------------------------------------- */
-static int select_one(int L, int d, int b, int k, const float *q, const float *key,
+/* kcmp (optional, [NB*d]): compressed keys phi(K_J) supplied by the caller (Eq. 9 with a learnable
+ * phi); when given they take the place of the block means and `key` is not read. */
+static int select_one(int L, int d, int b, int k, const float *q, const float *key, const float *kcmp,
                       int n_valid, int32_t *sel /* [NB*k] */, float *scores /* [NB*NB] or NULL */)
 {
     const int NB = n_blocks(L, b);
@@ -97,11 +99,11 @@ static int select_one(int L, int d, int b, int k, const float *q, const float *k
             for (int t = lo; t < hi; ++t) {
                 if (t < p0) continue;
                 aq = aq + q[(size_t)t * d + c];
-                ak = ak + key[(size_t)t * d + c];
+                if (!kcmp) ak = ak + key[(size_t)t * d + c];
                 ++cnt;
             }
             qsum[(size_t)I * d + c] = aq;
-            kmean[(size_t)I * d + c] = cnt > 0 ? ak / (float)cnt : 0.0f;
+            kmean[(size_t)I * d + c] = kcmp ? kcmp[(size_t)I * d + c] : (cnt > 0 ? ak / (float)cnt : 0.0f);
         }
     }
     if (scores)
@@ -147,10 +149,10 @@ static int select_one(int L, int d, int b, int k, const float *q, const float *k
  * listed pairs are written.  scores (optional) is [n_bh, NB, NB], entry
  * [I][J] valid for J_first <= J < I.
  */
-int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
-                         const float *Q, const float *K, const int32_t *valid_len,
-                         const int32_t *bh_list, int n_bh,
-                         int32_t *sel, float *scores)
+static int select_blocks_impl(int B, int H, int L, int d, int b, int k,
+                              const float *Q, const float *K, const float *Kcmp, const int32_t *valid_len,
+                              const int32_t *bh_list, int n_bh,
+                              int32_t *sel, float *scores)
 {
     if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || k < 1) return -2;
     const int NB = n_blocks(L, b);
@@ -164,7 +166,7 @@ int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
         if (n < 0) n = 0;
         if (n > L) n = L;
         const size_t off = (size_t)bh * L * d;
-        int rc = select_one(L, d, b, k, Q + off, K + off, n,
+        int rc = select_one(L, d, b, k, Q + off, K ? K + off : NULL, Kcmp ? Kcmp + (size_t)bh * NB * d : NULL, n,
                             sel + (size_t)bh * NB * k,
                             scores ? scores + (size_t)it * NB * NB : NULL);
         if (rc) {
@@ -173,6 +175,24 @@ int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
         }
     }
     return err;
+}
+
+int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
+                         const float *Q, const float *K, const int32_t *valid_len,
+                         const int32_t *bh_list, int n_bh,
+                         int32_t *sel, float *scores)
+{
+    return select_blocks_impl(B, H, L, d, b, k, Q, K, NULL, valid_len, bh_list, n_bh, sel, scores);
+}
+
+/* The same with caller-supplied compressed keys Kcmp [B,H,NB,d] (Eq. 9: phi is the caller's). */
+int oracle_select_blocks_cmp(int B, int H, int L, int d, int b, int k,
+                             const float *Q, const float *Kcmp, const int32_t *valid_len,
+                             const int32_t *bh_list, int n_bh,
+                             int32_t *sel, float *scores)
+{
+    if (!Kcmp) return -2;
+    return select_blocks_impl(B, H, L, d, b, k, Q, NULL, Kcmp, valid_len, bh_list, n_bh, sel, scores);
 }
 
 /* ------------------------------------------------------------------------- */

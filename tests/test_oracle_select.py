@@ -191,3 +191,80 @@ def test_edge_lengths(oracle):
     selk = oracle.select_blocks(x.Q, x.K, vl, w.block, 12)
     for I in range(w.NB):
         np.testing.assert_array_equal(selk[2, 0, I, :I + 1], np.arange(I + 1))
+
+
+# ---- caller-supplied compressed keys (Eq. 9 with the caller's phi) ---------------------------------
+
+def test_compressed_keys_hand_case(oracle):
+    # 4 blocks of 2 positions, d = 2, all valid.  Query sums per block: (2,0), (0,2), (2,2), (1,0).
+    # Compressed keys: phi_0 = (1,0), phi_1 = (0,3), phi_2 = (5,5) (never a candidate of an earlier block).
+    # Block 2 scores: 2*1 + 2*0 = 2 against block 0, 2*0 + 2*3 = 6 against block 1 -> picks 1.
+    # Block 3 scores: 1, 0, 5 -> picks 2; with k = 3 also 0.
+    L, d, b = 8, 2, 2
+    Q = np.zeros((1, 1, L, d), np.float32)
+    Q[0, 0, 0:2] = [1, 0]
+    Q[0, 0, 2:4] = [0, 1]
+    Q[0, 0, 4:6] = [1, 1]
+    Q[0, 0, 6] = [1, 0]
+    Kc = np.array([[[[1, 0], [0, 3], [5, 5], [9, 9]]]], np.float32)
+    vl = np.array([L], np.int32)
+    sel, sc = oracle.select_blocks_cmp(Q, Kc, vl, b, 2, want_scores=True)
+    np.testing.assert_array_equal(sel[0, 0], [[0, -1], [0, 1], [1, 2], [2, 3]])
+    np.testing.assert_array_equal(sc[0, 2, :2], [2.0, 6.0])
+    np.testing.assert_array_equal(sc[0, 3, :3], [1.0, 0.0, 5.0])
+    sel3 = oracle.select_blocks_cmp(Q, Kc, vl, b, 3)
+    np.testing.assert_array_equal(sel3[0, 0], [[0, -1, -1], [0, 1, -1], [0, 1, 2], [0, 2, 3]])
+
+
+def test_compressed_keys_equal_to_block_means_give_the_same_selection(oracle):
+    # phi = mean over the block's valid keys, accumulated here in fp32 in ascending position
+    # (np.float32 scalars round after every operation): the two entry points must then agree exactly
+    w = with_shape(WORKLOADS["cfg1"], B=3, H=2, L=83, block=8, topk=3, seed=77)
+    x = make_inputs(w)
+    B, H, L, d = x.Q.shape
+    NB = w.NB
+    Kc = np.zeros((B, H, NB, d), np.float32)
+    for r in range(B):
+        p0 = L - int(x.valid_len[r])
+        for h in range(H):
+            for J in range(NB):
+                acc = np.zeros(d, np.float32)
+                cnt = 0
+                for t in range(max(J * w.block, p0), min((J + 1) * w.block, L)):
+                    acc = (acc + x.K[r, h, t].astype(np.float32)).astype(np.float32)
+                    cnt += 1
+                if cnt:
+                    Kc[r, h, J] = acc / np.float32(cnt)
+    np.testing.assert_array_equal(oracle.select_blocks_cmp(x.Q, Kc, x.valid_len, w.block, w.topk),
+                                  oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk))
+
+
+def test_compressed_keys_brute_force(oracle):
+    # float64 scores from the definition; the chosen past blocks must be a best subset of their size
+    rng = np.random.default_rng(5)
+    B, H, L, d, b, k = 2, 2, 37, 6, 5, 3
+    NB = -(-L // b)
+    Q = rng.standard_normal((B, H, L, d)).astype(np.float32)
+    Kc = rng.standard_normal((B, H, NB, d)).astype(np.float32)
+    vl = np.array([L, 22], np.int32)
+    sel = oracle.select_blocks_cmp(Q, Kc, vl, b, k)
+    for r in range(B):
+        p0 = L - int(vl[r])
+        J_first = p0 // b
+        for h in range(H):
+            for I in range(NB):
+                lo, hi = max(I * b, p0), min((I + 1) * b, L)
+                if hi <= p0:
+                    assert (sel[r, h, I] == -1).all()
+                    continue
+                qsum = Q[r, h, lo:hi].astype(np.float64).sum(0)
+                cand = list(range(J_first, I))
+                sc = {J: float(qsum @ Kc[r, h, J].astype(np.float64)) for J in cand}
+                got = [int(J) for J in sel[r, h, I] if J >= 0]
+                assert got[-1] == I and got == sorted(got)
+                past = got[:-1]
+                assert len(past) == min(k - 1, len(cand))
+                if past:
+                    worst_in = min(sc[J] for J in past)
+                    best_out = max([sc[J] for J in cand if J not in past], default=-np.inf)
+                    assert worst_in >= best_out - 1e-5
