@@ -110,6 +110,19 @@ int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
                           void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The same selection with the block compression left to the caller (Sec. 3.4, Eq. 9: a learnable
+ * phi): Kcmp holds one compressed key phi(K_J) per key block and takes the place of Kmean_J in
+ * the score above, converted to fp32 as it is (rows of blocks before J_first are not read as
+ * candidates).  Everything else (query sums, score recipe, ranking, output) is unchanged.
+ *   Q           in   [B,H,L,d]
+ *   Kcmp        in   [B,H,NB,d], element type and alignment as Q
+ *   valid_len, sel, ws as above (same workspace size)
+ */
+int blossom_select_blocks_cmp(const blossom_params *p, const void *Q, const void *Kcmp,
+                              const int32_t *valid_len, int32_t *sel,
+                              void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Fused forward (Eq. 1 under the two masks, Eq. 16-19).  For every valid query i of block I:
  *   o_lt[i] = softmax over { j : block(j) in sel[I], j <= i, j valid } of scale*q_i.k_j, times V
  *   o_st[i] = softmax over { j : 0 <= i-j < window, j valid } of the same logits, times V

@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libblossom.so")
 F32, BF16 = 0, 1
 WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
-EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_attn_fwd", "blossom_attn_bwd",
+EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_cmp", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_strerror", "blossom_version")
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
 
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.blossom_workspace_bytes.argtypes = [pp, ctypes.c_int]
         L.blossom_select_blocks.restype = ctypes.c_int
         L.blossom_select_blocks.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
+        L.blossom_select_blocks_cmp.restype = ctypes.c_int
+        L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
         L.blossom_attn_fwd.argtypes = [pp, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, vp, fp, fp, vp,
                                        ctypes.c_size_t, vp]
@@ -159,6 +161,24 @@ def select_blocks(p: Params, Q, K, valid_len, sel=None, ws=None, stream=None):
                                      _ptr(ws), nbytes, _stream(stream))
     if rc:
         raise BlossomError(rc, "blossom_select_blocks")
+    return sel
+
+
+def select_blocks_cmp(p: Params, Q, Kcmp, valid_len, sel=None, ws=None, stream=None):
+    """blossom_select_blocks_cmp: Kcmp [B,H,NB,d] holds the caller's compressed keys."""
+    import torch
+    _check_tensor(Q, (p.B, p.H, p.L, p.d), _torch_dtype(p), "Q")
+    _check_tensor(Kcmp, (p.B, p.H, p.NB, p.d), _torch_dtype(p), "Kcmp")
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    if sel is None:
+        sel = torch.empty((p.B, p.H, p.NB, p.topk), dtype=torch.int32, device=Q.device)
+    _check_tensor(sel, (p.B, p.H, p.NB, p.topk), torch.int32, "sel")
+    ws, nbytes = _workspace(p, WS_SELECT, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_select_blocks_cmp(ctypes.byref(cp), _ptr(Q), _ptr(Kcmp), _ptr(valid_len), _ptr(sel),
+                                         _ptr(ws), nbytes, _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_select_blocks_cmp")
     return sel
 
 

@@ -84,7 +84,22 @@ int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
   if (!aligned16(Q) || !aligned16(K)) return BLOSSOM_ERR_ALIGN;
   rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
   if (rc) return rc;
-  launch_select(kp, p->dtype, Q, K, valid_len, sel, ws, (hipStream_t)hip_stream);
+  launch_select(kp, p->dtype, Q, K, false, valid_len, sel, ws, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+int blossom_select_blocks_cmp(const blossom_params *p, const void *Q, const void *Kcmp,
+                              const int32_t *valid_len, int32_t *sel, void *ws, size_t ws_bytes,
+                              void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (!Q || !Kcmp || !valid_len || !sel) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(Kcmp)) return BLOSSOM_ERR_ALIGN;
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
+  if (rc) return rc;
+  launch_select(kp, p->dtype, Q, Kcmp, true, valid_len, sel, ws, (hipStream_t)hip_stream);
   return launch_status();
 }
 

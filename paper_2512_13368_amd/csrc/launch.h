@@ -38,7 +38,8 @@ struct BwdArgs {
 
 // select.hip
 size_t select_workspace_bytes(const KParams &p);
-void launch_select(const KParams &p, int dtype, const void *Q, const void *K, const int *valid_len,
+// (kcmp: K holds the caller's compressed keys [B,H,NB,d] instead of the keys themselves)
+void launch_select(const KParams &p, int dtype, const void *Q, const void *K, bool kcmp, const int *valid_len,
                    int *sel, void *ws, hipStream_t st);
 
 // Backward workspace, carved from the caller's buffer.

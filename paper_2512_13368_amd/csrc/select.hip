@@ -16,7 +16,9 @@ namespace blossom {
 // in ascending order.  qsum  [B,H,NB,d]   (unnormalised sums of Q)
 //                     kmeanT[B,H,d,NB]   (means of K, transposed so that the scoring pass
 //                                         reads consecutive blocks with consecutive lanes)
-template <typename T, int D>
+// KCMP: K holds compressed keys [B,H,NB,d] supplied by the caller (Eq. 9 with the caller's phi);
+// they are copied as they are into the transposed fp32 layout instead of being pooled.
+template <typename T, int D, bool KCMP>
 __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, const T *__restrict__ K,
                                                    const int *__restrict__ valid_len,
                                                    float *__restrict__ qsum, float *__restrict__ kmeanT,
@@ -32,6 +34,13 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, cons
   const int bh = (int)(rem / p.NB);
   const int J = (int)(rem % p.NB);
   if (!which && J < p.NB - p.nq) return;  // serving mode: only the last query block is pooled
+  if (KCMP && which) {
+    float x[4];
+    load4(K + ((size_t)bh * p.NB + J) * D + c4, x);
+#pragma unroll
+    for (int e = 0; e < 4; ++e) kmeanT[((size_t)bh * D + c4 + e) * p.NB + J] = x[e];
+    return;
+  }
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
   const int lo = max(J * p.b, p0);
@@ -131,7 +140,7 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
 
 // ---- launchers ----------------------------------------------------------------------------
 template <typename T, int D>
-static void launch_select_t(const KParams &p, const void *Q, const void *K, const int *valid_len,
+static void launch_select_t(const KParams &p, const void *Q, const void *K, bool kcmp, const int *valid_len,
                             int *sel, void *ws, hipStream_t st)
 {
   float *qsum = reinterpret_cast<float *>(ws);
@@ -139,8 +148,12 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, cons
   const long tasks = 2L * p.B * p.H * p.NB;
   const int per_wg = 256 / (D / 4);
   const unsigned grid = (unsigned)((tasks + per_wg - 1) / per_wg);
-  hipLaunchKernelGGL((pool_kernel<T, D>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
-                     valid_len, qsum, kmeanT, p);
+  if (kcmp)
+    hipLaunchKernelGGL((pool_kernel<T, D, true>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
+                       valid_len, qsum, kmeanT, p);
+  else
+    hipLaunchKernelGGL((pool_kernel<T, D, false>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
+                       valid_len, qsum, kmeanT, p);
   hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
                      (size_t)p.NB * sizeof(unsigned long long), st,
                      qsum, kmeanT, valid_len, sel, p);
@@ -148,13 +161,13 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, cons
 
 size_t select_workspace_bytes(const KParams &p) { return 2 * (size_t)p.B * p.H * p.NB * p.d * sizeof(float); }
 
-void launch_select(const KParams &p, int dtype, const void *Q, const void *K, const int *valid_len,
+void launch_select(const KParams &p, int dtype, const void *Q, const void *K, bool kcmp, const int *valid_len,
                    int *sel, void *ws, hipStream_t st)
 {
   with_head_dim(p.d, [&](auto dim) {
     constexpr int D = decltype(dim)::value;
-    if (dtype == 0) launch_select_t<float, D>(p, Q, K, valid_len, sel, ws, st);
-    else launch_select_t<bf16_t, D>(p, Q, K, valid_len, sel, ws, st);
+    if (dtype == 0) launch_select_t<float, D>(p, Q, K, kcmp, valid_len, sel, ws, st);
+    else launch_select_t<bf16_t, D>(p, Q, K, kcmp, valid_len, sel, ws, st);
   });
 }
 

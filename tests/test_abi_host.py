@@ -71,6 +71,7 @@ def test_validation_codes_select(lib):
     assert _select(lib, _p(), ws_bytes=16) == -6
     assert _select(lib, _p(), ws=24) == -5
     assert lib.blossom_select_blocks(None, None, None, None, None, None, 0, None) == -1
+    assert lib.blossom_select_blocks_cmp(None, None, None, None, None, None, 0, None) == -1
 
 
 def test_validation_codes_fwd_bwd_dense(lib):

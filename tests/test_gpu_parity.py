@@ -360,6 +360,33 @@ def test_small_head_dims(dtype, d, H, L, b, k, w, sblk):
     run_case(wl, backward=True, check_dense=True, gate_scale=0.4)
 
 
+@pytest.mark.parametrize("dtype,d,b,L,k", [
+    ("fp32", 32, 8, 203, 3),
+    ("fp32", 8, 16, 200, 4),
+    ("bf16", 64, 64, 1000, 5),
+    ("bf16", 16, 32, 417, 2),
+])
+def test_select_with_compressed_keys(dtype, d, b, L, k):
+    # blossom_select_blocks_cmp: the caller's compressed keys replace the block means (Eq. 9 with a
+    # learnable phi); bit-exact against the oracle, in both the full and the serving mode
+    w = with_shape(WORKLOADS["cfg1"], name=f"cmp-{dtype}-{d}", B=5, H=3, L=L, d=d, block=b, topk=k, dtype=dtype,
+                   len_lo=1, len_hi=L, qkv_scaled=(dtype == "bf16"), seed=4100 + d + b)
+    x = make_inputs(w)
+    rng = np.random.default_rng(w.seed + 1)
+    Kc = rng.standard_normal((w.B, w.H, w.NB, d)).astype(np.float32)
+    tdt = torch.bfloat16 if dtype == "bf16" else torch.float32
+    Kc_dev = torch.from_numpy(Kc).cuda().to(tdt)
+    Kc = Kc_dev.float().cpu().numpy()   # what the kernel sees, exactly
+    dv = Dev(x)
+    sel = B.select_blocks_cmp(params(w), dv.Q, Kc_dev, dv.vl)
+    ref = oracle.select_blocks_cmp(x.Q, Kc, x.valid_len, b, k)
+    np.testing.assert_array_equal(sel.cpu().numpy(), ref)
+    # serving mode: only the last query block's row is written, and it is the same row
+    sel_last = torch.full_like(sel, -7)
+    B.select_blocks_cmp(params(w, last_block_only=1), dv.Q, Kc_dev, dv.vl, sel=sel_last)
+    assert torch.equal(sel_last[:, :, -1], sel[:, :, -1]) and bool((sel_last[:, :, :-1] == -7).all())
+
+
 def test_forced_gate():
     w = WORKLOADS["cfg1"]
     x = make_inputs(w, want_dO=True)
