@@ -17,7 +17,8 @@ from paper_2512_13368_amd.inputs import WORKLOADS, make_inputs, with_shape
 pytestmark = pytest.mark.gpu
 
 
-def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale=None, branches_coincide=False):
+def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale=None, branches_coincide=False,
+             scale=None):
     if x is None:
         x = make_inputs(w, want_dO=True)
     if gate_scale is not None:  # stronger gate weights exercise the gate path beyond alpha ~ 0.5
@@ -29,7 +30,8 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
     print(f"case {w.name} B{w.B} H{w.H} L{w.L} d{w.d} b{w.block} k{w.topk} w{w.window} {w.dtype} "
           f"bwd={backward}", flush=True)
     dv = Dev(x)
-    p = params(w, save_for_bwd=1)
+    sc = {} if scale is None else dict(softmax_scale=scale)   # None: the default 1/sqrt(d) on both sides
+    p = params(w, save_for_bwd=1, **sc)
     sel = B.select_blocks(p, dv.Q, dv.K, dv.vl)
     f = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
     g = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO) if backward else None
@@ -43,7 +45,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
     bh = None if pairs is None else np.asarray(pairs, np.int32)
     take = (lambda t: host(t).reshape(w.B * w.H, *t.shape[2:])[bh if bh is not None else slice(None)])
     fr = oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk,
-                         w.window, bh_list=bh, stis_block=w.stis_block)
+                         w.window, scale=scale, bh_list=bh, stis_block=w.stis_block)
     assert_close(take(f.o_lt), fr.o_lt, tol, "o_lt")
     assert_close(take(f.o_st), fr.o_st, tol, "o_st")
     assert_close(take(f.O), fr.O, tol, "O")
@@ -57,13 +59,13 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
             assert float(f.o_lt[r, :, :p0].abs().max()) == 0.0 and float(f.o_st[r, :, :p0].abs().max()) == 0.0
 
     # forward without the saved tensors gives the same O
-    p0_ = params(w, save_for_bwd=0)
+    p0_ = params(w, save_for_bwd=0, **sc)
     f2 = B.attn_fwd(p0_, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
     assert torch.equal(f2.O, f.O)
 
     if backward:
         gr = oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block,
-                             w.topk, w.window, bh_list=bh, stis_block=w.stis_block)
+                             w.topk, w.window, scale=scale, bh_list=bh, stis_block=w.stis_block)
         assert_close(take(g.dQ), gr.dQ, tol, "dQ")
         assert_close(take(g.dK), gr.dK, tol, "dK")
         assert_close(take(g.dV), gr.dV, tol, "dV")
@@ -91,7 +93,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
         lse = torch.empty((w.B, w.H, w.L), dtype=torch.float32, device="cuda")
         Od, _ = B.dense_causal_fwd(p, dv.Q, dv.K, dv.V, dv.vl, lse=lse)
         torch.cuda.synchronize()
-        Or, lr = oracle.dense_causal_fwd(x.Q, x.K, x.V, x.valid_len, bh_list=bh)
+        Or, lr = oracle.dense_causal_fwd(x.Q, x.K, x.V, x.valid_len, scale=scale, bh_list=bh)
         assert_close(take(Od), Or, tol, "dense O")
         assert_close(take(lse), lr, tol, "dense lse")
     return x, sel, f, g
@@ -385,6 +387,17 @@ def test_select_with_compressed_keys(dtype, d, b, L, k):
     sel_last = torch.full_like(sel, -7)
     B.select_blocks_cmp(params(w, last_block_only=1), dv.Q, Kc_dev, dv.vl, sel=sel_last)
     assert torch.equal(sel_last[:, :, -1], sel[:, :, -1]) and bool((sel_last[:, :, :-1] == -7).all())
+
+
+@pytest.mark.parametrize("name,shape,scale", [
+    ("cfg1", dict(), 0.4),                                                   # scalar kernels, fp32
+    ("cfg3", dict(B=3, L=32 * 7 + 5, len_lo=30, len_hi=32 * 7 + 5), 0.07),   # matrix cores, b = 32
+    ("cfg4", dict(B=2, H=2, L=64 * 5 + 9, len_lo=90, len_hi=64 * 5 + 9), 0.25),  # matrix cores, b = 64, sharper than 1/sqrt(d)
+])
+def test_caller_softmax_scale(name, shape, scale):
+    # softmax_scale > 0 replaces the default 1/sqrt(d) in every kernel family, forward and backward
+    run_case(with_shape(WORKLOADS[name], name=name + "-scale", **shape), backward=True, check_dense=True,
+             gate_scale=0.4, scale=scale)
 
 
 def test_forced_gate():
