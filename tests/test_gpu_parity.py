@@ -414,6 +414,17 @@ def test_forced_gate():
     torch.cuda.synchronize()
     assert torch.equal(f1.O, f1.o_lt) and torch.equal(f0.O, f0.o_st)
     assert_close(host(fn.O), 0.5 * (host(fn.o_lt) + host(fn.o_st)), 1e-6, "gate_b = NULL")
+    # backward: a NULL bias is a zero bias, and a NULL d_gate_b is simply not written
+    fz = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, torch.zeros_like(dv.gb))
+    fN = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, None)
+    gz = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, torch.zeros_like(dv.gb), fz, dv.dO)
+    outN = B.BwdOut(torch.empty_like(gz.dQ), torch.empty_like(gz.dK), torch.empty_like(gz.dV),
+                    torch.empty_like(gz.d_gate_w), None)
+    gN = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, None, fN, dv.dO, out=outN)
+    torch.cuda.synchronize()
+    assert torch.equal(fz.O, fN.O)
+    for a, b_ in ((gz.dQ, gN.dQ), (gz.dK, gN.dK), (gz.dV, gN.dV), (gz.d_gate_w, gN.d_gate_w)):
+        assert torch.equal(a, b_)
 
 
 def test_selection_only_large_and_invariances():
