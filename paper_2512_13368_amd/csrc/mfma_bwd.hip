@@ -171,8 +171,8 @@ __device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x
 // The same rows through LDS: the wavefront's 32 rows (this lane: row lane%32, channels
 // 32*mb + 8*g + 4*(lane/32) + e in acc[mb][4*g + e]) are written into its own 4 KB of staging rows
 // (free once the walk is over; chunks XOR-swizzled against bank conflicts) and leave as whole
-// 128-byte rows, 8 rows per store instruction.  Rows that are not kept are stored as zeros, rows
-// at or past rows_left not at all.
+// 128-byte rows, 8 rows per store instruction, non-temporal (nothing in this library reads the
+// gradients back).  Rows that are not kept are stored as zeros, rows at or past rows_left not at all.
 __device__ __forceinline__ void store_rows_bf16(uint16_t *dst_row0, int rows_left, uint16_t *pt, const f32x16 (&acc)[2],
                                                 float scale, bool keep)
 {
@@ -194,7 +194,9 @@ __device__ __forceinline__ void store_rows_bf16(uint16_t *dst_row0, int rows_lef
   for (int i = 0; i < 4; ++i) {
     const int rr = 8 * i + (el >> 3), c = el & 7;
     const uint4 v = *reinterpret_cast<const uint4 *>(pt + rr * D + ((c ^ (rr & 7)) * 8));
-    if (rr < rows_left) *reinterpret_cast<uint4 *>(dst_row0 + (size_t)rr * D + 8 * c) = v;
+    typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+    const u32x4_t vv = {v.x, v.y, v.z, v.w};
+    if (rr < rows_left) __builtin_nontemporal_store(vv, reinterpret_cast<u32x4_t *>(dst_row0 + (size_t)rr * D + 8 * c));
   }
 }
 
