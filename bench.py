@@ -28,8 +28,8 @@ import numpy as np
 # counters read for a plain copy of known size (FETCH_SIZE x2.000, WRITE_SIZE x1.000); the commands and the
 # raw readings are in profiles/cfg4_hbm_traffic.txt.  Other workloads: not measured (null).
 MEASURED_TRAFFIC_BYTES = {
-    ("cfg4", "fwd"): 561184213, ("cfg4", "fwd_saving_for_bwd"): 1110098132, ("cfg4", "bwd_gate"): 1006326904,
-    ("cfg4", "bwd_dq"): 932524748, ("cfg4", "bwd_dkv"): 1144832325, ("cfg4", "select"): 276987423,
+    ("cfg4", "fwd"): 562362246, ("cfg4", "fwd_saving_for_bwd"): 1113369366, ("cfg4", "bwd_gate"): 1006265795,
+    ("cfg4", "bwd_dq"): 916631857, ("cfg4", "bwd_dkv"): 1078798472, ("cfg4", "select"): 276989981,
 }
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
