@@ -58,7 +58,7 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >>
 
 // EQ15: the short-term mask is all of Eq. 15 with mask block BLK (compile-time, so that the plain
 // causal window compiles to exactly the code it had without it)
-template <int BLK, bool EQ15>
+template <int BLK, bool EQ15, bool SUB>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 32 ? 3 : 2, BLK == 32 ? 3 : 2))) void fwd_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const int *__restrict__ sel, const float *__restrict__ gate_w,
@@ -149,8 +149,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
 
   // window blocks J_lo..I come first in the walk; they depend on the valid length only
   const int J_first = p0 / BLK;
-  // With the full short-term mask (Eq. 15, mask block = BLK) the blocks I - 2^r below the window
-  // range follow: r = r0 .. r0 + n_pow - 1.
+  // With the full short-term mask (Eq. 15) the blocks I - 2^r below the window range follow:
+  // r = r0 .. r0 + n_pow - 1.  The mask block is BLK or a power of two below it (`sub`): then the
+  // mask-block distances 2^r below one tile reach into block I - 1, which joins the window range,
+  // the larger ones land on the same blocks I - 2^r' (at the row's own offset), and every
+  // short-term tile is masked element by element with the three cases of Eq. 15.
+  constexpr bool sub = EQ15 && SUB;  // (compile-time: the mask block = BLK variant keeps its code and registers)
+  const int sub_sh = sub ? __builtin_ctz((unsigned)p.sblk) : 0;
   int J_lo, n_win, n_st, r0 = 0;
   if (dense) {
     J_lo = J_first;
@@ -159,6 +164,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
   } else {
     const int lowpos = I * BLK - (p.w - 1);
     J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
+    if (sub) J_lo = min(J_lo, I - 1);
     J_lo = max(J_lo, J_first);
     n_win = I - J_lo + 1;
     n_st = n_win;
@@ -352,6 +358,21 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
     const int base = J * BLK + 32 * wv + 4 * lh;
     const unsigned span = (unsigned)(q - lo);  // wraps to huge when q < lo: handled by `any`
     const bool any = q >= lo;
+    if (EQ15 && sub && windowed) {
+      // window range as above, or (valid, causal and) a power-of-two mask-block distance, or a last-block key
+      const unsigned cspan = (unsigned)(q - p0);
+      const bool cany = q >= p0;
+      const int qmb = q >> sub_sh;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int key = base + 8 * (i >> 2) + (i & 3);
+        const int x = qmb - (key >> sub_sh);
+        const bool far = cany & ((unsigned)(key - p0) <= cspan) & ((x > 0 && (x & (x - 1)) == 0) | (key >= p.last_lo));
+        const bool vis = (any & ((unsigned)(key - lo) <= span)) | far;
+        s[i] = vis ? s[i] : kNegInf;
+      }
+      return;
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) {
       const int key = base + 8 * (i >> 2) + (i & 3);
@@ -440,7 +461,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
   auto tile = [&](const uint16_t *ks, const uint16_t *vs, int J, bool short_term, bool last) __attribute__((always_inline)) {
     const bool hp = (short_term ? hp_st : hp_lt) != 0;
     // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
-    const bool windowed = short_term && !(EQ15 && is_pow2(I - J));
+    const bool windowed = short_term && !(EQ15 && !sub && is_pow2(I - J));
     // The empty asm makes the read offsets look freshly computed: buffer base + offset is then
     // formed next to each read, where it folds into the instruction's immediate, instead of
     // being kept in one register per (buffer, fragment) across the whole loop.
@@ -683,7 +704,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
 
 bool fwd_mfma_supported(const KParams &p, int dtype)
 {
-  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || p.sblk == p.b);
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || (is_pow2(p.sblk) && p.sblk <= p.b));
 }
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)
@@ -696,10 +717,15 @@ void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)
                        a.dense, p);
   };
   const bool eq15 = p.sblk != 0 && !a.dense;
+  const bool sub = eq15 && p.sblk < p.b;  // mask block smaller than the tile
   if (p.b == 32) {
-    if (eq15) go(fwd_mfma_kernel<32, true>, 64); else go(fwd_mfma_kernel<32, false>, 64);
+    if (sub) go(fwd_mfma_kernel<32, true, true>, 64);
+    else if (eq15) go(fwd_mfma_kernel<32, true, false>, 64);
+    else go(fwd_mfma_kernel<32, false, false>, 64);
   } else {
-    if (eq15) go(fwd_mfma_kernel<64, true>, 128); else go(fwd_mfma_kernel<64, false>, 128);
+    if (sub) go(fwd_mfma_kernel<64, true, true>, 128);
+    else if (eq15) go(fwd_mfma_kernel<64, true, false>, 128);
+    else go(fwd_mfma_kernel<64, false, false>, 128);
   }
 }
 

@@ -227,6 +227,11 @@ def test_seeded_random_shapes():
     ("fp32", 32, 16, 4, 1, 131),     # window 1 and a short last block: last-block keys lie below the window tiles
     ("fp32", 8, 16, 3, 2, 100),      # mask block that is no power of two and does not divide the tile
     ("bf16", 16, 64, 1, 8, 1000),    # mask block 1 under a 64-row tile: 10 gathered runs per row
+    ("bf16", 64, 64, 1, 8, 1100),    # the matrix-core kernels with a mask block below the tile: the paper's block 1
+    ("bf16", 64, 32, 1, 8, 700),
+    ("bf16", 64, 64, 8, 3, 577),
+    ("bf16", 64, 32, 4, 40, 333),
+    ("bf16", 64, 64, 16, 1, 64 * 9),  # window 1, no ragged tail
 ])
 def test_full_short_term_mask(dtype, d, b, sblk, window, L):
     # stis_mode 1: window + whole blocks at power-of-two block distances + last block (Eq. 15, causal)
