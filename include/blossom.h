@@ -77,7 +77,8 @@ typedef struct {
                              With b_q = i / blk, b_k = j / blk query i sees key j <= i iff
                              i - j < window, or b_q - b_k = 2^r for an integer r >= 0, or
                              j >= L - blk.  Ignored when stis_mode is 0.  (bf16, d = 64,
-                             block 32 or 64 run on the matrix cores when blk == block.)          */
+                             block 32 or 64 run on the matrix cores when blk is a power of two
+                             not larger than block, e.g. the paper's blk = 1.)                   */
   int32_t last_block_only; /* 1: serving mode (Appendix C: only the representation of the last
                              position is scored).  blossom_select_blocks writes only the
                              selection row of the last query block, blossom_attn_fwd only the

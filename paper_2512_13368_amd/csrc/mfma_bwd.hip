@@ -229,7 +229,7 @@ __device__ __forceinline__ bf16x8 split_operand(uint32_t x, uint32_t y)
 //                     dS^T  = 2^S'' * G^T  -> bf16 -> B operand
 //                     dQ^T += K^T dS^T      (K^T through the transposing LDS read)
 // =============================================================================================
-template <int BLK, bool EQ15>
+template <int BLK, bool EQ15, bool SUB>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const int *__restrict__ sel, const uint16_t *__restrict__ g_lt,
@@ -291,8 +291,14 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   const int J_first = p0 / BLK;
   const int lowpos = I * BLK - (p.w - 1);
   int J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
+  // SUB: the mask block of Eq. 15 is a power of two below BLK.  The mask-block distances 2^r below
+  // one tile then reach into block I - 1, which joins the window range; the larger ones land on
+  // the blocks I - 2^r' as before; every short-term tile is masked element by element.
+  constexpr bool sub = EQ15 && SUB;
+  const int sub_sh = sub ? __builtin_ctz((unsigned)p.sblk) : 0;
+  if (sub) J_lo = min(J_lo, I - 1);
   J_lo = max(J_lo, J_first);
-  // With the full short-term mask (Eq. 15, mask block = BLK) the blocks I - 2^r below the window
+  // With the full short-term mask (Eq. 15) the blocks I - 2^r below the window
   // range follow the window blocks: r = r0 .. r0 + n_pow - 1.
   const int n_win = I - J_lo + 1;
   int n_st = n_win, r0 = 0;
@@ -388,7 +394,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
     const bool hp = (short_term ? hp_st : hp_lt) != 0;
     // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
-    const bool windowed = short_term && !(EQ15 && is_pow2(I - J));
+    const bool windowed = short_term && !(EQ15 && !sub && is_pow2(I - J));
     const bool masked = windowed || J == I || J * BLK < p0;
     int wlo = iq - p.w + 1;
     if (EQ15 && iq >= p.last_lo) wlo = min(wlo, p.last_lo);  // third case of Eq. 15: the last block is visible to its own rows
@@ -411,11 +417,26 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
       if (masked) {
         const int base = J * BLK + 32 * s + 4 * lh;
+        if (sub && windowed) {
+          // window range, or (valid, causal and) a power-of-two mask-block distance, or a last-block key
+          const unsigned cspan = (unsigned)(iq - p0);
+          const bool cany = iq >= p0;
+          const int qmb = iq >> sub_sh;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int key = base + 8 * (i >> 2) + (i & 3);
-          const bool vis = any & ((unsigned)(key - lo) <= span);
-          sacc[i] = vis ? sacc[i] : kNegInf;
+          for (int i = 0; i < 16; ++i) {
+            const int key = base + 8 * (i >> 2) + (i & 3);
+            const int x = qmb - (key >> sub_sh);
+            const bool far = cany & ((unsigned)(key - p0) <= cspan) & ((x > 0 && (x & (x - 1)) == 0) | (key >= p.last_lo));
+            const bool vis = (any & ((unsigned)(key - lo) <= span)) | far;
+            sacc[i] = vis ? sacc[i] : kNegInf;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int key = base + 8 * (i >> 2) + (i & 3);
+            const bool vis = any & ((unsigned)(key - lo) <= span);
+            sacc[i] = vis ? sacc[i] : kNegInf;
+          }
         }
       }
 #pragma unroll
@@ -486,7 +507,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 //                       dV^T += dO_x^T P,  dK^T += Q^T dS
 // =============================================================================================
 
-template <int BLK, bool EQ15>
+template <int BLK, bool EQ15, bool SUB>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const uint16_t *__restrict__ g_lt, const uint16_t *__restrict__ g_st,
@@ -537,8 +558,13 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   // ---- walk: window part I = J..I_hi, then the inverse selection list ----
   const long last_q = (long)J * BLK + (BLK - 1) + (p.w - 1);
-  const int I_hi = (int)min((long)(p.NB - 1), last_q / BLK);
-  // With the full short-term mask (Eq. 15, mask block = BLK) the query blocks J + 2^r above the
+  // SUB: the mask block of Eq. 15 is a power of two below BLK: block J + 1 joins the window range (the
+  // mask-block distances below one tile reach it), every short-term tile is masked element by element.
+  constexpr bool sub = EQ15 && SUB;
+  const int sub_sh = sub ? __builtin_ctz((unsigned)p.sblk) : 0;
+  int I_hi = (int)min((long)(p.NB - 1), last_q / BLK);
+  if (sub) I_hi = max(I_hi, min(J + 1, p.NB - 1));
+  // With the full short-term mask (Eq. 15) the query blocks J + 2^r above the
   // window range follow: r = r0 .. r0 + n_pow - 1.
   const int n_win = I_hi - J + 1;
   int n_st = n_win, r0 = 0;
@@ -585,7 +611,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto tile_body = [&](const uint16_t *qs, const uint16_t *gsm, int par, int Iq, bool short_term, bool hp)
                        __attribute__((always_inline)) {
     // band-masked by the window, unless Eq. 15 shows the whole block (power-of-two block distance)
-    const bool windowed = short_term && !(EQ15 && is_pow2(Iq - J));
+    const bool windowed = short_term && !(EQ15 && !sub && is_pow2(Iq - J));
     asm volatile("" : "+v"(ro.row[0]), "+v"(ro.row[1]), "+v"(ro.row[2]), "+v"(ro.row[3]), "+v"(ro.tr[0]), "+v"(ro.tr[1]), "+v"(ro.tr8[0]), "+v"(ro.tr8[1]));
     const bool masked = windowed || Iq == J || Iq * BLK < p0 || J * BLK < p0 || (Iq + 1) * BLK > p.L;
     // visible <=> key valid and lo_i <= i <= hi_i
@@ -606,11 +632,26 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
       if (masked) {
         const int base = Iq * BLK + 32 * s + 4 * lh;
+        if (sub && windowed) {
+          // window range, or (valid, causal and) a power-of-two mask-block distance, or a last-block key
+          const unsigned cspan = (unsigned)(p.L - 1 - lo_i);
+          const int kmb = j >> sub_sh;
+          const bool last = j >= p.last_lo;
 #pragma unroll
-        for (int i = 0; i < 16; ++i) {
-          const int qi = base + 8 * (i >> 2) + (i & 3);
-          const bool vis = any & ((unsigned)(qi - lo_i) <= span);
-          sacc[i] = vis ? sacc[i] : kNegInf;
+          for (int i = 0; i < 16; ++i) {
+            const int qi = base + 8 * (i >> 2) + (i & 3);
+            const int x = (qi >> sub_sh) - kmb;
+            const bool far = key_ok & ((unsigned)(qi - lo_i) <= cspan) & ((x > 0 && (x & (x - 1)) == 0) | last);
+            const bool vis = (any & ((unsigned)(qi - lo_i) <= span)) | far;
+            sacc[i] = vis ? sacc[i] : kNegInf;
+          }
+        } else {
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int qi = base + 8 * (i >> 2) + (i & 3);
+            const bool vis = any & ((unsigned)(qi - lo_i) <= span);
+            sacc[i] = vis ? sacc[i] : kNegInf;
+          }
         }
       }
 #pragma unroll
@@ -760,7 +801,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
 bool bwd_mfma_supported(const KParams &p, int dtype)
 {
-  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || p.sblk == p.b);
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || (is_pow2(p.sblk) && p.sblk <= p.b));
 }
 
 void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st)
@@ -779,12 +820,29 @@ void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, 
                        (const float *)a.o_lt, (const float *)a.o_st, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
   };
   const bool eq15 = p.sblk != 0;
+  const bool sub = eq15 && p.sblk < p.b;  // mask block smaller than the tile
   if (p.b == 32) {
-    if (do_dq) { if (eq15) go_dq(bwd_dq_mfma_kernel<32, true>, 64); else go_dq(bwd_dq_mfma_kernel<32, false>, 64); }
-    if (do_dkv) { if (eq15) go_dkv(bwd_dkv_mfma_kernel<32, true>, 64); else go_dkv(bwd_dkv_mfma_kernel<32, false>, 64); }
+    if (do_dq) {
+      if (sub) go_dq(bwd_dq_mfma_kernel<32, true, true>, 64);
+      else if (eq15) go_dq(bwd_dq_mfma_kernel<32, true, false>, 64);
+      else go_dq(bwd_dq_mfma_kernel<32, false, false>, 64);
+    }
+    if (do_dkv) {
+      if (sub) go_dkv(bwd_dkv_mfma_kernel<32, true, true>, 64);
+      else if (eq15) go_dkv(bwd_dkv_mfma_kernel<32, true, false>, 64);
+      else go_dkv(bwd_dkv_mfma_kernel<32, false, false>, 64);
+    }
   } else {
-    if (do_dq) { if (eq15) go_dq(bwd_dq_mfma_kernel<64, true>, 128); else go_dq(bwd_dq_mfma_kernel<64, false>, 128); }
-    if (do_dkv) { if (eq15) go_dkv(bwd_dkv_mfma_kernel<64, true>, 128); else go_dkv(bwd_dkv_mfma_kernel<64, false>, 128); }
+    if (do_dq) {
+      if (sub) go_dq(bwd_dq_mfma_kernel<64, true, true>, 128);
+      else if (eq15) go_dq(bwd_dq_mfma_kernel<64, true, false>, 128);
+      else go_dq(bwd_dq_mfma_kernel<64, false, false>, 128);
+    }
+    if (do_dkv) {
+      if (sub) go_dkv(bwd_dkv_mfma_kernel<64, true, true>, 128);
+      else if (eq15) go_dkv(bwd_dkv_mfma_kernel<64, true, false>, 128);
+      else go_dkv(bwd_dkv_mfma_kernel<64, false, false>, 128);
+    }
   }
 }
 

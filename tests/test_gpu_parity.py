@@ -134,6 +134,12 @@ def test_cfg4_full_size_sampled_full_short_term_mask():
     run_case(w, pairs=pick_pairs(w, 2), backward=True)
 
 
+def test_cfg4_full_size_sampled_paper_mask_block():
+    # cfg4 at full size with all of Eq. 15 and the paper's mask block 1 (matrix-core kernels, mask block below the tile)
+    w = with_shape(WORKLOADS["cfg4"], name="cfg4-eq15-blk1", stis_block=1, window=8)
+    run_case(w, pairs=pick_pairs(w, 2), backward=True)
+
+
 def test_cfg5_full_size_sampled():
     w = WORKLOADS["cfg5"]
     run_case(w, pairs=pick_pairs(w, 8), backward=True)
