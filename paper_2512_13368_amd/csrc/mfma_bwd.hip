@@ -228,6 +228,8 @@ __device__ __forceinline__ bf16x8 split_operand(uint32_t x, uint32_t y)
 //                     G^T   = V dO_x^T - c_x
 //                     dS^T  = 2^S'' * G^T  -> bf16 -> B operand
 //                     dQ^T += K^T dS^T      (K^T through the transposing LDS read)
+// EQ15: the short-term mask is all of Eq. 15, with mask block BLK or (SUB) a power of two below it;
+// compile-time variants of both kernels, so that the plain window keeps its code.
 // =============================================================================================
 template <int BLK, bool EQ15, bool SUB>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(

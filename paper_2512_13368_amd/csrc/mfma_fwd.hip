@@ -32,8 +32,9 @@
 // dot-product instructions execute on the matrix pipeline and would stall the MFMAs.
 //
 // The walk: the short-term branch first (window blocks by arithmetic; with the full mask of
-// Eq. 15, compile-time variant EQ15 with mask block = BLK, also the blocks 2^r before the query
-// block, and tiles at power-of-two distances are unmasked), then the long-term branch, whose
+// Eq. 15, compile-time variant EQ15, also the blocks 2^r before the query block: whole tiles when
+// the mask block is BLK, masked element by element in the variant SUB for smaller power-of-two
+// mask blocks), then the long-term branch, whose
 // block ids come from one scalar load per tile out of the selection row, issued a tile ahead.
 // Outputs leave through the wavefront's staging rows so that every store covers whole rows.
 #include "launch.h"
@@ -56,8 +57,8 @@ constexpr int vmcnt_imm(int n) { return (n & 15) | (7 << 4) | (15 << 8) | ((n >>
 
 }  // namespace
 
-// EQ15: the short-term mask is all of Eq. 15 with mask block BLK (compile-time, so that the plain
-// causal window compiles to exactly the code it had without it)
+// EQ15: the short-term mask is all of Eq. 15 with mask block BLK, or (SUB) a power of two below it
+// (compile-time, so that the plain causal window compiles to exactly the code it had without it)
 template <int BLK, bool EQ15, bool SUB>
 __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 32 ? 3 : 2, BLK == 32 ? 3 : 2))) void fwd_mfma_kernel(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
