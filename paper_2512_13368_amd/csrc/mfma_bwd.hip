@@ -419,7 +419,17 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
       if (masked) {
         const int base = J * BLK + 32 * s + 4 * lh;
-        if (sub && windowed) {
+        if (sub && windowed && J < J_lo && J * BLK >= p0) {
+          // a block I - 2^r' below the window range, all of it valid: visible iff row and key share
+          // the mask block within their tiles (no window, no last-block key, one possible power of two)
+          const int qo = iq & (BLK - 1);
+          const int kb = 32 * s + 4 * lh;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int ko = kb + 8 * (i >> 2) + (i & 3);
+            sacc[i] = (((qo ^ ko) >> sub_sh) == 0 && q_ok) ? sacc[i] : kNegInf;
+          }
+        } else if (sub && windowed) {
           // window range, or (valid, causal and) a power-of-two mask-block distance, or a last-block key
           const unsigned cspan = (unsigned)(iq - p0);
           const bool cany = iq >= p0;
@@ -634,7 +644,18 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
       }
       if (masked) {
         const int base = Iq * BLK + 32 * s + 4 * lh;
-        if (sub && windowed) {
+        if (sub && windowed && Iq > I_hi && (Iq + 1) * BLK <= p.L) {
+          // a whole query block J + 2^r' above the window range: visible iff row and key share the mask
+          // block within their tiles (no window; a last-block key lies in the last two blocks, whose
+          // rows are all inside the window range of their own and the previous block)
+          const int jo = j & (BLK - 1);
+          const int qb = 32 * s + 4 * lh;
+#pragma unroll
+          for (int i = 0; i < 16; ++i) {
+            const int qio = qb + 8 * (i >> 2) + (i & 3);
+            sacc[i] = (((jo ^ qio) >> sub_sh) == 0 && key_ok) ? sacc[i] : kNegInf;
+          }
+        } else if (sub && windowed) {
           // window range, or (valid, causal and) a power-of-two mask-block distance, or a last-block key
           const unsigned cspan = (unsigned)(p.L - 1 - lo_i);
           const int kmb = j >> sub_sh;

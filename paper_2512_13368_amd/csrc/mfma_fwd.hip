@@ -359,6 +359,19 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
     const int base = J * BLK + 32 * wv + 4 * lh;
     const unsigned span = (unsigned)(q - lo);  // wraps to huge when q < lo: handled by `any`
     const bool any = q >= lo;
+    if (EQ15 && sub && windowed && J < J_lo && J * BLK >= p0) {
+      // A block I - 2^r' below the window range, all of it valid: no key of it lies in a window or in
+      // the last block, and a mask-block distance 2^r' * (BLK / blk) + delta with |delta| < BLK / blk <=
+      // half of it is a power of two only for delta = 0: row and key share the mask block within their tiles.
+      const int qo = q & (BLK - 1);
+      const int kb = 32 * wv + 4 * lh;
+#pragma unroll
+      for (int i = 0; i < 16; ++i) {
+        const int ko = kb + 8 * (i >> 2) + (i & 3);
+        s[i] = (((qo ^ ko) >> sub_sh) == 0 && q >= p0) ? s[i] : kNegInf;
+      }
+      return;
+    }
     if (EQ15 && sub && windowed) {
       // window range as above, or (valid, causal and) a power-of-two mask-block distance, or a last-block key
       const unsigned cspan = (unsigned)(q - p0);
