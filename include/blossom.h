@@ -35,6 +35,12 @@
  *     library allocates nothing, frees nothing and never synchronises; all work
  *     is enqueued on `hip_stream` (a hipStream_t passed as void*, NULL = the
  *     default stream).  Outputs are overwritten, never accumulated into.
+ *   - Accuracy: against exact arithmetic on the same inputs, every output and gradient x obeys
+ *     |x - ref| <= tol * (|ref| + rms(ref)) with tol = 1e-4 for BLOSSOM_F32 and 2e-2 for
+ *     BLOSSOM_BF16 (bf16 storage and matrix-core operands, fp32 accumulation).  The bf16 bound
+ *     is claimed for rows that attend up to 2048 keys per branch; the rounding noise of the
+ *     bf16 probabilities grows with the square root of the keys per row, and beyond that range
+ *     isolated near-zero gradient elements can leave the bound by a small factor.
  *   - Errors: 0 on success, a negative BLOSSOM_ERR_* otherwise.  All argument
  *     checks run before the first HIP call, so they work on a host with no GPU.
  *     No global state; thread-safe.  Inputs are assumed finite.
@@ -130,8 +136,12 @@ int blossom_select_blocks_cmp(const blossom_params *p, const void *Q, const void
  *   alpha   = sigmoid( gate_w[h,0:d].o_lt[i] + gate_w[h,d:2d].o_st[i] + gate_b[h] )
  *   O[i]    = alpha*o_lt[i] + (1-alpha)*o_st[i]
  *   lse_x[i] = log sum exp of the branch's logits (natural log).
- *   sel        in   int32 [B,H,NB,topk] as written by blossom_select_blocks (entries must be
- *                   -1 or in [0,NB); each query block with a valid query must list itself)
+ *   sel        in   int32 [B,H,NB,topk] as written by blossom_select_blocks.  A row may also come
+ *                   from the caller: its entries in [0,NB) must be distinct, and each query
+ *                   block with a valid query must list itself; entries outside [0,NB) (such as
+ *                   -1) are skipped wherever they stand in the row, and blocks after the query
+ *                   block contribute nothing (causal mask).  Forward and backward read a row the
+ *                   same way.
  *   gate_w     in   fp32 [H,2d];  gate_b in fp32 [H] or NULL (= 0)
  *   O          out  [B,H,L,d]
  *   o_lt,o_st  out  fp32 [B,H,L,d], lse_lt,lse_st out fp32 [B,H,L]; required iff save_for_bwd

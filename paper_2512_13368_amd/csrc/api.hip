@@ -29,7 +29,8 @@ int check_params(const blossom_params *p, KParams *kp)
   if ((long)p->B * p->H * NB > 0x7FFFFFFFL) return BLOSSOM_ERR_SHAPE;
   if ((double)p->B * p->H * p->L * p->d > 9.0e18) return BLOSSOM_ERR_SHAPE;
   kp->B = p->B; kp->H = p->H; kp->L = p->L; kp->d = p->d;
-  kp->b = p->block; kp->k = p->topk; kp->w = p->window; kp->NB = (int)NB;
+  kp->b = p->block; kp->k = p->topk; kp->NB = (int)NB;
+  kp->w = p->window < p->L ? p->window : p->L;  // a window beyond L sees the same keys as L: keeps i + w inside int
   kp->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->d);
   kp->sblk = p->stis_mode == 1 ? (p->stis_block > 0 ? p->stis_block : p->block) : 0;
   kp->last_lo = kp->sblk > 0 ? p->L - kp->sblk : 0x3FFFFFFF;
@@ -56,6 +57,10 @@ int check_ws(const KParams &kp, int dtype, int which, const void *ws, size_t ws_
   if (!aligned16(ws)) return BLOSSOM_ERR_ALIGN;
   return BLOSSOM_OK;
 }
+
+// Called after the argument checks and before the first launch: drops an error that an unrelated
+// earlier HIP call of the process left behind, so that launch_status() reports this call's own.
+void clear_stale_error() { (void)hipGetLastError(); }
 
 int launch_status()
 {
@@ -84,6 +89,7 @@ int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
   if (!aligned16(Q) || !aligned16(K)) return BLOSSOM_ERR_ALIGN;
   rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
   if (rc) return rc;
+  clear_stale_error();
   launch_select(kp, p->dtype, Q, K, false, valid_len, sel, ws, (hipStream_t)hip_stream);
   return launch_status();
 }
@@ -99,6 +105,7 @@ int blossom_select_blocks_cmp(const blossom_params *p, const void *Q, const void
   if (!aligned16(Q) || !aligned16(Kcmp)) return BLOSSOM_ERR_ALIGN;
   rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
   if (rc) return rc;
+  clear_stale_error();
   launch_select(kp, p->dtype, Q, Kcmp, true, valid_len, sel, ws, (hipStream_t)hip_stream);
   return launch_status();
 }
@@ -124,6 +131,7 @@ int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, cons
     a.o_lt = o_lt; a.o_st = o_st; a.lse_lt = lse_lt; a.lse_st = lse_st;
   }
   a.dense = 0;
+  clear_stale_error();
   if (fwd_mfma_supported(kp, p->dtype)) launch_fwd_mfma(kp, a, (hipStream_t)hip_stream);
   else launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();
@@ -153,6 +161,7 @@ int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *
   a.gate_w = gate_w; a.gate_b = gate_b; a.o_lt = o_lt; a.o_st = o_st;
   a.lse_lt = lse_lt; a.lse_st = lse_st; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV;
   a.d_gate_w = d_gate_w; a.d_gate_b = d_gate_b; a.ws = ws;
+  clear_stale_error();
   launch_bwd(kp, p->dtype, a, stages & kBwdStageAll, (hipStream_t)hip_stream);
   return launch_status();
 }
@@ -186,6 +195,7 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
   FwdArgs a{};
   a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.O = O; a.lse_lt = lse;
   a.dense = 1;
+  clear_stale_error();
   if (fwd_mfma_supported(kp, p->dtype)) launch_fwd_mfma(kp, a, (hipStream_t)hip_stream);
   else launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();

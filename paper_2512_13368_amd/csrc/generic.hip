@@ -665,14 +665,17 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 
 }
 
 // =============================================================================================
-// Backward, step 3: inverse selection list.  For each key block J of a (row, head): the
-// ascending list of query blocks I whose selection holds J.  offs [B*H,(NB+1)], items [B*H,NB*k].
+// Backward, step 3: inverse selection list.  For each key block J of a (row, head): the list of
+// query blocks I whose selection holds J, in a fixed, deterministic order.
+// offs [B*H,(NB+1)], items [B*H,NB*k].
 // One workgroup of W wavefronts per (row, head); wavefront w owns a contiguous range of query
 // blocks and its own counters.  Counting and filling use LDS integer atomics, one selection
 // row per wavefront instruction: a row lists distinct blocks, and the LDS executes one
-// wavefront's instructions in order, so inside a wavefront's range each list comes out
-// ascending in I; the ranges are laid out one after the other per key block (the scan hands
-// each wavefront its base), so the whole list is ascending and the result is deterministic.
+// wavefront's instructions in order, so the order inside a wavefront's range is that of the
+// fill loop: by 64-entry chunk of the selection row, then by I (ascending in I whenever
+// topk <= 64); the ranges are laid out one after the other per key block (the scan hands each
+// wavefront its base).  The consumers sum over the list and need no particular order, only the
+// same one on every run.
 // =============================================================================================
 constexpr int kInvWaves = 4;      // wavefronts per (row, head) when the counters fit
 constexpr int kInvWavesMaxNB = 2048;
@@ -1019,21 +1022,22 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
   const bool mfma = bwd_mfma_supported(p, dtype);
 
   if (stages & kBwdStageGate) {
-    hipLaunchKernelGGL((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(256), 0, st,
+    BLOSSOM_LAUNCH((bwd_prep_kernel<T, D>), dim3(BH * w.nchunk), dim3(256), 0, st,
                        (const float *)a.o_lt, (const float *)a.o_st, (const T *)a.dO, a.valid_len, a.gate_w,
                        a.gate_b, w.rowstat, w.partial, a.lse_lt, a.lse_st, w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, p);
-    hipLaunchKernelGGL(bwd_gate_reduce1_kernel, dim3((unsigned)p.H, kGateSlices), dim3(256), 0, st, w.partial,
+    BLOSSOM_LAUNCH(bwd_gate_reduce1_kernel, dim3((unsigned)p.H, kGateSlices), dim3(256), 0, st, w.partial,
                        w.stage2, w.nchunk, p);
-    hipLaunchKernelGGL(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
+    BLOSSOM_LAUNCH(bwd_gate_reduce2_kernel, dim3((unsigned)p.H), dim3(256), 0, st, w.stage2, a.d_gate_w,
                        a.d_gate_b, p);
   }
   if (stages & kBwdStageInverse) {
     const int W = p.NB <= kInvWavesMaxNB ? kInvWaves : 1;
     const size_t lds = (size_t)W * (p.NB + 1) * sizeof(int) + (size_t)(p.NB + 1 + 3) / 4 * 4;
-    hipLaunchKernelGGL(inverse_list_kernel, dim3(BH), dim3(64 * W), lds, st, a.sel, a.valid_len, w.offs, w.items,
+    BLOSSOM_LAUNCH(inverse_list_kernel, dim3(BH), dim3(64 * W), lds, st, a.sel, a.valid_len, w.offs, w.items,
                        p);
   }
   if (mfma) {
+    if (launch_failed()) return;
     launch_bwd_mfma(p, a, w, stages, st);
     return;
   }
@@ -1047,6 +1051,7 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     };
     if (far) go(bwd_dq_generic_kernel<T, D, true>);
     else go(bwd_dq_generic_kernel<T, D, false>);
+    if (launch_failed()) return;
   }
   if (stages & kBwdStageDKV) {
     auto go = [&](auto kernel) {
@@ -1060,9 +1065,11 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     } else {
       if (far) {
         go(bwd_dkv_generic_kernel<T, D, 0, true>);
+        if (launch_failed()) return;
         go(bwd_dkv_generic_kernel<T, D, 1, true>);
       } else {
         go(bwd_dkv_generic_kernel<T, D, 0, false>);
+        if (launch_failed()) return;
         go(bwd_dkv_generic_kernel<T, D, 1, false>);
       }
     }

@@ -8,7 +8,18 @@
 
 #include "common.h"
 
+// Launches a kernel and leaves the enclosing (void) launcher at once if the launch failed, so that
+// no later kernel of a multi-kernel entry point is enqueued on what the failed one should have
+// written.  The error stays set for the entry point's final status check.
+#define BLOSSOM_LAUNCH(...)                              \
+  do {                                                   \
+    hipLaunchKernelGGL(__VA_ARGS__);                     \
+    if (hipPeekAtLastError() != hipSuccess) return;      \
+  } while (0)
+
 namespace blossom {
+
+inline bool launch_failed() { return hipPeekAtLastError() != hipSuccess; }
 
 // Pointers of one forward call (device memory; element type per `dtype`).
 struct FwdArgs {
@@ -46,7 +57,7 @@ void launch_select(const KParams &p, int dtype, const void *Q, const void *K, bo
 struct BwdWorkspace {
   float4 *rowstat;   // [B*H*L] (alpha, dz, D_lt, D_st)
   int *offs;         // [B*H,(NB+1)] inverse selection list: offsets
-  int *items;        // [B*H,NB*k]   inverse selection list: query blocks, ascending per key block;
+  int *items;        // [B*H,NB*k]   inverse selection list: query blocks per key block, in a fixed order;
                      //              bit kInvFewShift marks a query block whose long-term rows may see few keys
   float *partial;    // [B*H*nchunk,(2d+1)] partial gate-weight gradients
   float *stage2;     // [H,slices,(2d+1)] second reduction level

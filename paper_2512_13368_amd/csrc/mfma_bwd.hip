@@ -85,7 +85,7 @@ struct Stager {
   __device__ __forceinline__ void stage(const uint16_t *src_head, uint16_t *dst_tile, int blk) const
   {
     constexpr int TILE = BLK * D;
-    const char *src = reinterpret_cast<const char *>(src_head) + (size_t)blk * (TILE * 2);  // uniform
+    const char *src = reinterpret_cast<const char *>(src_head) + (size_t)max(blk, 0) * (TILE * 2);  // uniform (block -1: a skipped list entry, every key masked)
     lds_void *dst = (lds_void *)(dst_tile + 32 * wv * D);
     if (!ragged || blk != NB - 1) {
       __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 0, 0);
@@ -289,7 +289,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     asm volatile("" : "+v"(s_init), "+v"(g_init));  // register blocks, not one value copied at each use
   };
 
-  // ---- tile list: window blocks, then the selection list up to its first -1 ----
+  // ---- tile list: window blocks, then the selection list up to its last valid entry ----
   const int J_first = p0 / BLK;
   const int lowpos = I * BLK - (p.w - 1);
   int J_lo = lowpos <= 0 ? 0 : lowpos / BLK;
@@ -313,21 +313,16 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   int n_lt = 0;
   bool lt_few = true;  // the selected past blocks hold fewer than kFewKeys valid keys
   const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
-  {
-    bool open = true;
-    for (int e0 = 0; e0 < p.k; e0 += 64) {
-      const int e = e0 + lane;
-      const int J = e < p.k ? my_sel[e] : -1;
-      const unsigned long long okm = __ballot(J >= 0 && J < p.NB);
-      const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);
-      if (open) {
-        const bool mine = lane < lead;
-        const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
-        if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
-        n_lt += lead;
-        open = lead == 64;
-      }
-    }
+  // (entries outside [0, NB) are skipped wherever they stand: the walk runs up to the last valid
+  // entry, an invalid one in between costs one tile with every key masked)
+  for (int e0 = 0; e0 < p.k; e0 += 64) {
+    const int e = e0 + lane;
+    const int J = e < p.k ? my_sel[e] : -1;
+    const bool ok = J >= 0 && J < p.NB;
+    const unsigned long long okm = __ballot(ok);
+    if (okm != 0ull) n_lt = e0 + 64 - __builtin_clzll(okm);
+    const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
+    if (__ballot(ok && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
   }
   // Rows with only a few keys: dq is a sum of a few large dS*k terms that nearly cancel, so the
   // bf16 rounding of dS would dominate it.  Such wavefronts feed dS as a two-term bf16 sum.
@@ -381,7 +376,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto tile_of = [&](int t) -> int {
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    if (e >= 0) return ((const_int_ptr)my_sel)[e];
+    if (e >= 0) {
+      const int Js = ((const_int_ptr)my_sel)[e];
+      return (unsigned)Js < (unsigned)p.NB ? Js : -1;
+    }
     if (!EQ15) return J_lo + t;
     return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
   };
@@ -849,6 +847,7 @@ void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, 
       if (sub) go_dq(bwd_dq_mfma_kernel<32, true, true>, 64);
       else if (eq15) go_dq(bwd_dq_mfma_kernel<32, true, false>, 64);
       else go_dq(bwd_dq_mfma_kernel<32, false, false>, 64);
+      if (launch_failed()) return;
     }
     if (do_dkv) {
       if (sub) go_dkv(bwd_dkv_mfma_kernel<32, true, true>, 64);
@@ -860,6 +859,7 @@ void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, 
       if (sub) go_dq(bwd_dq_mfma_kernel<64, true, true>, 128);
       else if (eq15) go_dq(bwd_dq_mfma_kernel<64, true, false>, 128);
       else go_dq(bwd_dq_mfma_kernel<64, false, false>, 128);
+      if (launch_failed()) return;
     }
     if (do_dkv) {
       if (sub) go_dkv(bwd_dkv_mfma_kernel<64, true, true>, 128);

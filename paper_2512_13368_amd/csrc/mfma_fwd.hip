@@ -195,7 +195,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
   const unsigned v_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8) * 2u;  // bytes
   const bool ragged = p.L % BLK != 0;
   auto stage = [&](const char *src_head, unsigned lane_off, unsigned odd_xor, uint16_t *dst_tile, int J) __attribute__((always_inline)) {
-    const char *src = src_head + (size_t)J * (TILE * 2);  // uniform
+    const char *src = src_head + (size_t)max(J, 0) * (TILE * 2);  // uniform (block -1: any block will do, all of it is masked)
     lds_void *dst = (lds_void *)(dst_tile + 32 * wv * D);
     if (!ragged || J != p.NB - 1) {
       const unsigned lane_odd = lane_off ^ odd_xor;  // odd 8-row slices (K only: their swizzle differs)
@@ -240,7 +240,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
 #pragma unroll
     for (int c = 0; c < GATE_PER; ++c) gate_s[c * 2 * BLK + tid] = gate_mine[c];
 
-  // ---- tile list: window blocks J_lo..I, then the selection list up to its first -1 ----
+  // ---- tile list: window blocks J_lo..I, then the selection list up to its last valid entry ----
   // Every wavefront reads the whole selection row with one vector load per 64 entries and
   // derives the counts from ballots (no chain of dependent scalar loads).  The walk itself
   // fetches one entry per tile with a scalar load (see tile_raw): those do not touch the
@@ -250,22 +250,18 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
   if (dense) {
     n_all = I - J_first + 1;
   } else {
+    // Entries outside [0, NB) are skipped wherever they stand: the walk runs up to the last valid
+    // entry, and an invalid one in between costs one tile whose keys are all masked (block id -1).
     int n_lt = 0;
-    bool open = true;
     for (int e0 = 0; e0 < p.k; e0 += 64) {
       const int e = e0 + lane;
       const int J = e0 == 0 ? sel0 : (e < p.k ? my_sel[e] : -1);
       const bool ok = J >= 0 && J < p.NB;
       const unsigned long long okm = __ballot(ok);
-      const int lead = okm == ~0ull ? 64 : __builtin_ctzll(~okm);  // entries before the first -1
-      if (open) {
-        const bool mine = lane < lead;
-        // a full earlier block already brings a whole block of keys; only a partial first block may not
-        const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
-        if (__ballot(mine && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
-        n_lt += lead;
-        open = lead == 64;
-      }
+      if (okm != 0ull) n_lt = e0 + 64 - __builtin_clzll(okm);
+      // a full earlier block already brings a whole block of keys; only a partial first block may not
+      const int vcount = min((J + 1) * BLK, p.L) - max(J * BLK, p0);
+      if (__ballot(ok && J < I && vcount >= kFewKeys) != 0ull) lt_few = false;
     }
     n_all = n_st + n_lt;
   }
@@ -276,7 +272,10 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
     if (dense) return J_first + t;
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    if (e >= 0) return ((const_int_ptr)my_sel)[e];
+    if (e >= 0) {
+      const int J = ((const_int_ptr)my_sel)[e];
+      return (unsigned)J < (unsigned)p.NB ? J : -1;
+    }
     if (!EQ15) return J_lo + t;
     return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
   };

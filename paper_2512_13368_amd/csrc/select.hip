@@ -149,11 +149,11 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, bool
   const int per_wg = 256 / (D / 4);
   const unsigned grid = (unsigned)((tasks + per_wg - 1) / per_wg);
   if (kcmp)
-    hipLaunchKernelGGL((pool_kernel<T, D, true>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
-                       valid_len, qsum, kmeanT, p);
+    BLOSSOM_LAUNCH((pool_kernel<T, D, true>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
+                   valid_len, qsum, kmeanT, p);
   else
-    hipLaunchKernelGGL((pool_kernel<T, D, false>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
-                       valid_len, qsum, kmeanT, p);
+    BLOSSOM_LAUNCH((pool_kernel<T, D, false>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
+                   valid_len, qsum, kmeanT, p);
   hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
                      (size_t)p.NB * sizeof(unsigned long long), st,
                      qsum, kmeanT, valid_len, sel, p);

@@ -18,7 +18,7 @@ pytestmark = pytest.mark.gpu
 
 
 def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale=None, branches_coincide=False,
-             scale=None):
+             scale=None, sel_edit=None):
     if x is None:
         x = make_inputs(w, want_dO=True)
     if gate_scale is not None:  # stronger gate weights exercise the gate path beyond alpha ~ 0.5
@@ -33,13 +33,18 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
     sc = {} if scale is None else dict(softmax_scale=scale)   # None: the default 1/sqrt(d) on both sides
     p = params(w, save_for_bwd=1, **sc)
     sel = B.select_blocks(p, dv.Q, dv.K, dv.vl)
-    f = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
-    g = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO) if backward else None
     torch.cuda.synchronize()
 
     # --- selection: every (row, head), bit-exact ---
     sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk)
     np.testing.assert_array_equal(sel.cpu().numpy(), sel_ref)
+    if sel_edit is not None:  # a caller-built selection: both sides get the same edited rows
+        sel_ref = np.ascontiguousarray(sel_edit(sel_ref.copy()), dtype=np.int32)
+        sel = torch.from_numpy(sel_ref).cuda()
+
+    f = B.attn_fwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb)
+    g = B.attn_bwd(p, dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, f, dv.dO) if backward else None
+    torch.cuda.synchronize()
 
     # --- outputs: listed pairs ---
     bh = None if pairs is None else np.asarray(pairs, np.int32)
@@ -72,6 +77,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
         if bh is None and not branches_coincide:  # gate gradients sum over every pair
             assert_close(host(g.d_gate_w), gr.d_gate_w, tol, "d_gate_w")
             assert_close(host(g.d_gate_b), gr.d_gate_b, tol, "d_gate_b")
+        assert bh is None or not w.backward, "a workload whose outputs include the gate gradients runs every pair"
         if branches_coincide:
             # o_lt == o_st in exact arithmetic: the gate gradients are exactly zero there, so the
             # relative criterion has nothing to hold on to; the kernels' two branches round
@@ -114,7 +120,7 @@ def test_cfg3_reduced_all_elements():
 
 def test_cfg3_full_size_sampled():
     w = WORKLOADS["cfg3"]
-    run_case(w, pairs=pick_pairs(w, 12), backward=False)
+    run_case(w, pairs=pick_pairs(w, 12), backward=True)
 
 
 def test_cfg4_reduced_all_elements():
@@ -124,8 +130,14 @@ def test_cfg4_reduced_all_elements():
 
 
 def test_cfg4_full_size_sampled():
+    # The launch configuration the benchmark times (plain causal window, every query block), forward
+    # and backward.  The kernels deal (row, head) pairs to the eight XCDs in contiguous ranges of 16:
+    # two pairs of every range are compared (first and last pair of the workload among them).
     w = WORKLOADS["cfg4"]
-    run_case(w, pairs=pick_pairs(w, 3), backward=False)
+    total = w.B * w.H
+    pairs = sorted({int(t) for t in np.linspace(0, total - 1, 16).round()})
+    assert len(pairs) == 16 and all(sum(1 for q in pairs if q // 16 == r) == 2 for r in range(8))
+    run_case(w, pairs=pairs, backward=True)
 
 
 def test_cfg4_full_size_sampled_full_short_term_mask():
@@ -140,9 +152,10 @@ def test_cfg4_full_size_sampled_paper_mask_block():
     run_case(w, pairs=pick_pairs(w, 2), backward=True)
 
 
-def test_cfg5_full_size_sampled():
-    w = WORKLOADS["cfg5"]
-    run_case(w, pairs=pick_pairs(w, 8), backward=True)
+def test_cfg5_full_size_every_pair():
+    # the training-step workload at full size, every (row, head) pair: dQ, dK, dV element by element and
+    # the gate gradients, whose two-level reduction runs with its full chunk and slice counts only here
+    run_case(WORKLOADS["cfg5"], backward=True)
 
 
 @pytest.mark.parametrize("dtype,d,b", [("fp32", 32, 8), ("fp32", 64, 16), ("bf16", 32, 32), ("bf16", 64, 8),
@@ -157,6 +170,44 @@ def test_shape_matrix(dtype, d, b):
     # a full row (the two branches differ), a row starting inside a block, a row shorter than a block
     x.valid_len[:] = [L, L - b - 3, b // 2 + 1]
     run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
+
+
+@pytest.mark.parametrize("name,shape", [
+    ("cfg1", dict(topk=4)),                                                                  # scalar kernels, fp32
+    ("cfg2", dict(B=4, dtype="bf16", qkv_scaled=True)),                                      # scalar kernels, bf16
+    ("cfg3", dict(B=3, L=32 * 9 + 11, len_lo=40, len_hi=32 * 9 + 11, topk=5)),               # matrix cores, b = 32
+    ("cfg4", dict(B=2, H=2, L=64 * 9, len_lo=300, len_hi=64 * 9, topk=6)),                   # matrix cores, b = 64
+    ("cfg4", dict(B=1, H=2, L=64 * 70, len_lo=64 * 70, len_hi=64 * 70, topk=67, window=64)),  # a row read in two chunks
+])
+def test_selection_rows_with_holes(name, shape):
+    # A caller-built selection row may hold entries outside [0, NB) anywhere: every kernel family skips
+    # them where they stand (as the oracle's mask does) in forward, dQ and dK/dV alike.
+    w = with_shape(WORKLOADS[name], name=name + "-holes", **shape)
+
+    def punch(sel):
+        NB = sel.shape[2]
+        rng = np.random.default_rng(w.seed + 13)
+        for r in range(sel.shape[0]):
+            for h in range(sel.shape[1]):
+                for I in range(NB):
+                    row = sel[r, h, I]
+                    cnt = int((row >= 0).sum())
+                    if cnt < 3:
+                        continue
+                    kind = int(rng.integers(0, 4))
+                    if kind == 0:
+                        row[int(rng.integers(1, cnt - 1))] = -1            # a hole inside the list
+                    elif kind == 1:
+                        row[0] = NB + 3                                    # an id past the last block, up front
+                    elif kind == 2:
+                        row[0] = -1
+                        row[cnt - 2] = -5                                  # two holes
+                    # kind 3: the row stays as selected
+                    own = np.where(row == I)[0]
+                    assert own.size == 1                                   # the query's own block is still listed
+        return sel
+
+    run_case(w, backward=True, gate_scale=0.4, sel_edit=punch)
 
 
 @pytest.mark.parametrize("b,topk,window", [(64, 1, 5), (64, 2, 40), (32, 1, 200), (32, 2, 7), (64, 3, 20)])
@@ -357,6 +408,10 @@ def test_edge_cases():
     # k = 1 (own block only), w = 1 (self only), k larger than the number of blocks
     run_case(with_shape(base, name="k1w1", topk=1, window=1), backward=True)
     run_case(with_shape(base, name="kbig", topk=12, window=200), backward=True)
+    # the "unbounded window" idiom: the largest int, in both kernel families
+    run_case(with_shape(base, name="wmax", topk=2, window=2**31 - 1), backward=True)
+    run_case(with_shape(WORKLOADS["cfg3"], name="wmax-mc", B=2, H=2, L=32 * 6 + 5, len_lo=60, len_hi=32 * 6 + 5, topk=2,
+                        window=2**31 - 1), backward=True)
 
 
 @pytest.mark.parametrize("dtype,d,H,L,b,k,w,sblk", [
