@@ -64,7 +64,8 @@ enum {
   BLOSSOM_ERR_PARAM = -4,       /* topk < 1, window < 1, stis_block < 0, bad softmax_scale      */
   BLOSSOM_ERR_ALIGN = -5,       /* a tensor pointer is not 16-byte aligned                     */
   BLOSSOM_ERR_WORKSPACE = -6,   /* workspace NULL or smaller than blossom_workspace_bytes()    */
-  BLOSSOM_ERR_LAUNCH = -7       /* a kernel launch failed (hipGetLastError)                    */
+  BLOSSOM_ERR_LAUNCH = -7,      /* a kernel launch failed (hipGetLastError)                    */
+  BLOSSOM_ERR_TOO_LARGE = -8    /* blossom_select_blocks_static: scratch need beyond its maximum */
 };
 
 enum { BLOSSOM_F32 = 0, BLOSSOM_BF16 = 1 };
@@ -115,6 +116,23 @@ size_t blossom_workspace_bytes(const blossom_params *p, int which);
 int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
                           const int32_t *valid_len, int32_t *sel,
                           void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * blossom_select_blocks for callers that cannot allocate device memory and have no workspace to
+ * hand over: code under HIP graph capture, tight serving loops, harnesses that forbid
+ * allocation.  Same arguments, checks, kernels and results as blossom_select_blocks, minus the
+ * workspace: the pooled sums live in a static device array inside the library (16 MiB per GPU,
+ * held until the process ends), whose device address is looked up once per GPU.  Calls no
+ * hipMalloc/hipFree and no allocating routine.
+ *   Limit: 8*B*H*ceil(L/block)*d bytes <= 16 MiB (16777216), else BLOSSOM_ERR_TOO_LARGE and
+ *   nothing is launched (all five benchmark shapes fit: the largest needs 8 MiB).
+ *   Every call on a GPU uses that GPU's one array: calls that may overlap on one GPU (different
+ *   streams, different threads) race on it and must be ordered by the caller.  The array keeps
+ *   the last call's contents; nothing in it needs clearing between calls, because the pooling
+ *   pass writes every entry the scoring pass reads.
+ */
+int blossom_select_blocks_static(const blossom_params *p, const void *Q, const void *K,
+                                 const int32_t *valid_len, int32_t *sel, void *hip_stream);
 
 /*
  * The same selection with the block compression left to the caller (Sec. 3.4, Eq. 9: a learnable

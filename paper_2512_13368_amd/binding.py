@@ -17,7 +17,7 @@ LIB_PATH = os.path.join(_HERE, "libblossom.so")
 F32, BF16 = 0, 1
 WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
-EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_cmp", "blossom_attn_fwd", "blossom_attn_bwd",
+EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_strerror", "blossom_version")
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
 
@@ -55,6 +55,8 @@ def lib() -> ctypes.CDLL:
         L.blossom_workspace_bytes.argtypes = [pp, ctypes.c_int]
         L.blossom_select_blocks.restype = ctypes.c_int
         L.blossom_select_blocks.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
+        L.blossom_select_blocks_static.restype = ctypes.c_int
+        L.blossom_select_blocks_static.argtypes = [pp, vp, vp, i32p, i32p, vp]
         L.blossom_select_blocks_cmp.restype = ctypes.c_int
         L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
@@ -161,6 +163,24 @@ def select_blocks(p: Params, Q, K, valid_len, sel=None, ws=None, stream=None):
                                      _ptr(ws), nbytes, _stream(stream))
     if rc:
         raise BlossomError(rc, "blossom_select_blocks")
+    return sel
+
+
+def select_blocks_static(p: Params, Q, K, valid_len, sel, stream=None):
+    """blossom_select_blocks_static: no workspace, nothing allocated (the caller passes `sel`)."""
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    _check_tensor(Q, shp, _torch_dtype(p), "Q")
+    _check_tensor(K, shp, _torch_dtype(p), "K")
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    if sel is None:
+        raise ValueError("sel is required: this entry point allocates nothing")
+    _check_tensor(sel, (p.B, p.H, p.NB, p.topk), torch.int32, "sel")
+    cp = p.c()
+    rc = lib().blossom_select_blocks_static(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(valid_len), _ptr(sel),
+                                            _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_select_blocks_static")
     return sel
 
 

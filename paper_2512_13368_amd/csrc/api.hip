@@ -3,12 +3,37 @@
 #include "../../include/blossom.h"
 
 #include <cmath>
+#include <mutex>
 
 #include "launch.h"
 
 using namespace blossom;
 
+// Scratch of blossom_select_blocks_static: the pooled query sums and key means of one call.  Every
+// GPU the library runs on holds its own copy of the array until the process ends.  In host code the
+// array's name is only a handle for hipGetSymbolAddress; kernels get the address that call returns.
+constexpr size_t kStaticScratchBytes = 16u << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
 namespace {
+
+// Device address of `scratch` on the current device, looked up once per device.
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+void *static_scratch_ptr()
+{
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void *ptr = nullptr;
+    if (hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)) != hipSuccess) return nullptr;
+    g_scratch_ptr[dev] = ptr;
+  }
+  return g_scratch_ptr[dev];
+}
 
 bool aligned16(const void *p) { return (reinterpret_cast<uintptr_t>(p) & 15u) == 0; }
 
@@ -90,6 +115,24 @@ int blossom_select_blocks(const blossom_params *p, const void *Q, const void *K,
   rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
   if (rc) return rc;
   clear_stale_error();
+  launch_select(kp, p->dtype, Q, K, false, valid_len, sel, ws, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
+int blossom_select_blocks_static(const blossom_params *p, const void *Q, const void *K,
+                                 const int32_t *valid_len, int32_t *sel, void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (!Q || !K || !valid_len || !sel) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K)) return BLOSSOM_ERR_ALIGN;
+  if (select_workspace_bytes(kp) > kStaticScratchBytes) return BLOSSOM_ERR_TOO_LARGE;
+  void *ws = static_scratch_ptr();  // (first HIP call: after every argument check)
+  if (!ws) return BLOSSOM_ERR_LAUNCH;
+  clear_stale_error();
+  // The pooling pass writes every entry the scoring pass reads, so nothing of the previous call's
+  // contents has to be cleared.
   launch_select(kp, p->dtype, Q, K, false, valid_len, sel, ws, (hipStream_t)hip_stream);
   return launch_status();
 }
@@ -212,6 +255,7 @@ const char *blossom_strerror(int code)
     case BLOSSOM_ERR_ALIGN: return "tensor or workspace pointer not 16-byte aligned";
     case BLOSSOM_ERR_WORKSPACE: return "workspace missing or too small";
     case BLOSSOM_ERR_LAUNCH: return "kernel launch failed";
+    case BLOSSOM_ERR_TOO_LARGE: return "problem too large for the static scratch array (B*H*ceil(L/block)*d*8 bytes must be <= 16 MiB)";
     default: return "unknown error code";
   }
 }
