@@ -8,7 +8,13 @@ carries the stage times, the forward-only rate (the quantity the L=8192 target i
 on), a roofline object for the dominant kernel, the same-style dense causal kernel and the
 CPU oracle timed on a bounded sample of the same workload.
 
+The default run (workload cfg4, L=8192) also times the L=1024 training step (cfg5) the same way and
+reports it under "l1024_training_step".  Roofline entries count algorithmic work only: forward 4d
+flops per unmasked pair, the whole backward 10d (five contractions), bytes of valid positions.
+
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
+    python bench.py --stage <kernel>        one stage alone (for profilers)
+    python bench.py --stage ceiling         stripped tile loop of the forward: what the pipes allow
 """
 from __future__ import annotations
 
@@ -24,13 +30,39 @@ if ROOT not in sys.path:
 
 import numpy as np
 
-# HBM-side bytes per launch measured with rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE, scaled by what the same
-# counters read for a plain copy of known size (FETCH_SIZE x2.000, WRITE_SIZE x1.000); the commands and the
-# raw readings are in profiles/cfg4_hbm_traffic.txt.  Other workloads: not measured (null).
-MEASURED_TRAFFIC_BYTES = {
-    ("cfg4", "fwd"): 562362246, ("cfg4", "fwd_saving_for_bwd"): 1113369366, ("cfg4", "bwd_gate"): 1006265795,
-    ("cfg4", "bwd_dq"): 916631857, ("cfg4", "bwd_dkv"): 1078798472, ("cfg4", "select"): 276989981,
-}
+PROFILES = os.path.join(ROOT, "profiles")
+CSRC = os.path.join(ROOT, "paper_2512_13368_amd", "csrc")
+
+
+def sources_sha256():
+    """Hash of the kernel sources: a stored profile figure is only quoted for the code it was measured on."""
+    import hashlib
+    h = hashlib.sha256()
+    for name in sorted(os.listdir(CSRC)):
+        if name.endswith((".hip", ".h")):
+            h.update(name.encode())
+            h.update(open(os.path.join(CSRC, name), "rb").read())
+    return h.hexdigest()
+
+
+def profiled_traffic(workload):
+    """HBM-side bytes per launch from profiles/<workload>_hbm_traffic.txt (rocprofv3 --pmc FETCH_SIZE /
+    WRITE_SIZE, scaled by a plain copy of known size; the file gives the commands).  The file names the
+    hash of the kernel sources it was measured on; for any other sources nothing is quoted (None)."""
+    path = os.path.join(PROFILES, f"{workload}_hbm_traffic.txt")
+    if not os.path.exists(path):
+        return {}, None
+    table, sha = {}, None
+    for line in open(path):
+        t = line.split()
+        if len(t) == 3 and t[0] == "traffic_bytes":
+            table[t[1]] = int(t[2])
+        elif len(t) == 2 and t[0] == "sources_sha256":
+            sha = t[1]
+    if sha != sources_sha256():
+        return {}, sha
+    return table, sha
+
 
 HBM_PEAK_GBS = 8000.0          # MI355X HBM3E
 MFMA_BF16_PEAK_TFLOPS = 2500.0  # dense bf16 MFMA
@@ -83,134 +115,157 @@ def algorithmic_pairs(w, valid_len, sel):
     return lt, st, dense
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=20)
-    ap.add_argument("--warmup", type=int, default=3)
-    ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--input-sets", type=int, default=3,
-                    help="independent seeded input sets the timed steps rotate over, so that a small workload is not "
-                         "served from the 256 MB last-level cache (one set with --stage and --graph)")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture the step (select + forward + backward) in a HIP graph once and time its replays")
-    ap.add_argument("--shape", default="",
-                    help="overrides of the workload's fields, e.g. B=32,H=8,L=2000,len_lo=2000,len_hi=2000 "
-                         "(the efficiency-study shapes of the paper's Appendix B); the JSON line names them")
-    ap.add_argument("--stis-block", type=int, default=0,
-                    help="0: short-term mask = causal window (default); N >= 1: all of Eq. 15 with mask block N")
-    ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--stage", choices=["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_dq", "bwd_dkv", "dense", "serve",
-                                        "copy"],
-                    default=None,
-                    help="profiling aid: run only this stage --steps times (after the others ran once) "
-                         "and print its average time; the headline line is not produced")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
-              "(every (row, head) pair is independent in selection, forward and backward: rows shard over GPUs "
-              "with no exchange in forward and one small all-reduce of the gate gradients in backward).",
-              file=sys.stderr)
-        sys.exit(2)
+STAGES = ["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "dense", "serve", "copy"]
+PROBE_KINDS = ["matrix instructions only", "softmax VALU work only", "both, operands in registers",
+               "both, operands from LDS", "whole tile loop (with global->LDS staging)", "staging only"]
 
-    import torch
-    from paper_2512_13368_amd import binding as B
-    from paper_2512_13368_amd.inputs import WORKLOADS, bf16_bits, make_inputs, with_shape
 
-    w = WORKLOADS[args.workload]
-    if args.stis_block:
-        w = with_shape(w, stis_block=args.stis_block)
-    if args.shape:
-        kv = dict(t.split("=") for t in args.shape.split(","))
-        w = with_shape(w, name=w.name + "*", **{k_: int(v_) for k_, v_ in kv.items()})
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    n_sets = 1 if (args.stage or args.graph) else max(1, args.input_sets)
-    xs = [make_inputs(w, input_set=i, want_dO=True) for i in range(n_sets)]
-    x = xs[0]  # the per-kernel passes, the pair counts and the CPU baseline use the first set
+class Runner:
+    """Device buffers and launch closures of one workload (everything allocated once, up front)."""
 
-    def up(a):
-        if w.dtype == "bf16":
-            return torch.from_numpy(bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
-        return torch.from_numpy(a).to(dev)
+    def __init__(self, w, n_sets, torch, B, make_inputs, bf16_bits):
+        self.w, self.torch, self.B = w, torch, B
+        dev = torch.device("cuda:0")
+        self.xs = [make_inputs(w, input_set=i, want_dO=True) for i in range(n_sets)]
+        self.x = self.xs[0]  # the per-kernel passes, the pair counts and the CPU baseline use the first set
 
-    sets = [(up(xi.Q), up(xi.K), up(xi.V), up(xi.dO), torch.from_numpy(xi.valid_len).to(dev)) for xi in xs]
-    Q, K, V, dO, vl = sets[0]
-    gw = torch.from_numpy(x.gate_w).to(dev)
-    gb = torch.from_numpy(x.gate_b).to(dev)
-    dt = B.F32 if w.dtype == "fp32" else B.BF16
-    stis = dict(stis_mode=int(w.stis_block > 0), stis_block=w.stis_block)
-    p = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=1, **stis)
-    p_nosave = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=0, **stis)
-    p_serve = B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, save_for_bwd=0, last_block_only=1, **stis)
+        def up(a):
+            if w.dtype == "bf16":
+                return torch.from_numpy(bf16_bits(a).view(np.int16)).to(dev).view(torch.bfloat16)
+            return torch.from_numpy(a).to(dev)
 
-    # all buffers are allocated once, outside the timed region
-    tdt = torch.float32 if w.dtype == "fp32" else torch.bfloat16
-    shp = (w.B, w.H, w.L, w.d)
-    sel = torch.empty((w.B, w.H, w.NB, w.topk), dtype=torch.int32, device=dev)
-    mk = lambda: torch.empty(shp, dtype=tdt, device=dev)
-    mk32 = lambda: torch.empty(shp, dtype=torch.float32, device=dev)
-    fo = B.FwdOut(mk(), mk32(), mk32(), torch.empty(shp[:3], dtype=torch.float32, device=dev),
-                  torch.empty(shp[:3], dtype=torch.float32, device=dev))
-    fo_nosave = B.FwdOut(fo.O)
-    bo = B.BwdOut(mk(), mk(), mk(), torch.empty((w.H, 2 * w.d), dtype=torch.float32, device=dev),
-                  torch.empty((w.H,), dtype=torch.float32, device=dev))
-    ws_sel = torch.empty(max(1, B.workspace_bytes(p, B.WS_SELECT)), dtype=torch.uint8, device=dev)
-    ws_bwd = torch.empty(max(1, B.workspace_bytes(p, B.WS_BWD)), dtype=torch.uint8, device=dev)
-    O_dense = mk()
+        self.sets = [(up(xi.Q), up(xi.K), up(xi.V), up(xi.dO), torch.from_numpy(xi.valid_len).to(dev)) for xi in self.xs]
+        self.gw = torch.from_numpy(self.x.gate_w).to(dev)
+        self.gb = torch.from_numpy(self.x.gate_b).to(dev)
+        dt = B.F32 if w.dtype == "fp32" else B.BF16
+        stis = dict(stis_mode=int(w.stis_block > 0), stis_block=w.stis_block)
+        mkp = lambda **kw: B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window, dt, **stis, **kw)
+        self.p, self.p_nosave, self.p_serve = mkp(save_for_bwd=1), mkp(), mkp(last_block_only=1)
+        tdt = torch.float32 if w.dtype == "fp32" else torch.bfloat16
+        shp = (w.B, w.H, w.L, w.d)
+        mk = lambda: torch.empty(shp, dtype=tdt, device=dev)
+        mk32 = lambda: torch.empty(shp, dtype=torch.float32, device=dev)
+        self.sel = torch.empty((w.B, w.H, w.NB, w.topk), dtype=torch.int32, device=dev)
+        self.fo = B.FwdOut(mk(), mk32(), mk32(), torch.empty(shp[:3], dtype=torch.float32, device=dev),
+                           torch.empty(shp[:3], dtype=torch.float32, device=dev))
+        self.fo_nosave = B.FwdOut(self.fo.O)
+        self.bo = B.BwdOut(mk(), mk(), mk(), torch.empty((w.H, 2 * w.d), dtype=torch.float32, device=dev),
+                           torch.empty((w.H,), dtype=torch.float32, device=dev))
+        self.ws_sel = torch.empty(max(1, B.workspace_bytes(self.p, B.WS_SELECT)), dtype=torch.uint8, device=dev)
+        self.ws_bwd = torch.empty(max(1, B.workspace_bytes(self.p, B.WS_BWD)), dtype=torch.uint8, device=dev)
+        self.ws_fwd = torch.empty(max(1, B.workspace_bytes(self.p, B.WS_FWD)), dtype=torch.uint8, device=dev)
+        self.O_dense = mk()
 
-    def step(i=0):
-        Qi, Ki, Vi, dOi, vli = sets[i % n_sets]
-        B.select_blocks(p, Qi, Ki, vli, sel=sel, ws=ws_sel)
-        B.attn_fwd(p, Qi, Ki, Vi, vli, sel, gw, gb, out=fo)
-        B.attn_bwd(p, Qi, Ki, Vi, vli, sel, gw, gb, fo, dOi, out=bo, ws=ws_bwd)
+    def step(self, i=0):
+        B, p = self.B, self.p
+        Q, K, V, dO, vl = self.sets[i % len(self.sets)]
+        B.select_blocks(p, Q, K, vl, sel=self.sel, ws=self.ws_sel)
+        B.attn_fwd(p, Q, K, V, vl, self.sel, self.gw, self.gb, out=self.fo, ws=self.ws_fwd)
+        B.attn_bwd(p, Q, K, V, vl, self.sel, self.gw, self.gb, self.fo, dO, out=self.bo, ws=self.ws_bwd)
 
-    if args.stage:
-        step()  # every buffer a later stage reads is filled once
-        fn = {"select": lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel),
-              "fwd": lambda: B.attn_fwd(p_nosave, Q, K, V, vl, sel, gw, gb, out=fo_nosave),
-              "fwd_save": lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo),
-              "bwd": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd),
-              "bwd_gate": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
-                                             stages=B.BWD_GATE),
-              "bwd_dq": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
-                                           stages=B.BWD_DQ),
-              "bwd_dkv": lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd,
-                                            stages=B.BWD_DKV),
-              "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense),
-              # serving: selection and forward of the last query block only (the scored position)
-              "serve": lambda: (B.select_blocks(p_serve, Q, K, vl, sel=sel, ws=ws_sel),
-                                B.attn_fwd(p_serve, Q, K, V, vl, sel, gw, gb, out=fo_nosave)),
-              # a plain device copy of one [B,H,L,d] tensor: calibrates the HBM byte counters
-              "copy": lambda: O_dense.copy_(Q)}[args.stage]
-        for _ in range(args.warmup):
-            fn()
+    def stage_fn(self, name):
+        B, p = self.B, self.p
+        Q, K, V, dO, vl = self.sets[0]
+        sel, gw, gb, fo = self.sel, self.gw, self.gb, self.fo
+        bwd = lambda st: (lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=self.bo, ws=self.ws_bwd, stages=st))
+        return {
+            "select": lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=self.ws_sel),
+            "fwd": lambda: B.attn_fwd(self.p_nosave, Q, K, V, vl, sel, gw, gb, out=self.fo_nosave, ws=self.ws_fwd),
+            "fwd_save": lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo, ws=self.ws_fwd),
+            "bwd": bwd(B.BWD_ALL), "bwd_gate": bwd(B.BWD_GATE), "bwd_inverse": bwd(B.BWD_INVERSE),
+            "bwd_dq": bwd(B.BWD_DQ), "bwd_dkv": bwd(B.BWD_DKV),
+            "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=self.O_dense),
+            # serving: selection and forward of the last query block only (the scored position)
+            "serve": lambda: (B.select_blocks(self.p_serve, Q, K, vl, sel=sel, ws=self.ws_sel),
+                              B.attn_fwd(self.p_serve, Q, K, V, vl, sel, gw, gb, out=self.fo_nosave, ws=self.ws_fwd)),
+            # a plain device copy of one [B,H,L,d] tensor: calibrates the HBM byte counters
+            "copy": lambda: self.O_dense.copy_(Q),
+        }[name]
+
+    def timed(self, fn, reps):
+        """Average launch time in ms with HIP events on the stream the work is launched on."""
+        torch = self.torch
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        fn()
         torch.cuda.synchronize()
-        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-        e0.record()
-        for _ in range(args.steps):
+        ev0.record()
+        for _ in range(reps):
             fn()
-        e1.record()
+        ev1.record()
         torch.cuda.synchronize()
-        print(json.dumps({"stage": args.stage, "workload": w.name, "steps": args.steps,
-                          "avg_ms": round(e0.elapsed_time(e1) / args.steps, 4)}))
-        return
+        return ev0.elapsed_time(ev1) / reps
 
+    def kernel_times(self, reps, dense=True):
+        ms = {k_: self.timed(self.stage_fn(s_), reps) for k_, s_ in (
+            ("select", "select"), ("fwd", "fwd"), ("fwd_saving_for_bwd", "fwd_save"), ("bwd_gate", "bwd_gate"),
+            ("bwd_inverse_list", "bwd_inverse"), ("bwd_dq", "bwd_dq"), ("bwd_dkv", "bwd_dkv"), ("bwd", "bwd"))}
+        ms_dense = self.timed(self.stage_fn("dense"), max(2, reps // 4)) if dense else None
+        return ms, ms_dense
+
+    def work(self):
+        """Algorithmic work per launch: unmasked pairs from the selection lists, bytes from the valid positions."""
+        w = self.w
+        nnz_lt, nnz_st, nnz_dense = algorithmic_pairs(w, self.x.valid_len, self.sel.cpu().numpy())
+        pairs = nnz_lt + nnz_st
+        sz = 4 if w.dtype == "fp32" else 2
+        tensor = float(int(self.x.valid_len.sum())) * w.H * w.d   # elements of the valid positions of one tensor
+        d = w.d
+        # kernel -> (algorithmic flops, flops the kernel executes, bytes).  Forward: QK^T and PV (2d flops each per
+        # unmasked pair).  Backward: five contractions per pair in all (S, dP, dV, dK, dQ = 10d flops, 2.5 x
+        # forward); S and dP are needed by both backward kernels and recomputed in each, so each kernel is
+        # charged half of them algorithmically (dQ: 2d + 2d, dK/dV: 4d + 2d) and executes 6d resp. 8d.
+        # Bytes: every tensor a kernel has to read or write once, valid positions only.
+        table = {
+            "fwd": (4.0 * d * pairs, 4.0 * d * pairs, 4 * tensor * sz),                                   # Q,K,V | O
+            "fwd_saving_for_bwd": (4.0 * d * pairs, 4.0 * d * pairs, 4 * tensor * sz + 2 * tensor * 4),   # + o_lt, o_st
+            "bwd_dq": (4.0 * d * pairs, 6.0 * d * pairs, 5 * tensor * sz),                                # Q,K,V,dO | dQ
+            "bwd_dkv": (6.0 * d * pairs, 8.0 * d * pairs, 6 * tensor * sz),                               # Q,K,V,dO | dK,dV
+            "bwd_gate": (0.0, 0.0, tensor * (sz + 8)),                                                    # dO, o_lt, o_st
+            "select": (0.0, 0.0, 2 * tensor * sz),                                                        # Q, K
+            # the whole backward call: 10d flops per pair; Q,K,V,dO,o_lt,o_st read, dQ,dK,dV written
+            "bwd": (10.0 * d * pairs, 14.0 * d * pairs, 7 * tensor * sz + 2 * tensor * 4),
+        }
+        return table, dict(nnz_lt=nnz_lt, nnz_st=nnz_st, nnz_dense=nnz_dense, pairs=pairs)
+
+
+def roofline_entry(w, kernel, ms, table, traffic):
+    flops, flops_exec, nbytes = table[kernel]
+    mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
+    t = ms[kernel] * 1e-3
+    if flops / (mfma_peak * 1e12) >= nbytes / (HBM_PEAK_GBS * 1e9):
+        a = flops / t / 1e12
+        r = {"bound": "mfma" if w.dtype == "bf16" else "alu", "achieved": round(a, 2), "peak": mfma_peak,
+             "unit": "TFLOP/s", "frac": round(a / mfma_peak, 4)}
+        if flops_exec != flops:
+            r["frac_executed_incl_recompute"] = round(flops_exec / t / 1e12 / mfma_peak, 4)
+    else:
+        a = nbytes / t / 1e9
+        r = {"bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
+             "frac": round(a / HBM_PEAK_GBS, 4)}
+    r.update({"traffic": traffic.get(kernel), "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
+              "algorithmic_gflop": round(flops / 1e9, 2), "algorithmic_mb": round(nbytes / 1e6, 1)})
+    return r
+
+
+def measure_workload(w, args, mods, n_sets, headline):
+    """Times the step and its kernels on workload w; returns the fields of the JSON line (headline) or a
+    short summary (the second workload of the default run)."""
+    torch, B, make_inputs, bf16_bits = mods
+    R = Runner(w, n_sets, torch, B, make_inputs, bf16_bits)
     for i in range(args.warmup):
-        step(i)
+        R.step(i)
     torch.cuda.synchronize()
-    run_step = step
-    if args.graph:
+    run_step = R.step
+    if args.graph and headline:
         # the library allocates nothing and never synchronises: the step is captured as it is
         graph = torch.cuda.CUDAGraph()
         side = torch.cuda.Stream()
         side.wait_stream(torch.cuda.current_stream())
         with torch.cuda.stream(side):
-            step()
+            R.step()
             side.synchronize()
             with torch.cuda.graph(graph, stream=side):
-                step()
+                R.step()
         torch.cuda.current_stream().wait_stream(side)
         torch.cuda.synchronize()
         run_step = lambda i: graph.replay()
@@ -225,141 +280,207 @@ def main():
     wall = time.perf_counter() - t0
     ms_per_step = wall * 1e3 / args.steps
 
-    # ---- per-kernel times with HIP events on the launch stream (separate passes) ----
-    def timed(fn, reps):
-        ev0 = torch.cuda.Event(enable_timing=True)
-        ev1 = torch.cuda.Event(enable_timing=True)
-        fn()
-        torch.cuda.synchronize()
-        ev0.record()
-        for _ in range(reps):
-            fn()
-        ev1.record()
-        torch.cuda.synchronize()
-        return ev0.elapsed_time(ev1) / reps
-
     reps = max(3, args.steps)
-    bwd = lambda st: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=bo, ws=ws_bwd, stages=st)
-    ms = {
-        "select": timed(lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=ws_sel), reps),
-        "fwd": timed(lambda: B.attn_fwd(p_nosave, Q, K, V, vl, sel, gw, gb, out=fo_nosave), reps),
-        "fwd_saving_for_bwd": timed(lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo), reps),
-        "bwd_gate": timed(lambda: bwd(B.BWD_GATE), reps),
-        "bwd_inverse_list": timed(lambda: bwd(B.BWD_INVERSE), reps),
-        "bwd_dq": timed(lambda: bwd(B.BWD_DQ), reps),
-        "bwd_dkv": timed(lambda: bwd(B.BWD_DKV), reps),
-        "bwd": timed(lambda: bwd(B.BWD_ALL), reps),
-    }
-    ms_dense = None
-    if not args.no_dense:
-        ms_dense = timed(lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=O_dense), max(2, reps // 4))
-
-    # ---- algorithmic work (pairs from the selection lists; bytes = tensors touched once) ----
-    sel_h = sel.cpu().numpy()
-    nnz_lt, nnz_st, nnz_dense = algorithmic_pairs(w, x.valid_len, sel_h)
-    pairs = nnz_lt + nnz_st
-    tokens = int(x.valid_len.sum())
-    tokens_timed = sum(int(xs[i % n_sets].valid_len.sum()) for i in range(args.steps))  # over the timed steps
-    sz = 4 if w.dtype == "fp32" else 2
-    tensor = float(w.B) * w.H * w.L * w.d
-    mfma_peak = MFMA_BF16_PEAK_TFLOPS if w.dtype == "bf16" else FP32_VALU_PEAK_TFLOPS
-    # kernel -> (flops, bytes): contractions each kernel has to produce per unmasked pair (2d flops
-    # each) and tensors it has to read or write once
-    work = {
-        "fwd": (4.0 * w.d * pairs, 4 * tensor * sz),                                  # QK^T, PV | Q,K,V,O
-        "fwd_saving_for_bwd": (4.0 * w.d * pairs, 4 * tensor * sz + 2 * tensor * 4),  # + o_lt, o_st fp32
-        "bwd_dq": (6.0 * w.d * pairs, 5 * tensor * sz),                               # S, dP, dQ | Q,K,V,dO,dQ
-        "bwd_dkv": (8.0 * w.d * pairs, 6 * tensor * sz),                              # S, dP, dV, dK | Q,K,V,dO,dK,dV
-        "bwd_gate": (0.0, tensor * (sz + 8)),                                         # dO, o_lt, o_st
-        "select": (0.0, 2 * tensor * sz),                                             # Q, K
-    }
-
-    def roofline(kernel):
-        flops, nbytes = work[kernel]
-        t = ms[kernel] * 1e-3
-        t_mfma = flops / (mfma_peak * 1e12)
-        t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
-        if t_mfma >= t_hbm:
-            a = flops / t / 1e12
-            r = {"bound": "mfma", "achieved": round(a, 2), "peak": mfma_peak, "unit": "TFLOP/s",
-                 "frac": round(a / mfma_peak, 4)}
-        else:
-            a = nbytes / t / 1e9
-            r = {"bound": "hbm", "achieved": round(a, 1), "peak": HBM_PEAK_GBS, "unit": "GB/s",
-                 "frac": round(a / HBM_PEAK_GBS, 4)}
-        r.update({"traffic": None if w.stis_block else MEASURED_TRAFFIC_BYTES.get((w.name, kernel)), "kernel": kernel, "avg_launch_ms": round(ms[kernel], 4),
-                  "algorithmic_gflop": round(flops / 1e9, 2), "algorithmic_mb": round(nbytes / 1e6, 1)})
-        return r
-
+    ms, ms_dense = R.kernel_times(reps, dense=not args.no_dense)
+    table, cnt = R.work()
+    tokens = int(R.x.valid_len.sum())
+    tokens_timed = sum(int(R.xs[i % n_sets].valid_len.sum()) for i in range(args.steps))  # over the timed steps
+    traffic, traffic_sha = ({}, None) if (w.stis_block or args.shape) else profiled_traffic(w.name)
+    roof = lambda k_: roofline_entry(w, k_, ms, table, traffic)
     step_kernels = ["select", "fwd_saving_for_bwd", "bwd_gate", "bwd_dq", "bwd_dkv"]
     dominant = max(step_kernels, key=lambda k_: ms[k_])
     out = {
+        "ms_per_step": round(ms_per_step, 4),
+        "tokens_per_s": round(tokens_timed / wall, 1),
+        "config": {"workload": f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} b={w.block} k={w.topk} "
+                               f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}"
+                               + (f", short-term mask = all of Eq. 15 with mask block {w.stis_block}" if w.stis_block else ""),
+                   "tokens_per_step": tokens, "unmasked_pairs_lt": cnt["nnz_lt"], "unmasked_pairs_st": cnt["nnz_st"],
+                   "launch": "hip graph replay" if (args.graph and headline) else "stream", "input_sets": n_sets},
+        "kernels_ms": {k_: round(v, 4) for k_, v in ms.items()},
+        "fwd_tokens_per_s": round(tokens / ((ms["select"] + ms["fwd"]) * 1e-3), 1),
+        "roofline": roof(dominant),
+        "roofline_fwd": roof("fwd"),
+        "roofline_bwd": roof("bwd"),
+        "roofline_all": {k_: roof(k_)["frac"] for k_ in ("fwd", "fwd_saving_for_bwd", "bwd_dq", "bwd_dkv", "bwd",
+                                                          "bwd_gate", "select")},
+        "traffic_source": (f"profiles/{w.name}_hbm_traffic.txt" if traffic else None),
+    }
+    if ms_dense is not None:
+        flops_dense = 4.0 * w.d * cnt["nnz_dense"]
+        out["dense_causal"] = {"ms": round(ms_dense, 4), "tokens_per_s": round(tokens / (ms_dense * 1e-3), 1),
+                               "tflops": round(flops_dense / (ms_dense * 1e-3) / 1e12, 2),
+                               "sparse_fwd_speedup": round(ms_dense / (ms["select"] + ms["fwd"]), 3)}
+    return out, R
+
+
+def cpu_baseline(R):
+    """The CPU oracle on a bounded sample of the same workload (reported, not a target)."""
+    import oracle
+    w, x = R.w, R.x
+    threads = oracle.num_threads()
+    total_pairs = w.B * w.H
+
+    def run_oracle(n_pairs):
+        prs = np.linspace(0, total_pairs - 1, n_pairs).astype(np.int32)
+        t0 = time.perf_counter()
+        sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk, bh_list=prs)
+        sel_ref = np.where(sel_ref == -2, -1, sel_ref)
+        oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk, w.window,
+                        bh_list=prs, stis_block=w.stis_block)
+        oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block, w.topk,
+                        w.window, bh_list=prs, stis_block=w.stis_block)
+        dt_ = time.perf_counter() - t0
+        toks = float(sum(int(x.valid_len[int(bh) // w.H]) for bh in prs)) / w.H
+        return dt_, toks
+
+    n_pairs = min(total_pairs, threads)
+    cpu_s, sample_tokens = run_oracle(n_pairs)
+    if cpu_s < 8.0 and n_pairs < total_pairs:  # aim at about 15 s of CPU work
+        n_pairs = min(total_pairs, max(n_pairs + 1, int(n_pairs * 15.0 / max(cpu_s, 1e-3))))
+        cpu_s, sample_tokens = run_oracle(n_pairs)
+    cpu_model = "unknown"
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                cpu_model = line.split(":", 1)[1].strip()
+                break
+    except OSError:
+        pass
+    return {"value": round(sample_tokens / cpu_s, 2), "unit": "tokens/s", "cores": threads, "cpu": cpu_model,
+            "kind": "oracle",
+            "sample": f"{n_pairs} of {total_pairs} (row, head) pairs, select+fwd+bwd, {cpu_s:.1f} s; "
+                      f"tokens counted as pairs/H * valid_len"}
+
+
+def run_ceiling(args, torch, B):
+    """bench.py --stage ceiling: the stripped tile loop of the matrix-core forward (blossom_probe), one
+    launch per kind, timed with HIP events; prints what each pipe alone and all of them together cost per
+    64-query x 64-key tile and what that means for the cfg4 forward (311296 such tiles on 256 CUs)."""
+    dev = torch.device("cuda:0")
+    n = B.probe_bytes(0) // 2
+    g = torch.Generator(device=dev).manual_seed(7)
+    K = (torch.randn(n, device=dev, generator=g) / 8).to(torch.bfloat16)
+    V = (torch.randn(n, device=dev, generator=g) / 8).to(torch.bfloat16)
+    sink = torch.empty(B.probe_bytes(1) // 4, dtype=torch.float32, device=dev)
+    iters = 500
+    # a launch: PROBE_WORKGROUPS workgroups x 2 wavefronts x iters steps of 32 keys x 64 queries
+    #         = PROBE_WORKGROUPS x iters tiles of 64 x 64; 256 CUs work on them in parallel
+    tiles_per_cu = B.PROBE_WORKGROUPS * iters / 256.0
+    cfg4_tiles_per_cu = 311296 / 256.0      # 16384 query blocks x 19 tiles (3 window + 16 selected)
+    flops_alg = 284.4e9                     # cfg4 forward, algorithmic (4 d pairs)
+    res = {}
+    for kind, name in enumerate(PROBE_KINDS):
+        B.probe(kind, K, V, sink, iters)
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(3):
+            B.probe(kind, K, V, sink, iters)
+        e1.record()
+        torch.cuda.synchronize()
+        ns_tile = e0.elapsed_time(e1) / 3 * 1e6 / tiles_per_cu
+        us_fwd = ns_tile * cfg4_tiles_per_cu * 1e-3
+        res[name] = {"cu_ns_per_64x64_tile": round(ns_tile, 1), "cfg4_fwd_us_at_this_rate": round(us_fwd, 1),
+                     "cfg4_fwd_mfma_roofline_frac_at_this_rate": round(flops_alg / (us_fwd * 1e-6) / 2.5e15, 3)}
+    mf = res[PROBE_KINDS[0]]["cu_ns_per_64x64_tile"]
+    # kind 0 issues 18 matrix instructions of 32x32x16 per wavefront step, 36 per tile and CU over 4 SIMDs
+    res["mfma_sustained_tflops"] = round(36 * 32 * 32 * 16 * 2 / (mf * 1e-9) * 256 / 1e12, 1)
+    res["staging_bytes_per_clk_per_cu_at_2p1GHz"] = round(16384 / res[PROBE_KINDS[5]]["cu_ns_per_64x64_tile"] / 2.1, 1)
+    print(json.dumps({"stage": "ceiling", "iters": iters, "probe": res}))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="cfg4", help="cfg1..cfg5 (shapes of the five parity configs)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-second-workload", action="store_true",
+                    help="skip the L=1024 training-step workload (cfg5) that the default run times next to cfg4")
+    ap.add_argument("--input-sets", type=int, default=3,
+                    help="independent seeded input sets the timed steps rotate over, so that a small workload is not "
+                         "served from the 256 MB last-level cache (one set with --stage and --graph)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture the step (select + forward + backward) in a HIP graph once and time its replays")
+    ap.add_argument("--shape", default="",
+                    help="overrides of the workload's fields, e.g. B=32,H=8,L=2000,len_lo=2000,len_hi=2000 "
+                         "(the efficiency-study shapes of the paper's Appendix B); the JSON line names them")
+    ap.add_argument("--stis-block", type=int, default=0,
+                    help="0: short-term mask = causal window (default); N >= 1: all of Eq. 15 with mask block N")
+    ap.add_argument("--no-dense", action="store_true")
+    ap.add_argument("--stage", choices=STAGES + ["ceiling"], default=None,
+                    help="profiling aid: run only this stage --steps times (after the others ran once) "
+                         "and print its average time; the headline line is not produced.  'ceiling' runs the "
+                         "stripped tile loop of the matrix-core forward (what each pipe costs alone and together)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU; --gpus N with N > 1 is not supported "
+              "(every (row, head) pair is independent in selection, forward and backward: rows shard over GPUs "
+              "with no exchange in forward and one small all-reduce of the gate gradients in backward).",
+              file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    from paper_2512_13368_amd import binding as B
+    from paper_2512_13368_amd.inputs import WORKLOADS, bf16_bits, make_inputs, with_shape
+
+    torch.cuda.set_device(torch.device("cuda:0"))
+    if args.stage == "ceiling":
+        run_ceiling(args, torch, B)
+        return
+    w = WORKLOADS[args.workload]
+    if args.stis_block:
+        w = with_shape(w, stis_block=args.stis_block)
+    if args.shape:
+        kv = dict(t.split("=") for t in args.shape.split(","))
+        w = with_shape(w, name=w.name + "*", **{k_: int(v_) for k_, v_ in kv.items()})
+    mods = (torch, B, make_inputs, bf16_bits)
+    n_sets = 1 if (args.stage or args.graph) else max(1, args.input_sets)
+
+    if args.stage:
+        R = Runner(w, 1, *mods)
+        R.step()  # every buffer a later stage reads is filled once
+        fn = R.stage_fn(args.stage)
+        for _ in range(args.warmup):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        print(json.dumps({"stage": args.stage, "workload": w.name, "steps": args.steps,
+                          "avg_ms": round(e0.elapsed_time(e1) / args.steps, 4)}))
+        return
+
+    res, R = measure_workload(w, args, mods, n_sets, headline=True)
+    out = {
         "metric": "sparse-attn fwd+bwd tokens/sec (select + forward + backward per step)",
-        "value": round(tokens_timed / (wall), 1),
+        "value": res.pop("tokens_per_s"),
         "unit": "tokens/s",
         "n_gpus": 1,
         "steps": args.steps,
         "warmup": args.warmup,
-        "ms_per_step": round(ms_per_step, 4),
+        "ms_per_step": res.pop("ms_per_step"),
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
         "dtype": w.dtype if w.dtype == "bf16" else "f32",
         "data": "synthetic",
-        "config": {"workload": f"{w.name}: B={w.B} H={w.H} L={w.L} d={w.d} b={w.block} k={w.topk} "
-                               f"w={w.window} {w.dtype}, lens U[{w.len_lo},{w.len_hi}] left-padded, seed {w.seed}"
-                               + (f", short-term mask = all of Eq. 15 with mask block {w.stis_block}" if w.stis_block else ""),
-                   "tokens_per_step": tokens, "unmasked_pairs_lt": nnz_lt, "unmasked_pairs_st": nnz_st,
-                   "launch": "hip graph replay" if args.graph else "stream", "input_sets": n_sets},
-        "kernels_ms": {k_: round(v, 4) for k_, v in ms.items()},
-        "fwd_tokens_per_s": round(tokens / ((ms["select"] + ms["fwd"]) * 1e-3), 1),
-        "roofline": roofline(dominant),
-        "roofline_fwd": roofline("fwd"),
-        "roofline_all": {k_: roofline(k_)["frac"] for k_ in ("fwd", "fwd_saving_for_bwd", "bwd_dq", "bwd_dkv",
-                                                              "bwd_gate", "select")},
     }
-    if ms_dense is not None:
-        flops_dense = 4.0 * w.d * nnz_dense
-        out["dense_causal"] = {"ms": round(ms_dense, 4), "tokens_per_s": round(tokens / (ms_dense * 1e-3), 1),
-                               "tflops": round(flops_dense / (ms_dense * 1e-3) / 1e12, 2),
-                               "sparse_fwd_speedup": round(ms_dense / (ms["select"] + ms["fwd"]), 3)}
-
-    # ---- CPU oracle on a bounded sample of the same workload (reported, not a target) ----
+    out.update(res)
+    # ---- CPU oracle on a bounded sample of the same workload ----
     if not args.no_cpu_baseline:
-        import oracle
-        threads = oracle.num_threads()
-        total_pairs = w.B * w.H
-
-        def run_oracle(n_pairs):
-            prs = np.linspace(0, total_pairs - 1, n_pairs).astype(np.int32)
-            t0 = time.perf_counter()
-            sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk, bh_list=prs)
-            sel_ref = np.where(sel_ref == -2, -1, sel_ref)
-            oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk, w.window,
-                            bh_list=prs, stis_block=w.stis_block)
-            oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block, w.topk,
-                            w.window, bh_list=prs, stis_block=w.stis_block)
-            dt_ = time.perf_counter() - t0
-            toks = float(sum(int(x.valid_len[int(bh) // w.H]) for bh in prs)) / w.H
-            return dt_, toks
-
-        n_pairs = min(total_pairs, threads)
-        cpu_s, sample_tokens = run_oracle(n_pairs)
-        if cpu_s < 8.0 and n_pairs < total_pairs:  # aim at about 15 s of CPU work
-            n_pairs = min(total_pairs, max(n_pairs + 1, int(n_pairs * 15.0 / max(cpu_s, 1e-3))))
-            cpu_s, sample_tokens = run_oracle(n_pairs)
-        cpu_model = "unknown"
-        try:
-            for line in open("/proc/cpuinfo"):
-                if line.startswith("model name"):
-                    cpu_model = line.split(":", 1)[1].strip()
-                    break
-        except OSError:
-            pass
-        out["cpu_baseline"] = {"value": round(sample_tokens / cpu_s, 2), "unit": "tokens/s",
-                               "cores": threads, "cpu": cpu_model, "kind": "oracle",
-                               "sample": f"{n_pairs} of {total_pairs} (row, head) pairs, select+fwd+bwd, "
-                                         f"{cpu_s:.1f} s; tokens counted as pairs/H * valid_len"}
+        out["cpu_baseline"] = cpu_baseline(R)
+    # ---- the metric's other half: the L=1024 training step (cfg5), timed the same way in the same run ----
+    if args.workload == "cfg4" and not (args.shape or args.stis_block or args.no_second_workload or args.graph):
+        del R
+        torch.cuda.empty_cache()
+        res5, _ = measure_workload(WORKLOADS["cfg5"], args, mods, n_sets, headline=False)
+        out["l1024_training_step"] = res5
     print(json.dumps(out))
 
 

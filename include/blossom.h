@@ -221,6 +221,24 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
                              const int32_t *valid_len, void *O, float *lse,
                              void *ws, size_t ws_bytes, void *hip_stream);
 
+/*
+ * Measured ceilings of the matrix-core forward (Eq. 1 as tiled QK^T / softmax / PV for the
+ * long-term and short-term branches, Eq. 16-17) on the GPU at hand: a stripped copy of its
+ * steady-state tile loop for block size 64 and d = 64, with the same instruction mix and memory
+ * access patterns but no masks, reference moves, tile list, prologue or epilogue.  A benchmark
+ * times one launch and divides; no result is meaningful beyond "it ran".  The launch puts
+ * BLOSSOM_PROBE_WORKGROUPS workgroups of two wavefronts on the chip (256 CUs x 4 resident x 4
+ * rounds); every wavefront runs `iters` (even, >= 2) steps of 32 keys x 64 queries each.
+ *   kind   0 matrix instructions only; 1 softmax VALU work only; 2 both, operands in registers;
+ *          3 both, operands read from LDS; 4 the whole loop with global->LDS staging; 5 staging only
+ *   K, V   in   bf16, blossom_probe_bytes(0) bytes each (contents: any finite values)
+ *   sink   out  fp32, blossom_probe_bytes(1) bytes
+ * Errors: BLOSSOM_ERR_NULL, BLOSSOM_ERR_PARAM (kind, iters), BLOSSOM_ERR_ALIGN, BLOSSOM_ERR_LAUNCH.
+ */
+#define BLOSSOM_PROBE_WORKGROUPS 4096
+size_t blossom_probe_bytes(int which);
+int blossom_probe(int kind, const void *K, const void *V, float *sink, int iters, void *hip_stream);
+
 /* Static, human-readable text for an error code (host). */
 const char *blossom_strerror(int code);
 

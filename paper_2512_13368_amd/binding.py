@@ -18,7 +18,8 @@ F32, BF16 = 0, 1
 WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
 EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp", "blossom_attn_fwd", "blossom_attn_bwd",
-           "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_strerror", "blossom_version")
+           "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_probe_bytes", "blossom_probe", "blossom_strerror", "blossom_version")
+PROBE_WORKGROUPS = 4096
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
 
 
@@ -69,6 +70,10 @@ def lib() -> ctypes.CDLL:
         L.blossom_attn_bwd_stages.argtypes = L.blossom_attn_bwd.argtypes + [ctypes.c_uint]
         L.blossom_dense_causal_fwd.restype = ctypes.c_int
         L.blossom_dense_causal_fwd.argtypes = [pp, vp, vp, vp, i32p, vp, fp, vp, ctypes.c_size_t, vp]
+        L.blossom_probe_bytes.restype = ctypes.c_size_t
+        L.blossom_probe_bytes.argtypes = [ctypes.c_int]
+        L.blossom_probe.restype = ctypes.c_int
+        L.blossom_probe.argtypes = [ctypes.c_int, vp, vp, fp, ctypes.c_int, vp]
         L.blossom_strerror.restype = ctypes.c_char_p
         L.blossom_strerror.argtypes = [ctypes.c_int]
         L.blossom_version.restype = ctypes.c_char_p
@@ -315,3 +320,14 @@ def dense_causal_fwd(p: Params, Q, K, V, valid_len, O=None, lse=None, ws=None, s
     if rc:
         raise BlossomError(rc, "blossom_dense_causal_fwd")
     return O, lse
+
+
+def probe_bytes(which: int) -> int:
+    return int(lib().blossom_probe_bytes(which))
+
+
+def probe(kind: int, K, V, sink, iters: int, stream=None):
+    """blossom_probe: one launch of the stripped tile loop (the caller times it)."""
+    rc = lib().blossom_probe(int(kind), _ptr(K), _ptr(V), _ptr(sink), int(iters), _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_probe")

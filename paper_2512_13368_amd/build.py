@@ -21,6 +21,7 @@ SOURCES = {
     # (the forward kernel also reuses its bf16 staging rows as fp32 exchange space between wavefronts)
     "mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-strict-aliasing"],
     "mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "probe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",
