@@ -61,6 +61,10 @@ def lib() -> ctypes.CDLL:
         L.oracle_dense_causal_fwd.restype = _c_int
         L.oracle_dense_causal_fwd.argtypes = ([_c_int] * 4 + [_c_dbl, _c_int] + [_vp] * 4
                                               + [_vp, _c_int, _vp, _vp])
+        L.oracle_rope.restype = _c_int
+        L.oracle_rope.argtypes = [_c_int, _c_int, _c_int, _vp, _vp, _vp, _c_int, _vp]
+        L.oracle_rope_bwd.restype = _c_int
+        L.oracle_rope_bwd.argtypes = [_c_int, _c_int, _c_int, _vp, _vp, _vp, _vp]
         _lib = L
     return _lib
 
@@ -245,3 +249,27 @@ def dense_causal_fwd(Q, K, V, valid_len, scale=None, bh_list=None, f64=False):
                                        _p(vl), _p(bh), n_bh, _p(O), _p(lse))
     _check(rc, "dense_causal_fwd")
     return O, lse
+
+
+def rope(x, cos, sin, to_bf16=False):
+    """Step 0: rotary position embedding of x [..., L, d] (fp32 recipe of the C file's header) with the
+    caller's tables cos, sin [L, d/2] float32.  to_bf16 rounds the result to bf16 values."""
+    x = _in(x, False)
+    L, d = x.shape[-2:]
+    cos = _in(cos, False)
+    sin = _in(sin, False)
+    assert cos.shape == (L, d // 2) and sin.shape == (L, d // 2)
+    out = np.empty_like(x)
+    _check(lib().oracle_rope(int(x.size // (L * d)), L, d, _p(x), _p(cos), _p(sin), int(bool(to_bf16)), _p(out)), "rope")
+    return out
+
+
+def rope_bwd(g, cos, sin):
+    """Gradient w.r.t. the unrotated rows from the gradient g [..., L, d] (float64) w.r.t. the rotated ones."""
+    g = _in(g, True)
+    L, d = g.shape[-2:]
+    cos = _in(cos, False)
+    sin = _in(sin, False)
+    out = np.empty_like(g)
+    _check(lib().oracle_rope_bwd(int(g.size // (L * d)), L, d, _p(g), _p(cos), _p(sin), _p(out)), "rope_bwd")
+    return out

@@ -34,6 +34,8 @@
  *   6. Gate (Eq. 18-19): alpha = sigmoid(Wg . [o_lt ; o_st] + bg) per
  *      (position, head); O = alpha*o_lt + (1-alpha)*o_st.
  *   7. Backward: the chain rule through steps 4-6 with the selection frozen.
+ *   0. (ahead of step 1, optional) Rotary position embedding of Q and K (Sec. 3.3: applied to
+ *      the projected queries and keys before both branches): oracle_rope / oracle_rope_bwd.
  *
  * Both branch masks are materialised as L x L byte matrices and the attention
  * is the masked softmax of Eq. 1 written out; nothing is blocked, fused or
@@ -44,6 +46,13 @@
  *   Kmean_J[c] = (same kind of sum over K) / (float)count, IEEE division
  *   s[I][J]    = acc = +0.0f; for c = 0..d-1: acc = fmaf(Qsum_I[c], Kmean_J[c], acc)
  * Build with -ffp-contract=off and without fast-math.
+ *
+ * Canonical fp32 rotary recipe (the rotated values are rounded to the storage type and then
+ * decide the block selection, so both sides must produce the same bits).  The paper only names
+ * the method (RoFormer): channel pairs (2i, 2i+1) of the row at position m are rotated by the
+ * angle of table entry [m][i]; cos and sin tables are inputs, fp32 [L][d/2]:
+ *   t = x1*s (rounded);  x0' = fmaf(x0, c, -t);   u = x1*c (rounded);  x1' = fmaf(x0, s, u)
+ * then, for bf16 storage, round to nearest even.  Position m is the index in the padded row.
  *
  * Parity status: every function here is pinned by tests/test_oracle_*.py
  * (dense special case against a library attention routine, forced gates,
@@ -197,6 +206,61 @@ int oracle_select_blocks_cmp(int B, int H, int L, int d, int b, int k,
 
 /* ------------------------------------------------------------------------- */
 /* The two masks, materialised (Eq. 14 as a mask; Eq. 15, causal).             */
+/* ------------------------------------------------------------------------- */
+/* Step 0: rotary position embedding (Sec. 3.3).  x, out: [B*H][L][d] fp32;    */
+/* cosv, sinv: [L][d/2] fp32.  to_bf16 != 0 rounds the result to bf16 values.  */
+/* ------------------------------------------------------------------------- */
+static float round_to_bf16_value(float x)
+{
+    uint32_t u;
+    memcpy(&u, &x, 4);
+    const uint32_t lsb = (u >> 16) & 1u;
+    u = u + 0x7FFFu + lsb;          /* nearest, ties to even (finite inputs) */
+    u &= 0xFFFF0000u;
+    memcpy(&x, &u, 4);
+    return x;
+}
+
+int oracle_rope(int BH, int L, int d, const float *x, const float *cosv, const float *sinv, int to_bf16,
+                float *out)
+{
+    if (d % 2) return -1;
+    for (int r = 0; r < BH; ++r)
+        for (int m = 0; m < L; ++m)
+            for (int i = 0; i < d / 2; ++i) {
+                const size_t at = ((size_t)r * L + m) * d + 2 * i;
+                const float c = cosv[(size_t)m * (d / 2) + i], sn = sinv[(size_t)m * (d / 2) + i];
+                const float x0 = x[at], x1 = x[at + 1];
+                const float t = x1 * sn;
+                float y0 = fmaf(x0, c, -t);
+                const float u = x1 * c;
+                float y1 = fmaf(x0, sn, u);
+                if (to_bf16) {
+                    y0 = round_to_bf16_value(y0);
+                    y1 = round_to_bf16_value(y1);
+                }
+                out[at] = y0;
+                out[at + 1] = y1;
+            }
+    return 0;
+}
+
+/* Backward of the rotation: the gradient w.r.t. the unrotated row is the transpose rotation of */
+/* the gradient w.r.t. the rotated one (fp64).  g, out: [BH][L][d].                              */
+int oracle_rope_bwd(int BH, int L, int d, const double *g, const float *cosv, const float *sinv, double *out)
+{
+    if (d % 2) return -1;
+    for (int r = 0; r < BH; ++r)
+        for (int m = 0; m < L; ++m)
+            for (int i = 0; i < d / 2; ++i) {
+                const size_t at = ((size_t)r * L + m) * d + 2 * i;
+                const double c = cosv[(size_t)m * (d / 2) + i], sn = sinv[(size_t)m * (d / 2) + i];
+                out[at] = c * g[at] + sn * g[at + 1];
+                out[at + 1] = -sn * g[at] + c * g[at + 1];
+            }
+    return 0;
+}
+
 /* ------------------------------------------------------------------------- */
 static int is_power_of_two(int x) { return x >= 1 && (x & (x - 1)) == 0; }
 

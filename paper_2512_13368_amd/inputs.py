@@ -119,3 +119,13 @@ def make_inputs(w: Workload, input_set: int = 0, want_dO: bool | None = None) ->
         if w.dtype == "bf16":
             dO = round_to_bf16(dO)
     return Inputs(w, Q, K, V, valid_len, gate_w, gate_b, dO)
+
+
+def rope_tables(L: int, d: int, base: float = 10000.0):
+    """cos/sin tables [L, d/2] float32 of the rotary position embedding (Sec. 3.3): entry [m][i] holds the
+    angle m * base**(-2i/d), evaluated in float64 and rounded once.  An input of both the oracle and
+    the HIP path, like the gate weights; the rotation itself is theirs."""
+    m = np.arange(L, dtype=np.float64)[:, None]
+    inv = base ** (-2.0 * np.arange(d // 2, dtype=np.float64) / d)[None, :]
+    ang = m * inv
+    return np.cos(ang).astype(np.float32), np.sin(ang).astype(np.float32)
