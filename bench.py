@@ -115,7 +115,7 @@ def algorithmic_pairs(w, valid_len, sel):
     return lt, st, dense
 
 
-STAGES = ["select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "dense", "serve", "copy"]
+STAGES = ["select", "rope_select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "dense", "serve", "copy"]
 PROBE_KINDS = ["matrix instructions only", "softmax VALU work only", "both, operands in registers",
                "both, operands from LDS", "whole tile loop (with global->LDS staging)", "staging only"]
 
@@ -170,6 +170,8 @@ class Runner:
         bwd = lambda st: (lambda: B.attn_bwd(p, Q, K, V, vl, sel, gw, gb, fo, dO, out=self.bo, ws=self.ws_bwd, stages=st))
         return {
             "select": lambda: B.select_blocks(p, Q, K, vl, sel=sel, ws=self.ws_sel),
+            # selection with the rotary position embedding of Q and K fused into its pooling pass
+            "rope_select": lambda: self._rope_select()(),
             "fwd": lambda: B.attn_fwd(self.p_nosave, Q, K, V, vl, sel, gw, gb, out=self.fo_nosave, ws=self.ws_fwd),
             "fwd_save": lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo, ws=self.ws_fwd),
             "bwd": bwd(B.BWD_ALL), "bwd_gate": bwd(B.BWD_GATE), "bwd_inverse": bwd(B.BWD_INVERSE),
@@ -181,6 +183,17 @@ class Runner:
             # a plain device copy of one [B,H,L,d] tensor: calibrates the HBM byte counters
             "copy": lambda: self.O_dense.copy_(Q),
         }[name]
+
+    def _rope_select(self):
+        if getattr(self, "_rope_fn", None) is None:  # tables and output buffers are made on first use, once
+            from paper_2512_13368_amd.inputs import rope_tables
+            torch, B, w = self.torch, self.B, self.w
+            Q, K, V, dO, vl = self.sets[0]
+            cos, sin = (torch.from_numpy(t).to(Q.device) for t in rope_tables(w.L, w.d))
+            Qr, Kr = torch.empty_like(Q), torch.empty_like(K)
+            self._rope_fn = lambda: B.rope_select_blocks(self.p, Q, K, cos, sin, vl, Q_rot=Qr, K_rot=Kr, sel=self.sel,
+                                                        ws=self.ws_sel)
+        return self._rope_fn
 
     def timed(self, fn, reps):
         """Average launch time in ms with HIP events on the stream the work is launched on."""

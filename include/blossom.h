@@ -135,6 +135,24 @@ int blossom_select_blocks_static(const blossom_params *p, const void *Q, const v
                                  const int32_t *valid_len, int32_t *sel, void *hip_stream);
 
 /*
+ * Rotary position embedding (Sec. 3.3: RoPE is applied to the projected Q and K before both branches)
+ * fused into the pooling pass of blossom_select_blocks, which reads Q and K anyway: every position m of
+ * every row is rotated on the way in, channel pairs (2i, 2i+1) by the angle of table entry [m][i],
+ * rounded to the storage type and written to Q_rot / K_rot; the pooled sums, the scores and the
+ * selection are those of the rotated tensors, which are what blossom_attn_fwd / blossom_attn_bwd_rope
+ * then take as Q and K.  Against a separate rotation pass this saves one read of Q and of K.
+ * Fixed fp32 recipe (the rotated bits decide the selection):
+ *   t = x1*s;  x0' = fma(x0, c, -t);  u = x1*c;  x1' = fma(x0, s, u)     (c, s = cos, sin of the angle)
+ *   rope_cos, rope_sin  in   fp32 [L, d/2], 16-byte aligned (e.g. the angles m * 10000^(-2i/d))
+ *   Q_rot, K_rot        out  [B,H,L,d], element type as Q; padding positions are rotated too
+ *   everything else as blossom_select_blocks.  With last_block_only, Q_rot holds the last query
+ *   block only (K_rot is complete).
+ */
+int blossom_rope_select_blocks(const blossom_params *p, const void *Q, const void *K, const float *rope_cos,
+                               const float *rope_sin, const int32_t *valid_len, void *Q_rot, void *K_rot,
+                               int32_t *sel, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * The same selection with the block compression left to the caller (Sec. 3.4, Eq. 9: a learnable
  * phi): Kcmp holds one compressed key phi(K_J) per key block and takes the place of Kmean_J in
  * the score above, converted to fp32 as it is (rows of blocks before J_first are not read as
@@ -191,6 +209,21 @@ int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, cons
                      const void *dO,
                      void *dQ, void *dK, void *dV, float *d_gate_w, float *d_gate_b,
                      void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * blossom_attn_bwd for Q and K that came out of blossom_rope_select_blocks (pass Q_rot, K_rot as Q, K):
+ * dQ and dK are the gradients w.r.t. the tensors BEFORE the rotation, i.e. the kernels rotate every
+ * gradient row back (the transpose rotation, in fp32, before rounding to the storage type) in their
+ * store epilogues; no extra pass over dQ or dK.  dV and the gate gradients are unchanged.
+ *   rope_cos, rope_sin  in   the tables given to blossom_rope_select_blocks
+ */
+int blossom_attn_bwd_rope(const blossom_params *p, const void *Q, const void *K, const void *V,
+                          const int32_t *valid_len, const int32_t *sel,
+                          const float *gate_w, const float *gate_b,
+                          const void *o_lt, const void *o_st, const float *lse_lt, const float *lse_st,
+                          const void *dO, const float *rope_cos, const float *rope_sin,
+                          void *dQ, void *dK, void *dV, float *d_gate_w, float *d_gate_b,
+                          void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * The passes of blossom_attn_bwd one at a time, for profilers and benchmarks that need one

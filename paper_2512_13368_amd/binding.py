@@ -17,7 +17,8 @@ LIB_PATH = os.path.join(_HERE, "libblossom.so")
 F32, BF16 = 0, 1
 WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
-EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp", "blossom_attn_fwd", "blossom_attn_bwd",
+EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp",
+           "blossom_rope_select_blocks", "blossom_attn_bwd_rope", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_probe_bytes", "blossom_probe", "blossom_strerror", "blossom_version")
 PROBE_WORKGROUPS = 4096
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
@@ -58,6 +59,8 @@ def lib() -> ctypes.CDLL:
         L.blossom_select_blocks.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_select_blocks_static.restype = ctypes.c_int
         L.blossom_select_blocks_static.argtypes = [pp, vp, vp, i32p, i32p, vp]
+        L.blossom_rope_select_blocks.restype = ctypes.c_int
+        L.blossom_rope_select_blocks.argtypes = [pp, vp, vp, fp, fp, i32p, vp, vp, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_select_blocks_cmp.restype = ctypes.c_int
         L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
@@ -66,6 +69,9 @@ def lib() -> ctypes.CDLL:
         L.blossom_attn_bwd.restype = ctypes.c_int
         L.blossom_attn_bwd.argtypes = [pp, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, fp, fp, vp, vp, vp, vp,
                                        fp, fp, vp, ctypes.c_size_t, vp]
+        L.blossom_attn_bwd_rope.restype = ctypes.c_int
+        L.blossom_attn_bwd_rope.argtypes = [pp, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, fp, fp, vp, fp, fp, vp, vp, vp,
+                                            fp, fp, vp, ctypes.c_size_t, vp]
         L.blossom_attn_bwd_stages.restype = ctypes.c_int
         L.blossom_attn_bwd_stages.argtypes = L.blossom_attn_bwd.argtypes + [ctypes.c_uint]
         L.blossom_dense_causal_fwd.restype = ctypes.c_int
@@ -189,6 +195,36 @@ def select_blocks_static(p: Params, Q, K, valid_len, sel, stream=None):
     return sel
 
 
+def rope_select_blocks(p: Params, Q, K, rope_cos, rope_sin, valid_len, Q_rot=None, K_rot=None, sel=None, ws=None,
+                       stream=None):
+    """blossom_rope_select_blocks: returns (Q_rot, K_rot, sel)."""
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    dt = _torch_dtype(p)
+    _check_tensor(Q, shp, dt, "Q")
+    _check_tensor(K, shp, dt, "K")
+    _check_tensor(rope_cos, (p.L, p.d // 2), torch.float32, "rope_cos")
+    _check_tensor(rope_sin, (p.L, p.d // 2), torch.float32, "rope_sin")
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    if Q_rot is None:
+        Q_rot = torch.empty(shp, dtype=dt, device=Q.device)
+    if K_rot is None:
+        K_rot = torch.empty(shp, dtype=dt, device=Q.device)
+    _check_tensor(Q_rot, shp, dt, "Q_rot")
+    _check_tensor(K_rot, shp, dt, "K_rot")
+    if sel is None:
+        sel = torch.empty((p.B, p.H, p.NB, p.topk), dtype=torch.int32, device=Q.device)
+    _check_tensor(sel, (p.B, p.H, p.NB, p.topk), torch.int32, "sel")
+    ws, nbytes = _workspace(p, WS_SELECT, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_rope_select_blocks(ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(rope_cos), _ptr(rope_sin),
+                                          _ptr(valid_len), _ptr(Q_rot), _ptr(K_rot), _ptr(sel), _ptr(ws), nbytes,
+                                          _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_rope_select_blocks")
+    return Q_rot, K_rot, sel
+
+
 def select_blocks_cmp(p: Params, Q, Kcmp, valid_len, sel=None, ws=None, stream=None):
     """blossom_select_blocks_cmp: Kcmp [B,H,NB,d] holds the caller's compressed keys."""
     import torch
@@ -259,7 +295,8 @@ class BwdOut:
 
 
 def attn_bwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b, fwd: FwdOut, dO,
-             out: BwdOut | None = None, ws=None, stream=None, stages: int = BWD_ALL) -> BwdOut:
+             out: BwdOut | None = None, ws=None, stream=None, stages: int = BWD_ALL, rope=None) -> BwdOut:
+    """blossom_attn_bwd (or _stages); rope=(cos, sin) calls blossom_attn_bwd_rope instead."""
     import torch
     shp = (p.B, p.H, p.L, p.d)
     dt = _torch_dtype(p)
@@ -293,7 +330,13 @@ def attn_bwd(p: Params, Q, K, V, valid_len, sel, gate_w, gate_b, fwd: FwdOut, dO
     args = (ctypes.byref(cp), _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len), _ptr(sel), _ptr(gate_w), _ptr(gate_b),
             _ptr(fwd.o_lt), _ptr(fwd.o_st), _ptr(fwd.lse_lt), _ptr(fwd.lse_st), _ptr(dO), _ptr(out.dQ),
             _ptr(out.dK), _ptr(out.dV), _ptr(out.d_gate_w), _ptr(out.d_gate_b), _ptr(ws), nbytes, _stream(stream))
-    if stages == BWD_ALL:
+    if rope is not None:
+        _check_tensor(rope[0], (p.L, p.d // 2), torch.float32, "rope_cos")
+        _check_tensor(rope[1], (p.L, p.d // 2), torch.float32, "rope_sin")
+        if stages != BWD_ALL:
+            raise ValueError("blossom_attn_bwd_rope runs all passes")
+        rc = lib().blossom_attn_bwd_rope(*args[:13], _ptr(rope[0]), _ptr(rope[1]), *args[13:])
+    elif stages == BWD_ALL:
         rc = lib().blossom_attn_bwd(*args)
     else:
         rc = lib().blossom_attn_bwd_stages(*args, stages)

@@ -60,6 +60,8 @@ int check_params(const blossom_params *p, KParams *kp)
   kp->sblk = p->stis_mode == 1 ? (p->stis_block > 0 ? p->stis_block : p->block) : 0;
   kp->last_lo = kp->sblk > 0 ? p->L - kp->sblk : 0x3FFFFFFF;
   kp->nq = p->last_block_only ? 1 : (int)NB;
+  kp->rope_cos = nullptr;
+  kp->rope_sin = nullptr;
   return BLOSSOM_OK;
 }
 
@@ -137,6 +139,26 @@ int blossom_select_blocks_static(const blossom_params *p, const void *Q, const v
   return launch_status();
 }
 
+int blossom_rope_select_blocks(const blossom_params *p, const void *Q, const void *K, const float *rope_cos,
+                               const float *rope_sin, const int32_t *valid_len, void *Q_rot, void *K_rot,
+                               int32_t *sel, void *ws, size_t ws_bytes, void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (!Q || !K || !rope_cos || !rope_sin || !valid_len || !Q_rot || !K_rot || !sel) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(Q_rot) || !aligned16(K_rot) || !aligned16(rope_cos) ||
+      !aligned16(rope_sin))
+    return BLOSSOM_ERR_ALIGN;
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_SELECT, ws, ws_bytes);
+  if (rc) return rc;
+  kp.rope_cos = rope_cos;
+  kp.rope_sin = rope_sin;
+  clear_stale_error();
+  launch_select(kp, p->dtype, Q, K, false, valid_len, sel, ws, (hipStream_t)hip_stream, Q_rot, K_rot);
+  return launch_status();
+}
+
 int blossom_select_blocks_cmp(const blossom_params *p, const void *Q, const void *Kcmp,
                               const int32_t *valid_len, int32_t *sel, void *ws, size_t ws_bytes,
                               void *hip_stream)
@@ -180,16 +202,20 @@ int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, cons
   return launch_status();
 }
 
-int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *K, const void *V,
-                            const int32_t *valid_len, const int32_t *sel, const float *gate_w,
-                            const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
-                            const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
-                            float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream,
-                            unsigned stages)
+static int attn_bwd_impl(const blossom_params *p, const void *Q, const void *K, const void *V,
+                         const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                         const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                         const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
+                         float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream,
+                         unsigned stages, const float *rope_cos, const float *rope_sin)
 {
   KParams kp;
   int rc = check_params(p, &kp);
   if (rc) return rc;
+  if ((rope_cos == nullptr) != (rope_sin == nullptr)) return BLOSSOM_ERR_NULL;
+  if (!aligned16(rope_cos) || !aligned16(rope_sin)) return BLOSSOM_ERR_ALIGN;
+  kp.rope_cos = rope_cos;
+  kp.rope_sin = rope_sin;
   if (p->last_block_only) return BLOSSOM_ERR_UNSUPPORTED;  // serving mode has no backward
   if (!Q || !K || !V || !valid_len || !sel || !gate_w || !o_lt || !o_st || !lse_lt || !lse_st ||
       !dO || !dQ || !dK || !dV || !d_gate_w)
@@ -207,6 +233,29 @@ int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *
   clear_stale_error();
   launch_bwd(kp, p->dtype, a, stages & kBwdStageAll, (hipStream_t)hip_stream);
   return launch_status();
+}
+
+int blossom_attn_bwd_stages(const blossom_params *p, const void *Q, const void *K, const void *V,
+                            const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                            const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                            const float *lse_st, const void *dO, void *dQ, void *dK, void *dV,
+                            float *d_gate_w, float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream,
+                            unsigned stages)
+{
+  return attn_bwd_impl(p, Q, K, V, valid_len, sel, gate_w, gate_b, o_lt, o_st, lse_lt, lse_st, dO, dQ, dK, dV,
+                       d_gate_w, d_gate_b, ws, ws_bytes, hip_stream, stages, nullptr, nullptr);
+}
+
+int blossom_attn_bwd_rope(const blossom_params *p, const void *Q, const void *K, const void *V,
+                          const int32_t *valid_len, const int32_t *sel, const float *gate_w,
+                          const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                          const float *lse_st, const void *dO, const float *rope_cos, const float *rope_sin,
+                          void *dQ, void *dK, void *dV, float *d_gate_w, float *d_gate_b, void *ws,
+                          size_t ws_bytes, void *hip_stream)
+{
+  if (!rope_cos || !rope_sin) return BLOSSOM_ERR_NULL;
+  return attn_bwd_impl(p, Q, K, V, valid_len, sel, gate_w, gate_b, o_lt, o_st, lse_lt, lse_st, dO, dQ, dK, dV,
+                       d_gate_w, d_gate_b, ws, ws_bytes, hip_stream, kBwdStageAll, rope_cos, rope_sin);
 }
 
 int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, const void *V,

@@ -17,6 +17,9 @@ struct KParams {
   int sblk;     // mask block size of the full short-term mask (Eq. 15); 0 = local window only
   int last_lo;  // first of the last sblk positions (L - sblk); INT_MAX/2 when sblk == 0
   int nq;       // query blocks walked by select and forward: NB, or 1 (the last one) in serving mode
+  // rotary position embedding (Sec. 3.3): cos/sin tables fp32 [L, d/2], or nullptr.  Backward kernels
+  // then store dQ and dK rotated back (the gradient w.r.t. the rows before the rotation).
+  const float *rope_cos, *rope_sin;
 };
 
 // ---- short-term mask, Eq. 15 in its causal form (callers guarantee j <= i, both valid) ----
@@ -96,5 +99,22 @@ __device__ __forceinline__ void store4(bf16_t *p, const float (&o)[4])
 }
 
 __device__ __forceinline__ int clamp_len(int n, int L) { return n < 0 ? 0 : (n > L ? L : n); }
+
+// Backward of the rotary position embedding on one channel pair (2i, 2i+1) of the row at position m:
+// the transpose rotation, applied to the fp32 gradient before it is rounded to the storage type.
+__device__ __forceinline__ void unrope_pair(const KParams &p, int m, int pair, int half_d, float &g0, float &g1)
+{
+  const float c = p.rope_cos[(size_t)m * half_d + pair], s = p.rope_sin[(size_t)m * half_d + pair];
+  const float a = g0, b = g1;
+  g0 = fmaf(c, a, s * b);
+  g1 = fmaf(c, b, -(s * a));
+}
+template <int D>
+__device__ __forceinline__ void unrope_row(const KParams &p, int m, float (&g)[D])
+{
+  if (!p.rope_cos) return;
+#pragma unroll
+  for (int i = 0; i < D / 2; ++i) unrope_pair(p, m, i, D / 2, g[2 * i], g[2 * i + 1]);
+}
 
 }  // namespace blossom

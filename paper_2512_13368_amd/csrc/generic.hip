@@ -660,6 +660,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 
   if (phase == 0 && in_range) {
 #pragma unroll
     for (int c = 0; c < D; ++c) dq[c] *= p.scale;
+    unrope_row<D>(p, i, dq);
     store_row<T, D>(dQ + rowoff, dq);
   }
 }
@@ -946,6 +947,7 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     if (want_dk) {
 #pragma unroll
       for (int c = 0; c < D; ++c) acck[c] *= p.scale;
+      unrope_row<D>(p, j, acck);
       store_row<T, D>(dK + outoff, acck);
     }
     if (want_dv) store_row<T, D>(dV + outoff, accv);

@@ -50,8 +50,9 @@ struct BwdArgs {
 // select.hip
 size_t select_workspace_bytes(const KParams &p);
 // (kcmp: K holds the caller's compressed keys [B,H,NB,d] instead of the keys themselves)
+// (p.rope_cos set: the pooling pass rotates Q and K on the way in and writes them to Q_rot, K_rot)
 void launch_select(const KParams &p, int dtype, const void *Q, const void *K, bool kcmp, const int *valid_len,
-                   int *sel, void *ws, hipStream_t st);
+                   int *sel, void *ws, hipStream_t st, void *Q_rot = nullptr, void *K_rot = nullptr);
 
 // Backward workspace, carved from the caller's buffer.
 struct BwdWorkspace {

@@ -173,20 +173,31 @@ __device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x
 // (free once the walk is over; chunks XOR-swizzled against bank conflicts) and leave as whole
 // 128-byte rows, 8 rows per store instruction, non-temporal (nothing in this library reads the
 // gradients back).  Rows that are not kept are stored as zeros, rows at or past rows_left not at all.
+// `unrope` (dQ and dK when the caller's Q and K went through the rotary position embedding): the rows
+// are rotated back first; a lane's four consecutive channels are two whole channel pairs.  m_row0 is
+// the position of the first of the 32 rows, L the sequence length (rows past it are never stored).
 __device__ __forceinline__ void store_rows_bf16(uint16_t *dst_row0, int rows_left, uint16_t *pt, const f32x16 (&acc)[2],
-                                                float scale, bool keep)
+                                                float scale, bool keep, const KParams &p, bool unrope = false, int m_row0 = 0)
 {
   int el;  // the lane id, rebuilt here so that none of the addressing below is computed ahead of the walk
   asm volatile("v_mbcnt_lo_u32_b32 %0, -1, 0\n\tv_mbcnt_hi_u32_b32 %0, -1, %0" : "=v"(el));
   const int elq = el & 31, elh = el >> 5;
   const float sc = keep ? scale : 0.0f;
+  const bool rot = unrope && p.rope_cos != nullptr;
+  const int m = min(m_row0 + elq, p.L - 1);
 #pragma unroll
   for (int mb = 0; mb < 2; ++mb)
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
+      float v0 = acc[mb][4 * g], v1 = acc[mb][4 * g + 1], v2 = acc[mb][4 * g + 2], v3 = acc[mb][4 * g + 3];
+      if (rot) {
+        const int pair = 16 * mb + 4 * g + 2 * elh;  // channels 32*mb + 8*g + 4*elh + (0..3)
+        unrope_pair(p, m, pair, D / 2, v0, v1);
+        unrope_pair(p, m, pair + 1, D / 2, v2, v3);
+      }
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(acc[mb][4 * g] * sc) | ((uint32_t)f32_to_bf16(acc[mb][4 * g + 1] * sc) << 16);
-      pk.y = (uint32_t)f32_to_bf16(acc[mb][4 * g + 2] * sc) | ((uint32_t)f32_to_bf16(acc[mb][4 * g + 3] * sc) << 16);
+      pk.x = (uint32_t)f32_to_bf16(v0 * sc) | ((uint32_t)f32_to_bf16(v1 * sc) << 16);
+      pk.y = (uint32_t)f32_to_bf16(v2 * sc) | ((uint32_t)f32_to_bf16(v3 * sc) << 16);
       const int chunk = 4 * mb + g;  // 16-byte chunk of the row; this lane fills half elh of it
       *reinterpret_cast<uint2 *>(pt + elq * D + ((chunk ^ (elq & 7)) * 8) + 4 * elh) = pk;
     }
@@ -504,7 +515,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
   {  // (every wavefront is past the last barrier of the walk: the staging rows are free)
     const int row0 = I * BLK + 32 * wv;
-    store_rows_bf16(dQ + head + (size_t)row0 * D, p.L - row0, Ks0 + wv * 32 * D, dq, p.scale, q_ok);
+    store_rows_bf16(dQ + head + (size_t)row0 * D, p.L - row0, Ks0 + wv * 32 * D, dq, p.scale, q_ok, p, true, row0);
   }
 }
 
@@ -815,8 +826,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 
   {  // (every wavefront is past the last barrier of the walk: the staging rows are free)
     const int row0 = J * BLK + 32 * wv;
-    store_rows_bf16(dK + head + (size_t)row0 * D, p.L - row0, Qs0 + wv * 32 * D, dk, p.scale, key_ok);
-    store_rows_bf16(dV + head + (size_t)row0 * D, p.L - row0, Gs0 + wv * 32 * D, dv, 1.0f, key_ok);
+    store_rows_bf16(dK + head + (size_t)row0 * D, p.L - row0, Qs0 + wv * 32 * D, dk, p.scale, key_ok, p, true, row0);
+    store_rows_bf16(dV + head + (size_t)row0 * D, p.L - row0, Gs0 + wv * 32 * D, dv, 1.0f, key_ok, p);
   }
 }
 

@@ -69,6 +69,88 @@ __global__ __launch_bounds__(256) void pool_kernel(const T *__restrict__ Q, cons
   }
 }
 
+// ---- pooling with the rotary position embedding applied on the way in (Sec. 3.3) ------------
+// Every position (padding too) is rotated with the caller's cos/sin tables, rounded to the storage
+// type and written to Q_rot / K_rot; the pooled sums are taken over those rounded values, so that
+// selection, forward and backward all see the same rotated tensors.  Fixed fp32 recipe on channel
+// pairs (2i, 2i+1) at position m: t = x1*s; x0' = fma(x0, c, -t); u = x1*c; x1' = fma(x0, s, u).
+//
+// One workgroup per (tensor, row-head, run of kRopeRows positions): the run is one contiguous chunk
+// of memory, read and written with 16 bytes per lane, consecutive lanes on consecutive addresses.
+// The rotated values also go to LDS (fp32), from where one thread per (block of the run, channel)
+// takes the block's sum in ascending position order.
+constexpr int kRopeRows = 64;
+
+template <typename T, int D>
+__global__ __launch_bounds__(256) void rope_pool_kernel(const T *__restrict__ Q, const T *__restrict__ K,
+                                                        const int *__restrict__ valid_len,
+                                                        float *__restrict__ qsum, float *__restrict__ kmeanT,
+                                                        T *__restrict__ Q_rot, T *__restrict__ K_rot, KParams p)
+{
+  constexpr int EPT = 16 / (int)sizeof(T);  // elements of a 16-byte piece: 8 bf16 or 4 fp32
+  constexpr int PPR = D / EPT;              // pieces per row
+  __shared__ __attribute__((aligned(16))) float rot_s[kRopeRows][D];  // (rows are read with one channel per lane: no padding needed)
+  const int runs = (p.L + kRopeRows - 1) / kRopeRows;
+  const int BH = p.B * p.H;
+  const int which = blockIdx.x >= (unsigned)(BH * runs);
+  const int rem = (int)blockIdx.x - which * BH * runs;
+  const int bh = rem / runs, run = rem % runs;
+  const int t_lo = run * kRopeRows, t_hi = min(t_lo + kRopeRows, p.L);
+  const int J_lo = t_lo / p.b, J_hi = (t_hi - 1) / p.b;  // blocks of the run (kRopeRows is a multiple of every b)
+  if (!which && J_hi < p.NB - p.nq) return;              // serving mode: queries of the last block only
+  const T *src = (which ? K : Q) + ((size_t)bh * p.L + t_lo) * D;
+  T *dst = (which ? K_rot : Q_rot) + ((size_t)bh * p.L + t_lo) * D;
+  const int pieces = (t_hi - t_lo) * PPR;
+  for (int q = threadIdx.x; q < pieces; q += 256) {
+    const int r = q / PPR, c0 = (q % PPR) * EPT;
+    const int t = t_lo + r;
+    float x[EPT], y[EPT], cs[EPT / 2], sn[EPT / 2];
+    if constexpr (EPT == 8) {
+      load4(src + (size_t)q * EPT, reinterpret_cast<float(&)[4]>(x[0]));
+      load4(src + (size_t)q * EPT + 4, reinterpret_cast<float(&)[4]>(x[4]));
+      const float4 c = *reinterpret_cast<const float4 *>(p.rope_cos + (size_t)t * (D / 2) + c0 / 2);
+      const float4 s4 = *reinterpret_cast<const float4 *>(p.rope_sin + (size_t)t * (D / 2) + c0 / 2);
+      cs[0] = c.x; cs[1] = c.y; cs[2] = c.z; cs[3] = c.w;
+      sn[0] = s4.x; sn[1] = s4.y; sn[2] = s4.z; sn[3] = s4.w;
+    } else {
+      load4(src + (size_t)q * EPT, reinterpret_cast<float(&)[4]>(x[0]));
+      const float2 c = *reinterpret_cast<const float2 *>(p.rope_cos + (size_t)t * (D / 2) + c0 / 2);
+      const float2 s2 = *reinterpret_cast<const float2 *>(p.rope_sin + (size_t)t * (D / 2) + c0 / 2);
+      cs[0] = c.x; cs[1] = c.y;
+      sn[0] = s2.x; sn[1] = s2.y;
+    }
+#pragma unroll
+    for (int i = 0; i < EPT / 2; ++i) {
+      y[2 * i] = __fmaf_rn(x[2 * i], cs[i], -__fmul_rn(x[2 * i + 1], sn[i]));
+      y[2 * i + 1] = __fmaf_rn(x[2 * i], sn[i], __fmul_rn(x[2 * i + 1], cs[i]));
+    }
+#pragma unroll
+    for (int e = 0; e < EPT; ++e) y[e] = to_f32(from_f32<T>(y[e]));  // what the attention kernels will read
+#pragma unroll
+    for (int e = 0; e < EPT; e += 4)
+      *reinterpret_cast<float4 *>(&rot_s[r][c0 + e]) = make_float4(y[e], y[e + 1], y[e + 2], y[e + 3]);
+    store4(dst + (size_t)q * EPT, reinterpret_cast<float(&)[4]>(y[0]));
+    if constexpr (EPT == 8) store4(dst + (size_t)q * EPT + 4, reinterpret_cast<float(&)[4]>(y[4]));
+  }
+  __syncthreads();
+  const int p0 = p.L - clamp_len(valid_len[bh / p.H], p.L);
+  const int nblk = J_hi - J_lo + 1;
+  for (int e = threadIdx.x; e < nblk * D; e += 256) {
+    const int J = J_lo + e / D, c = e % D;
+    if (!which && J < p.NB - p.nq) continue;
+    const int lo = max(J * p.b, p0), hi = min((J + 1) * p.b, p.L);
+    float a = 0.0f;
+#pragma unroll 8
+    for (int t = lo; t < hi; ++t) a = a + rot_s[t - t_lo][c];
+    if (!which) {
+      qsum[((size_t)bh * p.NB + J) * D + c] = a;
+    } else {
+      const int cnt = hi - lo;
+      kmeanT[((size_t)bh * D + c) * p.NB + J] = cnt > 0 ? __fdiv_rn(a, (float)cnt) : 0.0f;
+    }
+  }
+}
+
 // ---- scoring + top-k ----------------------------------------------------------------------
 // One wavefront per (row, head, query block I).  Lane-strided candidates J_first <= J < I.
 // Each score becomes one 64-bit key in LDS: an order-preserving integer image of the fp32 score
@@ -141,19 +223,24 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
 // ---- launchers ----------------------------------------------------------------------------
 template <typename T, int D>
 static void launch_select_t(const KParams &p, const void *Q, const void *K, bool kcmp, const int *valid_len,
-                            int *sel, void *ws, hipStream_t st)
+                            int *sel, void *ws, void *Q_rot, void *K_rot, hipStream_t st)
 {
   float *qsum = reinterpret_cast<float *>(ws);
   float *kmeanT = qsum + (size_t)p.B * p.H * p.NB * D;
   const long tasks = 2L * p.B * p.H * p.NB;
   const int per_wg = 256 / (D / 4);
   const unsigned grid = (unsigned)((tasks + per_wg - 1) / per_wg);
-  if (kcmp)
+  if (kcmp) {
     BLOSSOM_LAUNCH((pool_kernel<T, D, true>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
                    valid_len, qsum, kmeanT, p);
-  else
+  } else if (p.rope_cos) {
+    const long rgrid = 2L * p.B * p.H * ((p.L + kRopeRows - 1) / kRopeRows);
+    BLOSSOM_LAUNCH((rope_pool_kernel<T, D>), dim3((unsigned)rgrid), dim3(256), 0, st,
+                   (const T *)Q, (const T *)K, valid_len, qsum, kmeanT, (T *)Q_rot, (T *)K_rot, p);
+  } else {
     BLOSSOM_LAUNCH((pool_kernel<T, D, false>), dim3(grid), dim3(256), 0, st, (const T *)Q, (const T *)K,
                    valid_len, qsum, kmeanT, p);
+  }
   hipLaunchKernelGGL((score_topk_kernel<D>), dim3((unsigned)(p.B * p.H * p.nq)), dim3(64),
                      (size_t)p.NB * sizeof(unsigned long long), st,
                      qsum, kmeanT, valid_len, sel, p);
@@ -162,12 +249,12 @@ static void launch_select_t(const KParams &p, const void *Q, const void *K, bool
 size_t select_workspace_bytes(const KParams &p) { return 2 * (size_t)p.B * p.H * p.NB * p.d * sizeof(float); }
 
 void launch_select(const KParams &p, int dtype, const void *Q, const void *K, bool kcmp, const int *valid_len,
-                   int *sel, void *ws, hipStream_t st)
+                   int *sel, void *ws, hipStream_t st, void *Q_rot, void *K_rot)
 {
   with_head_dim(p.d, [&](auto dim) {
     constexpr int D = decltype(dim)::value;
-    if (dtype == 0) launch_select_t<float, D>(p, Q, K, kcmp, valid_len, sel, ws, st);
-    else launch_select_t<bf16_t, D>(p, Q, K, kcmp, valid_len, sel, ws, st);
+    if (dtype == 0) launch_select_t<float, D>(p, Q, K, kcmp, valid_len, sel, ws, Q_rot, K_rot, st);
+    else launch_select_t<bf16_t, D>(p, Q, K, kcmp, valid_len, sel, ws, Q_rot, K_rot, st);
   });
 }
 

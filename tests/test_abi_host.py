@@ -103,11 +103,34 @@ def test_validation_codes_fwd_bwd_dense(lib):
     assert dense(p=_p(topk=0, window=0).c(), Q=None) == -1          # ignored fields never reject
 
 
+def test_validation_codes_rope_and_probe(lib):
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    cp = _p().c()
+    rs = lambda **k: lib.blossom_rope_select_blocks(ctypes.byref(k.get("p", cp)), a, a, k.get("cos", a), k.get("sin", a), a,
+                                                    k.get("Qr", a), a, a, k.get("ws", a), 1 << 30, None)
+    assert rs(cos=None) == -1 and rs(sin=None) == -1 and rs(Qr=None) == -1
+    assert rs(cos=vp(4100)) == -5
+    assert rs(ws=None) == -6
+    assert rs(p=_p(d=12).c()) == -3
+    br = lambda **k: lib.blossom_attn_bwd_rope(ctypes.byref(cp), a, a, a, a, a, a, None, a, a, a, a, a, k.get("cos", a),
+                                               k.get("sin", a), a, a, a, a, None, k.get("ws", a), 1 << 30, None)
+    assert br(cos=None) == -1 and br(sin=None) == -1
+    assert br(sin=vp(4104)) == -5
+    assert br(ws=None) == -6
+    assert lib.blossom_probe(0, None, a, a, 4, None) == -1
+    assert lib.blossom_probe(9, a, a, a, 4, None) == -4 and lib.blossom_probe(0, a, a, a, 3, None) == -4
+    assert B.probe_bytes(0) == 8 * 128 * 64 * 64 * 2 and B.probe_bytes(1) == 4096 * 128 * 4 and B.probe_bytes(2) == 0
+    # the selection entry point with its scratch inside the library: same checks as blossom_select_blocks
+    st = lambda **k: lib.blossom_select_blocks_static(ctypes.byref(k.get("p", cp)), k.get("Q", a), a, a, a, None)
+    assert st(Q=None) == -1 and st(Q=vp(4100)) == -5 and st(p=_p(topk=0).c()) == -4
+
+
 def test_strerror(lib):
     seen = set()
-    for code in range(0, -8, -1):
+    for code in range(0, -9, -1):
         s = B.strerror(code)
         assert s and s != "unknown error code"
         seen.add(s)
-    assert len(seen) == 8
+    assert len(seen) == 9
     assert B.strerror(-99) == "unknown error code"
