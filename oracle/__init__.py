@@ -46,6 +46,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_num_threads.restype = _c_int
         L.oracle_select_blocks.restype = _c_int
         L.oracle_select_blocks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
+        L.oracle_select_blocks_bidir.restype = _c_int
+        L.oracle_select_blocks_bidir.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
         L.oracle_select_blocks_cmp.restype = _c_int
         L.oracle_select_blocks_cmp.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
         L.oracle_build_masks.restype = _c_int
@@ -89,14 +91,23 @@ def _bh(bh_list, B, H):
     return a, int(a.size)
 
 
+def _stis(stis_block, block, bidir):
+    """Mask block as the C side takes it: 0 = causal window only, n = causal Eq. 15 with mask block n,
+    -n = the bidirectional form (Eq. 15 as printed, no causal mask in either branch) with mask block n."""
+    if not bidir:
+        return int(stis_block)
+    return -int(stis_block if stis_block > 0 else block)
+
+
 def _check(rc, what):
     if rc != 0:
         raise RuntimeError(f"oracle {what} failed with code {rc}")
 
 
-def select_blocks(Q, K, valid_len, block, topk, bh_list=None, want_scores=False):
+def select_blocks(Q, K, valid_len, block, topk, bh_list=None, want_scores=False, bidir=False):
     """Steps 1-3.  Q, K: [B,H,L,d] float32.  Returns sel [B,H,NB,k] int32 (rows of pairs
-    not in bh_list are left at -2) and, if asked, scores [n_bh,NB,NB] float32."""
+    not in bh_list are left at -2) and, if asked, scores [n_bh,NB,NB] float32.  bidir: candidates on
+    both sides of the query block (bidirectional backbone)."""
     Q = _in(Q, False)
     K = _in(K, False)
     B, H, L, d = Q.shape
@@ -106,8 +117,8 @@ def select_blocks(Q, K, valid_len, block, topk, bh_list=None, want_scores=False)
     bh, n_bh = _bh(bh_list, B, H)
     sel = np.full((B, H, NB, topk), -2, dtype=np.int32)
     scores = np.zeros((n_bh, NB, NB), dtype=np.float32) if want_scores else None
-    rc = lib().oracle_select_blocks(B, H, L, d, block, topk, _p(Q), _p(K), _p(vl), _p(bh), n_bh,
-                                    _p(sel), _p(scores))
+    fn = lib().oracle_select_blocks_bidir if bidir else lib().oracle_select_blocks
+    rc = fn(B, H, L, d, block, topk, _p(Q), _p(K), _p(vl), _p(bh), n_bh, _p(sel), _p(scores))
     _check(rc, "select_blocks")
     return (sel, scores) if want_scores else sel
 
@@ -131,7 +142,7 @@ def select_blocks_cmp(Q, Kcmp, valid_len, block, topk, bh_list=None, want_scores
     return (sel, scores) if want_scores else sel
 
 
-def build_masks(L, block, topk, window, n_valid, sel_bh, stis_block=0):
+def build_masks(L, block, topk, window, n_valid, sel_bh, stis_block=0, bidir=False):
     """The two materialised masks of one (row, head): uint8 [L,L] each.
 
     stis_block = 0: the short-term mask is the causal local window; >= 1: the causal form of all
@@ -141,7 +152,7 @@ def build_masks(L, block, topk, window, n_valid, sel_bh, stis_block=0):
     assert s.shape == (NB, topk)
     M_lt = np.zeros((L, L), dtype=np.uint8)
     M_st = np.zeros((L, L), dtype=np.uint8)
-    _check(lib().oracle_build_masks(L, block, topk, window, int(stis_block), int(n_valid), _p(s), _p(M_lt), _p(M_st)),
+    _check(lib().oracle_build_masks(L, block, topk, window, _stis(stis_block, block, bidir), int(n_valid), _p(s), _p(M_lt), _p(M_st)),
            "build_masks")
     return M_lt, M_st
 
@@ -173,7 +184,7 @@ class Fwd:
 
 
 def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale=None,
-             bh_list=None, f64=False, stis_block=0) -> Fwd:
+             bh_list=None, f64=False, stis_block=0, bidir=False) -> Fwd:
     Q = _in(Q, f64)
     K = _in(K, f64)
     V = _in(V, f64)
@@ -191,7 +202,7 @@ def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale
     z = lambda *s: np.zeros(s, dtype=np.float64)
     out = Fwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L), z(n_bh, L), z(n_bh, L), 0, 0)
     nnz = np.zeros(2, dtype=np.int64)
-    rc = lib().oracle_attn_fwd(B, H, L, d, block, topk, window, int(stis_block), float(scale), int(f64),
+    rc = lib().oracle_attn_fwd(B, H, L, d, block, topk, window, _stis(stis_block, block, bidir), float(scale), int(f64),
                                _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(bh), n_bh,
                                _p(out.O), _p(out.o_lt), _p(out.o_st), _p(out.lse_lt), _p(out.lse_st),
                                _p(out.alpha), _p(nnz))
@@ -210,7 +221,7 @@ class Bwd:
 
 
 def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, scale=None,
-             bh_list=None, f64=False, stis_block=0) -> Bwd:
+             bh_list=None, f64=False, stis_block=0, bidir=False) -> Bwd:
     Q = _in(Q, f64)
     K = _in(K, f64)
     V = _in(V, f64)
@@ -226,7 +237,7 @@ def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, s
     bh, n_bh = _bh(bh_list, B, H)
     z = lambda *s: np.zeros(s, dtype=np.float64)
     out = Bwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(H, 2 * d), z(H))
-    rc = lib().oracle_attn_bwd(B, H, L, d, block, topk, window, int(stis_block), float(scale), int(f64),
+    rc = lib().oracle_attn_bwd(B, H, L, d, block, topk, window, _stis(stis_block, block, bidir), float(scale), int(f64),
                                _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(dO),
                                _p(bh), n_bh, _p(out.dQ), _p(out.dK), _p(out.dV),
                                _p(out.d_gate_w), _p(out.d_gate_b))

@@ -87,8 +87,10 @@ int oracle_num_threads(void)
 /* ------------------------------------------------------------------------- */
 /* kcmp (optional, [NB*d]): compressed keys phi(K_J) supplied by the caller (Eq. 9 with a learnable
  * phi); when given they take the place of the block means and `key` is not read. */
+/* bidir: for a bidirectional backbone (no causal mask anywhere): the candidates of query block I are
+ * all other blocks that hold a valid key, J_first <= J < NB, J != I; otherwise only earlier ones. */
 static int select_one(int L, int d, int b, int k, const float *q, const float *key, const float *kcmp,
-                      int n_valid, int32_t *sel /* [NB*k] */, float *scores /* [NB*NB] or NULL */)
+                      int n_valid, int bidir, int32_t *sel /* [NB*k] */, float *scores /* [NB*NB] or NULL */)
 {
     const int NB = n_blocks(L, b);
     const int p0 = L - n_valid;
@@ -124,9 +126,11 @@ static int select_one(int L, int d, int b, int k, const float *q, const float *k
         for (int e = 0; e < k; ++e) out[e] = -1;
         const int hi = imin((I + 1) * b, L);
         if (hi <= p0) continue; /* no valid query in this block */
-        const int n_cand = I - J_first; /* candidates J_first .. I-1 */
+        const int J_end = bidir ? NB : I;             /* candidates J_first .. J_end-1, without I */
+        const int n_cand = bidir ? NB - J_first - 1 : I - J_first;
         const int take = imin(k - 1, n_cand);
-        for (int J = J_first; J < I; ++J) {
+        for (int J = J_first; J < J_end; ++J) {
+            if (J == I) continue;
             float acc = 0.0f;
             for (int c = 0; c < d; ++c)
                 acc = fmaf(qsum[(size_t)I * d + c], kmean[(size_t)J * d + c], acc);
@@ -136,17 +140,18 @@ static int select_one(int L, int d, int b, int k, const float *q, const float *k
         }
         for (int r = 0; r < take; ++r) {
             int best = -1;
-            for (int J = J_first; J < I; ++J) {
-                if (chosen[J]) continue;
+            for (int J = J_first; J < J_end; ++J) {
+                if (J == I || chosen[J]) continue;
                 /* strict '>' keeps the lowest index among equal scores */
                 if (best < 0 || sc[J] > sc[best]) best = J;
             }
             chosen[best] = 1;
         }
+        chosen[I] = 1; /* the query block's own block is always taken and counts toward k */
         int e = 0;
-        for (int J = J_first; J < I; ++J)
+        for (int J = J_first; J < (bidir ? NB : I + 1); ++J)
             if (chosen[J]) out[e++] = J;
-        out[e++] = I;
+        chosen[I] = 0;
     }
     free(qsum); free(kmean); free(sc); free(chosen);
     return 0;
@@ -158,7 +163,7 @@ static int select_one(int L, int d, int b, int k, const float *q, const float *k
  * listed pairs are written.  scores (optional) is [n_bh, NB, NB], entry
  * [I][J] valid for J_first <= J < I.
  */
-static int select_blocks_impl(int B, int H, int L, int d, int b, int k,
+static int select_blocks_impl(int B, int H, int L, int d, int b, int k, int bidir,
                               const float *Q, const float *K, const float *Kcmp, const int32_t *valid_len,
                               const int32_t *bh_list, int n_bh,
                               int32_t *sel, float *scores)
@@ -176,7 +181,7 @@ static int select_blocks_impl(int B, int H, int L, int d, int b, int k,
         if (n > L) n = L;
         const size_t off = (size_t)bh * L * d;
         int rc = select_one(L, d, b, k, Q + off, K ? K + off : NULL, Kcmp ? Kcmp + (size_t)bh * NB * d : NULL, n,
-                            sel + (size_t)bh * NB * k,
+                            bidir, sel + (size_t)bh * NB * k,
                             scores ? scores + (size_t)it * NB * NB : NULL);
         if (rc) {
 #pragma omp atomic write
@@ -191,7 +196,16 @@ int oracle_select_blocks(int B, int H, int L, int d, int b, int k,
                          const int32_t *bh_list, int n_bh,
                          int32_t *sel, float *scores)
 {
-    return select_blocks_impl(B, H, L, d, b, k, Q, K, NULL, valid_len, bh_list, n_bh, sel, scores);
+    return select_blocks_impl(B, H, L, d, b, k, 0, Q, K, NULL, valid_len, bh_list, n_bh, sel, scores);
+}
+
+/* The same for a bidirectional backbone (see select_one). */
+int oracle_select_blocks_bidir(int B, int H, int L, int d, int b, int k,
+                               const float *Q, const float *K, const int32_t *valid_len,
+                               const int32_t *bh_list, int n_bh,
+                               int32_t *sel, float *scores)
+{
+    return select_blocks_impl(B, H, L, d, b, k, 1, Q, K, NULL, valid_len, bh_list, n_bh, sel, scores);
 }
 
 /* The same with caller-supplied compressed keys Kcmp [B,H,NB,d] (Eq. 9: phi is the caller's). */
@@ -201,7 +215,7 @@ int oracle_select_blocks_cmp(int B, int H, int L, int d, int b, int k,
                              int32_t *sel, float *scores)
 {
     if (!Kcmp) return -2;
-    return select_blocks_impl(B, H, L, d, b, k, Q, NULL, Kcmp, valid_len, bh_list, n_bh, sel, scores);
+    return select_blocks_impl(B, H, L, d, b, k, 0, Q, NULL, Kcmp, valid_len, bh_list, n_bh, sel, scores);
 }
 
 /* ------------------------------------------------------------------------- */
@@ -264,26 +278,38 @@ int oracle_rope_bwd(int BH, int L, int d, const double *g, const float *cosv, co
 /* ------------------------------------------------------------------------- */
 static int is_power_of_two(int x) { return x >= 1 && (x & (x - 1)) == 0; }
 
+/* stis_blk < 0: the bidirectional form with mask block -stis_blk: Eq. 15 exactly as printed
+ * (|i-j| < w, |b_q-b_k| = 2^r, last block; no causal mask), and the selected blocks of the
+ * long-term branch seen whole. */
 static void build_masks_one(int L, int b, int k, int w, int stis_blk, int n_valid, const int32_t *sel,
                             uint8_t *M_lt, uint8_t *M_st)
 {
+    const int bidir = stis_blk < 0;
+    if (bidir) stis_blk = -stis_blk;
     const int p0 = L - n_valid;
     for (int i = 0; i < L; ++i) {
         const int32_t *si = sel + (size_t)(i / b) * k;
         for (int j = 0; j < L; ++j) {
             uint8_t lt = 0, st = 0;
             if (i >= p0 && j >= p0) {
-                if (j <= i) {
+                if (j <= i || bidir) {
                     const int bj = j / b;
                     for (int e = 0; e < k; ++e)
                         if (si[e] == bj) lt = 1;
                 }
                 const int dist = i - j;
-                if (dist >= 0 && dist < w) st = 1;                        /* Eq. 15, first case  */
-                if (stis_blk >= 1 && dist >= 0) {
+                if (!bidir) {
+                    if (dist >= 0 && dist < w) st = 1;                    /* Eq. 15, first case  */
+                    if (stis_blk >= 1 && dist >= 0) {
+                        const int bq = i / stis_blk, bk = j / stis_blk;
+                        if (is_power_of_two(bq - bk)) st = 1;             /* second case         */
+                        if (j >= L - stis_blk) st = 1;                    /* third case          */
+                    }
+                } else {
                     const int bq = i / stis_blk, bk = j / stis_blk;
-                    if (is_power_of_two(bq - bk)) st = 1;                 /* second case         */
-                    if (j >= L - stis_blk) st = 1;                        /* third case          */
+                    if (abs(dist) < w) st = 1;                            /* Eq. 15 as printed   */
+                    if (is_power_of_two(abs(bq - bk))) st = 1;
+                    if (j >= L - stis_blk) st = 1;
                 }
             }
             M_lt[(size_t)i * L + j] = lt;
