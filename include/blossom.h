@@ -8,9 +8,10 @@
  *     scored against the query (Eq. 10), the top-k blocks are kept (Eq. 13) and
  *     attention runs over the keys of the kept blocks only (Eq. 14, 16);
  *   - short-term branch (STIS, Sec. 3.5): attention under a local mask
- *     (Eq. 15, 17), always intersected with the causal mask j <= i:
- *     stis_mode 0 is the local-window term alone, stis_mode 1 the whole of
- *     Eq. 15 (window, whole blocks at power-of-two block distances, last block);
+ *     (Eq. 15, 17): stis_mode 0 is the local-window term alone, stis_mode 1 the
+ *     whole of Eq. 15 (window, whole blocks at power-of-two block distances, last
+ *     block), both intersected with the causal mask j <= i; stis_mode 2 is Eq. 15
+ *     as printed, symmetric, with no causal mask in either branch;
  *   - learnable gate (Sec. 3.6, Eq. 18-19): a sigmoid of a linear map of both
  *     branch outputs blends them.
  *
@@ -78,7 +79,12 @@ typedef struct {
   int32_t window;         /* w: query i sees keys j with 0 <= i-j < w in the short-term branch  */
   int32_t dtype;          /* BLOSSOM_F32 or BLOSSOM_BF16 (fp32 accumulation either way)         */
   float softmax_scale;    /* logits are softmax_scale * q.k ; 0.0f means 1/sqrt(d) (Eq. 1)      */
-  int32_t stis_mode;      /* 0 = causal local window; 1 = causal form of Eq. 15 (see stis_block) */
+  int32_t stis_mode;      /* 0 = causal local window; 1 = causal form of Eq. 15 (see stis_block);
+                             2 = bidirectional form, for backbones without a causal mask (Sec. 4.2):
+                             Eq. 15 as printed, |i-j| < window or |b_q-b_k| = 2^r or j >= L - blk, with
+                             mask block blk = stis_block (0 means `block`); the long-term branch takes its
+                             k-1 candidates from the blocks on BOTH sides of the query block and sees the
+                             selected blocks whole.  Every shape runs on the scalar kernels in this mode. */
   int32_t save_for_bwd;   /* fwd only: 1 = also write o_lt, o_st, lse_lt, lse_st                */
   int32_t stis_block;     /* stis_mode 1: mask block size blk of Eq. 15 (>= 1); 0 means `block`.
                              With b_q = i / blk, b_k = j / blk query i sees key j <= i iff

@@ -45,9 +45,9 @@ int check_params(const blossom_params *p, KParams *kp)
   if (p->d != 8 && p->d != 16 && p->d != 32 && p->d != 64) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->block != 8 && p->block != 16 && p->block != 32 && p->block != 64) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->dtype != BLOSSOM_F32 && p->dtype != BLOSSOM_BF16) return BLOSSOM_ERR_UNSUPPORTED;
-  if (p->stis_mode != 0 && p->stis_mode != 1) return BLOSSOM_ERR_UNSUPPORTED;
+  if (p->stis_mode < 0 || p->stis_mode > 2) return BLOSSOM_ERR_UNSUPPORTED;
   if (p->topk < 1 || p->window < 1) return BLOSSOM_ERR_PARAM;
-  if (p->stis_mode == 1 && p->stis_block < 0) return BLOSSOM_ERR_PARAM;
+  if (p->stis_mode >= 1 && p->stis_block < 0) return BLOSSOM_ERR_PARAM;
   if (!std::isfinite(p->softmax_scale) || p->softmax_scale < 0.0f) return BLOSSOM_ERR_PARAM;
   const long NB = ((long)p->L + p->block - 1) / p->block;
   if (NB > 4096) return BLOSSOM_ERR_SHAPE;
@@ -57,7 +57,8 @@ int check_params(const blossom_params *p, KParams *kp)
   kp->b = p->block; kp->k = p->topk; kp->NB = (int)NB;
   kp->w = p->window < p->L ? p->window : p->L;  // a window beyond L sees the same keys as L: keeps i + w inside int
   kp->scale = p->softmax_scale > 0.0f ? p->softmax_scale : 1.0f / std::sqrt((float)p->d);
-  kp->sblk = p->stis_mode == 1 ? (p->stis_block > 0 ? p->stis_block : p->block) : 0;
+  kp->sblk = p->stis_mode >= 1 ? (p->stis_block > 0 ? p->stis_block : p->block) : 0;
+  kp->bidir = p->stis_mode == 2;
   kp->last_lo = kp->sblk > 0 ? p->L - kp->sblk : 0x3FFFFFFF;
   kp->nq = p->last_block_only ? 1 : (int)NB;
   kp->rope_cos = nullptr;

@@ -17,6 +17,7 @@ struct KParams {
   int sblk;     // mask block size of the full short-term mask (Eq. 15); 0 = local window only
   int last_lo;  // first of the last sblk positions (L - sblk); INT_MAX/2 when sblk == 0
   int nq;       // query blocks walked by select and forward: NB, or 1 (the last one) in serving mode
+  int bidir;    // 1: bidirectional form (Eq. 15 as printed, no causal mask in either branch); sblk > 0 then
   // rotary position embedding (Sec. 3.3): cos/sin tables fp32 [L, d/2], or nullptr.  Backward kernels
   // then store dQ and dK rotated back (the gradient w.r.t. the rows before the rotation).
   const float *rope_cos, *rope_sin;
@@ -32,20 +33,23 @@ __host__ __device__ __forceinline__ bool holds_pow2(int lo, int hi)
   while (top <= hi / 2) top *= 2;  // largest power of two <= hi
   return top >= lo;
 }
+// (symmetric in i - j: the causal callers only ever ask about j <= i)
 __device__ __forceinline__ bool st_visible(const KParams &p, int i, int j)
 {
-  if (i - j < p.w) return true;
+  if (abs(i - j) < p.w) return true;
   if (p.sblk == 0) return false;
-  return j >= p.last_lo || is_pow2(i / p.sblk - j / p.sblk);
+  return j >= p.last_lo || is_pow2(abs(i / p.sblk - j / p.sblk));
 }
-// may any query of block I (size b) see any key of block J <= I through the second or third case?
+// may any query of block I (size b) see any key of block J through the second or third case?
+// (J <= I, or any J in the bidirectional form)
 __device__ __forceinline__ bool st_block_reach(const KParams &p, int I, int J)
 {
   if (p.sblk == 0) return false;
   const int q_lo = I * p.b, q_hi = min(I * p.b + p.b - 1, p.L - 1);
   const int k_lo = J * p.b, k_hi = min(J * p.b + p.b - 1, p.L - 1);
   if (k_hi >= p.last_lo) return true;
-  return holds_pow2(q_lo / p.sblk - k_hi / p.sblk, q_hi / p.sblk - k_lo / p.sblk);
+  if (J <= I) return holds_pow2(q_lo / p.sblk - k_hi / p.sblk, q_hi / p.sblk - k_lo / p.sblk);
+  return holds_pow2(k_lo / p.sblk - q_hi / p.sblk, k_hi / p.sblk - q_lo / p.sblk);
 }
 
 struct bf16_t {

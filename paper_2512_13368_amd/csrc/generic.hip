@@ -63,6 +63,13 @@ __device__ __forceinline__ int first_window_block(int I, int b, int w, int J_fir
   return J > J_first ? J : J_first;
 }
 
+// bidirectional form: last key block the window of a query of block I reaches
+__device__ __forceinline__ int last_window_block(int I, int b, int w, int NB)
+{
+  const long hi = (long)I * b + (b - 1) + (w - 1);
+  return (int)min((long)(NB - 1), hi / b);
+}
+
 // Far part of the short-term mask when the mask block is smaller than the tile (Eq. 15, second and
 // third case, below the window tiles): the rows of a query block then see different, short runs of
 // keys, so each lane reads its own keys straight from memory instead of walking whole tiles.
@@ -98,7 +105,8 @@ __device__ __forceinline__ void far_rows_of_key(const KParams &p, int j, int far
       if (!is_pow2(i / p.sblk - kb)) f(i);
 }
 // (host side: picks the instantiation)
-static inline bool far_by_rows(const KParams &p) { return p.sblk > 0 && p.sblk < p.b; }
+// (the bidirectional form walks whole tiles on both sides of the query block)
+static inline bool far_by_rows(const KParams &p) { return p.sblk > 0 && p.sblk < p.b && !p.bidir; }
 
 }  // namespace
 
@@ -177,7 +185,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 
     __syncthreads();
     for (int jj = phase; jj < b; jj += nph) {
       const int j = J * b + jj;
-      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || st_visible(p, i, j));
+      const bool vis = active && j < p.L && j >= p0 && (j <= i || p.bidir) && (!windowed || st_visible(p, i, j));
       if (vis) {
         float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // four independent chains
 #pragma unroll
@@ -283,6 +291,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 4 
         if (st_block_reach(p, I, J)) tile(J, true);
     }
     for (int J = J_win; J <= I; ++J) tile(J, true);
+    if (p.bidir) {  // Eq. 15 as printed: the same on the other side of the query block
+      const int J_whi = last_window_block(I, b, p.w, p.NB);
+      for (int J = I + 1; J < p.NB; ++J)
+        if (J <= J_whi || st_block_reach(p, I, J)) tile(J, true);
+    }
   }
   const float lse_st = finish();
   float z = gate_b ? gate_b[h] : 0.0f;
@@ -592,7 +605,7 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 
     __syncthreads();
     for (int jj = phase; jj < b; jj += nph) {
       const int j = J * b + jj;
-      const bool vis = active && j < p.L && j >= p0 && j <= i && (!windowed || st_visible(p, i, j));
+      const bool vis = active && j < p.L && j >= p0 && (j <= i || p.bidir) && (!windowed || st_visible(p, i, j));
       if (vis) {
         float s = 0.0f, gv = 0.0f;
 #pragma unroll
@@ -646,6 +659,11 @@ __global__ __launch_bounds__(64) __attribute__((amdgpu_waves_per_eu(D <= 32 ? 3 
         if (st_block_reach(p, I, J)) tile(J, true);
     }
     for (int J = J_win; J <= I; ++J) tile(J, true);
+    if (p.bidir) {  // Eq. 15 as printed: the same on the other side of the query block
+      const int J_whi = last_window_block(I, b, p.w, p.NB);
+      for (int J = I + 1; J < p.NB; ++J)
+        if (J <= J_whi || st_block_reach(p, I, J)) tile(J, true);
+    }
   }
   const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
   for (int e = 0; e < p.k; ++e) {
@@ -711,7 +729,7 @@ __global__ __launch_bounds__(64 * kInvWaves) void inverse_list_kernel(const int 
 #pragma unroll 8
     for (int I = I_lo; I < I_hi; ++I) {
       const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
-      if (J >= 0 && J <= I) atomicAdd(&mine[J], 1);
+      if (J >= 0 && J < p.NB && (J <= I || p.bidir)) atomicAdd(&mine[J], 1);
       // an earlier block with at least kInvFewKeys valid keys gives every row of I that many keys
       const int vcount = min((J + 1) * p.b, p.L) - max(J * p.b, p0);
       if (__ballot(J >= 0 && J < I && vcount >= kInvFewKeys) != 0ull && lane == 0) few[I] = 0;
@@ -751,7 +769,7 @@ __global__ __launch_bounds__(64 * kInvWaves) void inverse_list_kernel(const int 
 #pragma unroll 8
     for (int I = I_lo; I < I_hi; ++I) {
       const int J = e < p.k ? s[(size_t)I * p.k + e] : -1;
-      if (J >= 0 && J <= I) it[atomicAdd(&mine[J], 1)] = I | ((int)few[I] << kInvFewShift);
+      if (J >= 0 && J < p.NB && (J <= I || p.bidir)) it[atomicAdd(&mine[J], 1)] = I | ((int)few[I] << kInvFewShift);
     }
   }
 }
@@ -854,7 +872,7 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     __syncthreads();
     for (int ii = phase; ii < b; ii += nph) {
       const int i = I * b + ii;
-      const bool vis = key_ok && i < p.L && i >= p0 && j <= i && (!windowed || st_visible(p, i, j));
+      const bool vis = key_ok && i < p.L && i >= p0 && (j <= i || p.bidir) && (!windowed || st_visible(p, i, j));
       if (vis) {
         float s4[4] = {0.0f, 0.0f, 0.0f, 0.0f};  // four independent chains
 #pragma unroll
@@ -884,6 +902,12 @@ __global__ __launch_bounds__(64) void bwd_dkv_generic_kernel(const T *__restrict
     const long last_q = (long)J * b + (b - 1) + (p.w - 1);
     const int I_hi = (int)min((long)(p.NB - 1), last_q / b);
     for (int I = J; I <= I_hi; ++I) tile(I, true);
+    if (p.bidir) {  // query blocks before the key block: window reach, then the other cases of Eq. 15
+      const int I_first = p0 / b;
+      const int I_lo = first_window_block(J, b, p.w, I_first);
+      for (int I = I_first; I < J; ++I)
+        if (I >= I_lo || st_block_reach(p, I, J)) tile(I, true);
+    }
     if constexpr (FAR) {
       const float *wx = gate_w + (size_t)h * 2 * D + D;
       if (key_ok)

@@ -717,7 +717,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
 
 bool fwd_mfma_supported(const KParams &p, int dtype)
 {
-  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && (p.sblk == 0 || (is_pow2(p.sblk) && p.sblk <= p.b));
+  return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && !p.bidir &&
+         (p.sblk == 0 || (is_pow2(p.sblk) && p.sblk <= p.b));
 }
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)

@@ -186,26 +186,30 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
     return;
   }
   const int J_first = p0 / p.b;
-  const int n_cand = I - J_first;
-  const int take = min(p.k - 1, n_cand);
+  // candidates: the earlier blocks that hold a valid key; in the bidirectional form the later ones too.
+  // There the query's own block sits among them with the largest possible key, so it is always taken
+  // and comes out at its place in the ascending list.
+  const int J_end = p.bidir ? p.NB : I;
+  const int n_cand = p.bidir ? p.NB - J_first - 1 : I - J_first;
+  const int take = min(p.k - 1, n_cand) + (p.bidir ? 1 : 0);
   for (int c = lane; c < D; c += 64) qs[c] = qsum[((size_t)bh * p.NB + I) * D + c];
   __syncthreads();
   const float *km = kmeanT + (size_t)bh * D * p.NB;
-  for (int J = J_first + lane; J < I; J += 64) {
+  for (int J = J_first + lane; J < J_end; J += 64) {
     float acc = 0.0f;
 #pragma unroll 8
     for (int c = 0; c < D; ++c) acc = __fmaf_rn(qs[c], km[(size_t)c * p.NB + J], acc);
-    key_s[J] = rank_key(acc, J, p.NB);
+    key_s[J] = J == I ? ~0ull : rank_key(acc, J, p.NB);
   }
   __syncthreads();
   int base = 0;
-  for (int J0 = J_first; J0 < I; J0 += 64) {
+  for (int J0 = J_first; J0 < J_end; J0 += 64) {
     const int J = J0 + lane;
     bool chosen = false;
-    if (J < I) {
+    if (J < J_end) {
       const unsigned long long mine = key_s[J];
       int rank = 0;
-      for (int Jo = J_first; Jo < I; ++Jo) rank += key_s[Jo] > mine ? 1 : 0;
+      for (int Jo = J_first; Jo < J_end; ++Jo) rank += key_s[Jo] > mine ? 1 : 0;
       chosen = rank < take;
     }
     const unsigned long long mask = __ballot(chosen);
@@ -215,9 +219,12 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
     }
     base += __popcll(mask);
   }
-  // base == take here; the own block closes the list, the rest is padding
-  if (lane == 0) out[base] = I;
-  for (int e = base + 1 + lane; e < p.k; e += 64) out[e] = -1;
+  // base == take here; causal form: the own block closes the list; the rest is padding
+  if (!p.bidir) {
+    if (lane == 0) out[base] = I;
+    ++base;
+  }
+  for (int e = base + lane; e < p.k; e += 64) out[e] = -1;
 }
 
 // ---- launchers ----------------------------------------------------------------------------

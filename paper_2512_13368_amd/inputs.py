@@ -40,6 +40,7 @@ class Workload:
     seed: int
     backward: bool = False
     stis_block: int = 0  # 0: the short-term mask is the causal window; >= 1: all of Eq. 15 with this mask block size
+    bidir: bool = False  # True: bidirectional form (Eq. 15 as printed, no causal mask in either branch)
 
     @property
     def NB(self) -> int:

@@ -12,7 +12,7 @@ TOL = {"fp32": 1e-4, "bf16": 2e-2}
 
 def params(w: Workload, **kw) -> B.Params:
     return B.Params(w.B, w.H, w.L, w.d, w.block, w.topk, w.window,
-                    B.F32 if w.dtype == "fp32" else B.BF16, stis_mode=int(w.stis_block > 0),
+                    B.F32 if w.dtype == "fp32" else B.BF16, stis_mode=2 if w.bidir else int(w.stis_block > 0),
                     stis_block=w.stis_block, **kw)
 
 

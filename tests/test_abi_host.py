@@ -55,7 +55,7 @@ def test_validation_codes_select(lib):
     assert _select(lib, _p(d=48)) == -3
     assert _select(lib, _p(block=12)) == -3
     assert _select(lib, _p(dtype=7)) == -3
-    assert _select(lib, _p(stis_mode=2)) == -3                      # 0 and 1 are the defined masks
+    assert _select(lib, _p(stis_mode=3)) == -3                      # 0, 1 and 2 are the defined masks
     assert _select(lib, _p(stis_mode=1, stis_block=-1)) == -4
     assert _select(lib, _p(B=0)) == -2
     assert _select(lib, _p(L=0)) == -2

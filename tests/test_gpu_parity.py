@@ -36,7 +36,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
     torch.cuda.synchronize()
 
     # --- selection: every (row, head), bit-exact ---
-    sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk)
+    sel_ref = oracle.select_blocks(x.Q, x.K, x.valid_len, w.block, w.topk, bidir=w.bidir)
     np.testing.assert_array_equal(sel.cpu().numpy(), sel_ref)
     if sel_edit is not None:  # a caller-built selection: both sides get the same edited rows
         sel_ref = np.ascontiguousarray(sel_edit(sel_ref.copy()), dtype=np.int32)
@@ -50,7 +50,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
     bh = None if pairs is None else np.asarray(pairs, np.int32)
     take = (lambda t: host(t).reshape(w.B * w.H, *t.shape[2:])[bh if bh is not None else slice(None)])
     fr = oracle.attn_fwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, w.block, w.topk,
-                         w.window, scale=scale, bh_list=bh, stis_block=w.stis_block)
+                         w.window, scale=scale, bh_list=bh, stis_block=w.stis_block, bidir=w.bidir)
     assert_close(take(f.o_lt), fr.o_lt, tol, "o_lt")
     assert_close(take(f.o_st), fr.o_st, tol, "o_st")
     assert_close(take(f.O), fr.O, tol, "O")
@@ -70,7 +70,7 @@ def run_case(w, x=None, pairs=None, backward=None, check_dense=False, gate_scale
 
     if backward:
         gr = oracle.attn_bwd(x.Q, x.K, x.V, x.valid_len, sel_ref, x.gate_w, x.gate_b, x.dO, w.block,
-                             w.topk, w.window, scale=scale, bh_list=bh, stis_block=w.stis_block)
+                             w.topk, w.window, scale=scale, bh_list=bh, stis_block=w.stis_block, bidir=w.bidir)
         assert_close(take(g.dQ), gr.dQ, tol, "dQ")
         assert_close(take(g.dK), gr.dK, tol, "dK")
         assert_close(take(g.dV), gr.dV, tol, "dV")
@@ -298,6 +298,46 @@ def test_full_short_term_mask(dtype, d, b, sblk, window, L):
     x = make_inputs(w, want_dO=True)
     x.valid_len[:] = [L, L - b - 3, max(1, L // 3)]
     run_case(w, x=x, backward=True, gate_scale=0.4)
+
+
+@pytest.mark.parametrize("dtype,d,b,sblk,window,L,topk", [
+    ("fp32", 32, 8, 1, 8, 200, 4),       # the paper's mask setting: mask block 1, window 8
+    ("fp32", 8, 16, 1, 8, 100, 4),       # ... at its head size
+    ("fp32", 64, 16, 4, 6, 131, 3),      # mask blocks smaller than the tiles, ragged tail
+    ("fp32", 32, 16, 16, 20, 150, 3),    # mask block = tile
+    ("bf16", 32, 32, 8, 3, 300, 2),
+    ("bf16", 64, 16, 64, 5, 333, 5),     # mask blocks larger than the tiles
+    ("bf16", 64, 32, 32, 40, 647, 4),    # shapes the matrix cores serve in the causal forms: scalar kernels here
+    ("bf16", 64, 64, 0, 70, 700, 3),     # mask block 0 = the selection block
+    ("fp32", 16, 8, 3, 1, 90, 1),        # window 1, top-k 1 (own block only), mask block that is no power of two
+    ("fp32", 32, 8, 200, 2, 90, 20),     # one mask block and every block selected: both branches are full attention
+])
+def test_bidirectional_form(dtype, d, b, sblk, window, L, topk):
+    # stis_mode 2: Eq. 15 as printed (symmetric) and selected blocks seen whole, for bidirectional backbones
+    w = with_shape(WORKLOADS["cfg1"], name=f"bidir-{dtype}-{d}-{b}-{sblk}", B=3, H=2, L=L, d=d, block=b, topk=topk,
+                   window=window, dtype=dtype, len_lo=1, len_hi=L, qkv_scaled=(dtype == "bf16"), seed=2300 + d + b + sblk,
+                   stis_block=sblk, bidir=True)
+    x = make_inputs(w, want_dO=True)
+    x.valid_len[:] = [L, L - b - 3, max(1, L // 3)]
+    same = sblk >= L and topk >= w.NB
+    run_case(w, x=x, backward=True, gate_scale=0.4, branches_coincide=same)
+
+
+def test_bidirectional_serving_mode():
+    w = with_shape(WORKLOADS["cfg1"], name="bidir-serve", B=3, H=2, L=77, d=16, block=8, topk=3, window=5, stis_block=2,
+                   bidir=True, len_lo=20, len_hi=77)
+    x = make_inputs(w)
+    dv = Dev(x)
+    sel_all = B.select_blocks(params(w), dv.Q, dv.K, dv.vl)
+    f_all = B.attn_fwd(params(w), dv.Q, dv.K, dv.V, dv.vl, sel_all, dv.gw, dv.gb)
+    sel = torch.full_like(sel_all, -7)
+    B.select_blocks(params(w, last_block_only=1), dv.Q, dv.K, dv.vl, sel=sel)
+    O = torch.full_like(f_all.O, 3.0)
+    B.attn_fwd(params(w, last_block_only=1), dv.Q, dv.K, dv.V, dv.vl, sel, dv.gw, dv.gb, out=B.FwdOut(O))
+    torch.cuda.synchronize()
+    lo = (w.NB - 1) * w.block
+    assert torch.equal(sel[:, :, -1], sel_all[:, :, -1]) and torch.equal(O[:, :, lo:], f_all.O[:, :, lo:])
+    assert bool((O[:, :, :lo] == 3.0).all())
 
 
 @pytest.mark.parametrize("name,shape", [
