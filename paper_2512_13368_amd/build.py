@@ -20,6 +20,7 @@ SOURCES = {
     # with VALU instructions, and AGPR placement costs a register copy per element per tile
     # (the forward kernel also reuses its bf16 staging rows as fp32 exchange space between wavefronts)
     "mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-strict-aliasing"],
+    "mfma_fwd4.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-strict-aliasing"],
     "mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "probe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }

@@ -98,6 +98,8 @@ void launch_bwd(const KParams &p, int dtype, const BwdArgs &a, unsigned stages, 
 // mfma_fwd.hip: matrix-core forward for bf16, d = 64, b in {32, 64}
 bool fwd_mfma_supported(const KParams &p, int dtype);
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st);
+// mfma_fwd4.hip: the four-wavefront forward for block size 64 (launch_fwd_mfma dispatches to it)
+void launch_fwd_mfma4(const KParams &p, const FwdArgs &a, hipStream_t st);
 
 // mfma_bwd.hip: matrix-core dQ and dK/dV for bf16, d = 64, b in {32, 64}
 bool bwd_mfma_supported(const KParams &p, int dtype);

@@ -387,13 +387,14 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   auto tile_of = [&](int t) -> int {
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    if (e >= 0) {
-      const int Js = ((const_int_ptr)my_sel)[e];
-      return (unsigned)Js < (unsigned)p.NB ? Js : -1;
-    }
+    if (e >= 0) return ((const_int_ptr)my_sel)[e];  // raw: may be outside [0, NB), see list_entry
     if (!EQ15) return J_lo + t;
     return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
   };
+
+  // a raw tile-list value when it is consumed (a whole tile after its scalar load was issued): entries
+  // outside [0, NB) become -1, a tile whose keys are all masked
+  auto list_entry = [&](int raw) -> int { return (unsigned)raw < (unsigned)p.NB ? raw : -1; };
 
   Stager<BLK> sg;
   sg.init(wv, lane, p.L, p.NB);
@@ -484,8 +485,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
   };
 
-  int J_cur = tile_of(0);
-  int J_nxt = tile_of(min(1, n_all - 1));
+  int J_cur = list_entry(tile_of(0));
+  int J_nxt = list_entry(tile_of(min(1, n_all - 1)));
   sg.stage(k_lane, Ks0, J_cur);
   sg.stage(v_lane, Vs0, J_cur);
   __syncthreads();
@@ -506,7 +507,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
     }
     tile_body(k_cur, v_cur, J_cur, t < n_st);
     J_cur = J_nxt;
-    J_nxt = J_after;
+    J_nxt = list_entry(J_after);
     __syncthreads();
   };
   for (int t = 0; t < n_all; t += 2) {

@@ -272,12 +272,16 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
     if (dense) return J_first + t;
     const int e = __builtin_amdgcn_readfirstlane(t - n_st);
     typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    if (e >= 0) {
-      const int J = ((const_int_ptr)my_sel)[e];
-      return (unsigned)J < (unsigned)p.NB ? J : -1;
-    }
+    if (e >= 0) return ((const_int_ptr)my_sel)[e];  // raw: may be outside [0, NB), see list_entry
     if (!EQ15) return J_lo + t;
     return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
+  };
+
+  // a raw tile-list value when it is consumed (a whole tile after its scalar load was issued): entries
+  // outside [0, NB) become -1, a tile whose keys are all masked
+  auto list_entry = [&](int raw) -> int {
+    const int J = __builtin_amdgcn_readfirstlane(raw);
+    return (unsigned)J < (unsigned)p.NB ? J : -1;
   };
 
   // ---- per-lane LDS read offsets (elements) inside this wavefront's 32 rows ----
@@ -590,7 +594,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
   // V of tile t, then K of tile t+1; K of tile t (requested a step ago) is there once at most
   // those 8 are outstanding, V of tile t is waited for inside the tile.
   int J_cur = first_J;
-  int J_nxt = __builtin_amdgcn_readfirstlane(tile_raw(min(1, n_all - 1)));
+  int J_nxt = list_entry(tile_raw(min(1, n_all - 1)));
   auto step = [&](int t, uint16_t *k_cur, uint16_t *v_cur, uint16_t *k_nxt, uint16_t *v_nxt) __attribute__((always_inline)) {
     const int J_after = tile_raw(min(t + 2, n_all - 1));  // consumed at the end of this step
     const bool last = t + 1 >= n_all;
@@ -611,7 +615,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
     }
     tile(k_cur, V1 ? Vs0 : v_cur, J_cur, t < n_st, last);
     J_cur = J_nxt;
-    J_nxt = __builtin_amdgcn_readfirstlane(J_after);
+    J_nxt = list_entry(J_after);
     if (st_open && t + 1 >= n_st) close_st(k_cur, v_cur);  // the window tiles are done
   };
   for (int t = 0; t < n_all; t += 2) {
@@ -723,6 +727,10 @@ bool fwd_mfma_supported(const KParams &p, int dtype)
 
 void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st)
 {
+  if (p.b == 64) {  // block size 64: the four-wavefront kernel of mfma_fwd4.hip
+    launch_fwd_mfma4(p, a, st);
+    return;
+  }
   const unsigned grid = (unsigned)(p.B * p.H * p.nq);
   auto u16 = [](const void *x) { return reinterpret_cast<const uint16_t *>(x); };
   auto go = [&](auto kernel, unsigned threads) {
