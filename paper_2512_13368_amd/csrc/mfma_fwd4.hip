@@ -145,20 +145,20 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int ld_row = 16 * wv + (lane >> 3);  // + 8 for the second slice
   const unsigned k_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (lane >> 4)) * 8) * 2u;            // bytes
   const unsigned v_lane = (unsigned)(ld_row * D + ((lane & 7) ^ (2 * ((lane >> 3) & 3))) * 8) * 2u;  // bytes
-  const bool ragged = p.L % BLK != 0;
+  // (offsets inside a head stay below 2^31 bytes: one uniform 64-bit base per tensor, 32-bit lane offsets)
+  const int J_rag = p.L % BLK != 0 ? p.NB - 1 : -2;  // the one block whose rows run past the end, if any
   auto stage = [&](const char *src_head, unsigned lane_off, unsigned odd_xor, uint16_t *dst_tile, int J) __attribute__((always_inline)) {
-    const char *src = src_head + (size_t)max(J, 0) * (TILE * 2);  // uniform (block -1: a skipped list entry, all masked)
+    const unsigned joff = (unsigned)max(J, 0) * (unsigned)(TILE * 2);  // uniform (block -1: a skipped list entry, all masked)
     lds_void *dst = (lds_void *)(dst_tile + 16 * wv * D);
-    if (!ragged || J != p.NB - 1) {
-      __builtin_amdgcn_global_load_lds((glb_void *)(src + lane_off), dst, 16, 0, 0);
-      __builtin_amdgcn_global_load_lds((glb_void *)(src + (lane_off ^ odd_xor)), dst, 16, 1024, 0);
+    if (J != J_rag) {
+      __builtin_amdgcn_global_load_lds((glb_void *)(src_head + (joff + lane_off)), dst, 16, 0, 0);
+      __builtin_amdgcn_global_load_lds((glb_void *)(src_head + (joff + (lane_off ^ odd_xor))), dst, 16, 1024, 0);
     } else {  // last, partial block: rows past the end are clamped (they are causally masked anyway)
-      asm volatile("" : "+s"(J));
 #pragma unroll
       for (int u = 0; u < 2; ++u) {
         const int over = max(0, J * BLK + ld_row + 8 * u - (p.L - 1));
-        const unsigned off = ((u & 1) ? lane_off ^ odd_xor : lane_off) + (unsigned)((8 * u - over) * D * 2);
-        __builtin_amdgcn_global_load_lds((glb_void *)(src + off), (lds_void *)(dst_tile + (16 * wv + 8 * u) * D), 16, 0, 0);
+        const unsigned off = joff + ((u & 1) ? lane_off ^ odd_xor : lane_off) + (unsigned)((8 * u - over) * D * 2);
+        __builtin_amdgcn_global_load_lds((glb_void *)(src_head + off), (lds_void *)(dst_tile + (16 * wv + 8 * u) * D), 16, 0, 0);
       }
     }
   };
@@ -200,20 +200,26 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     }
     n_all = n_st + n_lt;
   }
-  auto tile_raw = [&](int t) -> int {
-    if (dense) return J_first + t;
-    const int e = __builtin_amdgcn_readfirstlane(t - n_st);
-    typedef const int __attribute__((address_space(4))) *const_int_ptr;  // read-only: loads become scalar
-    if (e >= 0) return ((const_int_ptr)my_sel)[e];  // raw: may be outside [0, NB), see list_entry
-    if (!EQ15) return J_lo + t;
-    return t < n_win ? J_lo + t : I - (1 << (r0 + t - n_win));
+  // The tile list, 64 entries at a time in one register (lane l: entry 64*c + l): window blocks by
+  // arithmetic, then the selection row; entries outside [0, NB) and entries past the end are -1 (a tile
+  // whose keys are all masked).  A step takes its block id with one v_readlane.
+  auto list_chunk = [&](int c) __attribute__((always_inline)) -> int {
+    const int t = 64 * c + lane;
+    int J;
+    if (dense) {
+      J = J_first + t;
+    } else if (t < n_st) {
+      J = (!EQ15 || t < n_win) ? J_lo + t : I - (1 << min(r0 + t - n_win, 30));
+    } else {
+      const int e = t - n_st;
+      J = e < p.k ? (e < 64 && n_st == 0 ? sel0 : my_sel[e]) : -1;
+      J = (unsigned)J < (unsigned)p.NB ? J : -1;
+    }
+    return t < n_all ? J : -1;
   };
-
-  // a raw tile-list value when it is consumed (a whole step after its scalar load was issued): entries
-  // outside [0, NB) become -1, a tile whose keys are all masked
-  auto list_entry = [&](int raw) -> int {
-    const int J = __builtin_amdgcn_readfirstlane(raw);
-    return (unsigned)J < (unsigned)p.NB ? J : -1;
+  int tl = list_chunk(0);
+  auto list_at = [&](int t) __attribute__((always_inline)) -> int {
+    return __builtin_amdgcn_readlane(tl, t & 63);
   };
 
   // ---- per-lane LDS read offsets (elements) inside the 32 key rows of half kh ----
@@ -247,6 +253,7 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     for (int i = 0; i < 16; ++i) { oacc[0][i] = 0.0f; oacc[1][i] = 0.0f; }
   };
 
+  const int J_whole = (p0 + BLK - 1) / BLK;  // first block without padding
   int hp_st, hp_lt;  // uniform: blocks whose rows may see fewer than kFewKeys4 keys feed P as hi + lo
   if (dense) {
     hp_st = 0;
@@ -356,9 +363,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const bool hp = (short_term ? hp_st : hp_lt) != 0;
     const bool windowed = short_term && !(EQ15 && !sub && is_pow2(I - J));
     asm volatile("" : "+v"(koff[0]), "+v"(koff[1]), "+v"(koff[2]), "+v"(koff[3]), "+v"(voff[0]), "+v"(voff[1]));
-    const int k_lo = J * BLK + 32 * kh, k_hi = k_lo + 31;
-    const int q_lo = qbase, q_hi = qbase + 31;
-    const bool full = k_hi <= q_lo && k_lo >= p0 && (!windowed || k_lo >= q_hi - p.w + 1);
+    // long-term tiles of whole earlier blocks (the usual case) need neither a mask nor any other test
+    bool full = !short_term && (unsigned)(J - J_whole) < (unsigned)(I - J_whole);
+    if (!full) {
+      const int k_lo = J * BLK + 32 * kh, k_hi = k_lo + 31;
+      const int q_lo = qbase, q_hi = qbase + 31;
+      full = J >= 0 && k_hi <= q_lo && k_lo >= p0 && (!windowed || k_lo >= q_hi - p.w + 1);
+      // no query of the group sees any of the 32 keys: later than all of them, padding, a skipped list
+      // entry, or (plain window) wholly below the window: nothing to compute
+      if (J < 0 || k_lo > q_hi || k_hi < p0 || (!EQ15 && windowed && k_hi < q_lo - p.w + 1)) return;
+    }
     bf16x8 kf[4];
 #pragma unroll
     for (int kk = 0; kk < 4; ++kk) kf[kk] = *reinterpret_cast<const bf16x8 *>(ks + koff[kk]);
@@ -437,7 +451,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   // ---- walk over the tile list ----
   f32x16 ost;  // normalised short-term output (this wavefront's channel block), parked during the long-term walk
   float lse_st = 0.0f;
-  bool st_open = !dense;
   reset();
   // Three buffer pairs, tiles requested two steps ahead: a tile's global->LDS loads have two whole
   // steps to land (the L2 latency under load is longer than one step of a wavefront).
@@ -445,8 +458,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   // barrier at the end of step t-1), process tile t, wait for this wavefront's own loads of tile t+1
   // (the four of tile t+2 stay in flight), barrier.
   int J_cur = first_J;
-  int J_n1 = list_entry(tile_raw(min(1, n_all - 1)));
-  int J_n2 = list_entry(tile_raw(min(2, n_all - 1)));
+  int J_n1 = list_at(1);
+  int J_n2 = list_at(2);
   if (n_all > 1) {
     stage(Kh, k_lane, 64u, Ks1, J_n1);
     stage(Vh, v_lane, 0u, Vs1, J_n1);
@@ -456,7 +469,6 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   }
   __syncthreads();  // tile 0 and the gate weights are in LDS
   auto step = [&](int t, uint16_t *k_cur, uint16_t *v_cur, uint16_t *k_fill, uint16_t *v_fill) __attribute__((always_inline)) {
-    const int J_n3 = tile_raw(min(t + 3, n_all - 1));  // consumed at the end of this step
     const bool more = t + 2 < n_all;
     if (more) {
       stage(Kh, k_lane, 64u, k_fill, J_n2);
@@ -465,13 +477,13 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     tile(k_cur, v_cur, J_cur, t < n_st);
     J_cur = J_n1;
     J_n1 = J_n2;
-    J_n2 = list_entry(J_n3);
-    if (st_open && t + 1 >= n_st) {  // the short-term tiles are done (the merge has its own barriers)
+    if (((t + 3) & 63) == 0 && t + 3 < n_all) tl = list_chunk((t + 3) >> 6);  // (once per 64 tiles)
+    J_n2 = list_at(t + 3);
+    if (t + 1 == n_st) {  // the short-term tiles are done (the merge has its own barriers)
       lse_st = close_branch(k_cur, v_cur);
       ost = fin;
       reset();
       set_ref(0.0f);
-      st_open = false;
     }
     if (more) __builtin_amdgcn_s_waitcnt(vmcnt_imm4(4));
     else __builtin_amdgcn_s_waitcnt(vmcnt_imm4(0));
