@@ -195,6 +195,61 @@ __global__ __launch_bounds__(64) void score_topk_kernel(const float *__restrict_
   for (int c = lane; c < D; c += 64) qs[c] = qsum[((size_t)bh * p.NB + I) * D + c];
   __syncthreads();
   const float *km = kmeanT + (size_t)bh * D * p.NB;
+  if (J_end - J_first <= 128 && J_end - J_first > 40) {  // (fewer candidates: the rank loop below is cheaper)
+    // Up to two candidates per lane, kept in registers.  Their scores are two independent chains over
+    // the channels; the k-th largest score image is found by a radix search from the top bit down
+    // (one ballot and one population count per bit and candidate slot: scalar work), and equal
+    // images are taken in ascending block order, which is the lower-index-wins rule.
+    const int Ja = J_first + lane, Jb = Ja + 64;
+    const bool has_a = Ja < J_end, has_b = Jb < J_end;
+    float acc_a = 0.0f, acc_b = 0.0f;
+    const float *ka = km + min(Ja, p.NB - 1), *kb = km + min(Jb, p.NB - 1);
+    if (J_end - J_first > 64) {
+#pragma unroll 16
+      for (int c = 0; c < D; ++c) {
+        acc_a = __fmaf_rn(qs[c], ka[(size_t)c * p.NB], acc_a);
+        acc_b = __fmaf_rn(qs[c], kb[(size_t)c * p.NB], acc_b);
+      }
+    } else {
+#pragma unroll 16
+      for (int c = 0; c < D; ++c) acc_a = __fmaf_rn(qs[c], ka[(size_t)c * p.NB], acc_a);
+    }
+    // 32-bit image of rank_key's upper word; the own block (bidirectional form) gets the largest value
+    auto image = [&](float sc, int J) -> unsigned {
+      if (J == I) return 0xFFFFFFFFu;
+      return (unsigned)(rank_key(sc, 0, 1) >> 32);
+    };
+    const unsigned ua = image(acc_a, Ja), ub = image(acc_b, Jb);
+    unsigned prefix = 0;
+    int remaining = take;
+    if (take > 0) {
+      for (int bit = 31; bit >= 0; --bit) {
+        const unsigned test = prefix | (1u << bit);
+        const unsigned himask = ~((1u << bit) - 1u);
+        const int cnt = __popcll(__ballot(has_a && (ua & himask) == test)) +
+                        __popcll(__ballot(has_b && (ub & himask) == test));
+        if (cnt >= remaining) prefix = test;  // the k-th largest has this bit set
+        else remaining -= cnt;                // everything with this bit set lies above it
+      }
+    }
+    // prefix: the take-th largest image; `remaining` of the candidates equal to it are still to be taken
+    const unsigned long long eq_a = __ballot(has_a && ua == prefix), eq_b = __ballot(has_b && ub == prefix);
+    const unsigned long long lt_mask = (1ull << lane) - 1ull;
+    const bool ch_a = take > 0 && has_a && (ua > prefix || (ua == prefix && __popcll(eq_a & lt_mask) < remaining));
+    const bool ch_b = take > 0 && has_b &&
+                      (ub > prefix || (ub == prefix && __popcll(eq_a) + __popcll(eq_b & lt_mask) < remaining));
+    const unsigned long long ma = __ballot(ch_a), mb = __ballot(ch_b);
+    if (ch_a) out[__popcll(ma & lt_mask)] = Ja;
+    const int na = __popcll(ma);
+    if (ch_b) out[na + __popcll(mb & lt_mask)] = Jb;
+    int base = na + __popcll(mb);
+    if (!p.bidir) {
+      if (lane == 0) out[base] = I;
+      ++base;
+    }
+    for (int e = base + lane; e < p.k; e += 64) out[e] = -1;
+    return;
+  }
   for (int J = J_first + lane; J < J_end; J += 64) {
     float acc = 0.0f;
 #pragma unroll 8
