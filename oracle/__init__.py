@@ -51,18 +51,22 @@ def lib() -> ctypes.CDLL:
         L.oracle_select_blocks_cmp.restype = _c_int
         L.oracle_select_blocks_cmp.argtypes = [_c_int] * 6 + [_vp, _vp, _vp, _vp, _c_int, _vp, _vp]
         L.oracle_build_masks.restype = _c_int
-        L.oracle_build_masks.argtypes = [_c_int] * 6 + [_vp, _vp, _vp]
+        L.oracle_build_masks.argtypes = [_c_int] * 7 + [_vp, _vp, _vp]
         L.oracle_masked_attention.restype = _c_int
         L.oracle_masked_attention.argtypes = [_c_int, _c_int, _vp, _vp, _vp, _vp, _c_dbl, _vp, _vp]
         L.oracle_attn_fwd.restype = _c_int
-        L.oracle_attn_fwd.argtypes = ([_c_int] * 8 + [_c_dbl, _c_int] + [_vp] * 7 + [_vp, _c_int]
+        L.oracle_attn_fwd.argtypes = ([_c_int] * 9 + [_c_dbl, _c_int] + [_vp] * 7 + [_vp, _c_int]
                                       + [_vp] * 7)
         L.oracle_attn_bwd.restype = _c_int
-        L.oracle_attn_bwd.argtypes = ([_c_int] * 8 + [_c_dbl, _c_int] + [_vp] * 8 + [_vp, _c_int]
+        L.oracle_attn_bwd.argtypes = ([_c_int] * 9 + [_c_dbl, _c_int] + [_vp] * 8 + [_vp, _c_int]
                                       + [_vp] * 5)
         L.oracle_dense_causal_fwd.restype = _c_int
         L.oracle_dense_causal_fwd.argtypes = ([_c_int] * 4 + [_c_dbl, _c_int] + [_vp] * 4
                                               + [_vp, _c_int, _vp, _vp])
+        L.oracle_select_positions.restype = _c_int
+        L.oracle_select_positions.argtypes = [_c_int] * 9 + [_c_dbl, _vp, _vp, _vp, _vp, _vp]
+        L.oracle_canon_exp.restype = ctypes.c_float
+        L.oracle_canon_exp.argtypes = [ctypes.c_float]
         L.oracle_rope.restype = _c_int
         L.oracle_rope.argtypes = [_c_int, _c_int, _c_int, _vp, _vp, _vp, _c_int, _vp]
         L.oracle_rope_bwd.restype = _c_int
@@ -142,17 +146,17 @@ def select_blocks_cmp(Q, Kcmp, valid_len, block, topk, bh_list=None, want_scores
     return (sel, scores) if want_scores else sel
 
 
-def build_masks(L, block, topk, window, n_valid, sel_bh, stis_block=0, bidir=False):
+def build_masks(L, block, topk, window, n_valid, sel_bh, stis_block=0, bidir=False, per_position=False):
     """The two materialised masks of one (row, head): uint8 [L,L] each.
 
     stis_block = 0: the short-term mask is the causal local window; >= 1: the causal form of all
     three terms of Eq. 15 with that mask block size."""
     s = np.ascontiguousarray(sel_bh, dtype=np.int32)
-    NB = -(-L // block)
+    NB = L if per_position else -(-L // block)
     assert s.shape == (NB, topk)
     M_lt = np.zeros((L, L), dtype=np.uint8)
     M_st = np.zeros((L, L), dtype=np.uint8)
-    _check(lib().oracle_build_masks(L, block, topk, window, _stis(stis_block, block, bidir), int(n_valid), _p(s), _p(M_lt), _p(M_st)),
+    _check(lib().oracle_build_masks(L, block, 1 if per_position else block, topk, window, _stis(stis_block, block, bidir), int(n_valid), _p(s), _p(M_lt), _p(M_st)),
            "build_masks")
     return M_lt, M_st
 
@@ -184,7 +188,7 @@ class Fwd:
 
 
 def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale=None,
-             bh_list=None, f64=False, stis_block=0, bidir=False) -> Fwd:
+             bh_list=None, f64=False, stis_block=0, bidir=False, per_position=False) -> Fwd:
     Q = _in(Q, f64)
     K = _in(K, f64)
     V = _in(V, f64)
@@ -193,7 +197,7 @@ def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale
         scale = 1.0 / np.sqrt(d)
     vl = np.ascontiguousarray(valid_len, dtype=np.int32)
     sel = np.ascontiguousarray(sel, dtype=np.int32)
-    NB = -(-L // block)
+    NB = L if per_position else -(-L // block)
     assert sel.shape == (B, H, NB, topk)
     gw = _in(gate_w, f64)
     assert gw.shape == (H, 2 * d)
@@ -202,7 +206,7 @@ def attn_fwd(Q, K, V, valid_len, sel, gate_w, gate_b, block, topk, window, scale
     z = lambda *s: np.zeros(s, dtype=np.float64)
     out = Fwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L), z(n_bh, L), z(n_bh, L), 0, 0)
     nnz = np.zeros(2, dtype=np.int64)
-    rc = lib().oracle_attn_fwd(B, H, L, d, block, topk, window, _stis(stis_block, block, bidir), float(scale), int(f64),
+    rc = lib().oracle_attn_fwd(B, H, L, d, block, 1 if per_position else block, topk, window, _stis(stis_block, block, bidir), float(scale), int(f64),
                                _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(bh), n_bh,
                                _p(out.O), _p(out.o_lt), _p(out.o_st), _p(out.lse_lt), _p(out.lse_st),
                                _p(out.alpha), _p(nnz))
@@ -221,7 +225,7 @@ class Bwd:
 
 
 def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, scale=None,
-             bh_list=None, f64=False, stis_block=0, bidir=False) -> Bwd:
+             bh_list=None, f64=False, stis_block=0, bidir=False, per_position=False) -> Bwd:
     Q = _in(Q, f64)
     K = _in(K, f64)
     V = _in(V, f64)
@@ -237,7 +241,7 @@ def attn_bwd(Q, K, V, valid_len, sel, gate_w, gate_b, dO, block, topk, window, s
     bh, n_bh = _bh(bh_list, B, H)
     z = lambda *s: np.zeros(s, dtype=np.float64)
     out = Bwd(z(n_bh, L, d), z(n_bh, L, d), z(n_bh, L, d), z(H, 2 * d), z(H))
-    rc = lib().oracle_attn_bwd(B, H, L, d, block, topk, window, _stis(stis_block, block, bidir), float(scale), int(f64),
+    rc = lib().oracle_attn_bwd(B, H, L, d, block, 1 if per_position else block, topk, window, _stis(stis_block, block, bidir), float(scale), int(f64),
                                _p(Q), _p(K), _p(V), _p(vl), _p(sel), _p(gw), _p(gb), _p(dO),
                                _p(bh), n_bh, _p(out.dQ), _p(out.dK), _p(out.dV),
                                _p(out.d_gate_w), _p(out.d_gate_b))
@@ -284,3 +288,27 @@ def rope_bwd(g, cos, sin):
     out = np.empty_like(g)
     _check(lib().oracle_rope_bwd(int(g.size // (L * d)), L, d, _p(g), _p(cos), _p(sin), _p(out)), "rope_bwd")
     return out
+
+
+def canon_exp(x: float) -> float:
+    """The canonical fp32 exponential of the printed selection rule (x <= 0)."""
+    return float(lib().oracle_canon_exp(ctypes.c_float(x)))
+
+
+def select_positions(Q, K, valid_len, cmp_block, stride, sel_block, topk, score_scale=1.0, want_scores=False):
+    """The selection rule of Sec. 3.4 as printed (Eq. 8-13): Q [B,H,L,d], K [B,G,L,d] float32 (G key/value
+    groups, H = G*Hg).  Returns sel [B,G,L,k] int32 (one ascending, -1 padded row per position and group) and,
+    if asked, the group scores [B,G,L,ceil(L/sel_block)] float32."""
+    Q = _in(Q, False)
+    K = _in(K, False)
+    B, H, L, d = Q.shape
+    G = K.shape[1]
+    assert K.shape == (B, G, L, d) and H % G == 0
+    vl = np.ascontiguousarray(valid_len, dtype=np.int32)
+    NBs = -(-L // sel_block)
+    sel = np.full((B, G, L, topk), -2, dtype=np.int32)
+    scores = np.zeros((B, G, L, NBs), dtype=np.float32) if want_scores else None
+    rc = lib().oracle_select_positions(B, H, G, L, d, cmp_block, stride, sel_block, topk, float(score_scale),
+                                       _p(Q), _p(K), _p(vl), _p(sel), _p(scores))
+    _check(rc, "select_positions")
+    return (sel, scores) if want_scores else sel

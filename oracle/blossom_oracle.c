@@ -34,6 +34,9 @@
  *   6. Gate (Eq. 18-19): alpha = sigmoid(Wg . [o_lt ; o_st] + bg) per
  *      (position, head); O = alpha*o_lt + (1-alpha)*o_st.
  *   7. Backward: the chain rule through steps 4-6 with the selection frozen.
+ *   1'-3'. (instead of 1-3, SURVEY's NEXT-2) The selection rule as the paper prints it, per query
+ *      position and key/value group: oracle_select_positions; the attention steps then read one
+ *      selection row per position (qb = 1).
  *   0. (ahead of step 1, optional) Rotary position embedding of Q and K (Sec. 3.3: applied to
  *      the projected queries and keys before both branches): oracle_rope / oracle_rope_bwd.
  *
@@ -276,19 +279,178 @@ int oracle_rope_bwd(int BH, int L, int d, const double *g, const float *cosv, co
 }
 
 /* ------------------------------------------------------------------------- */
+/* The selection rule of Sec. 3.4 as printed (Eq. 8-13): overlapping compression */
+/* blocks, per-position softmax scores, score mapping to selection blocks,       */
+/* group sum over the query heads that share a key/value head, top-k per         */
+/* position.                                                                     */
+/*                                                                               */
+/*   Q [B,H,L,d], K [B,G,L,d] fp32; H = G*Hg, query head h uses key head h / Hg  */
+/*   (Eq. 4-5 with contiguous groups).  Row r has n valid positions, left padded.*/
+/*   Eq. 8:  compression block m covers positions [m*s, m*s + l), m = 0..M-1,    */
+/*           M = floor((L - l)/s) + 1  (none when L < l).                        */
+/*   Eq. 9:  phi = mean over the block's valid keys (the paper's learnable MLP   */
+/*           is unspecified; same reading as the hot path).                      */
+/*   Eq. 10: for query position t the eligible blocks are those that end at or   */
+/*           before t and hold a valid key (m*s + l - 1 <= t, m*s + l - 1 >= p0):*/
+/*           S_cmp[t][m] = softmax over them of score_scale * q_t . Kcmp_m       */
+/*           (the printed formula has no scale: score_scale = 1).                */
+/*   Eq. 11: S_sel[t][j] = sum_{a=0}^{l'/s-1} sum_{c=0}^{l/s-1} S_cmp[t][(l'/s) j - a - c]  */
+/*           (indices outside the eligible blocks contribute nothing);           */
+/*           requires s | l and s | l'.  (The text also asks for l <= l', but the  */
+/*           paper's own setting, Appendix E, is l = 32, l' = 16: the formula is  */
+/*           applied as printed either way.)                                     */
+/*   Eq. 12: the scores of the Hg query heads of a group are added.              */
+/*   Eq. 13: per (position, group) the block holding t is always taken and       */
+/*           counts toward k (as in the hot path); the other k-1 come from the   */
+/*           earlier selection blocks j < t / l' that hold a valid key, ordered  */
+/*           by (score descending, index ascending); written ascending, -1 padded.*/
+/*                                                                               */
+/* Canonical fp32 arithmetic (the result is a set of integers, so both sides must */
+/* round alike): sums ascending from +0.0f; dot products as fmaf chains over the  */
+/* channels; one fp32 multiply by score_scale; x - max in fp32; the exponential   */
+/* below; the normaliser as a sequential sum; one IEEE division per score; Eq. 11 */
+/* in the printed loop order (a outer, c inner), Eq. 12 heads ascending.          */
+/* canon_exp(x), x <= 0: y = x * log2(e) (one multiply), n = rint(y) (ties even), */
+/* f = y - n (exact), 2^f by the degree-7 Taylor polynomial of e^(f ln 2) in      */
+/* Horner form with fmaf, scaled by 2^n exactly; 0 when n < -125.                 */
+/* ------------------------------------------------------------------------- */
+static float canon_exp(float x)
+{
+    static const float c[8] = {1.0f, 0.693147182f, 0.240226507f, 0.0555041087f, 0.00961812911f,
+                               0.00133335581f, 0.000154035304f, 1.52527338e-05f};
+    const float y = x * 1.44269502f;
+    const float n = rintf(y);
+    if (n < -125.0f) return 0.0f;
+    const float f = y - n;
+    float pz = c[7];
+    for (int i = 6; i >= 0; --i) pz = fmaf(pz, f, c[i]);
+    return ldexpf(pz, (int)n);
+}
+
+float oracle_canon_exp(float x) { return canon_exp(x); }
+
+int oracle_select_positions(int B, int H, int G, int L, int d, int l, int s, int lsel, int k, double score_scale,
+                            const float *Q, const float *K, const int32_t *valid_len,
+                            int32_t *sel /* [B,G,L,k] */, float *scores /* [B,G,L,NBs] or NULL */)
+{
+    if (B < 1 || H < 1 || G < 1 || H % G || L < 1 || d < 1 || k < 1) return -2;
+    if (l < 1 || s < 1 || lsel < 1 || l % s || lsel % s) return -2;
+    const int Hg = H / G;
+    const int M = L >= l ? (L - l) / s + 1 : 0;
+    const int NBs = n_blocks(L, lsel);
+    const int ra = lsel / s, rc = l / s;
+    const float fscale = (float)score_scale;
+    int err = 0;
+#pragma omp parallel for schedule(dynamic, 1)
+    for (int bg = 0; bg < B * G; ++bg) {
+        const int r = bg / G, g = bg % G;
+        int n = valid_len[r];
+        if (n < 0) n = 0;
+        if (n > L) n = L;
+        const int p0 = L - n;
+        float *kcmp = (float *)calloc((size_t)(M > 0 ? M : 1) * d, sizeof(float));
+        float *scmp = (float *)calloc((size_t)(M > 0 ? M : 1), sizeof(float));
+        float *ssel = (float *)calloc((size_t)NBs, sizeof(float));
+        float *sgrp = (float *)calloc((size_t)NBs, sizeof(float));
+        uint8_t *chosen = (uint8_t *)calloc((size_t)NBs, 1);
+        if (!kcmp || !scmp || !ssel || !sgrp || !chosen) {
+#pragma omp atomic write
+            err = -1;
+        } else {
+            const float *key = K + (size_t)bg * L * d;
+            for (int m = 0; m < M; ++m)              /* Eq. 8-9 */
+                for (int c = 0; c < d; ++c) {
+                    float a = 0.0f;
+                    int cnt = 0;
+                    for (int t = m * s; t < m * s + l; ++t) {
+                        if (t < p0) continue;
+                        a = a + key[(size_t)t * d + c];
+                        ++cnt;
+                    }
+                    kcmp[(size_t)m * d + c] = cnt > 0 ? a / (float)cnt : 0.0f;
+                }
+            for (int t = 0; t < L; ++t) {
+                int32_t *out = sel + ((size_t)bg * L + t) * k;
+                for (int e = 0; e < k; ++e) out[e] = -1;
+                float *sc_out = scores ? scores + ((size_t)bg * L + t) * NBs : NULL;
+                if (sc_out)
+                    for (int j = 0; j < NBs; ++j) sc_out[j] = 0.0f;
+                if (t < p0) continue;
+                for (int j = 0; j < NBs; ++j) sgrp[j] = 0.0f;
+                /* eligible compression blocks: m_lo .. m_hi */
+                int m_hi = -1, m_lo = 0;
+                if (t - l + 1 >= 0) m_hi = imin(M - 1, (t - l + 1) / s);
+                {
+                    const int need = p0 - l + 1; /* m*s >= need */
+                    m_lo = need <= 0 ? 0 : (need + s - 1) / s;
+                }
+                for (int hh = 0; hh < Hg; ++hh) {   /* Eq. 10, 11 per head; Eq. 12 over the group */
+                    const float *q = Q + (((size_t)r * H + (size_t)g * Hg + hh) * L + t) * d;
+                    float mx = -INFINITY;
+                    for (int m = m_lo; m <= m_hi; ++m) {
+                        float acc = 0.0f;
+                        for (int c = 0; c < d; ++c) acc = fmaf(q[c], kcmp[(size_t)m * d + c], acc);
+                        scmp[m] = acc * fscale;
+                        if (scmp[m] > mx) mx = scmp[m];
+                    }
+                    float z = 0.0f;
+                    for (int m = m_lo; m <= m_hi; ++m) {
+                        scmp[m] = canon_exp(scmp[m] - mx);
+                        z = z + scmp[m];
+                    }
+                    for (int m = m_lo; m <= m_hi; ++m) scmp[m] = scmp[m] / z;
+                    for (int j = 0; j < NBs; ++j) {
+                        float acc = 0.0f;
+                        for (int a = 0; a < ra; ++a)
+                            for (int c = 0; c < rc; ++c) {
+                                const int idx = ra * j - a - c;
+                                if (idx >= m_lo && idx <= m_hi) acc = acc + scmp[idx];
+                            }
+                        ssel[j] = acc;
+                    }
+                    for (int j = 0; j < NBs; ++j) sgrp[j] = sgrp[j] + ssel[j];
+                }
+                if (sc_out)
+                    for (int j = 0; j < NBs; ++j) sc_out[j] = sgrp[j];
+                /* Eq. 13 */
+                const int jt = t / lsel, j_first = p0 / lsel;
+                const int take = imin(k - 1, jt - j_first);
+                for (int j = 0; j < NBs; ++j) chosen[j] = 0;
+                for (int rr = 0; rr < take; ++rr) {
+                    int best = -1;
+                    for (int j = j_first; j < jt; ++j) {
+                        if (chosen[j]) continue;
+                        if (best < 0 || sgrp[j] > sgrp[best]) best = j;  /* strict: lowest index among equals */
+                    }
+                    chosen[best] = 1;
+                }
+                chosen[jt] = 1;
+                int e = 0;
+                for (int j = j_first; j <= jt; ++j)
+                    if (chosen[j]) out[e++] = j;
+            }
+        }
+        free(kcmp); free(scmp); free(ssel); free(sgrp); free(chosen);
+    }
+    return err;
+}
+
+/* ------------------------------------------------------------------------- */
 static int is_power_of_two(int x) { return x >= 1 && (x & (x - 1)) == 0; }
 
 /* stis_blk < 0: the bidirectional form with mask block -stis_blk: Eq. 15 exactly as printed
  * (|i-j| < w, |b_q-b_k| = 2^r, last block; no causal mask), and the selected blocks of the
  * long-term branch seen whole. */
-static void build_masks_one(int L, int b, int k, int w, int stis_blk, int n_valid, const int32_t *sel,
+/* qb: query granularity of the selection rows: row i reads the list of entry i / qb.  qb = b is the
+ * per-query-block selection of the hot path; qb = 1 a selection per query position (Eq. 13 as printed). */
+static void build_masks_one(int L, int b, int qb, int k, int w, int stis_blk, int n_valid, const int32_t *sel,
                             uint8_t *M_lt, uint8_t *M_st)
 {
     const int bidir = stis_blk < 0;
     if (bidir) stis_blk = -stis_blk;
     const int p0 = L - n_valid;
     for (int i = 0; i < L; ++i) {
-        const int32_t *si = sel + (size_t)(i / b) * k;
+        const int32_t *si = sel + (size_t)(i / qb) * k;
         for (int j = 0; j < L; ++j) {
             uint8_t lt = 0, st = 0;
             if (i >= p0 && j >= p0) {
@@ -318,12 +480,13 @@ static void build_masks_one(int L, int b, int k, int w, int stis_blk, int n_vali
     }
 }
 
-int oracle_build_masks(int L, int b, int k, int w, int stis_blk, int n_valid, const int32_t *sel_bh,
+int oracle_build_masks(int L, int b, int qb, int k, int w, int stis_blk, int n_valid, const int32_t *sel_bh,
                        uint8_t *M_lt, uint8_t *M_st)
 {
     if (n_valid < 0) n_valid = 0;
     if (n_valid > L) n_valid = L;
-    build_masks_one(L, b, k, w, stis_blk, n_valid, sel_bh, M_lt, M_st);
+    if (qb < 1) return -2;
+    build_masks_one(L, b, qb, k, w, stis_blk, n_valid, sel_bh, M_lt, M_st);
     return 0;
 }
 
@@ -410,7 +573,7 @@ static double load1(const void *src, int is_f64, size_t idx)
 /*   O, o_lt, o_st [n_bh,L,d]; lse_lt, lse_st, alpha [n_bh,L]; any may be NULL */
 /*   nnz [2]: number of unmasked (i,j) pairs in the two branches, summed.      */
 /* ------------------------------------------------------------------------- */
-int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, int stis_blk, double scale,
+int oracle_attn_fwd(int B, int H, int L, int d, int b, int qb, int k, int w, int stis_blk, double scale,
                     int in_f64, const void *Q, const void *K, const void *V,
                     const int32_t *valid_len, const int32_t *sel,
                     const void *gate_w, const void *gate_b,
@@ -418,8 +581,8 @@ int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, int stis_bl
                     double *O, double *o_lt, double *o_st,
                     double *lse_lt, double *lse_st, double *alpha, long long *nnz)
 {
-    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || k < 1 || w < 1) return -2;
-    const int NB = n_blocks(L, b);
+    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || qb < 1 || k < 1 || w < 1) return -2;
+    const int NBq = n_blocks(L, qb);
     const int total = bh_list ? n_bh : B * H;
     const size_t Ld = (size_t)L * d;
     long long nnz_lt = 0, nnz_st = 0;
@@ -448,7 +611,7 @@ int oracle_attn_fwd(int B, int H, int L, int d, int b, int k, int w, int stis_bl
             widen(Q, in_f64, (size_t)bh * Ld, Ld, q);
             widen(K, in_f64, (size_t)bh * Ld, Ld, key);
             widen(V, in_f64, (size_t)bh * Ld, Ld, v);
-            build_masks_one(L, b, k, w, stis_blk, n, sel + (size_t)bh * NB * k, M_lt, M_st);
+            build_masks_one(L, b, qb, k, w, stis_blk, n, sel + (size_t)bh * NBq * k, M_lt, M_st);
             long long c_lt = 0, c_st = 0;
             masked_attention(L, d, q, key, v, M_lt, scale, ol, ll, &c_lt);
             masked_attention(L, d, q, key, v, M_st, scale, os, ls, &c_st);
@@ -524,15 +687,15 @@ static void masked_attention_bwd(int L, int d, const double *q, const double *ke
  * dQ, dK, dV [n_bh,L,d] compact; d_gate_w [H,2d], d_gate_b [H] are summed over
  * the listed pairs only, in list order.
  */
-int oracle_attn_bwd(int B, int H, int L, int d, int b, int k, int w, int stis_blk, double scale,
+int oracle_attn_bwd(int B, int H, int L, int d, int b, int qb, int k, int w, int stis_blk, double scale,
                     int in_f64, const void *Q, const void *K, const void *V,
                     const int32_t *valid_len, const int32_t *sel,
                     const void *gate_w, const void *gate_b, const void *dO,
                     const int32_t *bh_list, int n_bh,
                     double *dQ, double *dK, double *dV, double *d_gate_w, double *d_gate_b)
 {
-    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || k < 1 || w < 1) return -2;
-    const int NB = n_blocks(L, b);
+    if (B < 1 || H < 1 || L < 1 || d < 1 || b < 1 || qb < 1 || k < 1 || w < 1) return -2;
+    const int NBq = n_blocks(L, qb);
     const int total = bh_list ? n_bh : B * H;
     const size_t Ld = (size_t)L * d;
     const int G = 2 * d + 1;
@@ -571,7 +734,7 @@ int oracle_attn_bwd(int B, int H, int L, int d, int b, int k, int w, int stis_bl
             widen(K, in_f64, (size_t)bh * Ld, Ld, key);
             widen(V, in_f64, (size_t)bh * Ld, Ld, v);
             widen(dO, in_f64, (size_t)bh * Ld, Ld, g);
-            build_masks_one(L, b, k, w, stis_blk, n, sel + (size_t)bh * NB * k, M_lt, M_st);
+            build_masks_one(L, b, qb, k, w, stis_blk, n, sel + (size_t)bh * NBq * k, M_lt, M_st);
             masked_attention(L, d, q, key, v, M_lt, scale, ol, ll, NULL);
             masked_attention(L, d, q, key, v, M_st, scale, os, ls, NULL);
             double *gp = gpart + (size_t)it * G;
