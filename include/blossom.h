@@ -141,6 +141,35 @@ int blossom_select_blocks_static(const blossom_params *p, const void *Q, const v
                                  const int32_t *valid_len, int32_t *sel, void *hip_stream);
 
 /*
+ * The selection rule as the paper prints it (Sec. 3.4, Eq. 8-13), per query POSITION and key/value group
+ * (grouped-query attention, Eq. 4-5: H query heads share G = kv_groups key heads, head h uses key head
+ * h / (H/G)).  p->block is the selection block size l', p->topk is k, p->window and the stis fields are
+ * not used.  Steps, all in a fixed fp32 arithmetic (sums ascending from +0, fused-multiply-add chains over
+ * the channels, one sequential sum for the softmax normaliser, one IEEE division per score, a fixed
+ * polynomial exponential), so that the integers that come out have one right answer:
+ *   Eq. 8   compression block m covers positions [m*s, m*s+l), m < M = floor((L-l)/s)+1 (s | l, s | l';
+ *           l may exceed l' as in the paper's own setting l = 32, s = 16, l' = 16);
+ *   Eq. 9   compressed key = mean of the block's valid keys;
+ *   Eq. 10  for position t: softmax over the compression blocks that end at or before t and hold a
+ *           valid key of score_scale * q_t . Kcmp_m (score_scale 0 means 1, the printed formula);
+ *   Eq. 11  S_sel[j] = sum_{a < l'/s} sum_{c < l/s} S_cmp[(l'/s) j - a - c];
+ *   Eq. 12  the scores of the H/G query heads of a group are added;
+ *   Eq. 13  the block holding t plus the best min(k-1, .) earlier selection blocks that hold a valid
+ *           key, by (score descending, index ascending); ascending list, -1 padded; padding positions
+ *           get all -1.
+ *   Q        in   [B,H,L,d];  K in [B,G,L,d]  (element type p->dtype, 16-byte aligned)
+ *   sel_pos  out  int32 [B,G,L,topk]
+ *   ws       scratch, >= blossom_select_positions_workspace_bytes(...), 16-byte aligned
+ * Limits: ceil(L/l') <= 512 selection blocks; BLOSSOM_ERR_SHAPE beyond.  (The attention kernels of this
+ * library take one selection row per query block; a per-position selection is consumed by the caller.)
+ */
+size_t blossom_select_positions_workspace_bytes(const blossom_params *p, int32_t kv_groups, int32_t cmp_block,
+                                                int32_t cmp_stride);
+int blossom_select_positions(const blossom_params *p, int32_t kv_groups, int32_t cmp_block, int32_t cmp_stride,
+                             float score_scale, const void *Q, const void *K, const int32_t *valid_len,
+                             int32_t *sel_pos, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
  * Rotary position embedding (Sec. 3.3: RoPE is applied to the projected Q and K before both branches)
  * fused into the pooling pass of blossom_select_blocks, which reads Q and K anyway: every position m of
  * every row is rotated on the way in, channel pairs (2i, 2i+1) by the angle of table entry [m][i],

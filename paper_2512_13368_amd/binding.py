@@ -18,7 +18,8 @@ F32, BF16 = 0, 1
 WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
 EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp",
-           "blossom_rope_select_blocks", "blossom_attn_bwd_rope", "blossom_attn_fwd", "blossom_attn_bwd",
+           "blossom_rope_select_blocks", "blossom_attn_bwd_rope", "blossom_select_positions_workspace_bytes",
+           "blossom_select_positions", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_probe_bytes", "blossom_probe", "blossom_strerror", "blossom_version")
 PROBE_WORKGROUPS = 4096
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
@@ -61,6 +62,11 @@ def lib() -> ctypes.CDLL:
         L.blossom_select_blocks_static.argtypes = [pp, vp, vp, i32p, i32p, vp]
         L.blossom_rope_select_blocks.restype = ctypes.c_int
         L.blossom_rope_select_blocks.argtypes = [pp, vp, vp, fp, fp, i32p, vp, vp, i32p, vp, ctypes.c_size_t, vp]
+        L.blossom_select_positions_workspace_bytes.restype = ctypes.c_size_t
+        L.blossom_select_positions_workspace_bytes.argtypes = [pp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32]
+        L.blossom_select_positions.restype = ctypes.c_int
+        L.blossom_select_positions.argtypes = [pp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
+                                               vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_select_blocks_cmp.restype = ctypes.c_int
         L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
@@ -374,3 +380,26 @@ def probe(kind: int, K, V, sink, iters: int, stream=None):
     rc = lib().blossom_probe(int(kind), _ptr(K), _ptr(V), _ptr(sink), int(iters), _stream(stream))
     if rc:
         raise BlossomError(rc, "blossom_probe")
+
+
+def select_positions(p: Params, kv_groups: int, cmp_block: int, cmp_stride: int, Q, K, valid_len, score_scale: float = 0.0,
+                     sel_pos=None, ws=None, stream=None):
+    """blossom_select_positions: the printed selection rule, one row per position and key/value group.
+    p.block is the selection block size, p.topk is k.  Returns sel_pos int32 [B,G,L,topk]."""
+    import torch
+    dt = _torch_dtype(p)
+    _check_tensor(Q, (p.B, p.H, p.L, p.d), dt, "Q")
+    _check_tensor(K, (p.B, kv_groups, p.L, p.d), dt, "K")
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    if sel_pos is None:
+        sel_pos = torch.empty((p.B, kv_groups, p.L, p.topk), dtype=torch.int32, device=Q.device)
+    _check_tensor(sel_pos, (p.B, kv_groups, p.L, p.topk), torch.int32, "sel_pos")
+    cp = p.c()
+    need = int(lib().blossom_select_positions_workspace_bytes(ctypes.byref(cp), kv_groups, cmp_block, cmp_stride))
+    if ws is None:
+        ws = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
+    rc = lib().blossom_select_positions(ctypes.byref(cp), kv_groups, cmp_block, cmp_stride, float(score_scale), _ptr(Q),
+                                        _ptr(K), _ptr(valid_len), _ptr(sel_pos), _ptr(ws), ws.numel(), _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_select_positions")
+    return sel_pos

@@ -15,6 +15,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = {
     "api.hip": [],
     "select.hip": ["-ffp-contract=off"],
+    "select_pos.hip": ["-ffp-contract=off"],
     "generic.hip": [],
     # accumulators of the matrix instructions stay in VGPRs: the online softmax rescales them
     # with VALU instructions, and AGPR placement costs a register copy per element per tile

@@ -126,6 +126,27 @@ def test_validation_codes_rope_and_probe(lib):
     assert st(Q=None) == -1 and st(Q=vp(4100)) == -5 and st(p=_p(topk=0).c()) == -4
 
 
+def test_validation_codes_select_positions(lib):
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    f32 = ctypes.c_float
+    call = lambda p, G=2, l=32, s=16, sc=0.0, Q=a, ws=a, n=1 << 30: lib.blossom_select_positions(
+        ctypes.byref(p.c()), G, l, s, f32(sc), Q, a, a, a, ws, n, None)
+    ok = _p(H=4, L=200, d=8, block=16, topk=4)
+    assert call(ok, Q=None) == -1
+    assert call(ok, G=3) == -4                       # heads not divisible by the groups
+    assert call(ok, s=5) == -4                       # the stride divides neither block size
+    assert call(ok, l=24, s=16) == -4
+    assert call(ok, sc=-1.0) == -4
+    assert call(_p(H=4, L=200, d=12, block=16, topk=4)) == -3
+    assert call(_p(H=4, L=16 * 600, d=8, block=16, topk=4)) == -2   # more than 512 selection blocks
+    assert call(ok, ws=None) == -6 and call(ok, n=8) == -6
+    assert call(ok, Q=vp(4100)) == -5
+    need = lib.blossom_select_positions_workspace_bytes(ctypes.byref(ok.c()), 2, 32, 16)
+    assert need == 2 * 2 * 8 * ((200 - 32) // 16 + 1) * 4
+    assert lib.blossom_select_positions_workspace_bytes(ctypes.byref(ok.c()), 3, 32, 16) == 0
+
+
 def test_strerror(lib):
     seen = set()
     for code in range(0, -9, -1):
