@@ -161,9 +161,8 @@ __device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x
     for (int g = 0; g < 4; ++g) {
       const int d0 = 32 * mb + 8 * g + 4 * lh;
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(acc[mb][4 * g] * scale) | ((uint32_t)f32_to_bf16(acc[mb][4 * g + 1] * scale) << 16);
-      pk.y = (uint32_t)f32_to_bf16(acc[mb][4 * g + 2] * scale) |
-             ((uint32_t)f32_to_bf16(acc[mb][4 * g + 3] * scale) << 16);
+      pk.x = pack2_bf16(acc[mb][4 * g] * scale, acc[mb][4 * g + 1] * scale);
+      pk.y = pack2_bf16(acc[mb][4 * g + 2] * scale, acc[mb][4 * g + 3] * scale);
       *reinterpret_cast<uint2 *>(row + d0) = pk;
     }
 }
@@ -196,8 +195,8 @@ __device__ __forceinline__ void store_rows_bf16(uint16_t *dst_row0, int rows_lef
         unrope_pair(p, m, pair + 1, D / 2, v2, v3);
       }
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(v0 * sc) | ((uint32_t)f32_to_bf16(v1 * sc) << 16);
-      pk.y = (uint32_t)f32_to_bf16(v2 * sc) | ((uint32_t)f32_to_bf16(v3 * sc) << 16);
+      pk.x = pack2_bf16(v0 * sc, v1 * sc);
+      pk.y = pack2_bf16(v2 * sc, v3 * sc);
       const int chunk = 4 * mb + g;  // 16-byte chunk of the row; this lane fills half elh of it
       *reinterpret_cast<uint2 *>(pt + elq * D + ((chunk ^ (elq & 7)) * 8) + 4 * elh) = pk;
     }

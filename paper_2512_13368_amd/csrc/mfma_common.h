@@ -45,6 +45,13 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned pid, unsigned total)
 //    are 8 distinct values because swz differs in bits 1-2 between rows with equal bits 2-3.
 __device__ __forceinline__ int swz(int r) { return (((r & 3) << 1) | ((r >> 2) & 1)) ^ (((r >> 3) & 1) << 1); }
 
+// two floats -> one register of two bf16 (round to nearest even in hardware: v_cvt_pk_bf16_f32)
+__device__ __forceinline__ uint32_t pack2_bf16(float a, float b)
+{
+  const bf16x2 v = {(__bf16)a, (__bf16)b};
+  return __builtin_bit_cast(uint32_t, v);
+}
+
 // bf16 pair -> two floats and back (round to nearest even through the hardware conversion)
 __device__ __forceinline__ float bf_lo(uint32_t w) { return __uint_as_float(w << 16); }
 __device__ __forceinline__ float bf_hi(uint32_t w) { return __uint_as_float(w & 0xFFFF0000u); }

@@ -665,8 +665,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
 #pragma unroll
       for (int g = 0; g < 4; ++g) {
         uint2 pk;
-        pk.x = (uint32_t)f32_to_bf16(o4(mb, g, 0)) | ((uint32_t)f32_to_bf16(o4(mb, g, 1)) << 16);
-        pk.y = (uint32_t)f32_to_bf16(o4(mb, g, 2)) | ((uint32_t)f32_to_bf16(o4(mb, g, 3)) << 16);
+        pk.x = pack2_bf16(o4(mb, g, 0), o4(mb, g, 1));
+        pk.y = pack2_bf16(o4(mb, g, 2), o4(mb, g, 3));
         const int chunk = 4 * mb + g;  // 16-byte chunk (8 channels); this lane fills half lh of it
         *reinterpret_cast<uint2 *>(pt + elq * D + ((chunk ^ (elq & 7)) * 8) + 4 * elh) = pk;
       }

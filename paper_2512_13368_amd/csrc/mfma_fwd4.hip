@@ -529,8 +529,8 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
     for (int g = 0; g < 4; ++g) {
       uint2 pk;
-      pk.x = (uint32_t)f32_to_bf16(o4(g, 0)) | ((uint32_t)f32_to_bf16(o4(g, 1)) << 16);
-      pk.y = (uint32_t)f32_to_bf16(o4(g, 2)) | ((uint32_t)f32_to_bf16(o4(g, 3)) << 16);
+      pk.x = pack2_bf16(o4(g, 0), o4(g, 1));
+      pk.y = pack2_bf16(o4(g, 2), o4(g, 3));
       // 16-byte chunk g of the row's 4 (8 channels); this lane fills half elh of it
       *reinterpret_cast<uint2 *>(pt + elq * 32 + ((g ^ (elq & 3)) * 8) + 4 * elh) = pk;
     }
