@@ -388,8 +388,10 @@ __global__ __launch_bounds__(256) void bwd_prep_kernel(const float *__restrict__
 
   for (int base = 0; base < kPrepRows; base += RPS) {
     const int i = chunk * kPrepRows + base + wave * RPW + rg;
-    const bool inb = i < p.L;
-    const bool valid = inb && i >= p0;
+    const bool valid = i < p.L && i >= p0;
+    // rows of blocks that hold no valid position are never read by the kernels that follow: nothing is
+    // written for them (pad rows of a partly valid block are staged with their tile and get zeros)
+    const bool inb = i < p.L && i >= (p0 / p.b) * p.b;
     float g[4] = {0.f, 0.f, 0.f, 0.f}, ol[4] = {0.f, 0.f, 0.f, 0.f}, os[4] = {0.f, 0.f, 0.f, 0.f};
     if (valid) {
       const size_t ro = head + (size_t)i * D + c4;

@@ -147,27 +147,8 @@ __device__ __forceinline__ void load_frags(const uint16_t *row, int lh, float c,
   }
 }
 
-// store 2 x 16 accumulators (d x rows, transposed) of this lane's row as bf16, scaled
-__device__ __forceinline__ void store_row_bf16(uint16_t *row, int lh, const f32x16 (&acc)[2], float scale, bool keep)
-{
-  if (!keep) {
-#pragma unroll
-    for (int c = 0; c < 32; c += 8) *reinterpret_cast<uint4 *>(row + 32 * lh + c) = make_uint4(0u, 0u, 0u, 0u);
-    return;
-  }
-#pragma unroll
-  for (int mb = 0; mb < 2; ++mb)
-#pragma unroll
-    for (int g = 0; g < 4; ++g) {
-      const int d0 = 32 * mb + 8 * g + 4 * lh;
-      uint2 pk;
-      pk.x = pack2_bf16(acc[mb][4 * g] * scale, acc[mb][4 * g + 1] * scale);
-      pk.y = pack2_bf16(acc[mb][4 * g + 2] * scale, acc[mb][4 * g + 3] * scale);
-      *reinterpret_cast<uint2 *>(row + d0) = pk;
-    }
-}
-
-// The same rows through LDS: the wavefront's 32 rows (this lane: row lane%32, channels
+// Stores 2 x 16 accumulators (d x rows, transposed) as bf16, scaled, through LDS: the wavefront's 32 rows
+// (this lane: row lane%32, channels
 // 32*mb + 8*g + 4*(lane/32) + e in acc[mb][4*g + e]) are written into its own 4 KB of staging rows
 // (free once the walk is over; chunks XOR-swizzled against bank conflicts) and leave as whole
 // 128-byte rows, 8 rows per store instruction, non-temporal (nothing in this library reads the
@@ -276,7 +257,7 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
   for (int i = 0; i < 16; ++i) { dq[0][i] = 0.0f; dq[1][i] = 0.0f; }
   if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query: gradients are zero
-    if (iq < p.L) store_row_bf16(dQ + rowoff, lh, dq, 0.0f, false);
+    zero_rows(dQ + head, q0, 32, p.L, lane);
     return;
   }
 
@@ -565,10 +546,8 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 #pragma unroll
   for (int i = 0; i < 16; ++i) { dk[0][i] = 0.0f; dk[1][i] = 0.0f; dv[0][i] = 0.0f; dv[1][i] = 0.0f; }
   if (min((J + 1) * BLK, p.L) <= p0) {  // no valid key
-    if (j < p.L) {
-      store_row_bf16(dK + rowoff, lh, dk, 0.0f, false);
-      store_row_bf16(dV + rowoff, lh, dv, 0.0f, false);
-    }
+    zero_rows(dK + head, J * BLK + 32 * wv, 32, p.L, lane);
+    zero_rows(dV + head, J * BLK + 32 * wv, 32, p.L, lane);
     return;
   }
   const float c2 = p.scale * kLog2e;

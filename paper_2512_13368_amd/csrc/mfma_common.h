@@ -45,6 +45,18 @@ __device__ __forceinline__ unsigned xcd_remap(unsigned pid, unsigned total)
 //    are 8 distinct values because swz differs in bits 1-2 between rows with equal bits 2-3.
 __device__ __forceinline__ int swz(int r) { return (((r & 3) << 1) | ((r >> 2) & 1)) ^ (((r >> 3) & 1) << 1); }
 
+// Zero-fills rows row0 .. row0+nrows-1 (those below L) of a (row, head) slice [L][D]: the rows are
+// contiguous in memory, so a wavefront writes 1 KB per instruction instead of 64 row pieces.
+template <typename T>
+__device__ __forceinline__ void zero_rows(T *head_ptr, int row0, int nrows, int L, int lane)
+{
+  char *base = reinterpret_cast<char *>(head_ptr + (size_t)row0 * D);
+  const int bytes = max(0, min(nrows, L - row0)) * D * (int)sizeof(T);
+  typedef unsigned u32x4_t __attribute__((ext_vector_type(4)));
+  const u32x4_t z = {0u, 0u, 0u, 0u};
+  for (int o = lane * 16; o < bytes; o += 1024) __builtin_nontemporal_store(z, reinterpret_cast<u32x4_t *>(base + o));
+}
+
 // two floats -> one register of two bf16 (round to nearest even in hardware: v_cvt_pk_bf16_f32)
 __device__ __forceinline__ uint32_t pack2_bf16(float a, float b)
 {

@@ -129,21 +129,15 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(BLK == 
 #pragma unroll
   for (int g = 0; g < NQ; ++g) q_ok[g] = iq[g] < p.L && iq[g] >= p0;
 
-  if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query in the block: zero outputs
-    if (iq[0] < p.L) {
-      const size_t ro = head + (size_t)iq[0] * D + 32 * lh;
-#pragma unroll
-      for (int c = 0; c < 32; c += 8) *reinterpret_cast<uint4 *>(O + ro + c) = make_uint4(0u, 0u, 0u, 0u);
-      if (o_lt_out)
-#pragma unroll
-        for (int c = 0; c < 32; c += 4) {
-          *reinterpret_cast<float4 *>(o_lt_out + ro + c) = make_float4(0.f, 0.f, 0.f, 0.f);
-          *reinterpret_cast<float4 *>(o_st_out + ro + c) = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-      if (lh == 0) {
-        if (lse_lt_out) lse_lt_out[(size_t)bh * p.L + iq[0]] = 0.0f;
-        if (lse_st_out) lse_st_out[(size_t)bh * p.L + iq[0]] = 0.0f;
-      }
+  if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query in the block: zero outputs (this wavefront's 32 rows)
+    zero_rows(O + head, qbase[0], 32, p.L, lane);
+    if (o_lt_out) {
+      zero_rows(o_lt_out + head, qbase[0], 32, p.L, lane);
+      zero_rows(o_st_out + head, qbase[0], 32, p.L, lane);
+    }
+    if (iq[0] < p.L && lh == 0) {
+      if (lse_lt_out) lse_lt_out[(size_t)bh * p.L + iq[0]] = 0.0f;
+      if (lse_st_out) lse_st_out[(size_t)bh * p.L + iq[0]] = 0.0f;
     }
     return;
   }

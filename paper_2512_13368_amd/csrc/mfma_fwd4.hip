@@ -91,21 +91,16 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
   const int p0 = p.L - n;
   const bool q_ok = iq < p.L && iq >= p0;
 
-  if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query in the block: zero outputs (this wavefront's quarter)
-    if (iq < p.L) {
-      const size_t ro = head + (size_t)iq * D + 32 * kh + 16 * lh;
-#pragma unroll
-      for (int c = 0; c < 16; c += 8) *reinterpret_cast<uint4 *>(O + ro + c) = make_uint4(0u, 0u, 0u, 0u);
-      if (o_lt_out)
-#pragma unroll
-        for (int c = 0; c < 16; c += 4) {
-          *reinterpret_cast<float4 *>(o_lt_out + ro + c) = make_float4(0.f, 0.f, 0.f, 0.f);
-          *reinterpret_cast<float4 *>(o_st_out + ro + c) = make_float4(0.f, 0.f, 0.f, 0.f);
-        }
-      if (lh == 0 && kh == 0) {
-        if (lse_lt_out) lse_lt_out[(size_t)bh * p.L + iq] = 0.0f;
-        if (lse_st_out) lse_st_out[(size_t)bh * p.L + iq] = 0.0f;
-      }
+  if (min((I + 1) * BLK, p.L) <= p0) {  // no valid query in the block: zero outputs (16 rows per wavefront)
+    const int zr = I * BLK + 16 * wv;
+    zero_rows(O + head, zr, 16, p.L, lane);
+    if (o_lt_out) {
+      zero_rows(o_lt_out + head, zr, 16, p.L, lane);
+      zero_rows(o_st_out + head, zr, 16, p.L, lane);
+    }
+    if (iq < p.L && lh == 0 && kh == 0) {
+      if (lse_lt_out) lse_lt_out[(size_t)bh * p.L + iq] = 0.0f;
+      if (lse_st_out) lse_st_out[(size_t)bh * p.L + iq] = 0.0f;
     }
     return;
   }
