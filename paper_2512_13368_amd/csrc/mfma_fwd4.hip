@@ -318,10 +318,12 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
     const float mx = row_max(s);
     const bool upd = fresh ? mx != kNegInf : mx > kRaise4;
     const float dlt = upd ? mx : 0.0f;
-    const float alpha = (upd && !fresh) ? __builtin_amdgcn_exp2f(-dlt) : 1.0f;
-    l_run *= alpha;
+    if (__any(upd && !fresh)) {  // (a row that has met no key yet has nothing to rescale)
+      const float alpha = (upd && !fresh) ? __builtin_amdgcn_exp2f(-dlt) : 1.0f;
+      l_run *= alpha;
 #pragma unroll
-    for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
+      for (int i = 0; i < 16; ++i) { oacc[0][i] *= alpha; oacc[1][i] *= alpha; }
+    }
 #pragma unroll
     for (int i = 0; i < 16; ++i) s[i] -= dlt;
     set_ref(m_ref + dlt);
@@ -385,11 +387,18 @@ __global__ __launch_bounds__(256) __attribute__((amdgpu_waves_per_eu(3, 3))) voi
 #pragma unroll
     for (int kk = 1; kk < 4; ++kk) s = __builtin_amdgcn_mfma_f32_32x32x16_bf16(kf[kk], qf[kk], s, 0, 0, 0);
     if (!full) mask(J, windowed, s);
+    // The exponentials are taken once: against the current reference, unless a row of the wavefront has
+    // met no visible key yet (then the reference is placed first); a row sum that ran away repeats the
+    // pass after raising the reference, which cannot run away again.
     bf16x8 pf[2];
-    float tsum = expo(s, pf);
-    if (__any(fresh || !(tsum <= kSumLimit4))) {
-      move_ref(s);
+    float tsum;
+    bool placed = __any(fresh);
+#pragma unroll 1
+    for (;;) {
+      if (placed) move_ref(s);
       tsum = expo(s, pf);
+      if (placed || !__any(!(tsum <= kSumLimit4))) break;
+      placed = true;
     }
     l_run += tsum;
     pv(vf, pf);
