@@ -1069,6 +1069,11 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     launch_bwd_mfma(p, a, w, stages, st);
     return;
   }
+  if (bwd_f32_mfma_supported(p, dtype)) {
+    if (launch_failed()) return;
+    launch_bwd_f32_mfma(p, a, w, stages, st);
+    return;
+  }
   const size_t lds = 2 * (size_t)p.b * (D + 1) * sizeof(float);  // two tiles of b rows
   const bool far = far_by_rows(p);
   if (stages & kBwdStageDQ) {
