@@ -22,8 +22,7 @@ SOURCES = {
     # (the forward kernel also reuses its bf16 staging rows as fp32 exchange space between wavefronts)
     "mfma_fwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-strict-aliasing"],
     "mfma_fwd4.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1", "-fno-strict-aliasing"],
-    "mfma_fwd_f32.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
-    "mfma_bwd_f32.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "mfma_f32.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "probe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
 }

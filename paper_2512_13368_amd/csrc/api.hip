@@ -199,7 +199,7 @@ int blossom_attn_fwd(const blossom_params *p, const void *Q, const void *K, cons
   a.dense = 0;
   clear_stale_error();
   if (fwd_mfma_supported(kp, p->dtype)) launch_fwd_mfma(kp, a, (hipStream_t)hip_stream);
-  else if (fwd_f32_mfma_supported(kp, p->dtype)) launch_fwd_f32_mfma(kp, a, (hipStream_t)hip_stream);
+  else if (fwd_res_supported(kp, p->dtype)) launch_fwd_res(kp, p->dtype, a, (hipStream_t)hip_stream);
   else launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();
 }
@@ -291,7 +291,7 @@ int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void 
   a.dense = 1;
   clear_stale_error();
   if (fwd_mfma_supported(kp, p->dtype)) launch_fwd_mfma(kp, a, (hipStream_t)hip_stream);
-  else if (fwd_f32_mfma_supported(kp, p->dtype)) launch_fwd_f32_mfma(kp, a, (hipStream_t)hip_stream);
+  else if (fwd_res_supported(kp, p->dtype)) launch_fwd_res(kp, p->dtype, a, (hipStream_t)hip_stream);
   else launch_fwd_generic(kp, p->dtype, a, (hipStream_t)hip_stream);
   return launch_status();
 }

@@ -1069,9 +1069,9 @@ static void launch_bwd_t(const KParams &p, int dtype, const BwdArgs &a, unsigned
     launch_bwd_mfma(p, a, w, stages, st);
     return;
   }
-  if (bwd_f32_mfma_supported(p, dtype)) {
+  if (bwd_res_supported(p, dtype)) {
     if (launch_failed()) return;
-    launch_bwd_f32_mfma(p, a, w, stages, st);
+    launch_bwd_res(p, dtype, a, w, stages, st);
     return;
   }
   const size_t lds = 2 * (size_t)p.b * (D + 1) * sizeof(float);  // two tiles of b rows

@@ -101,13 +101,12 @@ void launch_fwd_mfma(const KParams &p, const FwdArgs &a, hipStream_t st);
 // mfma_fwd4.hip: the four-wavefront forward for block size 64 (launch_fwd_mfma dispatches to it)
 void launch_fwd_mfma4(const KParams &p, const FwdArgs &a, hipStream_t st);
 
-// mfma_fwd_f32.hip: forward on the fp32 matrix instructions for fp32, d = 32, b in {8, 16}, K and V of a head resident in LDS
-bool fwd_f32_mfma_supported(const KParams &p, int dtype);
-void launch_fwd_f32_mfma(const KParams &p, const FwdArgs &a, hipStream_t st);
-
-// mfma_bwd_f32.hip: dQ and dK/dV on the fp32 matrix instructions, same range as mfma_fwd_f32.hip
-bool bwd_f32_mfma_supported(const KParams &p, int dtype);
-void launch_bwd_f32_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st);
+// mfma_f32.hip: forward, dQ and dK/dV on the fp32 matrix instructions for short sequences (fp32 or bf16
+// storage, d in {8, 16, 32}, b in {8, 16}, the streamed tensors of a head resident in LDS)
+bool fwd_res_supported(const KParams &p, int dtype);
+void launch_fwd_res(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
+bool bwd_res_supported(const KParams &p, int dtype);
+void launch_bwd_res(const KParams &p, int dtype, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st);
 
 // mfma_bwd.hip: matrix-core dQ and dK/dV for bf16, d = 64, b in {32, 64}
 bool bwd_mfma_supported(const KParams &p, int dtype);

@@ -1,6 +1,6 @@
-"""GPU parity of the fp32 matrix-instruction kernels for short sequences (fp32 storage, d = 32, block 8 or 16,
-K/V or Q/dO of a whole head resident in LDS): forward, dQ and dK/dV against the CPU oracle, at the shapes
-where those kernels take over from the scalar-ALU ones and at the edges of that range."""
+"""GPU parity of the fp32 matrix-instruction kernels for short sequences (fp32 or bf16 storage, d in {8, 16, 32},
+block 8 or 16, K/V or Q/dO of a whole head resident in LDS): forward, dQ and dK/dV against the CPU oracle, at
+the shapes where those kernels take over from the scalar-ALU ones and at the edges of that range."""
 import numpy as np
 import pytest
 import torch
@@ -86,3 +86,28 @@ def test_just_outside_the_resident_range():
     # one block more than the resident kernels take: the scalar-ALU kernels serve the shape, same answers
     run_case(with_shape(WORKLOADS["cfg2"], name="f32-L224", B=3, H=2, L=224, len_lo=30, len_hi=224, seed=990),
              backward=True)
+
+
+@pytest.mark.parametrize("dtype,d,b,L,topk,window,sblk", [
+    ("fp32", 8, 16, 197, 4, 8, 1),      # the paper's own hyperparameters: hidden 64 over 8 heads, mask block 1
+    ("fp32", 16, 16, 200, 4, 8, 1),     # ML-1M head size
+    ("bf16", 8, 8, 120, 3, 8, 2),       # bf16 storage, block 8, a small mask block
+    ("bf16", 16, 16, 150, 4, 24, 16),   # mask block = selection block
+    ("bf16", 32, 16, 200, 4, 16, 0),    # bf16 storage, plain window
+    ("fp32", 32, 8, 90, 3, 8, 4),
+])
+def test_head_sizes_storage_types_and_full_short_term_mask(dtype, d, b, L, topk, window, sblk):
+    w = with_shape(WORKLOADS["cfg2"], name=f"res-{dtype}-d{d}-b{b}-s{sblk}", B=5, H=16 // (d // 8 if d < 32 else 4),
+                   L=L, d=d, block=b, topk=topk, window=window, dtype=dtype, qkv_scaled=(dtype == "bf16"), len_lo=1,
+                   len_hi=L, stis_block=sblk, seed=1200 + d + b + sblk)
+    x = make_inputs(w, want_dO=True)
+    x.valid_len[:4] = [L, max(1, L - b - 3), min(L, b // 2 + 1), 0]
+    run_case(w, x=x, backward=True, check_dense=True, gate_scale=0.4)
+
+
+def test_long_rows_with_more_than_64_kb_of_lds():
+    # the efficiency-study length 1000 at the paper's hyperparameters: K and V of a head take 96 KB of LDS,
+    # dK/dV's Q, dO and row constants 120 KB; one workgroup per CU
+    w = with_shape(WORKLOADS["cfg2"], name="res-L1000", B=8, H=8, L=1000, d=8, block=16, topk=4, window=8, len_lo=300,
+                   len_hi=1000, stis_block=1, seed=1301)
+    run_case(w, backward=True, pairs=[0, 7, 21, 38, 63])
