@@ -25,8 +25,8 @@
 //   P_ij = exp(scale*q_i.k_j - lse_x,i),  dS_ij = P_ij * (dO_x,i.v_j - D_x,i),
 //   dQ_i = scale * sum_j dS_ij k_j,  dK_j = scale * sum_i dS_ij q_i,  dV_j = sum_i P_ij dO_x,i;
 // dO_x is never materialised: a lane forms the operand elements it feeds from dO, a_x, dz and Wg_x.
-// Tile lists, masks (the causal window or all of Eq. 15 in its causal form), gate, outputs and
-// padding rules are those of the scalar kernels of generic.hip; shapes outside this range stay there.
+// Tile lists, masks (the causal window, or all of Eq. 15 in its causal or its bidirectional form), gate,
+// outputs and padding rules are those of the scalar kernels of generic.hip; shapes outside this range stay there.
 #include "launch.h"
 
 namespace blossom {
@@ -99,6 +99,14 @@ __device__ __forceinline__ void store_grad_row(T *dst_row, const f32x4 (&a)[Geo<
       }
       store4(dst_row + 16 * mb + 4 * g, v);
     }
+}
+
+// bidirectional form: last block the window of a row of block I reaches (key blocks of a query block, or
+// query blocks of a key block: the window is symmetric)
+__device__ __forceinline__ int window_reach_hi(int I, int b, int w, int NB)
+{
+  const long hi = (long)I * b + (b - 1) + (w - 1);
+  return (int)min((long)(NB - 1), hi / b);
 }
 
 // element `c` of a gate-row half, zero past the head dimension
@@ -190,7 +198,7 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
       for (int r = 0; r < 4; ++r) {
         const int ko = 4 * g + r;
         const int key = J * BK + ko;
-        const bool vis = active && ko < BK && key >= p0 && key <= iq && (!windowed || st_visible(p, iq, key));
+        const bool vis = active && ko < BK && key >= p0 && key < p.L && (key <= iq || p.bidir) && (!windowed || st_visible(p, iq, key));
         s[r] = vis ? s[r] : kNegInfF;
         mx = fmaxf(mx, s[r]);
       }
@@ -248,6 +256,11 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
       for (int J = J_first; J < J_win; ++J)
         if (st_block_reach(p, I, J)) tile(J, true);
       for (int J = J_win; J <= I; ++J) tile(J, true);
+      if (p.bidir) {  // Eq. 15 as printed: the same on the other side of the query block
+        const int J_whi = window_reach_hi(I, BK, p.w, p.NB);
+        for (int J = I + 1; J < p.NB; ++J)
+          if (J <= J_whi || st_block_reach(p, I, J)) tile(J, true);
+      }
     }
     const float lse_st = finish();
     f32x4 ost[NMB];
@@ -380,7 +393,7 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
       for (int r = 0; r < 4; ++r) {
         const int ko = 4 * g + r;
         const int key = J * BK + ko;
-        const bool vis = active && ko < BK && key >= p0 && key <= iq && (!windowed || st_visible(p, iq, key));
+        const bool vis = active && ko < BK && key >= p0 && key < p.L && (key <= iq || p.bidir) && (!windowed || st_visible(p, iq, key));
         ds[r] = vis ? __builtin_amdgcn_exp2f(s[r] - l2) * (gv[r] - Dx) : 0.0f;
       }
       const float *kc = Ks + (J * BK + 4 * g) * LDR + q;  // row = key 4g + r, column = channel 16*mb + q
@@ -402,6 +415,11 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
       for (int J = J_first; J < J_win; ++J)
         if (st_block_reach(p, I, J)) tile(J, true);
       for (int J = J_win; J <= I; ++J) tile(J, true);
+      if (p.bidir) {  // Eq. 15 as printed: the same on the other side of the query block
+        const int J_whi = window_reach_hi(I, BK, p.w, p.NB);
+        for (int J = I + 1; J < p.NB; ++J)
+          if (J <= J_whi || st_block_reach(p, I, J)) tile(J, true);
+      }
     }
     // long-term branch: selected blocks
 #pragma unroll
@@ -534,7 +552,7 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dkv_res_kernel(
       for (int r = 0; r < 4; ++r) {
         const int qo = 4 * g + r;
         const int i = r0 + qo;
-        const bool vis = key_ok && qo < BK && i >= j && (!windowed || st_visible(p, i, j));
+        const bool vis = key_ok && qo < BK && (i >= j || p.bidir) && (!windowed || st_visible(p, i, j));
         pr[r] = vis ? __builtin_amdgcn_exp2f(s[r] - l2_s[i]) : 0.0f;
         ds[r] = pr[r] * (gv[r] - Dx_s[i]);
         const float al = ax_s[i];
@@ -560,6 +578,13 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dkv_res_kernel(
       for (int I = J; I <= I_hi; ++I) tile(I, true);
       for (int I = I_hi + 1; I < p.NB; ++I)
         if (st_block_reach(p, I, J)) tile(I, true);
+      if (p.bidir) {  // query blocks before the key block
+        const int I_first = p0 / BK;
+        const int lowpos = J * BK - (p.w - 1);
+        const int I_lo = max(lowpos <= 0 ? 0 : lowpos / BK, I_first);
+        for (int I = I_first; I < J; ++I)
+          if (I >= I_lo || st_block_reach(p, I, J)) tile(I, true);
+      }
     }
     // long-term branch: query blocks that selected this key block
     for (int e = e_lo; e < e_hi; ++e) {
@@ -586,7 +611,7 @@ bool res_shape(const KParams &p)
   // One workgroup per (row, head): enough of them to fill the chip, or so little work that it does not matter.
   // A mask block of Eq. 15 below the block size makes nearly every earlier block a short-term tile here (the
   // scalar kernels gather the few keys per row instead): only short sequences take that.
-  return (p.d == 8 || p.d == 16 || p.d == 32) && (p.b == 8 || p.b == 16) && !p.bidir &&
+  return (p.d == 8 || p.d == 16 || p.d == 32) && (p.b == 8 || p.b == 16) &&
          ((long)p.B * p.H >= 64 || p.L <= 256) && (p.sblk == 0 || p.sblk >= p.b || p.L <= 256);
 }
 
