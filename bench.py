@@ -8,8 +8,9 @@ carries the stage times, the forward-only rate (the quantity the L=8192 target i
 on), a roofline object for the dominant kernel, the same-style dense causal kernel and the
 CPU oracle timed on a bounded sample of the same workload.
 
-The default run (workload cfg4, L=8192) also times the L=1024 training step (cfg5) the same way and
-reports it under "l1024_training_step".  Roofline entries count algorithmic work only: forward 4d
+The default run (workload cfg4, L=8192) also times the L=1024 training step (cfg5) and the paper's own
+short-sequence shape (cfg2, L=200, fp32) the same way and reports them under "l1024_training_step" and
+"l200_training_step".  Roofline entries count algorithmic work only: forward 4d
 flops per unmasked pair, the whole backward 10d (five contractions), bytes of valid positions.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
@@ -492,8 +493,13 @@ def main():
     if args.workload == "cfg4" and not (args.shape or args.stis_block or args.no_second_workload or args.graph):
         del R
         torch.cuda.empty_cache()
-        res5, _ = measure_workload(WORKLOADS["cfg5"], args, mods, n_sets, headline=False)
+        res5, R5 = measure_workload(WORKLOADS["cfg5"], args, mods, n_sets, headline=False)
         out["l1024_training_step"] = res5
+        # ---- and the paper's own regime: the short-sequence recommender shape (cfg2: L = 200, fp32), same step ----
+        del R5
+        torch.cuda.empty_cache()
+        res2, _ = measure_workload(WORKLOADS["cfg2"], args, mods, n_sets, headline=False)
+        out["l200_training_step"] = res2
     print(json.dumps(out))
 
 
