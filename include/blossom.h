@@ -160,14 +160,35 @@ int blossom_select_blocks_static(const blossom_params *p, const void *Q, const v
  *   Q        in   [B,H,L,d];  K in [B,G,L,d]  (element type p->dtype, 16-byte aligned)
  *   sel_pos  out  int32 [B,G,L,topk]
  *   ws       scratch, >= blossom_select_positions_workspace_bytes(...), 16-byte aligned
- * Limits: ceil(L/l') <= 512 selection blocks; BLOSSOM_ERR_SHAPE beyond.  (The attention kernels of this
- * library take one selection row per query block; a per-position selection is consumed by the caller.)
+ * Limits: ceil(L/l') <= 512 selection blocks; BLOSSOM_ERR_SHAPE beyond.  (blossom_attn_fwd_positions below
+ * consumes such a selection for short sequences; blossom_attn_fwd / blossom_attn_bwd take one selection row
+ * per query block.)
  */
 size_t blossom_select_positions_workspace_bytes(const blossom_params *p, int32_t kv_groups, int32_t cmp_block,
                                                 int32_t cmp_stride);
 int blossom_select_positions(const blossom_params *p, int32_t kv_groups, int32_t cmp_block, int32_t cmp_stride,
                              float score_scale, const void *Q, const void *K, const int32_t *valid_len,
                              int32_t *sel_pos, void *ws, size_t ws_bytes, void *hip_stream);
+
+/*
+ * Forward under a per-position selection (Sec. 3.4-3.6: Eq. 14 with the selection of Eq. 13 taken per query
+ * position, Eq. 16-19; grouped-query attention, Eq. 4-5): the long-term branch of query position t of head h
+ * attends the keys j <= t of the selection blocks listed in row [b, h / (H/G), t] of sel_pos; short-term
+ * branch, gate and padding rules are those of blossom_attn_fwd (p->window, p->stis_mode 0 or 1, p->stis_block).
+ * p->block is the selection block size l' (8 or 16), p->topk is k.
+ *   Q               in   [B,H,L,d];  K, V in [B,G,L,d]  (element type p->dtype, 16-byte aligned), G = kv_groups | H
+ *   sel_pos         in   int32 [B,G,L,topk]: ids of selection blocks or -1 (entries outside [0, ceil(L/l')) are
+ *                        skipped), as blossom_select_positions writes them
+ *   O               out  [B,H,L,d]
+ *   o_lt, o_st      out  fp32 [B,H,L,d], or NULL;  lse_lt, lse_st  out  fp32 [B,H,L], or NULL
+ * Served by the kernels that keep a head's K and V resident in LDS: d in {8, 16, 32}, l' in {8, 16}, at most 64
+ * selection blocks, K and V of one (row, group) within 144 KB as fp32 rows (L <= 480 at d = 32, <= 900 at d <= 16);
+ * BLOSSOM_ERR_UNSUPPORTED beyond, for stis_mode 2 and for last_block_only.  Forward only; needs no workspace.
+ */
+int blossom_attn_fwd_positions(const blossom_params *p, int32_t kv_groups, const void *Q, const void *K, const void *V,
+                               const int32_t *valid_len, const int32_t *sel_pos, const float *gate_w,
+                               const float *gate_b, void *O, void *o_lt, void *o_st, float *lse_lt, float *lse_st,
+                               void *hip_stream);
 
 /*
  * Rotary position embedding (Sec. 3.3: RoPE is applied to the projected Q and K before both branches)

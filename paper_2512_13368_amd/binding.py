@@ -19,7 +19,7 @@ WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
 EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp",
            "blossom_rope_select_blocks", "blossom_attn_bwd_rope", "blossom_select_positions_workspace_bytes",
-           "blossom_select_positions", "blossom_attn_fwd", "blossom_attn_bwd",
+           "blossom_select_positions", "blossom_attn_fwd_positions", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_probe_bytes", "blossom_probe", "blossom_strerror", "blossom_version")
 PROBE_WORKGROUPS = 4096
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
@@ -67,6 +67,8 @@ def lib() -> ctypes.CDLL:
         L.blossom_select_positions.restype = ctypes.c_int
         L.blossom_select_positions.argtypes = [pp, ctypes.c_int32, ctypes.c_int32, ctypes.c_int32, ctypes.c_float,
                                                vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
+        L.blossom_attn_fwd_positions.restype = ctypes.c_int
+        L.blossom_attn_fwd_positions.argtypes = [pp, ctypes.c_int32] + [vp] * 12 + [vp]
         L.blossom_select_blocks_cmp.restype = ctypes.c_int
         L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
@@ -403,3 +405,33 @@ def select_positions(p: Params, kv_groups: int, cmp_block: int, cmp_stride: int,
     if rc:
         raise BlossomError(rc, "blossom_select_positions")
     return sel_pos
+
+
+def attn_fwd_positions(p: Params, kv_groups: int, Q, K, V, valid_len, sel_pos, gate_w, gate_b=None, out: FwdOut | None = None,
+                       want_branches: bool = False, stream=None) -> FwdOut:
+    """blossom_attn_fwd_positions: forward under one selection row per query position and key/value group
+    (K, V [B,G,L,d], sel_pos [B,G,L,topk]).  `want_branches` also returns o_lt, o_st, lse_lt, lse_st."""
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    dt = _torch_dtype(p)
+    _check_tensor(Q, shp, dt, "Q")
+    for t, nm in ((K, "K"), (V, "V")):
+        _check_tensor(t, (p.B, kv_groups, p.L, p.d), dt, nm)
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    _check_tensor(sel_pos, (p.B, kv_groups, p.L, p.topk), torch.int32, "sel_pos")
+    _check_tensor(gate_w, (p.H, 2 * p.d), torch.float32, "gate_w")
+    _check_tensor(gate_b, (p.H,), torch.float32, "gate_b")
+    if out is None:
+        out = FwdOut(torch.empty(shp, dtype=dt, device=Q.device))
+        if want_branches:
+            out.o_lt = torch.empty(shp, dtype=torch.float32, device=Q.device)
+            out.o_st = torch.empty(shp, dtype=torch.float32, device=Q.device)
+            out.lse_lt = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
+            out.lse_st = torch.empty(shp[:3], dtype=torch.float32, device=Q.device)
+    cp = p.c()
+    rc = lib().blossom_attn_fwd_positions(ctypes.byref(cp), kv_groups, _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len), _ptr(sel_pos),
+                                          _ptr(gate_w), _ptr(gate_b), _ptr(out.O), _ptr(out.o_lt), _ptr(out.o_st),
+                                          _ptr(out.lse_lt), _ptr(out.lse_st), _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_attn_fwd_positions")
+    return out

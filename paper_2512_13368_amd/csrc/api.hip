@@ -270,6 +270,30 @@ int blossom_attn_bwd(const blossom_params *p, const void *Q, const void *K, cons
                                  dK, dV, d_gate_w, d_gate_b, ws, ws_bytes, hip_stream, kBwdStageAll);
 }
 
+int blossom_attn_fwd_positions(const blossom_params *p, int32_t kv_groups, const void *Q, const void *K, const void *V,
+                               const int32_t *valid_len, const int32_t *sel_pos, const float *gate_w,
+                               const float *gate_b, void *O, void *o_lt, void *o_st, float *lse_lt, float *lse_st,
+                               void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (kv_groups < 1 || p->H % kv_groups != 0) return BLOSSOM_ERR_PARAM;
+  if (!Q || !K || !V || !valid_len || !sel_pos || !gate_w || !O) return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(O)) return BLOSSOM_ERR_ALIGN;
+  if ((o_lt && !aligned16(o_lt)) || (o_st && !aligned16(o_st))) return BLOSSOM_ERR_ALIGN;
+  if (!fwd_positions_supported(kp, p->dtype)) return BLOSSOM_ERR_UNSUPPORTED;
+  FwdArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.sel = sel_pos;
+  a.gate_w = gate_w; a.gate_b = gate_b; a.O = O;
+  a.o_lt = o_lt; a.o_st = o_st; a.lse_lt = lse_lt; a.lse_st = lse_st;
+  a.dense = 0;
+  a.kv_groups = kv_groups;
+  clear_stale_error();
+  launch_fwd_res(kp, p->dtype, a, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
 int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
                              const int32_t *valid_len, void *O, float *lse, void *ws,
                              size_t ws_bytes, void *hip_stream)

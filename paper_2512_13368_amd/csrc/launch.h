@@ -32,6 +32,7 @@ struct FwdArgs {
   void *o_lt, *o_st;       // or nullptr
   float *lse_lt, *lse_st;  // or nullptr (dense mode: lse_lt = lse)
   int dense;               // 1: dense causal attention, single branch, no gate
+  int kv_groups;           // > 0: `sel` holds one row per query position and key/value group [B,G,L,k], K and V are [B,G,L,d]
 };
 
 struct BwdArgs {
@@ -105,6 +106,7 @@ void launch_fwd_mfma4(const KParams &p, const FwdArgs &a, hipStream_t st);
 // storage, d in {8, 16, 32}, b in {8, 16}, the streamed tensors of a head resident in LDS)
 bool fwd_res_supported(const KParams &p, int dtype);
 void launch_fwd_res(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
+bool fwd_positions_supported(const KParams &p, int dtype);
 bool bwd_res_supported(const KParams &p, int dtype);
 void launch_bwd_res(const KParams &p, int dtype, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st);
 

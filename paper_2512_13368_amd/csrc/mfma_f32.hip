@@ -118,12 +118,16 @@ __device__ __forceinline__ float gate_at(const float *half, int c) { return c < 
 // =============================================================================================
 // forward
 // =============================================================================================
-template <typename T, int D, int BK>
+// PERPOS: the long-term branch takes one selection row per query POSITION and key/value group (the
+// selection rule as printed, Eq. 8-13 with Eq. 4-5): K and V are [B,G,L,d], `sel` is [B,G,L,k] with
+// selection blocks of BK positions; a lane folds its row into a bit per key block, and the walk visits the
+// blocks any of the tile's rows selected, each row seeing its own.
+template <typename T, int D, int BK, bool PERPOS>
 __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, const int *__restrict__ valid_len,
     const int *__restrict__ sel, const float *__restrict__ gate_w, const float *__restrict__ gate_b,
     T *__restrict__ O, float *__restrict__ o_lt_out, float *__restrict__ o_st_out, float *__restrict__ lse_lt_out,
-    float *__restrict__ lse_st_out, int dense, KParams p)
+    float *__restrict__ lse_st_out, int dense, int kv_groups, KParams p)
 {
   constexpr int NS = Geo<D>::NS, NMB = Geo<D>::NMB, LDR = Geo<D>::LDR;
   extern __shared__ __attribute__((aligned(16))) float lds_res[];
@@ -139,7 +143,10 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
   const size_t head = (size_t)bh * p.L * D;
-  stage_head<T, D>(K + head, V + head, Ks, Vs, rows, p.L, tid);
+  // (grouped-query attention: head h reads the keys and values of group h / (H/G))
+  const int kvh = PERPOS ? (bh / p.H) * kv_groups + h / (p.H / kv_groups) : bh;
+  const size_t head_kv = (size_t)kvh * p.L * D;
+  stage_head<T, D>(K + head_kv, V + head_kv, Ks, Vs, rows, p.L, tid);
   __syncthreads();
 
   const int q = lane & 15, g = lane >> 4;
@@ -177,8 +184,16 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
 #pragma unroll
     for (int s = 0; s < NS; ++s) qf[s] = active ? to_f32(Q[rowoff + 4 * s + g]) * c2 : 0.0f;
     // the selection row, 64 entries per register (requested now, used after the short-term branch)
-    const int *my_sel = dense ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
-    int sel_v = (!dense && lane < p.k) ? my_sel[lane] : -1;
+    const int *my_sel = (dense || PERPOS) ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
+    int sel_v = (!dense && !PERPOS && lane < p.k) ? my_sel[lane] : -1;
+    unsigned long long lt_mask = 0ull;  // PERPOS: bit J set iff this lane's position selected block J
+    if (PERPOS && active) {
+      const int *prow = sel + ((size_t)kvh * p.L + iq) * p.k;
+      for (int e = 0; e < p.k; ++e) {
+        const int v = prow[e];
+        if (v >= 0 && v < p.NB) lt_mask |= 1ull << v;
+      }
+    }
 
     float m, l;
     auto reset = [&]() {
@@ -198,7 +213,8 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
       for (int r = 0; r < 4; ++r) {
         const int ko = 4 * g + r;
         const int key = J * BK + ko;
-        const bool vis = active && ko < BK && key >= p0 && key < p.L && (key <= iq || p.bidir) && (!windowed || st_visible(p, iq, key));
+        const bool vis = active && ko < BK && key >= p0 && key < p.L && (key <= iq || p.bidir) &&
+                         (windowed ? st_visible(p, iq, key) : (!PERPOS || dense || ((lt_mask >> J) & 1ull)));
         s[r] = vis ? s[r] : kNegInfF;
         mx = fmaxf(mx, s[r]);
       }
@@ -269,6 +285,10 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
 
     // ---- long-term branch: selected blocks (entries outside [0, NB) are skipped) ----
     reset();
+    if (PERPOS) {
+      for (int J = J_first; J <= I; ++J)
+        if (__ballot((lt_mask >> J) & 1ull) != 0ull) tile(J, false);
+    } else
     for (int e0 = 0; e0 < p.k; e0 += 64) {
       if (e0 > 0) sel_v = e0 + lane < p.k ? my_sel[e0 + lane] : -1;
       const int ne = min(64, p.k - e0);
@@ -644,6 +664,14 @@ bool fwd_res_supported(const KParams &p, int dtype)
   return res_shape(p) && res_kv_lds_bytes(p, p.d) <= kResLdsMax;
 }
 
+// the per-position form exists in this kernel family only: what the shape has to satisfy, whatever the batch
+bool fwd_positions_supported(const KParams &p, int dtype)
+{
+  (void)dtype;
+  return (p.d == 8 || p.d == 16 || p.d == 32) && (p.b == 8 || p.b == 16) && !p.bidir && p.NB <= 64 && p.nq == p.NB &&
+         res_kv_lds_bytes(p, p.d) <= kResLdsMax;
+}
+
 bool bwd_res_supported(const KParams &p, int dtype)
 {
   (void)dtype;
@@ -657,11 +685,14 @@ static void launch_fwd_res_t(const KParams &p, const FwdArgs &a, hipStream_t st)
   const size_t lds = res_kv_lds_bytes(p, p.d);
   with_res_dims(p, [&](auto dim, auto bk) {
     constexpr int D = decltype(dim)::value, BK = decltype(bk)::value;
-    auto kernel = fwd_res_kernel<T, D, BK>;
-    want_lds(kernel, lds);
-    hipLaunchKernelGGL(kernel, dim3((unsigned)(p.B * p.H)), dim3(64 * kResWaves), lds, st, (const T *)a.Q, (const T *)a.K,
-                       (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st,
-                       a.lse_lt, a.lse_st, a.dense, p);
+    auto go = [&](auto kernel) {
+      want_lds(kernel, lds);
+      hipLaunchKernelGGL(kernel, dim3((unsigned)(p.B * p.H)), dim3(64 * kResWaves), lds, st, (const T *)a.Q, (const T *)a.K,
+                         (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.gate_b, (T *)a.O, (float *)a.o_lt, (float *)a.o_st,
+                         a.lse_lt, a.lse_st, a.dense, a.kv_groups, p);
+    };
+    if (a.kv_groups > 0) go(fwd_res_kernel<T, D, BK, true>);
+    else go(fwd_res_kernel<T, D, BK, false>);
   });
 }
 

@@ -147,6 +147,23 @@ def test_validation_codes_select_positions(lib):
     assert lib.blossom_select_positions_workspace_bytes(ctypes.byref(ok.c()), 3, 32, 16) == 0
 
 
+def test_validation_codes_attn_fwd_positions(lib):
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    call = lambda p, G=2, Q=a, O=a, sel=a, o_lt=None: lib.blossom_attn_fwd_positions(
+        ctypes.byref(p.c()), G, Q, a, a, a, sel, a, None, O, o_lt, None, None, None, None)
+    ok = _p(H=4, L=200, d=8, block=16, topk=4, window=8)
+    assert call(ok, Q=None) == -1 and call(ok, sel=None) == -1 and call(ok, O=None) == -1
+    assert call(ok, G=3) == -4 and call(ok, G=0) == -4       # the groups must divide the heads
+    assert call(ok, Q=vp(4100)) == -5 and call(ok, o_lt=vp(4100)) == -5
+    assert call(_p(H=4, L=200, d=8, block=32, topk=4, window=8)) == -3    # selection block outside {8, 16}
+    assert call(_p(H=4, L=200, d=64, block=16, topk=4, window=8)) == -3   # head size outside {8, 16, 32}
+    assert call(_p(H=4, L=16 * 65, d=8, block=16, topk=4, window=8)) == -3  # more than 64 selection blocks
+    assert call(_p(H=4, L=200, d=8, block=16, topk=4, window=8, stis_mode=2, stis_block=1)) == -3
+    assert call(_p(H=4, L=200, d=8, block=16, topk=4, window=8, last_block_only=1)) == -3
+    assert call(_p(H=4, L=200, d=8, block=16, topk=0, window=8)) == -4
+
+
 def test_strerror(lib):
     seen = set()
     for code in range(0, -9, -1):

@@ -53,3 +53,66 @@ def test_select_positions_ties_and_limits():
     with pytest.raises(B.BlossomError):   # stride must divide both block sizes
         B.select_positions(B.Params(1, 2, 64, 8, 8, 3, 1, B.F32), 1, 8, 3, torch.zeros((1, 2, 64, 8), device="cuda"),
                            torch.zeros((1, 1, 64, 8), device="cuda"), torch.tensor([64], dtype=torch.int32, device="cuda"))
+
+
+@pytest.mark.parametrize("dtype,Bn,H,G,L,d,l,s,lsel,k,window,stis_mode,stis_block", [
+    ("fp32", 3, 8, 4, 200, 8, 32, 16, 16, 4, 8, 1, 1),    # the paper's own setting: hidden 64 over 8 heads, mask block 1, window 8
+    ("fp32", 2, 8, 2, 100, 16, 32, 16, 16, 4, 8, 0, 0),   # 2 key/value heads, plain window
+    ("fp32", 2, 4, 1, 197, 32, 16, 8, 8, 3, 12, 0, 0),    # one group of four heads, selection block 8, ragged tail
+    ("bf16", 2, 4, 4, 333, 16, 32, 16, 16, 6, 20, 1, 16),  # bf16 storage, no sharing, mask block = selection block
+])
+def test_attention_under_a_per_position_selection(dtype, Bn, H, G, L, d, l, s, lsel, k, window, stis_mode, stis_block):
+    # the printed path end to end on the GPU: blossom_select_positions -> blossom_attn_fwd_positions, against
+    # the oracle's attention under the same per-position selection (its K, V and selection rows repeated per head)
+    from gpu_util import TOL, assert_close, host
+    rng = np.random.default_rng(77 + L + d + k)
+    Q = rng.standard_normal((Bn, H, L, d)).astype(np.float32)
+    K = rng.standard_normal((Bn, G, L, d)).astype(np.float32)
+    V = rng.standard_normal((Bn, G, L, d)).astype(np.float32)
+    if dtype == "bf16":
+        Q, K, V = (round_to_bf16(x / np.sqrt(d)) for x in (Q, K, V))
+    gw = (rng.standard_normal((H, 2 * d)) * 0.3).astype(np.float32)
+    gb = (rng.standard_normal(H) * 0.5).astype(np.float32)
+    vl = rng.integers(1, L + 1, Bn).astype(np.int32)
+    vl[0] = L
+    print(f"per-position attention {dtype} B{Bn} H{H} G{G} L{L} d{d} l'{lsel} k{k} w{window} stis {stis_mode}/{stis_block}", flush=True)
+    dt = B.F32 if dtype == "fp32" else B.BF16
+    p_sel = B.Params(Bn, H, L, d, lsel, k, 1, dt)
+    p = B.Params(Bn, H, L, d, lsel, k, window, dt, stis_mode=stis_mode, stis_block=stis_block)
+    Qd, Kd, Vd = to_dev(Q, dtype), to_dev(K, dtype), to_dev(V, dtype)
+    vld = torch.from_numpy(vl).cuda()
+    sel_pos = B.select_positions(p_sel, G, l, s, Qd, Kd, vld)
+    f = B.attn_fwd_positions(p, G, Qd, Kd, Vd, vld, sel_pos, torch.from_numpy(gw).cuda(), torch.from_numpy(gb).cuda(),
+                             want_branches=True)
+    torch.cuda.synchronize()
+    sel_ref = oracle.select_positions(Q, K, vl, l, s, lsel, k)
+    np.testing.assert_array_equal(sel_pos.cpu().numpy(), sel_ref)
+    rep = H // G
+    fr = oracle.attn_fwd(Q, np.repeat(K, rep, 1), np.repeat(V, rep, 1), vl, np.repeat(sel_ref, rep, 1), gw, gb, lsel, k, window,
+                         per_position=True, stis_block=(stis_block if stis_mode else 0))
+    tol = TOL[dtype]
+    flat = lambda t: host(t).reshape(Bn * H, *t.shape[2:])
+    assert_close(flat(f.o_lt), fr.o_lt, tol, "o_lt")
+    assert_close(flat(f.o_st), fr.o_st, tol, "o_st")
+    assert_close(flat(f.O), fr.O, tol, "O")
+    assert_close(flat(f.lse_lt), fr.lse_lt, tol, "lse_lt")
+    assert_close(flat(f.lse_st), fr.lse_st, tol, "lse_st")
+    for r in range(Bn):   # pad rows are exactly zero
+        p0 = L - int(vl[r])
+        if p0 > 0:
+            assert float(f.O[r, :, :p0].float().abs().max()) == 0.0
+    # the same call without the branch outputs gives the same O
+    f2 = B.attn_fwd_positions(p, G, Qd, Kd, Vd, vld, sel_pos, torch.from_numpy(gw).cuda(), torch.from_numpy(gb).cuda())
+    assert torch.equal(f2.O, f.O)
+
+
+def test_per_position_attention_limits():
+    z = lambda *s: torch.zeros(s, device="cuda")
+    vl = torch.tensor([64], dtype=torch.int32, device="cuda")
+    gw = z(2, 16)
+    with pytest.raises(B.BlossomError):   # groups must divide the heads
+        B.attn_fwd_positions(B.Params(1, 3, 64, 8, 16, 2, 8, B.F32), 2, z(1, 3, 64, 8), z(1, 2, 64, 8), z(1, 2, 64, 8), vl,
+                             torch.zeros((1, 2, 64, 2), dtype=torch.int32, device="cuda"), z(3, 16))
+    with pytest.raises(B.BlossomError):   # selection block 32 is outside the kernels that serve this form
+        B.attn_fwd_positions(B.Params(1, 2, 64, 8, 32, 2, 8, B.F32), 1, z(1, 2, 64, 8), z(1, 1, 64, 8), z(1, 1, 64, 8), vl,
+                             torch.zeros((1, 1, 64, 2), dtype=torch.int32, device="cuda"), gw)
