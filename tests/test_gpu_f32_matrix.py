@@ -111,3 +111,27 @@ def test_long_rows_with_more_than_64_kb_of_lds():
     w = with_shape(WORKLOADS["cfg2"], name="res-L1000", B=8, H=8, L=1000, d=8, block=16, topk=4, window=8, len_lo=300,
                    len_hi=1000, stis_block=1, seed=1301)
     run_case(w, backward=True, pairs=[0, 7, 21, 38, 63])
+
+
+def test_seeded_random_shapes_in_the_resident_range():
+    # 60 seeded draws over storage type, head size, block size, length, top-k, window, mask block and form
+    rng = np.random.default_rng(4242)
+    for case in range(60):
+        dtype = "bf16" if rng.random() < 0.35 else "fp32"
+        d = int(rng.choice([8, 16, 32]))
+        b = int(rng.choice([8, 16]))
+        nb = int(rng.integers(1, 27))
+        L = max(2, nb * b - int(rng.integers(0, b)))
+        topk = int(rng.choice([1, 2, 3, 4, 5, nb, nb + 3]))
+        window = int(rng.choice([1, 2, b - 1, b, b + 1, 2 * b + 5, 3 * b, L, L + 7]))
+        bidir = bool(rng.random() < 0.25)
+        sblk = int(rng.choice([0, 0, b, 1, 3, 2 * b, 4, b // 2]))
+        if bidir and sblk == 0:
+            sblk = int(rng.choice([1, b, 4]))
+        w = with_shape(WORKLOADS["cfg1"], name=f"rr{case}", B=4, H=int(rng.choice([2, 3, 16])), L=L, d=d, block=b,
+                       topk=max(1, topk), window=max(1, window), dtype=dtype, len_lo=0, len_hi=L,
+                       qkv_scaled=(dtype == "bf16"), seed=424200 + case, stis_block=sblk, bidir=bidir)
+        x = make_inputs(w, want_dO=True)
+        x.valid_len[:] = [L, int(rng.integers(0, L + 1)), int(rng.integers(0, L + 1)), min(L, 1 + int(rng.integers(0, b)))]
+        same = w.topk >= w.NB and (w.window >= L or sblk >= L)
+        run_case(w, x=x, backward=True, check_dense=(case % 4 == 0 and not bidir), gate_scale=0.4, branches_coincide=same)
