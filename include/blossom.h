@@ -183,12 +183,32 @@ int blossom_select_positions(const blossom_params *p, int32_t kv_groups, int32_t
  *   o_lt, o_st      out  fp32 [B,H,L,d], or NULL;  lse_lt, lse_st  out  fp32 [B,H,L], or NULL
  * Served by the kernels that keep a head's K and V resident in LDS: d in {8, 16, 32}, l' in {8, 16}, at most 64
  * selection blocks, K and V of one (row, group) within 144 KB as fp32 rows (L <= 480 at d = 32, <= 900 at d <= 16);
- * BLOSSOM_ERR_UNSUPPORTED beyond, for stis_mode 2 and for last_block_only.  Forward only; needs no workspace.
+ * BLOSSOM_ERR_UNSUPPORTED beyond, for stis_mode 2 and for last_block_only.  Needs no workspace.
  */
 int blossom_attn_fwd_positions(const blossom_params *p, int32_t kv_groups, const void *Q, const void *K, const void *V,
                                const int32_t *valid_len, const int32_t *sel_pos, const float *gate_w,
                                const float *gate_b, void *O, void *o_lt, void *o_st, float *lse_lt, float *lse_st,
                                void *hip_stream);
+
+/*
+ * Backward of blossom_attn_fwd_positions (the gradients of Eq. 14, 16-19 under the per-position selection of
+ * Eq. 13, grouped-query attention of Eq. 4-5), for training a model that takes the selection rule as printed.
+ * Same formulas as blossom_attn_bwd with the long-term set of query position t read from row
+ * [b, h / (H/G), t] of sel_pos; dK and dV of a key head are the sums over the H/G query heads that share it.
+ *   Q, dO, dQ       [B,H,L,d];  K, V, dK, dV  [B,G,L,d]  (element type p->dtype, 16-byte aligned)
+ *   sel_pos         in   int32 [B,G,L,topk], as given to the forward
+ *   o_lt, o_st, lse_lt, lse_st   in   as the forward wrote them (all four required)
+ *   d_gate_w        out  fp32 [H,2d];  d_gate_b  out fp32 [H] or NULL
+ *   ws              scratch, >= blossom_workspace_bytes(p, BLOSSOM_WS_BWD), 16-byte aligned
+ * Every output element is written (padding rows get zeros); no atomics, so results do not depend on timing.
+ * Limits: those of blossom_attn_fwd_positions, with Q, dO and the per-position constants of one head within
+ * 144 KB of LDS (L <= 432 at d = 32, <= 736 at d <= 16 with l' = 16; 64 blocks, L <= 512, with l' = 8); BLOSSOM_ERR_UNSUPPORTED beyond.
+ */
+int blossom_attn_bwd_positions(const blossom_params *p, int32_t kv_groups, const void *Q, const void *K, const void *V,
+                               const int32_t *valid_len, const int32_t *sel_pos, const float *gate_w,
+                               const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                               const float *lse_st, const void *dO, void *dQ, void *dK, void *dV, float *d_gate_w,
+                               float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
  * Rotary position embedding (Sec. 3.3: RoPE is applied to the projected Q and K before both branches)

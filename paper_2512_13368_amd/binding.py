@@ -19,7 +19,7 @@ WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
 EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp",
            "blossom_rope_select_blocks", "blossom_attn_bwd_rope", "blossom_select_positions_workspace_bytes",
-           "blossom_select_positions", "blossom_attn_fwd_positions", "blossom_attn_fwd", "blossom_attn_bwd",
+           "blossom_select_positions", "blossom_attn_fwd_positions", "blossom_attn_bwd_positions", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_probe_bytes", "blossom_probe", "blossom_strerror", "blossom_version")
 PROBE_WORKGROUPS = 4096
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
@@ -69,6 +69,9 @@ def lib() -> ctypes.CDLL:
                                                vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd_positions.restype = ctypes.c_int
         L.blossom_attn_fwd_positions.argtypes = [pp, ctypes.c_int32] + [vp] * 12 + [vp]
+        L.blossom_attn_bwd_positions.restype = ctypes.c_int
+        L.blossom_attn_bwd_positions.argtypes = [pp, ctypes.c_int32, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, fp, fp, vp, vp,
+                                                 vp, vp, fp, fp, vp, ctypes.c_size_t, vp]
         L.blossom_select_blocks_cmp.restype = ctypes.c_int
         L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
@@ -434,4 +437,50 @@ def attn_fwd_positions(p: Params, kv_groups: int, Q, K, V, valid_len, sel_pos, g
                                           _ptr(out.lse_lt), _ptr(out.lse_st), _stream(stream))
     if rc:
         raise BlossomError(rc, "blossom_attn_fwd_positions")
+    return out
+
+
+def attn_bwd_positions(p: Params, kv_groups: int, Q, K, V, valid_len, sel_pos, gate_w, gate_b, fwd: FwdOut, dO,
+                       out: BwdOut | None = None, ws=None, stream=None) -> BwdOut:
+    """blossom_attn_bwd_positions: backward of attn_fwd_positions (dQ [B,H,L,d]; dK, dV [B,G,L,d]: the
+    gradients of the query heads of a group added up)."""
+    import torch
+    shp = (p.B, p.H, p.L, p.d)
+    kv_shp = (p.B, kv_groups, p.L, p.d)
+    dt = _torch_dtype(p)
+    for t, nm, sh in ((Q, "Q", shp), (K, "K", kv_shp), (V, "V", kv_shp), (dO, "dO", shp)):
+        if t is None:
+            raise ValueError(f"{nm} is required")
+        _check_tensor(t, sh, dt, nm)
+    for t, nm in ((fwd.o_lt, "o_lt"), (fwd.o_st, "o_st")):
+        if t is None:
+            raise ValueError(f"{nm} is required")
+        _check_tensor(t, shp, torch.float32, nm)
+    for t, nm in ((fwd.lse_lt, "lse_lt"), (fwd.lse_st, "lse_st")):
+        if t is None:
+            raise ValueError(f"{nm} is required")
+        _check_tensor(t, shp[:3], torch.float32, nm)
+    _check_tensor(valid_len, (p.B,), torch.int32, "valid_len")
+    _check_tensor(sel_pos, (p.B, kv_groups, p.L, p.topk), torch.int32, "sel_pos")
+    _check_tensor(gate_w, (p.H, 2 * p.d), torch.float32, "gate_w")
+    _check_tensor(gate_b, (p.H,), torch.float32, "gate_b")
+    if out is None:
+        out = BwdOut(torch.empty(shp, dtype=dt, device=Q.device), torch.empty(kv_shp, dtype=dt, device=Q.device),
+                     torch.empty(kv_shp, dtype=dt, device=Q.device),
+                     torch.empty((p.H, 2 * p.d), dtype=torch.float32, device=Q.device),
+                     torch.empty((p.H,), dtype=torch.float32, device=Q.device))
+    _check_tensor(out.dQ, shp, dt, "dQ")
+    _check_tensor(out.dK, kv_shp, dt, "dK")
+    _check_tensor(out.dV, kv_shp, dt, "dV")
+    _check_tensor(out.d_gate_w, (p.H, 2 * p.d), torch.float32, "d_gate_w")
+    _check_tensor(out.d_gate_b, (p.H,), torch.float32, "d_gate_b")
+    ws, nbytes = _workspace(p, WS_BWD, ws, Q.device)
+    cp = p.c()
+    rc = lib().blossom_attn_bwd_positions(ctypes.byref(cp), kv_groups, _ptr(Q), _ptr(K), _ptr(V), _ptr(valid_len),
+                                          _ptr(sel_pos), _ptr(gate_w), _ptr(gate_b), _ptr(fwd.o_lt), _ptr(fwd.o_st),
+                                          _ptr(fwd.lse_lt), _ptr(fwd.lse_st), _ptr(dO), _ptr(out.dQ), _ptr(out.dK),
+                                          _ptr(out.dV), _ptr(out.d_gate_w), _ptr(out.d_gate_b), _ptr(ws), nbytes,
+                                          _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_attn_bwd_positions")
     return out

@@ -294,6 +294,38 @@ int blossom_attn_fwd_positions(const blossom_params *p, int32_t kv_groups, const
   return launch_status();
 }
 
+int blossom_attn_bwd_positions(const blossom_params *p, int32_t kv_groups, const void *Q, const void *K, const void *V,
+                               const int32_t *valid_len, const int32_t *sel_pos, const float *gate_w,
+                               const float *gate_b, const void *o_lt, const void *o_st, const float *lse_lt,
+                               const float *lse_st, const void *dO, void *dQ, void *dK, void *dV, float *d_gate_w,
+                               float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (kv_groups < 1 || p->H % kv_groups != 0) return BLOSSOM_ERR_PARAM;
+  if (!Q || !K || !V || !valid_len || !sel_pos || !gate_w || !o_lt || !o_st || !lse_lt || !lse_st || !dO || !dQ ||
+      !dK || !dV || !d_gate_w)
+    return BLOSSOM_ERR_NULL;
+  if (!aligned16(Q) || !aligned16(K) || !aligned16(V) || !aligned16(o_lt) || !aligned16(o_st) || !aligned16(dO) ||
+      !aligned16(dQ) || !aligned16(dK) || !aligned16(dV))
+    return BLOSSOM_ERR_ALIGN;
+  if (!bwd_positions_supported(kp, p->dtype)) return BLOSSOM_ERR_UNSUPPORTED;
+  rc = check_ws(kp, p->dtype, BLOSSOM_WS_BWD, ws, ws_bytes);
+  if (rc) return rc;
+  BwdArgs a{};
+  a.Q = Q; a.K = K; a.V = V; a.valid_len = valid_len; a.sel = sel_pos;
+  a.gate_w = gate_w; a.gate_b = gate_b; a.o_lt = o_lt; a.o_st = o_st;
+  a.lse_lt = lse_lt; a.lse_st = lse_st; a.dO = dO; a.dQ = dQ; a.dK = dK; a.dV = dV;
+  a.d_gate_w = d_gate_w; a.d_gate_b = d_gate_b; a.ws = ws;
+  clear_stale_error();
+  // the per-row pass (gate gradient, the constants of each row) reads neither the selection nor K and V
+  launch_bwd(kp, p->dtype, a, kBwdStageGate, (hipStream_t)hip_stream);
+  if (launch_failed()) return launch_status();
+  launch_bwd_positions(kp, p->dtype, a, bwd_carve(kp, p->dtype, ws), kv_groups, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
 int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
                              const int32_t *valid_len, void *O, float *lse, void *ws,
                              size_t ws_bytes, void *hip_stream)

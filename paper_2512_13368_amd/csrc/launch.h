@@ -108,6 +108,8 @@ bool fwd_res_supported(const KParams &p, int dtype);
 void launch_fwd_res(const KParams &p, int dtype, const FwdArgs &a, hipStream_t st);
 bool fwd_positions_supported(const KParams &p, int dtype);
 bool bwd_res_supported(const KParams &p, int dtype);
+bool bwd_positions_supported(const KParams &p, int dtype);
+void launch_bwd_positions(const KParams &p, int dtype, const BwdArgs &a, const BwdWorkspace &w, int kv_groups, hipStream_t st);
 void launch_bwd_res(const KParams &p, int dtype, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st);
 
 // mfma_bwd.hip: matrix-core dQ and dK/dV for bf16, d = 64, b in {32, 64}

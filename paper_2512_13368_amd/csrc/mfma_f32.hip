@@ -335,12 +335,13 @@ __global__ __launch_bounds__(64 * kResWaves) void fwd_res_kernel(
 // =============================================================================================
 // dQ
 // =============================================================================================
-template <typename T, int D, int BK>
+// (PERPOS: as in the forward: `sel` is [B,G,L,k], K and V are [B,G,L,d])
+template <typename T, int D, int BK, bool PERPOS>
 __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
     const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, const int *__restrict__ valid_len,
     const int *__restrict__ sel, const float *__restrict__ gate_w, const float *__restrict__ lse_lt,
     const float *__restrict__ lse_st, const T *__restrict__ dO, const float4 *__restrict__ rowstat, T *__restrict__ dQ,
-    KParams p)
+    int kv_groups, KParams p)
 {
   constexpr int NS = Geo<D>::NS, NMB = Geo<D>::NMB, LDR = Geo<D>::LDR;
   extern __shared__ __attribute__((aligned(16))) float lds_res[];
@@ -356,7 +357,9 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
   const int n = clamp_len(valid_len[bh / p.H], p.L);
   const int p0 = p.L - n;
   const size_t head = (size_t)bh * p.L * D;
-  stage_head<T, D>(K + head, V + head, Ks, Vs, rows, p.L, tid);
+  const int kvh = PERPOS ? (bh / p.H) * kv_groups + h / (p.H / kv_groups) : bh;
+  const size_t head_kv = (size_t)kvh * p.L * D;
+  stage_head<T, D>(K + head_kv, V + head_kv, Ks, Vs, rows, p.L, tid);
   __syncthreads();
 
   const int q = lane & 15, g = lane >> 4;
@@ -394,8 +397,16 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
     const float4 st = active ? rowstat[lrow] : make_float4(0.f, 0.f, 0.f, 0.f);
     const float l2_lt = active ? lse_lt[lrow] * kLog2eF : kHugeF;  // rows that take no part: every probability zero
     const float l2_st = active ? lse_st[lrow] * kLog2eF : kHugeF;
-    const int *my_sel = sel + ((size_t)bh * p.NB + I) * p.k;
-    int sel_v = lane < p.k ? my_sel[lane] : -1;
+    const int *my_sel = PERPOS ? nullptr : sel + ((size_t)bh * p.NB + I) * p.k;
+    int sel_v = (!PERPOS && lane < p.k) ? my_sel[lane] : -1;
+    unsigned long long lt_mask = 0ull;  // PERPOS: bit J set iff this lane's position selected block J
+    if (PERPOS && active) {
+      const int *prow = sel + ((size_t)kvh * p.L + iq) * p.k;
+      for (int e = 0; e < p.k; ++e) {
+        const int v = prow[e];
+        if (v >= 0 && v < p.NB) lt_mask |= 1ull << v;
+      }
+    }
 
     float gx[NS];  // dO_x of the branch being walked
     float l2, Dx;
@@ -413,7 +424,8 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
       for (int r = 0; r < 4; ++r) {
         const int ko = 4 * g + r;
         const int key = J * BK + ko;
-        const bool vis = active && ko < BK && key >= p0 && key < p.L && (key <= iq || p.bidir) && (!windowed || st_visible(p, iq, key));
+        const bool vis = active && ko < BK && key >= p0 && key < p.L && (key <= iq || p.bidir) &&
+                         (windowed ? st_visible(p, iq, key) : (!PERPOS || ((lt_mask >> J) & 1ull)));
         ds[r] = vis ? __builtin_amdgcn_exp2f(s[r] - l2) * (gv[r] - Dx) : 0.0f;
       }
       const float *kc = Ks + (J * BK + 4 * g) * LDR + q;  // row = key 4g + r, column = channel 16*mb + q
@@ -446,6 +458,10 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dq_res_kernel(
     for (int s = 0; s < NS; ++s) gx[s] = fmaf(st.x, gr[s], st.y * wl[s]);
     l2 = l2_lt;
     Dx = st.z;
+    if (PERPOS) {
+      for (int J = J_first; J <= I; ++J)
+        if (__ballot((lt_mask >> J) & 1ull) != 0ull) tile(J, false);
+    } else
     for (int e0 = 0; e0 < p.k; e0 += 64) {
       if (e0 > 0) sel_v = e0 + lane < p.k ? my_sel[e0 + lane] : -1;
       const int ne = min(64, p.k - e0);
@@ -619,11 +635,188 @@ __global__ __launch_bounds__(64 * kResWaves) void bwd_dkv_res_kernel(
 }
 
 // =============================================================================================
+// dK, dV under a per-position selection with grouped key/value heads: K, V, dK, dV are [B,G,L,d].
+// One workgroup per (row, group).  The H/G query heads of the group all add into the same dK and dV,
+// so a wavefront keeps the accumulators of its key block while the workgroup stages one head after
+// the other (Q, dO and the per-row constants of that head), rounds of eight key blocks at a time.
+// The selection rows of the group become one 64-bit word per position in LDS (bit J: block J
+// selected) and their OR per query block: the long-term walk of key block J visits the query
+// blocks whose word has bit J, each row testing its own.
+// =============================================================================================
+template <typename T, int D, int BK>
+__global__ __launch_bounds__(64 * kResWaves) void bwd_dkv_pos_kernel(
+    const T *__restrict__ Q, const T *__restrict__ K, const T *__restrict__ V, const int *__restrict__ valid_len,
+    const int *__restrict__ sel_pos, const float *__restrict__ gate_w, const float *__restrict__ lse_lt,
+    const float *__restrict__ lse_st, const T *__restrict__ dO, const float4 *__restrict__ rowstat, T *__restrict__ dK,
+    T *__restrict__ dV, int kv_groups, KParams p)
+{
+  constexpr int NS = Geo<D>::NS, NMB = Geo<D>::NMB, LDR = Geo<D>::LDR;
+  extern __shared__ __attribute__((aligned(16))) float lds_res[];
+  const int rows = res_rows(p);
+  float *Qs = lds_res;
+  float *Gs = Qs + rows * LDR;  // dO rows
+  float *rc = Gs + rows * LDR;  // per row: alpha, dz, D_lt, D_st, lse2_lt, lse2_st (six arrays of `rows`)
+  unsigned long long *pmask = reinterpret_cast<unsigned long long *>(rc + 6 * rows);  // [rows] selection bits per position
+  unsigned long long *bmask = pmask + rows;                                            // [NB] their OR per query block
+
+  const int tid = threadIdx.x;
+  const int lane = tid & 63;
+  const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
+  const int bg = blockIdx.x;               // (row, group)
+  const int r_b = bg / kv_groups, grp = bg % kv_groups;
+  const int hpg = p.H / kv_groups;         // query heads per group
+  const int n = clamp_len(valid_len[r_b], p.L);
+  const int p0 = p.L - n;
+  const size_t head_kv = (size_t)bg * p.L * D;
+
+  for (int i = tid; i < rows; i += 64 * kResWaves) {
+    unsigned long long m = 0ull;
+    if (i < p.L && i >= p0) {
+      const int *prow = sel_pos + ((size_t)bg * p.L + i) * p.k;
+      for (int e = 0; e < p.k; ++e) {
+        const int v = prow[e];
+        if (v >= 0 && v < p.NB) m |= 1ull << v;
+      }
+    }
+    pmask[i] = m;
+  }
+  __syncthreads();
+  for (int I = tid; I < p.NB; I += 64 * kResWaves) {
+    unsigned long long m = 0ull;
+    for (int t = 0; t < BK; ++t) m |= pmask[I * BK + t];
+    bmask[I] = m;
+  }
+
+  const int kq = lane & 15, g = lane >> 4;
+  const float c2 = p.scale * kLog2eF;
+
+  for (int J0 = 0; J0 < p.NB; J0 += kResWaves) {  // rounds of eight key blocks, one per wavefront
+    const int J = J0 + wv;
+    const bool have = J < p.NB && min((J + 1) * BK, p.L) > p0;  // (uniform) a key block with a valid key
+    const int j = J * BK + kq;
+    const bool in_range = J < p.NB && kq < BK && j < p.L;
+    const bool key_ok = in_range && j >= p0;
+    const int row = min(max(j, 0), p.L - 1);
+    const size_t rowoff = head_kv + (size_t)row * D;
+    f32x4 dk[NMB], dv[NMB];
+#pragma unroll
+    for (int mb = 0; mb < NMB; ++mb) {
+      dk[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+      dv[mb] = f32x4{0.f, 0.f, 0.f, 0.f};
+    }
+    float kf[NS], vf[NS];
+#pragma unroll
+    for (int s = 0; s < NS; ++s) {
+      kf[s] = key_ok ? to_f32(K[rowoff + 4 * s + g]) * c2 : 0.0f;
+      vf[s] = key_ok ? to_f32(V[rowoff + 4 * s + g]) : 0.0f;
+    }
+
+    for (int hh = 0; hh < hpg; ++hh) {
+      const int h = grp * hpg + hh;
+      const int bh = r_b * p.H + h;
+      const size_t head = (size_t)bh * p.L * D;
+      __syncthreads();  // every wavefront is done with the previous head's rows (and, the first time, bmask is written)
+      stage_head<T, D>(Q + head, dO + head, Qs, Gs, rows, p.L, tid);
+      for (int r = tid; r < rows; r += 64 * kResWaves) {
+        float4 st = make_float4(0.f, 0.f, 0.f, 0.f);
+        float a = kHugeF, b = kHugeF;  // rows that take no part: every probability zero
+        if (r < p.L && r >= p0) {
+          st = rowstat[(size_t)bh * p.L + r];
+          a = lse_lt[(size_t)bh * p.L + r] * kLog2eF;
+          b = lse_st[(size_t)bh * p.L + r] * kLog2eF;
+        }
+        rc[r] = st.x;
+        rc[rows + r] = st.y;
+        rc[2 * rows + r] = st.z;
+        rc[3 * rows + r] = st.w;
+        rc[4 * rows + r] = a;
+        rc[5 * rows + r] = b;
+      }
+      __syncthreads();
+      if (!have) continue;
+
+      const float *wrow = gate_w + (size_t)h * 2 * D;
+      float wl[NS], ws[NS], wlc[NMB], wsc[NMB];
+#pragma unroll
+      for (int s = 0; s < NS; ++s) {
+        wl[s] = wrow[4 * s + g];
+        ws[s] = wrow[D + 4 * s + g];
+      }
+#pragma unroll
+      for (int mb = 0; mb < NMB; ++mb) {
+        wlc[mb] = gate_at<D>(wrow, 16 * mb + kq);
+        wsc[mb] = gate_at<D>(wrow + D, 16 * mb + kq);
+      }
+
+      auto tile = [&](int I, bool windowed) {
+        const int r0 = I * BK;
+        const float *ax_s = rc;
+        const float *dz_s = rc + rows;
+        const float *Dx_s = rc + (windowed ? 3 : 2) * rows;
+        const float *l2_s = rc + (windowed ? 5 : 4) * rows;
+        const float *qt = Qs + (r0 + kq) * LDR + g;
+        const float *gt = Gs + (r0 + kq) * LDR + g;
+        const float al_m = ax_s[r0 + kq], dz_m = dz_s[r0 + kq];
+        const float a_m = windowed ? 1.0f - al_m : al_m;
+        f32x4 s = {0.f, 0.f, 0.f, 0.f}, gv = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+        for (int t = 0; t < NS; ++t) {
+          s = __builtin_amdgcn_mfma_f32_16x16x4f32(qt[4 * t], kf[t], s, 0, 0, 0);
+          gv = __builtin_amdgcn_mfma_f32_16x16x4f32(fmaf(a_m, gt[4 * t], dz_m * (windowed ? ws[t] : wl[t])), vf[t], gv, 0, 0, 0);
+        }
+        float pr[4], ds[4], a_r[4], dz_r[4];
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const int qo = 4 * g + r;
+          const int i = r0 + qo;
+          const bool vis = key_ok && qo < BK && i >= j &&
+                           (windowed ? st_visible(p, i, j) : (((pmask[i] >> J) & 1ull) != 0ull));
+          pr[r] = vis ? __builtin_amdgcn_exp2f(s[r] - l2_s[i]) : 0.0f;
+          ds[r] = pr[r] * (gv[r] - Dx_s[i]);
+          const float al = ax_s[i];
+          a_r[r] = windowed ? 1.0f - al : al;
+          dz_r[r] = dz_s[i];
+        }
+        const float *gc = Gs + (r0 + 4 * g) * LDR + kq;
+        const float *qc = Qs + (r0 + 4 * g) * LDR + kq;
+#pragma unroll
+        for (int r = 0; r < 4; ++r)
+#pragma unroll
+          for (int mb = 0; mb < NMB; ++mb) {
+            const float gxe = fmaf(a_r[r], gc[r * LDR + 16 * mb], dz_r[r] * (windowed ? wsc[mb] : wlc[mb]));
+            dv[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(gxe, pr[r], dv[mb], 0, 0, 0);
+            dk[mb] = __builtin_amdgcn_mfma_f32_16x16x4f32(qc[r * LDR + 16 * mb], ds[r], dk[mb], 0, 0, 0);
+          }
+      };
+
+      {  // short-term branch of this head
+        const long last_q = (long)J * BK + (BK - 1) + (p.w - 1);
+        const int I_hi = (int)min((long)(p.NB - 1), last_q / BK);
+        for (int I = J; I <= I_hi; ++I) tile(I, true);
+        for (int I = I_hi + 1; I < p.NB; ++I)
+          if (st_block_reach(p, I, J)) tile(I, true);
+      }
+      // long-term branch: query blocks with a position that selected this key block
+      for (int I = J; I < p.NB; ++I)
+        if ((bmask[I] >> J) & 1ull) tile(I, false);
+    }
+    if (in_range) {
+      store_grad_row<T, D>(dK + rowoff, dk, key_ok ? p.scale : 0.0f, p, true, row, g);
+      store_grad_row<T, D>(dV + rowoff, dv, key_ok ? 1.0f : 0.0f, p, false, row, g);
+    }
+  }
+}
+
+// =============================================================================================
 // launchers
 // =============================================================================================
 namespace {
 
 size_t res_kv_lds_bytes(const KParams &p, int D) { return 2 * (size_t)res_rows(p) * ((D < 16 ? 16 : D) + 4) * sizeof(float); }
+size_t res_pos_dkv_lds_bytes(const KParams &p, int D)
+{
+  return res_kv_lds_bytes(p, D) + 6 * (size_t)res_rows(p) * sizeof(float) + ((size_t)res_rows(p) + p.NB) * sizeof(unsigned long long);
+}
 size_t res_dkv_lds_bytes(const KParams &p, int D) { return res_kv_lds_bytes(p, D) + 6 * (size_t)res_rows(p) * sizeof(float); }
 
 bool res_shape(const KParams &p)
@@ -710,10 +903,10 @@ static void launch_bwd_res_t(const KParams &p, const BwdArgs &a, const BwdWorksp
     constexpr int D = decltype(dim)::value, BK = decltype(bk)::value;
     if (stages & kBwdStageDQ) {
       const size_t lds = res_kv_lds_bytes(p, p.d);
-      auto kernel = bwd_dq_res_kernel<T, D, BK>;
+      auto kernel = bwd_dq_res_kernel<T, D, BK, false>;
       want_lds(kernel, lds);
       hipLaunchKernelGGL(kernel, dim3(grid), dim3(64 * kResWaves), lds, st, (const T *)a.Q, (const T *)a.K, (const T *)a.V,
-                         a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO, w.rowstat, (T *)a.dQ, p);
+                         a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO, w.rowstat, (T *)a.dQ, 0, p);
       if (launch_failed()) return;
     }
     if (stages & kBwdStageDKV) {
@@ -731,6 +924,44 @@ void launch_bwd_res(const KParams &p, int dtype, const BwdArgs &a, const BwdWork
 {
   if (dtype == 0) launch_bwd_res_t<float>(p, a, w, stages, st);
   else launch_bwd_res_t<bf16_t>(p, a, w, stages, st);
+}
+
+bool bwd_positions_supported(const KParams &p, int dtype)
+{
+  return fwd_positions_supported(p, dtype) && res_pos_dkv_lds_bytes(p, p.d) <= kResLdsMax;
+}
+
+// dQ [B,H,L,d] and dK, dV [B,G,L,d] under a per-position selection (a.sel = sel_pos [B,G,L,k]); the per-row pass
+// has filled w.rowstat
+template <typename T>
+static void launch_bwd_pos_t(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, int kv_groups, hipStream_t st)
+{
+  with_res_dims(p, [&](auto dim, auto bk) {
+    constexpr int D = decltype(dim)::value, BK = decltype(bk)::value;
+    {
+      const size_t lds = res_kv_lds_bytes(p, p.d);
+      auto kernel = bwd_dq_res_kernel<T, D, BK, true>;
+      want_lds(kernel, lds);
+      hipLaunchKernelGGL(kernel, dim3((unsigned)(p.B * p.H)), dim3(64 * kResWaves), lds, st, (const T *)a.Q, (const T *)a.K,
+                         (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO, w.rowstat,
+                         (T *)a.dQ, kv_groups, p);
+      if (launch_failed()) return;
+    }
+    {
+      const size_t lds = res_pos_dkv_lds_bytes(p, p.d);
+      auto kernel = bwd_dkv_pos_kernel<T, D, BK>;
+      want_lds(kernel, lds);
+      hipLaunchKernelGGL(kernel, dim3((unsigned)(p.B * kv_groups)), dim3(64 * kResWaves), lds, st, (const T *)a.Q,
+                         (const T *)a.K, (const T *)a.V, a.valid_len, a.sel, a.gate_w, a.lse_lt, a.lse_st, (const T *)a.dO,
+                         w.rowstat, (T *)a.dK, (T *)a.dV, kv_groups, p);
+    }
+  });
+}
+
+void launch_bwd_positions(const KParams &p, int dtype, const BwdArgs &a, const BwdWorkspace &w, int kv_groups, hipStream_t st)
+{
+  if (dtype == 0) launch_bwd_pos_t<float>(p, a, w, kv_groups, st);
+  else launch_bwd_pos_t<bf16_t>(p, a, w, kv_groups, st);
 }
 
 }  // namespace blossom

@@ -164,6 +164,22 @@ def test_validation_codes_attn_fwd_positions(lib):
     assert call(_p(H=4, L=200, d=8, block=16, topk=0, window=8)) == -4
 
 
+def test_validation_codes_attn_bwd_positions(lib):
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    call = lambda p, G=2, Q=a, dK=a, sel=a, lse=a, ws=a, n=1 << 40: lib.blossom_attn_bwd_positions(
+        ctypes.byref(p.c()), G, Q, a, a, a, sel, a, None, a, a, lse, a, a, a, dK, a, a, None, ws, n, None)
+    ok = _p(H=4, L=200, d=8, block=16, topk=4, window=8)
+    assert call(ok, Q=None) == -1 and call(ok, sel=None) == -1 and call(ok, dK=None) == -1 and call(ok, lse=None) == -1
+    assert call(ok, G=3) == -4 and call(ok, G=0) == -4
+    assert call(ok, Q=vp(4100)) == -5 and call(ok, dK=vp(4100)) == -5
+    assert call(ok, ws=None) == -6 and call(ok, n=16) == -6 and call(ok, ws=vp(4100)) == -5
+    assert call(_p(H=4, L=200, d=8, block=32, topk=4, window=8)) == -3
+    assert call(_p(H=4, L=480, d=32, block=16, topk=4, window=8)) == -3   # the forward's limit, beyond the backward's
+    assert call(_p(H=4, L=432, d=32, block=16, topk=4, window=8), ws=None) == -6   # the longest the backward takes
+    assert call(_p(H=4, L=200, d=8, block=16, topk=4, window=8, stis_mode=2, stis_block=1)) == -3
+
+
 def test_strerror(lib):
     seen = set()
     for code in range(0, -9, -1):

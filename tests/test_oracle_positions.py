@@ -152,3 +152,42 @@ def test_attention_under_a_per_position_selection():
                 if j >= 0:
                     want[max(j * lsel, p0):min((j + 1) * lsel, t + 1)] = 1
         assert np.array_equal(M_lt[t], want), t
+
+
+def test_per_position_backward_finite_differences():
+    # the gradients under a per-position selection are the central differences of the oracle's own forward
+    # (float64), also with every head of a group reading the same K, V and selection rows: the gradient
+    # of a shared key is then the sum over the heads that read it
+    B, H, G, L, d, lsel, k, w = 1, 4, 2, 37, 4, 8, 2, 3
+    rng = np.random.default_rng(12)
+    Q, dO = rng.standard_normal((B, H, L, d)), rng.standard_normal((B, H, L, d))
+    K, V = rng.standard_normal((B, G, L, d)), rng.standard_normal((B, G, L, d))
+    vl = np.array([30], np.int32)
+    gw = rng.standard_normal((H, 2 * d)) * 0.3
+    gb = rng.standard_normal(H) * 0.2
+    selg = oracle.select_positions(Q.astype(np.float32), K.astype(np.float32), vl, 8, 4, lsel, k)
+    rep = H // G
+    sel = np.repeat(selg, rep, 1)
+    kw = dict(f64=True, stis_block=2, per_position=True)
+    g = oracle.attn_bwd(Q, np.repeat(K, rep, 1), np.repeat(V, rep, 1), vl, sel, gw, gb, dO, lsel, k, w, **kw)
+    dK = g.dK.reshape(B, G, rep, L, d).sum(2)
+    dV = g.dV.reshape(B, G, rep, L, d).sum(2)
+    dQ = g.dQ.reshape(B, H, L, d)
+    loss = lambda q_, k_, v_: float(np.sum(oracle.attn_fwd(q_, np.repeat(k_, rep, 1), np.repeat(v_, rep, 1), vl, sel, gw, gb,
+                                                           lsel, k, w, **kw).O * dO.reshape(B * H, L, d)))
+    eps = 1e-6
+    for name, arr, grad in (("Q", Q, dQ), ("K", K, dK), ("V", V, dV)):
+        heads = arr.shape[1]
+        for idx in [(0, 0, 9, 1), (0, heads - 1, 36, 3), (0, 0, 20, 0), (0, heads - 1, 7, 2), (0, 0, 31, 2)]:
+            hi, lo = arr.copy(), arr.copy()
+            hi[idx] += eps
+            lo[idx] -= eps
+            args = lambda a: (a if name == "Q" else Q, a if name == "K" else K, a if name == "V" else V)
+            fd = (loss(*args(hi)) - loss(*args(lo))) / (2 * eps)
+            got = grad[idx]
+            assert abs(fd - got) <= 1e-6 * (abs(fd) + 1.0), (name, idx, fd, got)
+    p0 = L - 30
+    assert np.all(dQ[:, :, :p0] == 0) and np.all(dK[:, :, :p0] == 0) and np.all(dV[:, :, :p0] == 0)
+    assert np.abs(dK[:, :, p0:]).min() > 0
+    # two positions of one block with different selection rows exist (else this would not test the per-position form)
+    assert any(not np.array_equal(selg[0, 0, t], selg[0, 0, t + 1]) for t in range(p0, L - 1) if t // lsel == (t + 1) // lsel)
