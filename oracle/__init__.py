@@ -57,6 +57,8 @@ def lib() -> ctypes.CDLL:
         L.oracle_attn_fwd.restype = _c_int
         L.oracle_attn_fwd.argtypes = ([_c_int] * 9 + [_c_dbl, _c_int] + [_vp] * 7 + [_vp, _c_int]
                                       + [_vp] * 7)
+        L.oracle_out_proj_ln.restype = _c_int
+        L.oracle_out_proj_ln.argtypes = [_c_int] * 5 + [_vp] * 6 + [_c_dbl] + [_vp] * 3
         L.oracle_attn_bwd.restype = _c_int
         L.oracle_attn_bwd.argtypes = ([_c_int] * 9 + [_c_dbl, _c_int] + [_vp] * 8 + [_vp, _c_int]
                                       + [_vp] * 5)
@@ -312,3 +314,25 @@ def select_positions(Q, K, valid_len, cmp_block, stride, sel_block, topk, score_
                                        _p(Q), _p(K), _p(vl), _p(sel), _p(scores))
     _check(rc, "select_positions")
     return (sel, scores) if want_scores else sel
+
+
+def out_proj_ln(O, Wt, H_prev, gamma, beta, eps, bias=None, want_stats=False):
+    """The layer around the attention (Eq. 4 and the equation after Eq. 19, dropout = identity):
+    S = LayerNorm(H_prev + Concat_h(O[:, h]) W^O (+ bias)).  O [B,H,L,d], Wt [Dm, H*d] (W^O transposed),
+    H_prev [B,L,Dm], gamma, beta [Dm]; float64 throughout.  Returns S [B,L,Dm] (and mean, rstd [B,L])."""
+    O = _in(O, True)
+    B, H, L, d = O.shape
+    Wt = _in(Wt, True)
+    Dm = Wt.shape[0]
+    assert Wt.shape == (Dm, H * d)
+    H_prev = _in(H_prev, True)
+    assert H_prev.shape == (B, L, Dm)
+    gamma, beta = _in(gamma, True), _in(beta, True)
+    assert gamma.shape == (Dm,) and beta.shape == (Dm,)
+    bias = None if bias is None else _in(bias, True)
+    S = np.empty((B, L, Dm), dtype=np.float64)
+    mean = np.empty((B, L), dtype=np.float64)
+    rstd = np.empty((B, L), dtype=np.float64)
+    _check(lib().oracle_out_proj_ln(B, H, L, d, Dm, _p(O), _p(Wt), _p(bias), _p(H_prev), _p(gamma), _p(beta),
+                                    float(eps), _p(S), _p(mean), _p(rstd)), "out_proj_ln")
+    return (S, mean, rstd) if want_stats else S

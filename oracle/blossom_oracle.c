@@ -827,3 +827,56 @@ int oracle_dense_causal_fwd(int B, int H, int L, int d, double scale,
     }
     return err;
 }
+
+/* ------------------------------------------------------------------------- */
+/* The layer around the attention (Sec. 2.1 Eq. 4: the heads are concatenated  */
+/* and multiplied by W^O; Sec. 3.6, the equation after Eq. 19: the result is    */
+/* added to the layer's input and normalised; dropout is the identity here):    */
+/*   c[b,t,h*d + e] = O[b,h,t,e]                    (Concat(head_1..head_H))    */
+/*   z[b,t,n] = Hprev[b,t,n] + bias[n] + sum_j c[b,t,j] * Wt[n,j]               */
+/*   mean = sum_n z / Dm;  var = sum_n (z - mean)^2 / Dm;  rstd = 1/sqrt(var+eps)*/
+/*   S[b,t,n] = (z - mean) * rstd * gamma[n] + beta[n]                          */
+/* Wt [Dm, H*d] holds W^O transposed (row n = column n of the printed matrix).  */
+/* All fp64; bias may be NULL; mean, rstd [B,L] may be NULL.                    */
+/* ------------------------------------------------------------------------- */
+int oracle_out_proj_ln(int B, int H, int L, int d, int Dm, const double *O, const double *Wt, const double *bias,
+                       const double *Hprev, const double *gamma, const double *beta, double eps, double *S,
+                       double *mean_out, double *rstd_out)
+{
+    if (B < 1 || H < 1 || L < 1 || d < 1 || Dm < 1) return -1;
+    const int Kc = H * d;
+    int failed = 0;
+    /* every (b, t) is independent: rows are spread over the threads, each with its own z */
+#pragma omp parallel for schedule(static)
+    for (long bt = 0; bt < (long)B * L; ++bt) {
+        const int b = (int)(bt / L), t = (int)(bt % L);
+        double *z = (double *)malloc((size_t)Dm * sizeof(double));
+        if (!z) {
+#pragma omp atomic write
+            failed = 1;
+            continue;
+        }
+        {
+            for (int n = 0; n < Dm; ++n) {
+                double acc = 0.0;
+                for (int h = 0; h < H; ++h)
+                    for (int e = 0; e < d; ++e)
+                        acc += O[(((size_t)b * H + h) * L + t) * d + e] * Wt[(size_t)n * Kc + (size_t)h * d + e];
+                z[n] = Hprev[((size_t)b * L + t) * Dm + n] + (bias ? bias[n] : 0.0) + acc;
+            }
+            double mean = 0.0;
+            for (int n = 0; n < Dm; ++n) mean += z[n];
+            mean /= Dm;
+            double var = 0.0;
+            for (int n = 0; n < Dm; ++n) var += (z[n] - mean) * (z[n] - mean);
+            var /= Dm;
+            const double rstd = 1.0 / sqrt(var + eps);
+            for (int n = 0; n < Dm; ++n)
+                S[((size_t)b * L + t) * Dm + n] = (z[n] - mean) * rstd * gamma[n] + beta[n];
+            if (mean_out) mean_out[(size_t)b * L + t] = mean;
+            if (rstd_out) rstd_out[(size_t)b * L + t] = rstd;
+        }
+        free(z);
+    }
+    return failed ? -2 : 0;
+}
