@@ -211,6 +211,32 @@ int blossom_attn_bwd_positions(const blossom_params *p, int32_t kv_groups, const
                                float *d_gate_b, void *ws, size_t ws_bytes, void *hip_stream);
 
 /*
+ * The layer around the attention, fused into one pass (Sec. 2.1 Eq. 4: the heads are concatenated and multiplied
+ * by the output projection W^O; Sec. 3.6, the equation after Eq. 19: the result is added to the layer's input and
+ * normalised, S = LayerNorm(H_prev + O_Blossom); dropout is the identity, as at inference):
+ *   z[b,t,n] = H_prev[b,t,n] + bias[n] + sum_{h,e} O[b,h,t,e] * W_O_t[n, h*d + e]
+ *   mean = sum_n z / d_model;  var = sum_n (z - mean)^2 / d_model;  rstd = 1 / sqrt(var + ln_eps)
+ *   S[b,t,n] = (z - mean) * rstd * ln_gamma[n] + ln_beta[n]
+ * O is read in the layout blossom_attn_fwd writes, so neither the concatenated heads, nor the projection's
+ * output, nor the residual sum ever exist in memory.  Products and sums in fp32.  Every position is computed
+ * (a padding row has O = 0 and gives LayerNorm(H_prev + bias)).  Of p only B, H, L, d and dtype are used.
+ *   O        in   [B,H,L,d]              element type p->dtype, 16-byte aligned
+ *   W_O_t    in   [d_model, H*d]         p->dtype: row n holds column n of the printed W^O (the layout in which
+ *                                         linear layers usually keep their weight, out-features x in-features)
+ *   bias     in   fp32 [d_model] or NULL (the printed formula has none)
+ *   H_prev   in   [B,L,d_model]          p->dtype
+ *   ln_gamma, ln_beta   in  fp32 [d_model];  ln_eps >= 0
+ *   S        out  [B,L,d_model]          p->dtype
+ *   mean, rstd  out  fp32 [B,L] or NULL  (what a LayerNorm backward needs)
+ * Shapes: bf16 with d = 64 and d_model 256 or 512 runs on the matrix cores; otherwise d_model a multiple of 8 up
+ * to 1024 and H*d <= 1024 on scalar FMAs; BLOSSOM_ERR_UNSUPPORTED beyond.  Forward only: the backward of this
+ * layer is two dense matrix products and stays with the caller.  Needs no workspace.
+ */
+int blossom_out_proj_ln(const blossom_params *p, int32_t d_model, const void *O, const void *W_O_t, const float *bias,
+                        const void *H_prev, const float *ln_gamma, const float *ln_beta, float ln_eps, void *S,
+                        float *mean, float *rstd, void *hip_stream);
+
+/*
  * Rotary position embedding (Sec. 3.3: RoPE is applied to the projected Q and K before both branches)
  * fused into the pooling pass of blossom_select_blocks, which reads Q and K anyway: every position m of
  * every row is rotated on the way in, channel pairs (2i, 2i+1) by the angle of table entry [m][i],

@@ -19,7 +19,7 @@ WS_SELECT, WS_FWD, WS_BWD, WS_DENSE = 0, 1, 2, 3
 
 EXPORTS = ("blossom_workspace_bytes", "blossom_select_blocks", "blossom_select_blocks_static", "blossom_select_blocks_cmp",
            "blossom_rope_select_blocks", "blossom_attn_bwd_rope", "blossom_select_positions_workspace_bytes",
-           "blossom_select_positions", "blossom_attn_fwd_positions", "blossom_attn_bwd_positions", "blossom_attn_fwd", "blossom_attn_bwd",
+           "blossom_select_positions", "blossom_attn_fwd_positions", "blossom_attn_bwd_positions", "blossom_out_proj_ln", "blossom_attn_fwd", "blossom_attn_bwd",
            "blossom_attn_bwd_stages", "blossom_dense_causal_fwd", "blossom_probe_bytes", "blossom_probe", "blossom_strerror", "blossom_version")
 PROBE_WORKGROUPS = 4096
 BWD_GATE, BWD_INVERSE, BWD_DQ, BWD_DKV, BWD_ALL = 1, 2, 4, 8, 15
@@ -72,6 +72,8 @@ def lib() -> ctypes.CDLL:
         L.blossom_attn_bwd_positions.restype = ctypes.c_int
         L.blossom_attn_bwd_positions.argtypes = [pp, ctypes.c_int32, vp, vp, vp, i32p, i32p, fp, fp, vp, vp, fp, fp, vp, vp,
                                                  vp, vp, fp, fp, vp, ctypes.c_size_t, vp]
+        L.blossom_out_proj_ln.restype = ctypes.c_int
+        L.blossom_out_proj_ln.argtypes = [pp, ctypes.c_int32, vp, vp, fp, vp, fp, fp, ctypes.c_float, vp, fp, fp, vp]
         L.blossom_select_blocks_cmp.restype = ctypes.c_int
         L.blossom_select_blocks_cmp.argtypes = [pp, vp, vp, i32p, i32p, vp, ctypes.c_size_t, vp]
         L.blossom_attn_fwd.restype = ctypes.c_int
@@ -484,3 +486,30 @@ def attn_bwd_positions(p: Params, kv_groups: int, Q, K, V, valid_len, sel_pos, g
     if rc:
         raise BlossomError(rc, "blossom_attn_bwd_positions")
     return out
+
+
+def out_proj_ln(p: Params, d_model: int, O, W_O_t, H_prev, ln_gamma, ln_beta, ln_eps: float, bias=None, S=None,
+                want_stats: bool = False, stream=None):
+    """blossom_out_proj_ln: S = LayerNorm(H_prev + Concat_h(O[:, h]) W^O (+ bias)); W_O_t is [d_model, H*d].
+    Returns S, or (S, mean, rstd) with want_stats."""
+    import torch
+    dt = _torch_dtype(p)
+    _check_tensor(O, (p.B, p.H, p.L, p.d), dt, "O")
+    _check_tensor(W_O_t, (d_model, p.H * p.d), dt, "W_O_t")
+    _check_tensor(H_prev, (p.B, p.L, d_model), dt, "H_prev")
+    _check_tensor(ln_gamma, (d_model,), torch.float32, "ln_gamma")
+    _check_tensor(ln_beta, (d_model,), torch.float32, "ln_beta")
+    _check_tensor(bias, (d_model,), torch.float32, "bias")
+    if S is None:
+        S = torch.empty((p.B, p.L, d_model), dtype=dt, device=O.device)
+    _check_tensor(S, (p.B, p.L, d_model), dt, "S")
+    mean = rstd = None
+    if want_stats:
+        mean = torch.empty((p.B, p.L), dtype=torch.float32, device=O.device)
+        rstd = torch.empty((p.B, p.L), dtype=torch.float32, device=O.device)
+    cp = p.c()
+    rc = lib().blossom_out_proj_ln(ctypes.byref(cp), d_model, _ptr(O), _ptr(W_O_t), _ptr(bias), _ptr(H_prev), _ptr(ln_gamma),
+                                   _ptr(ln_beta), float(ln_eps), _ptr(S), _ptr(mean), _ptr(rstd), _stream(stream))
+    if rc:
+        raise BlossomError(rc, "blossom_out_proj_ln")
+    return (S, mean, rstd) if want_stats else S

@@ -25,6 +25,7 @@ SOURCES = {
     "mfma_f32.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "mfma_bwd.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
     "probe.hip": ["-mllvm", "-amdgpu-mfma-vgpr-form=1"],
+    "out_proj.hip": ["-fno-strict-aliasing"],
 }
 
 COMMON = ["--offload-arch=gfx950", "-O3", "-std=c++17", "-fPIC", "-Wall",

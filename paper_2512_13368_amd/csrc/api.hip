@@ -326,6 +326,29 @@ int blossom_attn_bwd_positions(const blossom_params *p, int32_t kv_groups, const
   return launch_status();
 }
 
+int blossom_out_proj_ln(const blossom_params *p, int32_t d_model, const void *O, const void *W_O_t, const float *bias,
+                        const void *H_prev, const float *ln_gamma, const float *ln_beta, float ln_eps, void *S,
+                        float *mean, float *rstd, void *hip_stream)
+{
+  KParams kp;
+  int rc = check_params(p, &kp);
+  if (rc) return rc;
+  if (d_model < 1 || !std::isfinite(ln_eps) || ln_eps < 0.0f) return BLOSSOM_ERR_PARAM;
+  if (!O || !W_O_t || !H_prev || !ln_gamma || !ln_beta || !S) return BLOSSOM_ERR_NULL;
+  if (!aligned16(O) || !aligned16(W_O_t) || !aligned16(H_prev) || !aligned16(S) || !aligned16(ln_gamma) ||
+      !aligned16(ln_beta) || !aligned16(bias))
+    return BLOSSOM_ERR_ALIGN;
+  OutProjArgs a{};
+  a.B = p->B; a.H = p->H; a.L = p->L; a.d = p->d; a.Dm = d_model; a.dtype = p->dtype;
+  a.O = O; a.Wt = W_O_t; a.bias = bias; a.Hprev = H_prev; a.gamma = ln_gamma; a.beta = ln_beta; a.eps = ln_eps;
+  a.S = S; a.mean = mean; a.rstd = rstd;
+  if (!out_proj_supported(a)) return BLOSSOM_ERR_UNSUPPORTED;
+  if ((double)p->B * p->L * d_model > 9.0e18) return BLOSSOM_ERR_SHAPE;
+  clear_stale_error();
+  launch_out_proj(a, (hipStream_t)hip_stream);
+  return launch_status();
+}
+
 int blossom_dense_causal_fwd(const blossom_params *p, const void *Q, const void *K, const void *V,
                              const int32_t *valid_len, void *O, float *lse, void *ws,
                              size_t ws_bytes, void *hip_stream)

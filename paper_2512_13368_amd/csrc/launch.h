@@ -116,4 +116,19 @@ void launch_bwd_res(const KParams &p, int dtype, const BwdArgs &a, const BwdWork
 bool bwd_mfma_supported(const KParams &p, int dtype);
 void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, unsigned stages, hipStream_t st);
 
+// out_proj.hip: output projection + residual + LayerNorm around the attention (Eq. 4, the equation after Eq. 19)
+struct OutProjArgs {
+  int B, H, L, d, Dm, dtype;      // dtype 0 = fp32, 1 = bf16 (O, Wt, Hprev, S)
+  const void *O;                  // [B,H,L,d]
+  const void *Wt;                 // [Dm, H*d]
+  const float *bias;              // [Dm] or nullptr
+  const void *Hprev;              // [B,L,Dm]
+  const float *gamma, *beta;      // [Dm]
+  float eps;
+  void *S;                        // [B,L,Dm]
+  float *mean, *rstd;             // [B,L] or nullptr
+};
+bool out_proj_supported(const OutProjArgs &a);
+void launch_out_proj(const OutProjArgs &a, hipStream_t st);
+
 }  // namespace blossom

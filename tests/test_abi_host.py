@@ -180,6 +180,19 @@ def test_validation_codes_attn_bwd_positions(lib):
     assert call(_p(H=4, L=200, d=8, block=16, topk=4, window=8, stis_mode=2, stis_block=1)) == -3
 
 
+def test_validation_codes_out_proj_ln(lib):
+    vp = ctypes.c_void_p
+    a = vp(4096)
+    call = lambda p, Dm=64, O=a, W=a, S=a, g=a, bias=None, eps=1e-5: lib.blossom_out_proj_ln(
+        ctypes.byref(p.c()), Dm, O, W, bias, a, g, a, ctypes.c_float(eps), S, None, None, None)
+    ok = _p(H=2, L=200, d=32, block=16, topk=4)
+    assert call(ok, O=None) == -1 and call(ok, W=None) == -1 and call(ok, S=None) == -1 and call(ok, g=None) == -1
+    assert call(ok, Dm=0) == -4 and call(ok, eps=-1.0) == -4 and call(ok, eps=float("nan")) == -4
+    assert call(ok, O=vp(4100)) == -5 and call(ok, bias=vp(4100)) == -5
+    assert call(ok, Dm=2048) == -3 and call(ok, Dm=60) == -3          # beyond 1024; no multiple of 8
+    assert call(_p(H=32, L=200, d=64, block=16, topk=4)) == -3          # H*d beyond 1024 on the scalar kernel
+
+
 def test_strerror(lib):
     seen = set()
     for code in range(0, -9, -1):
