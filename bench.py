@@ -116,7 +116,7 @@ def algorithmic_pairs(w, valid_len, sel):
     return lt, st, dense
 
 
-STAGES = ["select", "rope_select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "dense", "serve", "copy"]
+STAGES = ["select", "rope_select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "dense", "serve", "copy", "out_proj"]
 PROBE_KINDS = ["matrix instructions only", "softmax VALU work only", "both, operands in registers",
                "both, operands from LDS", "whole tile loop (with global->LDS staging)", "staging only"]
 
@@ -183,7 +183,22 @@ class Runner:
                               B.attn_fwd(self.p_serve, Q, K, V, vl, sel, gw, gb, out=self.fo_nosave, ws=self.ws_fwd)),
             # a plain device copy of one [B,H,L,d] tensor: calibrates the HBM byte counters
             "copy": lambda: self.O_dense.copy_(Q),
+            # the layer around the attention: output projection + residual + LayerNorm on the forward's output
+            "out_proj": lambda: self._out_proj()(),
         }[name]
+
+    def _out_proj(self):
+        if getattr(self, "_op_fn", None) is None:  # weights and buffers are made on first use, once
+            torch, B, w = self.torch, self.B, self.w
+            Q = self.sets[0][0]
+            Dm = w.H * w.d
+            g = torch.Generator(device="cpu").manual_seed(4242)
+            Wt = (torch.randn((Dm, Dm), generator=g) / Dm ** 0.5).to(Q.dtype).to(Q.device)
+            Hp = torch.randn((w.B, w.L, Dm), generator=g).to(Q.dtype).to(Q.device)
+            gamma, beta = torch.ones(Dm, device=Q.device), torch.zeros(Dm, device=Q.device)
+            S = torch.empty_like(Hp)
+            self._op_fn = lambda: B.out_proj_ln(self.p, Dm, self.fo.O, Wt, Hp, gamma, beta, 1e-5, S=S)
+        return self._op_fn
 
     def _rope_select(self):
         if getattr(self, "_rope_fn", None) is None:  # tables and output buffers are made on first use, once

@@ -128,45 +128,49 @@ __global__ __launch_bounds__(kGenThreads) void outproj_generic_kernel(
 // ------------------------------------------------------------------------------------------------
 using namespace mfma;
 
-constexpr int kOpWaves = 8;
-constexpr int kOpPos = 128;            // positions of a workgroup
 constexpr int kOpRowBytes = 144;       // a staged row: 64 bf16 + 16 bytes (rows of 36 words: 16-byte reads of 16 rows hit 64 distinct banks)
-constexpr int kOpSlabBytes = kOpPos * kOpRowBytes;
+// One wavefront per 64 features, each over all positions of the workgroup: d_model 512 takes 8 wavefronts and 128
+// positions (four 32-position blocks per wavefront, 128 accumulator registers, one workgroup per CU); d_model 256
+// takes 4 wavefronts and 64 positions (two blocks, three workgroups per CU, whose load, multiply and store phases overlap).
+template <int DM> struct OpGeo {
+  static constexpr int kWaves = DM / 64;
+  static constexpr int kPos = DM == 512 ? 128 : 64;
+  static constexpr int kSlabBytes = kPos * kOpRowBytes;
+};
 
 // feature (relative to the wavefront's first) that row m of M block mb carries: lane half g = (m/4)%2 ends
 // up holding, for its position, the 32 consecutive features 32 g + 16 mb + 4 (m/8) + m%4
 __device__ __forceinline__ int op_feature(int mb, int m) { return 32 * ((m >> 2) & 1) + 16 * mb + 4 * (m >> 3) + (m & 3); }
 
 template <int DM>
-__global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
+__global__ __launch_bounds__(64 * OpGeo<DM>::kWaves) void outproj_mfma_kernel(
     const uint16_t *__restrict__ O, const uint16_t *__restrict__ Wt, const float *__restrict__ bias,
     const uint16_t *__restrict__ Hprev, const float *__restrict__ gamma, const float *__restrict__ beta, float eps,
     uint16_t *__restrict__ S, float *__restrict__ mean_out, float *__restrict__ rstd_out, int B, int H, int L)
 {
-  constexpr int FW = DM / 64;          // feature groups (wavefronts side by side over the features)
-  constexpr int PH = kOpWaves / FW;    // position parts (1 or 2)
-  constexpr int NBW = (kOpPos / 32) / PH;  // 32-position N blocks per wavefront (4 or 2)
+  constexpr int FW = OpGeo<DM>::kWaves;  // wavefronts side by side over the features
+  constexpr int kOpPos = OpGeo<DM>::kPos, kOpSlabBytes = OpGeo<DM>::kSlabBytes;
+  constexpr int NBW = kOpPos / 32;       // 32-position N blocks per wavefront (4 or 2)
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
-  float *red1 = reinterpret_cast<float *>(lds_raw + 2 * kOpSlabBytes);  // [FW][128] sums
-  float *red2 = red1 + FW * kOpPos;                                      // [FW][128] squared deviations
+  float *red1 = reinterpret_cast<float *>(lds_raw + 2 * kOpSlabBytes);  // [FW][kOpPos] sums
+  float *red2 = red1 + FW * kOpPos;                                      // [FW][kOpPos] squared deviations
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
-  const int wf = wv % FW, wp = wv / FW;
+  const int wf = wv;
   const int c = lane & 31, g = lane >> 5;
   const int K = H * 64;
   const int tiles = (L + kOpPos - 1) / kOpPos;
   const int b = blockIdx.x / tiles, l0 = (blockIdx.x % tiles) * kOpPos;
   const int fbase = wf * 64;
-  const int pbase = wp * (NBW * 32);
 
-  // staging: 1024 16-byte pieces per slab, two per thread (rows tid/8 and 64 + tid/8, piece tid%8)
+  // staging: 8 16-byte pieces per row, two pieces per thread (rows tid/8 and kOpPos/2 + tid/8, piece tid%8)
   const int st_col = tid & 7;
   const uint16_t *st_src0 = O + ((size_t)b * H * L + min(l0 + (tid >> 3), L - 1)) * 64 + st_col * 8;  // head 0; a head
-  const uint16_t *st_src1 = O + ((size_t)b * H * L + min(l0 + 64 + (tid >> 3), L - 1)) * 64 + st_col * 8;  // further is L*64 on
+  const uint16_t *st_src1 = O + ((size_t)b * H * L + min(l0 + kOpPos / 2 + (tid >> 3), L - 1)) * 64 + st_col * 8;  // further is L*64 on
   const int st_dst0 = (tid >> 3) * kOpRowBytes + st_col * 16;
-  const int st_dst1 = st_dst0 + 64 * kOpRowBytes;
+  const int st_dst1 = st_dst0 + (kOpPos / 2) * kOpRowBytes;
   const size_t head_step = (size_t)L * 64;
   // this lane's weight rows (as supplier of row m = c of the two M blocks) at the k run 32 g .. 32 g + 31 of a slab
   const uint16_t *wsrc0 = Wt + (size_t)(fbase + op_feature(0, c)) * K + 32 * g;
@@ -204,7 +208,7 @@ __global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
         wnext[1][ks] = *reinterpret_cast<const bf16x8 *>(wsrc1 + (size_t)(h + 1) * 64 + 8 * ks);
       }
     }
-    const unsigned char *rows = lds_raw + (h & 1) * kOpSlabBytes + (pbase + c) * kOpRowBytes + 64 * g;
+    const unsigned char *rows = lds_raw + (h & 1) * kOpSlabBytes + c * kOpRowBytes + 64 * g;
 #pragma unroll
     for (int ks = 0; ks < 4; ++ks) {
       bf16x8 of[NBW];
@@ -228,17 +232,36 @@ __global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
     __syncthreads();
   }
 
-  // epilogue: accumulator index 16 mb + 4 i + r of the lane is feature f0 + 16 mb + 4 i + r of position pbase + 32 nb + c
+  // epilogue: accumulator index 16 mb + 4 i + r of the lane is feature f0 + 16 mb + 4 i + r of position 32 nb + c
+  // H_prev comes in and S goes out through a 32-row area of LDS per wavefront (the slabs are free now): global
+  // memory sees whole 128-byte rows (8 lanes each), the accumulator layout reads and writes its 16-byte pieces
+  // there.  Only the wavefront itself touches its area: wave_barrier() orders its LDS writes and reads.
   const int f0 = fbase + 32 * g;
+  unsigned char *area = lds_raw + wv * (32 * kOpRowBytes);
+  const int er = lane >> 3, ec = lane & 7;  // as mover of whole rows: row 8 j + er, piece ec
   float s1[NBW];
+  uint4 mv[4];
+#pragma unroll
+  for (int j = 0; j < 4; ++j) {
+    const int t = min(l0 + 8 * j + er, L - 1);
+    mv[j] = *reinterpret_cast<const uint4 *>(Hprev + ((size_t)b * L + t) * DM + fbase + 8 * ec);
+  }
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb) {
-    const int t = min(l0 + pbase + 32 * nb + c, L - 1);
-    const uint16_t *hp = Hprev + ((size_t)b * L + t) * DM + f0;
+#pragma unroll
+    for (int j = 0; j < 4; ++j) *reinterpret_cast<uint4 *>(area + (8 * j + er) * kOpRowBytes + 16 * ec) = mv[j];
+    if (nb + 1 < NBW) {  // the next block's rows travel meanwhile
+#pragma unroll
+      for (int j = 0; j < 4; ++j) {
+        const int t = min(l0 + 32 * (nb + 1) + 8 * j + er, L - 1);
+        mv[j] = *reinterpret_cast<const uint4 *>(Hprev + ((size_t)b * L + t) * DM + fbase + 8 * ec);
+      }
+    }
+    __builtin_amdgcn_wave_barrier();
     float s = 0.0f;
 #pragma unroll
     for (int q = 0; q < 4; ++q) {  // 8 features: M block q/2, rows i = 2 (q%2), 2 (q%2) + 1
-      const uint4 hv = *reinterpret_cast<const uint4 *>(hp + 8 * q);
+      const uint4 hv = *reinterpret_cast<const uint4 *>(area + c * kOpRowBytes + 64 * g + 16 * q);
       const uint32_t hw[4] = {hv.x, hv.y, hv.z, hv.w};
       float bv[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
       if (bias) {
@@ -255,8 +278,9 @@ __global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
         s += a;
       }
     }
+    __builtin_amdgcn_wave_barrier();  // the area is read before the next block's rows land in it
     s1[nb] = s + __shfl_xor(s, 32);  // with the lane that holds the other 32 features of the column
-    if (g == 0) red1[wf * kOpPos + pbase + 32 * nb + c] = s1[nb];
+    if (g == 0) red1[wf * kOpPos + 32 * nb + c] = s1[nb];
   }
   __syncthreads();
   float mean[NBW], rstd[NBW];
@@ -264,7 +288,7 @@ __global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
   for (int nb = 0; nb < NBW; ++nb) {
     float s = 0.0f;
 #pragma unroll
-    for (int f = 0; f < FW; ++f) s += red1[f * kOpPos + pbase + 32 * nb + c];
+    for (int f = 0; f < FW; ++f) s += red1[f * kOpPos + 32 * nb + c];
     mean[nb] = s * (1.0f / (float)DM);
     float v = 0.0f;
 #pragma unroll
@@ -275,44 +299,56 @@ __global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
         v = fmaf(dlt, dlt, v);
       }
     v += __shfl_xor(v, 32);
-    if (g == 0) red2[wf * kOpPos + pbase + 32 * nb + c] = v;
+    if (g == 0) red2[wf * kOpPos + 32 * nb + c] = v;
   }
   __syncthreads();
 #pragma unroll
   for (int nb = 0; nb < NBW; ++nb) {
     float v = 0.0f;
 #pragma unroll
-    for (int f = 0; f < FW; ++f) v += red2[f * kOpPos + pbase + 32 * nb + c];
+    for (int f = 0; f < FW; ++f) v += red2[f * kOpPos + 32 * nb + c];
     rstd[nb] = 1.0f / sqrtf(v * (1.0f / (float)DM) + eps);
   }
+  float gm[4][8], bt[4][8];
 #pragma unroll
   for (int q = 0; q < 4; ++q) {
     const float4 g0 = *reinterpret_cast<const float4 *>(gamma + f0 + 8 * q);
     const float4 g1 = *reinterpret_cast<const float4 *>(gamma + f0 + 8 * q + 4);
     const float4 e0 = *reinterpret_cast<const float4 *>(beta + f0 + 8 * q);
     const float4 e1 = *reinterpret_cast<const float4 *>(beta + f0 + 8 * q + 4);
-    const float gm[8] = {g0.x, g0.y, g0.z, g0.w, g1.x, g1.y, g1.z, g1.w};
-    const float bt[8] = {e0.x, e0.y, e0.z, e0.w, e1.x, e1.y, e1.z, e1.w};
+    gm[q][0] = g0.x; gm[q][1] = g0.y; gm[q][2] = g0.z; gm[q][3] = g0.w;
+    gm[q][4] = g1.x; gm[q][5] = g1.y; gm[q][6] = g1.z; gm[q][7] = g1.w;
+    bt[q][0] = e0.x; bt[q][1] = e0.y; bt[q][2] = e0.z; bt[q][3] = e0.w;
+    bt[q][4] = e1.x; bt[q][5] = e1.y; bt[q][6] = e1.z; bt[q][7] = e1.w;
+  }
 #pragma unroll
-    for (int nb = 0; nb < NBW; ++nb) {
-      const int t = l0 + pbase + 32 * nb + c;
-      if (t >= L) continue;
+  for (int nb = 0; nb < NBW; ++nb) {
+#pragma unroll
+    for (int q = 0; q < 4; ++q) {
       float y[8];
 #pragma unroll
       for (int e = 0; e < 8; ++e)
-        y[e] = fmaf((acc[q >> 1][nb][8 * (q & 1) + e] - mean[nb]) * rstd[nb], gm[e], bt[e]);
+        y[e] = fmaf((acc[q >> 1][nb][8 * (q & 1) + e] - mean[nb]) * rstd[nb], gm[q][e], bt[q][e]);
       uint4 o;
       o.x = pack2_bf16(y[0], y[1]);
       o.y = pack2_bf16(y[2], y[3]);
       o.z = pack2_bf16(y[4], y[5]);
       o.w = pack2_bf16(y[6], y[7]);
-      *reinterpret_cast<uint4 *>(S + ((size_t)b * L + t) * DM + f0 + 8 * q) = o;
+      *reinterpret_cast<uint4 *>(area + c * kOpRowBytes + 64 * g + 16 * q) = o;
     }
+    __builtin_amdgcn_wave_barrier();
+#pragma unroll
+    for (int j = 0; j < 4; ++j) {
+      const int t = l0 + 32 * nb + 8 * j + er;
+      const uint4 o = *reinterpret_cast<const uint4 *>(area + (8 * j + er) * kOpRowBytes + 16 * ec);
+      if (t < L) *reinterpret_cast<uint4 *>(S + ((size_t)b * L + t) * DM + fbase + 8 * ec) = o;
+    }
+    __builtin_amdgcn_wave_barrier();
   }
   if (wf == 0 && g == 0) {
 #pragma unroll
     for (int nb = 0; nb < NBW; ++nb) {
-      const int t = l0 + pbase + 32 * nb + c;
+      const int t = l0 + 32 * nb + c;
       if (t < L) {
         if (mean_out) mean_out[(size_t)b * L + t] = mean[nb];
         if (rstd_out) rstd_out[(size_t)b * L + t] = rstd[nb];
@@ -321,7 +357,11 @@ __global__ __launch_bounds__(64 * kOpWaves) void outproj_mfma_kernel(
   }
 }
 
-size_t op_mfma_lds_bytes(int Dm) { return 2 * (size_t)kOpSlabBytes + 2 * (size_t)(Dm / 64) * kOpPos * sizeof(float); }
+int op_mfma_pos(int Dm) { return Dm == 512 ? OpGeo<512>::kPos : OpGeo<256>::kPos; }
+size_t op_mfma_lds_bytes(int Dm)
+{
+  return 2 * (size_t)op_mfma_pos(Dm) * kOpRowBytes + 2 * (size_t)(Dm / 64) * op_mfma_pos(Dm) * sizeof(float);
+}
 
 size_t op_generic_lds_bytes(int K, int Dm)
 {
@@ -343,10 +383,11 @@ bool out_proj_supported(const OutProjArgs &a)
 void launch_out_proj(const OutProjArgs &a, hipStream_t st)
 {
   if (op_mfma_shape(a)) {
-    const unsigned grid = (unsigned)(a.B * ((a.L + kOpPos - 1) / kOpPos));
+    const int tp = op_mfma_pos(a.Dm);
+    const unsigned grid = (unsigned)(a.B * ((a.L + tp - 1) / tp));
     const size_t lds = op_mfma_lds_bytes(a.Dm);
     auto go = [&](auto kernel) {
-      hipLaunchKernelGGL(kernel, dim3(grid), dim3(64 * kOpWaves), lds, st, (const uint16_t *)a.O, (const uint16_t *)a.Wt,
+      hipLaunchKernelGGL(kernel, dim3(grid), dim3(a.Dm), lds, st, (const uint16_t *)a.O, (const uint16_t *)a.Wt,
                          a.bias, (const uint16_t *)a.Hprev, a.gamma, a.beta, a.eps, (uint16_t *)a.S, a.mean, a.rstd, a.B, a.H,
                          a.L);
     };
