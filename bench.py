@@ -12,6 +12,8 @@ The default run (workload cfg4, L=8192) also times the L=1024 training step (cfg
 short-sequence shape (cfg2, L=200, fp32) the same way and reports them under "l1024_training_step" and
 "l200_training_step".  Roofline entries count algorithmic work only: forward 4d
 flops per unmasked pair, the whole backward 10d (five contractions), bytes of valid positions.
+"out_proj_ln" times the layer around the attention (output projection + residual + LayerNorm in one
+kernel, every position) on the forward's output buffer; it is not part of the step.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
     python bench.py --stage <kernel>        one stage alone (for profilers)
@@ -335,6 +337,15 @@ def measure_workload(w, args, mods, n_sets, headline):
                                                           "bwd_gate", "select")},
         "traffic_source": (f"profiles/{w.name}_hbm_traffic.txt" if traffic else None),
     }
+    if not args.shape:
+        # the layer around the attention (output projection + residual + LayerNorm, every position): HBM-bound by design
+        ms_op = R.timed(R.stage_fn("out_proj"), reps)
+        sz, Dm = (4 if w.dtype == "fp32" else 2), w.H * w.d
+        op_bytes = (3 * w.B * w.L * Dm + Dm * Dm) * sz
+        out["out_proj_ln"] = {"ms": round(ms_op, 4), "bound": "hbm", "achieved": round(op_bytes / (ms_op * 1e-3) / 1e9, 1),
+                              "peak": 8000.0, "unit": "GB/s", "frac": round(op_bytes / (ms_op * 1e-3) / 8e12, 4),
+                              "traffic": traffic.get("out_proj"), "algorithmic_mb": round(op_bytes / 1e6, 1),
+                              "tflops": round(2.0 * w.B * w.L * Dm * Dm / (ms_op * 1e-3) / 1e12, 1)}
     if ms_dense is not None:
         flops_dense = 4.0 * w.d * cnt["nnz_dense"]
         out["dense_causal"] = {"ms": round(ms_dense, 4), "tokens_per_s": round(tokens / (ms_dense * 1e-3), 1),
