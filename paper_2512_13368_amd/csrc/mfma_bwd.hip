@@ -222,26 +222,25 @@ __device__ __forceinline__ bf16x8 split_operand(uint32_t x, uint32_t y)
 // EQ15: the short-term mask is all of Eq. 15, with mask block BLK or (SUB) a power of two below it;
 // compile-time variants of both kernels, so that the plain window keeps its code.
 // =============================================================================================
+// (pid: the workgroup's index among the dQ workgroups of the launch; Ks0..Vs1: four staging tiles of BLK*D halfwords
+// in LDS, 1 KB aligned, distinct objects)
 template <int BLK, bool EQ15, bool SUB>
-__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(
+__device__ __forceinline__ void bwd_dq_body(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const int *__restrict__ sel, const uint16_t *__restrict__ g_lt,
     const uint16_t *__restrict__ g_st, const uint4 *__restrict__ rowI_lt, const uint4 *__restrict__ rowI_st,
     const uint16_t *__restrict__ dO, const float4 *__restrict__ rowstat, const float *__restrict__ gate_w,
-    const float *__restrict__ o_lt, const float *__restrict__ o_st, uint16_t *__restrict__ dQ, KParams p)
+    const float *__restrict__ o_lt, const float *__restrict__ o_st, uint16_t *__restrict__ dQ, KParams p, unsigned pid,
+    uint16_t *Ks0, uint16_t *Ks1, uint16_t *Vs0, uint16_t *Vs1)
 {
   constexpr int UNITS = BLK / 32;
   constexpr int TILE = BLK * D;
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks0[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Ks1[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs0[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Vs1[TILE];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);  // uniform: MFMA regions must be scalar branches
   const int lq = lane & 31, lh = lane >> 5;
-  const unsigned vid = xcd_remap(blockIdx.x, (unsigned)(p.B * p.H * p.NB));
+  const unsigned vid = xcd_remap(pid, (unsigned)(p.B * p.H * p.NB));
   const int bh = (int)(vid / p.NB);
   const int I = p.NB - 1 - (int)(vid % p.NB);
   const int n = clamp_len(valid_len[bh / p.H], p.L);
@@ -510,28 +509,24 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
 // =============================================================================================
 
 template <int BLK, bool EQ15, bool SUB>
-__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
+__device__ __forceinline__ void bwd_dkv_body(
     const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
     const int *__restrict__ valid_len, const uint16_t *__restrict__ g_lt, const uint16_t *__restrict__ g_st,
     const uint4 *__restrict__ rowI_lt, const uint4 *__restrict__ rowI_st, const int *__restrict__ offs,
     const int *__restrict__ items, const uint16_t *__restrict__ dO, const float4 *__restrict__ rowstat,
     const float *__restrict__ gate_w, const float *__restrict__ o_lt, const float *__restrict__ o_st,
-    uint16_t *__restrict__ dK, uint16_t *__restrict__ dV, KParams p)
+    uint16_t *__restrict__ dK, uint16_t *__restrict__ dV, KParams p, unsigned pid, uint16_t *Qs0, uint16_t *Qs1,
+    uint16_t *Gs0, uint16_t *Gs1, uint4 (*rc_s)[BLK])
 {
+  // (rc_s: per-row constants of the staged query tile: splits of -lse2 (x, y) and of -c_x (z, w))
   constexpr int UNITS = BLK / 32;
   constexpr int TILE = BLK * D;
-  __shared__ __attribute__((aligned(1024))) uint16_t Qs0[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Qs1[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Gs0[TILE];
-  __shared__ __attribute__((aligned(1024))) uint16_t Gs1[TILE];
-  // per-row constants of the staged query tile: splits of -lse2 (x, y) and of -c_x (z, w)
-  __shared__ __attribute__((aligned(16))) uint4 rc_s[2][BLK];
 
   const int tid = threadIdx.x;
   const int lane = tid & 63;
   const int wv = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int lq = lane & 31, lh = lane >> 5;
-  const unsigned vid = xcd_remap(blockIdx.x, (unsigned)(p.B * p.H * p.NB));
+  const unsigned vid = xcd_remap(pid, (unsigned)(p.B * p.H * p.NB));
   const int bh = (int)(vid / p.NB);
   const int J = (int)(vid % p.NB);  // early key blocks are selected by more query blocks: start them first
   const int n = clamp_len(valid_len[bh / p.H], p.L);
@@ -810,6 +805,58 @@ __global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2)))
   }
 }
 
+#define BWD_LDS_TILES(BLK)                                                   \
+  __shared__ __attribute__((aligned(1024))) uint16_t lds_t0[(BLK) * D];      \
+  __shared__ __attribute__((aligned(1024))) uint16_t lds_t1[(BLK) * D];      \
+  __shared__ __attribute__((aligned(1024))) uint16_t lds_t2[(BLK) * D];      \
+  __shared__ __attribute__((aligned(1024))) uint16_t lds_t3[(BLK) * D]
+
+#define BWD_DQ_PARAMS                                                                                              \
+  const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,                  \
+      const int *__restrict__ valid_len, const int *__restrict__ sel, const uint16_t *__restrict__ g_lt,           \
+      const uint16_t *__restrict__ g_st, const uint4 *__restrict__ rowI_lt, const uint4 *__restrict__ rowI_st,     \
+      const uint16_t *__restrict__ dO, const float4 *__restrict__ rowstat, const float *__restrict__ gate_w,       \
+      const float *__restrict__ o_lt, const float *__restrict__ o_st, uint16_t *__restrict__ dQ
+#define BWD_DQ_ARGS Q, K, V, valid_len, sel, g_lt, g_st, rowI_lt, rowI_st, dO, rowstat, gate_w, o_lt, o_st, dQ
+#define BWD_DKV_ARGS Q, K, V, valid_len, g_lt, g_st, rowI_lt, rowI_st, offs, items, dO, rowstat, gate_w, o_lt, o_st, dK, dV
+
+template <int BLK, bool EQ15, bool SUB>
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dq_mfma_kernel(BWD_DQ_PARAMS, KParams p)
+{
+  BWD_LDS_TILES(BLK);
+  bwd_dq_body<BLK, EQ15, SUB>(BWD_DQ_ARGS, p, blockIdx.x, lds_t0, lds_t1, lds_t2, lds_t3);
+}
+
+template <int BLK, bool EQ15, bool SUB>
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_dkv_mfma_kernel(
+    const uint16_t *__restrict__ Q, const uint16_t *__restrict__ K, const uint16_t *__restrict__ V,
+    const int *__restrict__ valid_len, const uint16_t *__restrict__ g_lt, const uint16_t *__restrict__ g_st,
+    const uint4 *__restrict__ rowI_lt, const uint4 *__restrict__ rowI_st, const int *__restrict__ offs,
+    const int *__restrict__ items, const uint16_t *__restrict__ dO, const float4 *__restrict__ rowstat,
+    const float *__restrict__ gate_w, const float *__restrict__ o_lt, const float *__restrict__ o_st,
+    uint16_t *__restrict__ dK, uint16_t *__restrict__ dV, KParams p)
+{
+  BWD_LDS_TILES(BLK);
+  __shared__ __attribute__((aligned(16))) uint4 rc_s[2][BLK];
+  bwd_dkv_body<BLK, EQ15, SUB>(BWD_DKV_ARGS, p, blockIdx.x, lds_t0, lds_t1, lds_t2, lds_t3, rc_s);
+}
+
+// dQ and dK/dV in ONE launch (the full backward call): the first B*H*NB workgroups take the key blocks, the
+// rest the query blocks.  The two kernels need the same workgroup shape, the same two wavefronts per SIMD and
+// nearly the same LDS, so nothing is lost by the union, and the short dQ workgroups fill the slots that the
+// tail of the skewed dK/dV walks leaves idle (and one launch gap goes).
+template <int BLK, bool EQ15, bool SUB>
+__global__ __launch_bounds__(BLK * 2) __attribute__((amdgpu_waves_per_eu(2, 2))) void bwd_both_mfma_kernel(
+    BWD_DQ_PARAMS, const int *__restrict__ offs, const int *__restrict__ items, uint16_t *__restrict__ dK,
+    uint16_t *__restrict__ dV, KParams p)
+{
+  BWD_LDS_TILES(BLK);  // the four staging tiles serve either role
+  __shared__ __attribute__((aligned(16))) uint4 rc_s[2][BLK];
+  const unsigned n = (unsigned)(p.B * p.H * p.NB);
+  if (blockIdx.x < n) bwd_dkv_body<BLK, EQ15, SUB>(BWD_DKV_ARGS, p, blockIdx.x, lds_t0, lds_t1, lds_t2, lds_t3, rc_s);
+  else bwd_dq_body<BLK, EQ15, SUB>(BWD_DQ_ARGS, p, blockIdx.x - n, lds_t0, lds_t1, lds_t2, lds_t3);
+}
+
 bool bwd_mfma_supported(const KParams &p, int dtype)
 {
   return dtype == 1 && p.d == 64 && (p.b == 32 || p.b == 64) && !p.bidir &&
@@ -833,6 +880,23 @@ void launch_bwd_mfma(const KParams &p, const BwdArgs &a, const BwdWorkspace &w, 
   };
   const bool eq15 = p.sblk != 0;
   const bool sub = eq15 && p.sblk < p.b;  // mask block smaller than the tile
+  if (do_dq && do_dkv && 2ull * grid <= 0x7FFFFFFFull) {
+    auto go = [&](auto kernel, unsigned threads) {
+      hipLaunchKernelGGL(kernel, dim3(2 * grid), dim3(threads), 0, st, u16(a.Q), u16(a.K), u16(a.V), a.valid_len, a.sel,
+                         w.g_lt, w.g_st, w.rowI_lt, w.rowI_st, u16(a.dO), w.rowstat, a.gate_w, (const float *)a.o_lt,
+                         (const float *)a.o_st, (uint16_t *)a.dQ, w.offs, w.items, (uint16_t *)a.dK, (uint16_t *)a.dV, p);
+    };
+    if (p.b == 32) {
+      if (sub) go(bwd_both_mfma_kernel<32, true, true>, 64);
+      else if (eq15) go(bwd_both_mfma_kernel<32, true, false>, 64);
+      else go(bwd_both_mfma_kernel<32, false, false>, 64);
+    } else {
+      if (sub) go(bwd_both_mfma_kernel<64, true, true>, 128);
+      else if (eq15) go(bwd_both_mfma_kernel<64, true, false>, 128);
+      else go(bwd_both_mfma_kernel<64, false, false>, 128);
+    }
+    return;
+  }
   if (p.b == 32) {
     if (do_dq) {
       if (sub) go_dq(bwd_dq_mfma_kernel<32, true, true>, 64);
