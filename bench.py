@@ -118,7 +118,8 @@ def algorithmic_pairs(w, valid_len, sel):
     return lt, st, dense
 
 
-STAGES = ["select", "rope_select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "dense", "serve", "copy", "out_proj"]
+STAGES = ["select", "rope_select", "fwd", "fwd_save", "bwd", "bwd_gate", "bwd_inverse", "bwd_dq", "bwd_dkv", "bwd_dq_dkv", "dense", "serve", "copy",
+          "out_proj"]
 PROBE_KINDS = ["matrix instructions only", "softmax VALU work only", "both, operands in registers",
                "both, operands from LDS", "whole tile loop (with global->LDS staging)", "staging only"]
 
@@ -179,6 +180,8 @@ class Runner:
             "fwd_save": lambda: B.attn_fwd(p, Q, K, V, vl, sel, gw, gb, out=fo, ws=self.ws_fwd),
             "bwd": bwd(B.BWD_ALL), "bwd_gate": bwd(B.BWD_GATE), "bwd_inverse": bwd(B.BWD_INVERSE),
             "bwd_dq": bwd(B.BWD_DQ), "bwd_dkv": bwd(B.BWD_DKV),
+            # dQ and dK/dV as the full call launches them (one grid on the matrix-core kernels)
+            "bwd_dq_dkv": bwd(B.BWD_DQ | B.BWD_DKV),
             "dense": lambda: B.dense_causal_fwd(p, Q, K, V, vl, O=self.O_dense),
             # serving: selection and forward of the last query block only (the scored position)
             "serve": lambda: (B.select_blocks(self.p_serve, Q, K, vl, sel=sel, ws=self.ws_sel),
@@ -229,7 +232,8 @@ class Runner:
     def kernel_times(self, reps, dense=True):
         ms = {k_: self.timed(self.stage_fn(s_), reps) for k_, s_ in (
             ("select", "select"), ("fwd", "fwd"), ("fwd_saving_for_bwd", "fwd_save"), ("bwd_gate", "bwd_gate"),
-            ("bwd_inverse_list", "bwd_inverse"), ("bwd_dq", "bwd_dq"), ("bwd_dkv", "bwd_dkv"), ("bwd", "bwd"))}
+            ("bwd_inverse_list", "bwd_inverse"), ("bwd_dq", "bwd_dq"), ("bwd_dkv", "bwd_dkv"), ("bwd_dq_dkv", "bwd_dq_dkv"),
+            ("bwd", "bwd"))}
         ms_dense = self.timed(self.stage_fn("dense"), max(2, reps // 4)) if dense else None
         return ms, ms_dense
 
@@ -251,6 +255,8 @@ class Runner:
             "fwd_saving_for_bwd": (4.0 * d * pairs, 4.0 * d * pairs, 4 * tensor * sz + 2 * tensor * 4),   # + o_lt, o_st
             "bwd_dq": (4.0 * d * pairs, 6.0 * d * pairs, 5 * tensor * sz),                                # Q,K,V,dO | dQ
             "bwd_dkv": (6.0 * d * pairs, 8.0 * d * pairs, 6 * tensor * sz),                               # Q,K,V,dO | dK,dV
+            # both in one launch, as the full backward call runs them: Q,K,V,dO read once, dQ,dK,dV written
+            "bwd_dq_dkv": (10.0 * d * pairs, 14.0 * d * pairs, 7 * tensor * sz),
             "bwd_gate": (0.0, 0.0, tensor * (sz + 8)),                                                    # dO, o_lt, o_st
             "select": (0.0, 0.0, 2 * tensor * sz),                                                        # Q, K
             # the whole backward call: 10d flops per pair; Q,K,V,dO,o_lt,o_st read, dQ,dK,dV written
@@ -318,7 +324,11 @@ def measure_workload(w, args, mods, n_sets, headline):
     tokens_timed = sum(int(R.xs[i % n_sets].valid_len.sum()) for i in range(args.steps))  # over the timed steps
     traffic, traffic_sha = ({}, None) if (w.stis_block or args.shape) else profiled_traffic(w.name)
     roof = lambda k_: roofline_entry(w, k_, ms, table, traffic)
-    step_kernels = ["select", "fwd_saving_for_bwd", "bwd_gate", "bwd_dq", "bwd_dkv"]
+    # the launches of a step: on the bf16 matrix-core shapes a full backward call runs dQ and dK/dV as one kernel
+    # (same condition as the library's dispatch); elsewhere they are two launches
+    one_launch = w.dtype == "bf16" and w.d == 64 and w.block in (32, 64) and not w.bidir and \
+        (w.stis_block == 0 or (w.stis_block <= w.block and w.stis_block & (w.stis_block - 1) == 0))
+    step_kernels = ["select", "fwd_saving_for_bwd", "bwd_gate"] + (["bwd_dq_dkv"] if one_launch else ["bwd_dq", "bwd_dkv"])
     dominant = max(step_kernels, key=lambda k_: ms[k_])
     out = {
         "ms_per_step": round(ms_per_step, 4),
@@ -333,7 +343,7 @@ def measure_workload(w, args, mods, n_sets, headline):
         "roofline": roof(dominant),
         "roofline_fwd": roof("fwd"),
         "roofline_bwd": roof("bwd"),
-        "roofline_all": {k_: roof(k_)["frac"] for k_ in ("fwd", "fwd_saving_for_bwd", "bwd_dq", "bwd_dkv", "bwd",
+        "roofline_all": {k_: roof(k_)["frac"] for k_ in ("fwd", "fwd_saving_for_bwd", "bwd_dq", "bwd_dkv", "bwd_dq_dkv", "bwd",
                                                           "bwd_gate", "select")},
         "traffic_source": (f"profiles/{w.name}_hbm_traffic.txt" if traffic else None),
     }
