@@ -219,7 +219,8 @@ int blossom_attn_bwd_positions(const blossom_params *p, int32_t kv_groups, const
  *   S[b,t,n] = (z - mean) * rstd * ln_gamma[n] + ln_beta[n]
  * O is read in the layout blossom_attn_fwd writes, so neither the concatenated heads, nor the projection's
  * output, nor the residual sum ever exist in memory.  Products and sums in fp32.  Every position is computed
- * (a padding row has O = 0 and gives LayerNorm(H_prev + bias)).  Of p only B, H, L, d and dtype are used.
+ * (a padding row has O = 0 and gives LayerNorm(H_prev + bias)).  Of p only B, H, L, d and dtype are used (the
+ * block must pass the same checks as for the other calls).
  *   O        in   [B,H,L,d]              element type p->dtype, 16-byte aligned
  *   W_O_t    in   [d_model, H*d]         p->dtype: row n holds column n of the printed W^O (the layout in which
  *                                         linear layers usually keep their weight, out-features x in-features)
