@@ -57,6 +57,33 @@ def test_out_proj_ln_matches_the_oracle(dtype, Bn, H, L, d, Dm, with_bias):
     assert S2 is out and torch.equal(S2, S)
 
 
+def test_out_proj_ln_seeded_random_shapes():
+    # 30 seeded draws over both kernels: storage type, head size and count, model width (multiples of 8), length
+    rng = np.random.default_rng(20251)
+    for case in range(30):
+        dtype = "bf16" if rng.random() < 0.5 else "fp32"
+        d = int(rng.choice([8, 16, 32, 64]))
+        H = int(rng.integers(1, 9))
+        if dtype == "bf16" and d == 64 and rng.random() < 0.7:
+            Dm = int(rng.choice([256, 512]))                       # the matrix-core kernel
+        else:
+            Dm = 8 * int(rng.integers(1, 65))
+        Bn, L = int(rng.integers(1, 4)), int(rng.integers(1, 301))
+        with_bias = bool(rng.random() < 0.5)
+        eps = float(rng.choice([1e-12, 1e-5, 1e-3]))
+        O, Wt, Hp, gamma, beta, bias = _inputs(dtype, Bn, H, L, d, Dm, 7000 + case)
+        print(f"out_proj_ln draw {case}: {dtype} B{Bn} H{H} L{L} d{d} Dm{Dm} bias {with_bias} eps {eps}", flush=True)
+        p = B.Params(Bn, H, L, d, 16, 1, 1, B.F32 if dtype == "fp32" else B.BF16)
+        S, mean, rstd = B.out_proj_ln(p, Dm, to_dev(O, dtype), to_dev(Wt, dtype), to_dev(Hp, dtype), torch.from_numpy(gamma).cuda(),
+                                      torch.from_numpy(beta).cuda(), eps, bias=torch.from_numpy(bias).cuda() if with_bias else None,
+                                      want_stats=True)
+        torch.cuda.synchronize()
+        ref, mref, rref = oracle.out_proj_ln(O, Wt, Hp, gamma, beta, eps, bias=bias if with_bias else None, want_stats=True)
+        assert_close(host(S), ref, TOL[dtype], f"S (draw {case})")
+        assert_close(host(mean), mref, 1e-4, f"mean (draw {case})")
+        assert_close(host(rstd), rref, 1e-4, f"rstd (draw {case})")
+
+
 def test_out_proj_ln_after_the_attention():
     # the layer as a model runs it: selection, attention, then the fused projection + residual + LayerNorm
     # on the attention's own output buffer; against the oracle's chain
