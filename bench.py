@@ -18,6 +18,7 @@ kernel, every position) on the forward's output buffer; it is not part of the st
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload cfg4]
     python bench.py --stage <kernel>        one stage alone (for profilers)
     python bench.py --stage ceiling         stripped tile loop of the forward: what the pipes allow
+    python bench.py --stage positions       the path under the selection rule as printed, at the paper's own setting
 """
 from __future__ import annotations
 
@@ -403,6 +404,57 @@ def cpu_baseline(R):
                       f"tokens counted as pairs/H * valid_len"}
 
 
+def run_positions(args, torch, B):
+    """bench.py --stage positions: the path under the selection rule as the paper prints it (Sec. 3.4, Eq. 8-13
+    per position, grouped key/value heads) at the paper's own setting (Appendix E: hidden 64 over 8 heads, 4
+    key/value groups, compression blocks of 32 with stride 16, selection blocks of 16, k = 4, window 8, mask block
+    1, fp32, lengths U[20,200], batch 2048): blossom_select_positions, blossom_attn_fwd_positions,
+    blossom_attn_bwd_positions, each timed alone with HIP events, and the three as one training step."""
+    dev = torch.device("cuda:0")
+    Bn, H, G, L, d, l, s_, lsel, k, w = 2048, 8, 4, 200, 8, 32, 16, 16, 4, 8
+    g = torch.Generator(device="cpu").manual_seed(2512)
+    rnd = lambda *shape: torch.randn(shape, generator=g).to(dev)
+    Q, dO = rnd(Bn, H, L, d), rnd(Bn, H, L, d)
+    K, V = rnd(Bn, G, L, d), rnd(Bn, G, L, d)
+    vl = torch.randint(20, L + 1, (Bn,), generator=g, dtype=torch.int32).to(dev)
+    gw, gb = (0.02 * torch.randn((H, 2 * d), generator=g)).to(dev), torch.zeros(H, device=dev)
+    p_sel = B.Params(Bn, H, L, d, lsel, k, 1, B.F32)
+    p = B.Params(Bn, H, L, d, lsel, k, w, B.F32, stis_mode=1, stis_block=1)
+    sel = B.select_positions(p_sel, G, l, s_, Q, K, vl)
+    need = torch.empty(max(16, int(B.lib().blossom_select_positions_workspace_bytes(ctypes_byref(p_sel), G, l, s_))),
+                       dtype=torch.uint8, device=dev)
+    f = B.attn_fwd_positions(p, G, Q, K, V, vl, sel, gw, gb, want_branches=True)
+    ws = torch.empty(max(16, B.workspace_bytes(p, B.WS_BWD)), dtype=torch.uint8, device=dev)
+    bo = B.attn_bwd_positions(p, G, Q, K, V, vl, sel, gw, gb, f, dO, ws=ws)
+    fns = {"select_positions": lambda: B.select_positions(p_sel, G, l, s_, Q, K, vl, sel_pos=sel, ws=need),
+           "fwd_positions": lambda: B.attn_fwd_positions(p, G, Q, K, V, vl, sel, gw, gb, out=f),
+           "bwd_positions": lambda: B.attn_bwd_positions(p, G, Q, K, V, vl, sel, gw, gb, f, dO, out=bo, ws=ws)}
+    fns["step"] = lambda: [fn() for fn in (fns["select_positions"], fns["fwd_positions"], fns["bwd_positions"])]
+    ms = {}
+    for name, fn in fns.items():
+        for _ in range(max(1, args.warmup)):
+            fn()
+        torch.cuda.synchronize()
+        e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        e0.record()
+        for _ in range(args.steps):
+            fn()
+        e1.record()
+        torch.cuda.synchronize()
+        ms[name] = round(e0.elapsed_time(e1) / args.steps, 4)
+    tokens = int(vl.sum().item())
+    sel_bytes = (Q.numel() + K.numel()) * 4 + sel.numel() * 4
+    print(json.dumps({"stage": "positions", "shape": f"B={Bn} H={H} G={G} L={L} d={d} l={l} s={s_} l'={lsel} k={k} w={w} "
+                                                      f"mask block 1 fp32, lens U[20,{L}]",
+                      "ms": ms, "tokens_per_step": tokens, "step_tokens_per_s": round(tokens / (ms["step"] * 1e-3), 1),
+                      "select_positions_gbs": round(sel_bytes / (ms["select_positions"] * 1e-3) / 1e9, 1)}))
+
+
+def ctypes_byref(p):
+    import ctypes
+    return ctypes.byref(p.c())
+
+
 def run_ceiling(args, torch, B):
     """bench.py --stage ceiling: the stripped tile loop of the matrix-core forward (blossom_probe), one
     launch per kind, timed with HIP events; prints what each pipe alone and all of them together cost per
@@ -460,7 +512,7 @@ def main():
     ap.add_argument("--stis-block", type=int, default=0,
                     help="0: short-term mask = causal window (default); N >= 1: all of Eq. 15 with mask block N")
     ap.add_argument("--no-dense", action="store_true")
-    ap.add_argument("--stage", choices=STAGES + ["ceiling"], default=None,
+    ap.add_argument("--stage", choices=STAGES + ["ceiling", "positions"], default=None,
                     help="profiling aid: run only this stage --steps times (after the others ran once) "
                          "and print its average time; the headline line is not produced.  'ceiling' runs the "
                          "stripped tile loop of the matrix-core forward (what each pipe costs alone and together)")
@@ -479,6 +531,9 @@ def main():
     torch.cuda.set_device(torch.device("cuda:0"))
     if args.stage == "ceiling":
         run_ceiling(args, torch, B)
+        return
+    if args.stage == "positions":
+        run_positions(args, torch, B)
         return
     w = WORKLOADS[args.workload]
     if args.stis_block:

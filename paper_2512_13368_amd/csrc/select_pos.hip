@@ -205,6 +205,106 @@ __global__ __launch_bounds__(256) void pos_select_kernel(const T *__restrict__ Q
   for (int e = base + 1 + lane; e < p.k; e += 64) out[e] = -1;
 }
 
+// ---- Eq. 10-13 for short sequences: one LANE per position, a wavefront per 64 consecutive positions of a
+// (row, group).  With at most 64 compression blocks and 64 selection blocks a position's whole chain fits one
+// lane: logits, softmax, Eq. 11 and the group sums run as plain sequential loops in exactly the order of the
+// arithmetic recipe above (so the integers are those of the wavefront-per-position kernel), the scores sit in an
+// LDS column per lane (index*64 + lane: no bank conflicts), and the top-k is k-1 passes over the candidates.
+// The compression-block index is the same in every lane of a step, so the compressed keys are broadcast loads.
+constexpr int kLaneMaxBlocks = 64;
+
+template <typename T, int D>
+__global__ __launch_bounds__(64) void pos_select_lane_kernel(const T *__restrict__ Q, const float *__restrict__ kcmpT,
+                                                             const int *__restrict__ valid_len, int *__restrict__ sel,
+                                                             PosParams p)
+{
+  extern __shared__ float lane_lds[];  // [M][64] scores of the current head, then [NBs][64] group sums
+  const int lane = threadIdx.x;
+  const int chunks = (p.L + 63) / 64;
+  const int bg = blockIdx.x / chunks;
+  const int t = (blockIdx.x % chunks) * 64 + lane;
+  const int r = bg / p.G, g = bg % p.G;
+  const int Hg = p.H / p.G;
+  float *es = lane_lds + lane;
+  float *sg = lane_lds + (size_t)p.M * 64 + lane;
+  const int p0 = p.L - clamp_len(valid_len[r], p.L);
+  if (t >= p.L) return;
+  int *out = sel + ((size_t)bg * p.L + t) * p.k;
+  if (t < p0) {
+    for (int e = 0; e < p.k; ++e) out[e] = -1;
+    return;
+  }
+  int m_hi = -1;
+  if (t - p.l + 1 >= 0) m_hi = min(p.M - 1, (t - p.l + 1) / p.s);
+  const int need = p0 - p.l + 1;
+  const int m_lo = need <= 0 ? 0 : (need + p.s - 1) / p.s;
+  const int n_m = m_hi - m_lo + 1;
+  const int jt = t / p.lsel, j_first = p0 / p.lsel;
+  const int n_cand = jt - j_first;  // candidates j_first .. jt-1
+  const int ra = p.lsel / p.s, rc = p.l / p.s;
+  for (int j = 0; j < n_cand; ++j) sg[j * 64] = 0.0f;
+  const float *km = kcmpT + (size_t)bg * D * p.M;
+  for (int hh = 0; hh < Hg; ++hh) {
+    const T *qrow = Q + (((size_t)r * p.H + (size_t)g * Hg + hh) * p.L + t) * D;
+    float q[D];
+#pragma unroll
+    for (int c4 = 0; c4 < D / 4; ++c4) {
+      float x[4];
+      load4(qrow + 4 * c4, x);
+#pragma unroll
+      for (int e = 0; e < 4; ++e) q[4 * c4 + e] = x[e];
+    }
+    if (n_m > 0) {
+      float mx = -__builtin_huge_valf();
+      for (int m = m_lo; m <= m_hi; ++m) {  // Eq. 10: logits
+        float acc = 0.0f;
+#pragma unroll
+        for (int c = 0; c < D; ++c) acc = __fmaf_rn(q[c], km[(size_t)c * p.M + m], acc);
+        const float x = __fmul_rn(acc, p.fscale);
+        es[(m - m_lo) * 64] = x;
+        mx = fmaxf(mx, x);
+      }
+      float z = 0.0f;  // the normaliser: one sequential sum in ascending block order
+      for (int i = 0; i < n_m; ++i) {
+        const float e = canon_exp(__fsub_rn(es[i * 64], mx));
+        es[i * 64] = e;
+        z = z + e;
+      }
+      for (int i = 0; i < n_m; ++i) es[i * 64] = __fdiv_rn(es[i * 64], z);
+    }
+    for (int j = j_first; j < jt; ++j) {  // Eq. 11 in its printed loop order, Eq. 12 over the heads
+      float acc = 0.0f;
+      for (int a = 0; a < ra; ++a)
+        for (int c = 0; c < rc; ++c) {
+          const int idx = ra * j - a - c;
+          if (idx >= m_lo && idx <= m_hi) acc = acc + es[(idx - m_lo) * 64];
+        }
+      sg[(j - j_first) * 64] = sg[(j - j_first) * 64] + acc;
+    }
+  }
+  // Eq. 13: the own block and the best min(k-1, n_cand) earlier ones by (score descending, index ascending)
+  const int take = min(p.k - 1, n_cand);
+  unsigned long long chosen = 0ull;
+  for (int pass = 0; pass < take; ++pass) {
+    int best = -1;
+    unsigned best_img = 0u;
+    for (int j = 0; j < n_cand; ++j) {
+      if ((chosen >> j) & 1ull) continue;
+      const unsigned img = score_image(sg[j * 64]);
+      if (best < 0 || img > best_img) {  // strictly greater: equal scores keep the lower index
+        best = j;
+        best_img = img;
+      }
+    }
+    chosen |= 1ull << best;
+  }
+  int base = 0;
+  for (int j = 0; j < n_cand; ++j)
+    if ((chosen >> j) & 1ull) out[base++] = j_first + j;
+  out[base++] = jt;
+  for (; base < p.k; ++base) out[base] = -1;
+}
+
 int fill_pos_params(const blossom_params *p, int G, int l, int s, float score_scale, PosParams *pp)
 {
   if (!p) return BLOSSOM_ERR_NULL;
@@ -234,6 +334,13 @@ void launch_pos(const PosParams &pp, const void *Q, const void *K, const int *va
     const int per_wg = 256 / (D / 4);
     BLOSSOM_LAUNCH((cmp_pool_kernel<T, D>), dim3((unsigned)((tasks + per_wg - 1) / per_wg)), dim3(256), 0, st,
                    (const T *)K, valid_len, kcmpT, pp);
+  }
+  if (pp.M <= kLaneMaxBlocks && pp.NBs <= kLaneMaxBlocks) {  // short sequences: a lane per position
+    const unsigned chunks = (unsigned)((pp.L + 63) / 64);
+    const size_t lds_lane = 64 * (size_t)(pp.M + pp.NBs) * sizeof(float);
+    hipLaunchKernelGGL((pos_select_lane_kernel<T, D>), dim3((unsigned)(pp.B * pp.G) * chunks), dim3(64), lds_lane, st,
+                       (const T *)Q, kcmpT, valid_len, sel, pp);
+    return;
   }
   const long items = (long)pp.B * pp.G * pp.L;
   const size_t lds = 4 * (size_t)(D + pp.M + 1) * sizeof(float);

@@ -20,6 +20,9 @@ pytestmark = pytest.mark.gpu
     ("fp32", 2, 2, 2, 50, 32, 16, 4, 8, 3, 1.0),       # l > l', four-fold overlap
     ("fp32", 1, 2, 1, 20, 8, 32, 16, 16, 4, 0.0),      # shorter than one compression block: own block only
     ("bf16", 1, 2, 2, 4096, 64, 32, 16, 16, 16, 0.0),  # 256 selection blocks, 255 compression blocks
+    ("fp32", 2, 4, 2, 1024, 16, 32, 16, 16, 5, 0.0),   # 64 selection blocks, 63 compression blocks: the longest a lane per position takes
+    ("fp32", 2, 4, 2, 1040, 16, 32, 16, 16, 5, 0.0),   # one selection block more: a wavefront per position
+    ("bf16", 3, 6, 2, 257, 32, 16, 8, 16, 8, 0.5),     # three heads per group, k beyond the candidates of early positions
 ])
 def test_select_positions_matches_the_oracle(dtype, Bn, H, G, L, d, l, s, lsel, k, scale):
     rng = np.random.default_rng(31 + L + d + k)
