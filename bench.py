@@ -421,8 +421,7 @@ def run_positions(args, torch, B):
     p_sel = B.Params(Bn, H, L, d, lsel, k, 1, B.F32)
     p = B.Params(Bn, H, L, d, lsel, k, w, B.F32, stis_mode=1, stis_block=1)
     sel = B.select_positions(p_sel, G, l, s_, Q, K, vl)
-    need = torch.empty(max(16, int(B.lib().blossom_select_positions_workspace_bytes(ctypes_byref(p_sel), G, l, s_))),
-                       dtype=torch.uint8, device=dev)
+    need = torch.empty(max(16, B.select_positions_workspace_bytes(p_sel, G, l, s_)), dtype=torch.uint8, device=dev)
     f = B.attn_fwd_positions(p, G, Q, K, V, vl, sel, gw, gb, want_branches=True)
     ws = torch.empty(max(16, B.workspace_bytes(p, B.WS_BWD)), dtype=torch.uint8, device=dev)
     bo = B.attn_bwd_positions(p, G, Q, K, V, vl, sel, gw, gb, f, dO, ws=ws)
@@ -448,11 +447,6 @@ def run_positions(args, torch, B):
                                                       f"mask block 1 fp32, lens U[20,{L}]",
                       "ms": ms, "tokens_per_step": tokens, "step_tokens_per_s": round(tokens / (ms["step"] * 1e-3), 1),
                       "select_positions_gbs": round(sel_bytes / (ms["select_positions"] * 1e-3) / 1e9, 1)}))
-
-
-def ctypes_byref(p):
-    import ctypes
-    return ctypes.byref(p.c())
 
 
 def run_ceiling(args, torch, B):

@@ -389,6 +389,11 @@ def probe(kind: int, K, V, sink, iters: int, stream=None):
         raise BlossomError(rc, "blossom_probe")
 
 
+def select_positions_workspace_bytes(p: Params, kv_groups: int, cmp_block: int, cmp_stride: int) -> int:
+    cp = p.c()
+    return int(lib().blossom_select_positions_workspace_bytes(ctypes.byref(cp), kv_groups, cmp_block, cmp_stride))
+
+
 def select_positions(p: Params, kv_groups: int, cmp_block: int, cmp_stride: int, Q, K, valid_len, score_scale: float = 0.0,
                      sel_pos=None, ws=None, stream=None):
     """blossom_select_positions: the printed selection rule, one row per position and key/value group.
@@ -402,7 +407,7 @@ def select_positions(p: Params, kv_groups: int, cmp_block: int, cmp_stride: int,
         sel_pos = torch.empty((p.B, kv_groups, p.L, p.topk), dtype=torch.int32, device=Q.device)
     _check_tensor(sel_pos, (p.B, kv_groups, p.L, p.topk), torch.int32, "sel_pos")
     cp = p.c()
-    need = int(lib().blossom_select_positions_workspace_bytes(ctypes.byref(cp), kv_groups, cmp_block, cmp_stride))
+    need = select_positions_workspace_bytes(p, kv_groups, cmp_block, cmp_stride)
     if ws is None:
         ws = torch.empty(max(need, 16), dtype=torch.uint8, device=Q.device)
     rc = lib().blossom_select_positions(ctypes.byref(cp), kv_groups, cmp_block, cmp_stride, float(score_scale), _ptr(Q),
